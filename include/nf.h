@@ -1,0 +1,237 @@
+/*
+ * nf.h - C ABI of the nano-batched decoder-layer library for MI355X (gfx950).
+ *
+ * One call of nf_layer_forward() runs one LLaMA-style decoder-layer iteration
+ * over a dense batch that mixes the chunk tokens of prefill requests with one
+ * token of every decode request (paper Sec. 2.1 for the operation order,
+ * Sec. 2.2 for the operation classes, Sec. 3.1 "Batch size" for the dense
+ * batch).  The batch may be split into nano-batches whose compute-bound GEMM
+ * nano-operations run concurrently with the memory-bound paged decode
+ * attention of other nano-batches (Sec. 3.7, Sec. 4.1, Sec. 5).
+ *
+ * Conventions
+ *   - All structs live in HOST memory.  Every pointer inside them, and every
+ *     buffer argument, is a DEVICE pointer unless its comment says "host".
+ *   - bf16 tensors are row-major with the contraction dimension contiguous.
+ *     Accumulation, softmax and row statistics are fp32; indices are int32.
+ *   - The caller owns every device buffer it passes (weights, KV pages, batch
+ *     arrays, activations, workspace).  The library owns only what its opaque
+ *     handles hold (streams, events, the small device-side work lists of a
+ *     plan) and frees it in the matching *_destroy call.
+ *   - Every function returns NF_OK (0) or a negative nf_status; nothing throws
+ *     or aborts across the ABI.  Arguments are validated on the host (using the
+ *     host mirrors in nf_batch) before anything is launched.
+ *   - Calls are asynchronous with respect to the GPU: they return after
+ *     enqueueing.  Work is ordered after everything previously enqueued on the
+ *     hipStream_t passed as `hip_stream`, and its results are visible once that
+ *     stream drains.  A handle must not be used from two threads at once.
+ */
+#ifndef NF_H_
+#define NF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nf_status {
+  NF_OK = 0,
+  NF_EINVAL = -1,     /* null pointer, negative size, unsupported option          */
+  NF_ESHAPE = -2,     /* model or batch shape the kernels do not support          */
+  NF_EWORKSPACE = -3, /* workspace too small (see nf_workspace_bytes)             */
+  NF_EPAGES = -4,     /* page table does not cover a request, or id out of range  */
+  NF_EHIP = -5,       /* a HIP call failed; see nf_last_hip_error                 */
+  NF_EPLAN = -6,      /* plan does not match the batch, or is malformed           */
+  NF_ENOMEM = -7,     /* host allocation failed                                   */
+  NF_EIO = -8         /* profile cache file could not be read or written          */
+} nf_status;
+
+/* Model shape of one decoder layer (Sec. 3.1 "Model configuration"). */
+typedef struct nf_model_desc {
+  int32_t hidden;      /* D_model                                                  */
+  int32_t n_q_heads;   /* Hq                                                       */
+  int32_t n_kv_heads;  /* Hkv; R_GQA = Hq / Hkv                                    */
+  int32_t head_dim;    /* dh: 64 or 128                                            */
+  int32_t ffn_inner;   /* I_model                                                  */
+  int32_t n_experts;   /* 0 or 1: dense FFN; >1: mixture of experts (Sec. 4.1.4)   */
+  int32_t top_k;       /* experts per token (MoE only)                             */
+  int32_t page_size;   /* tokens per KV page; must be 16                           */
+  float rms_eps;
+  float rope_theta;
+} nf_model_desc;
+
+/* bf16 weights of one layer. */
+typedef struct nf_layer_weights {
+  const void *g_attn_norm; /* [D]                                                  */
+  const void *w_qkv;       /* [(Hq+2Hkv)*dh, D]  rows: Q heads, K heads, V heads    */
+  const void *w_o;         /* [D, Hq*dh]                                           */
+  const void *g_ffn_norm;  /* [D]                                                  */
+  const void *w_gate_up;   /* [E][2I, D]  gate rows, then up rows                  */
+  const void *w_down;      /* [E][D, I]                                            */
+  const void *w_router;    /* [E, D], NULL for a dense layer                       */
+} nf_layer_weights;
+
+/*
+ * Paged KV cache of this layer (Sec. 4.2.2: pages are scattered in device
+ * memory).  One page holds page_size = 16 tokens:
+ *   pages[p][0][h] = K block of kv head h, [16 tokens][dh]   (token-major)
+ *   pages[p][1][h] = V block of kv head h, [dh][16 tokens]   (dimension-major)
+ * i.e. bf16 [num_pages][2][Hkv][16*dh].  The dimension-major V block lets the
+ * attention kernel feed V to the matrix cores without a transpose.
+ * nf_layer_forward WRITES the K/V of the batch's tokens into their slots.
+ */
+typedef struct nf_kv_cache {
+  void *pages;
+  int64_t num_pages;
+} nf_kv_cache;
+
+/*
+ * Dense batch.  Token order: the prefill requests first (the tokens of one
+ * request contiguous), then one token per decode request.
+ * ctx_len[r] counts the tokens of request r cached BEFORE this iteration; the
+ * token with index t of request r sits at position ctx_len[r] + (t - q_indptr[r]).
+ * The page list of request r, page_ids[page_indptr[r] .. page_indptr[r+1]),
+ * must cover ctx_len[r] + q_len[r] tokens.
+ * The host_* arrays are host copies of the same data, used for validation,
+ * planning and grid sizing; the device arrays are read by the kernels.
+ */
+typedef struct nf_batch {
+  int32_t n_tokens;
+  int32_t n_prefill_reqs;
+  int32_t n_decode_reqs;
+  const int32_t *q_indptr;         /* [n_reqs + 1]                                 */
+  const int32_t *ctx_len;          /* [n_reqs]                                     */
+  const int32_t *page_indptr;      /* [n_reqs + 1]                                 */
+  const int32_t *page_ids;         /* [page_indptr[n_reqs]]                        */
+  const int32_t *host_q_indptr;    /* host                                         */
+  const int32_t *host_ctx_len;     /* host                                         */
+  const int32_t *host_page_indptr; /* host                                         */
+  const int32_t *host_page_ids;    /* host; may be NULL (then page ids are not range-checked) */
+} nf_batch;
+
+typedef struct nf_ctx nf_ctx;   /* device, lane streams (with CU masks), events, profile tables */
+typedef struct nf_plan nf_plan; /* nano-batch pipeline for one batch + its device work lists      */
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on HIP device `device` (makes it current for the calling thread). */
+int nf_ctx_create(int device, nf_ctx **out);
+void nf_ctx_destroy(nf_ctx *ctx);
+/* hipError_t value of the last failed HIP call made through ctx (0 if none). */
+int nf_last_hip_error(const nf_ctx *ctx);
+/* Static string for a status code. */
+const char *nf_strerror(int status);
+/* Number of compute units of the context's device. */
+int nf_ctx_num_cus(const nf_ctx *ctx);
+/* Host-only validation of a model shape and a batch against a pool of num_pages pages:
+ * the checks nf_layer_forward performs before launching anything.  Needs no GPU. */
+int nf_check_batch(const nf_model_desc *model, const nf_batch *batch, int64_t num_pages);
+
+/* ---- planning (Sec. 4.1: automated pipeline search) ---------------------------------------- */
+
+/*
+ * Kernel profiling for the auto-search (Sec. 4.1.1): times every dense
+ * operation of `model` alone for batch sizes granule, 2*granule, ... max_tokens
+ * and on every CU share in the search set, times decode attention alone on
+ * those CU shares, and times GEMM || attention pairs to obtain the
+ * R -> P resource-mapping table.  Results are kept in ctx and, if cache_path
+ * (host string) is not NULL, written to / read from that text file.
+ * Synchronous; allocates and frees its own scratch device memory.
+ */
+int nf_profile(nf_ctx *ctx, const nf_model_desc *model, int max_tokens, int granule,
+               const char *cache_path);
+
+/*
+ * Auto-search (Sec. 4.1.2 - 4.1.3): chooses the number, sizes, order and CU
+ * share of the nano-operations for this batch from the profiles held by ctx
+ * (built-in analytic estimates if nf_profile was never run).  Uses only the
+ * host mirrors of `batch` plus the device arrays' addresses.
+ * max_nano = 0 searches; max_nano = 1 yields the unsplit single-stream plan;
+ * max_nano = n > 1 bounds the number of nano-batches.
+ * granule: nano-batch boundaries are multiples of it (128 is the GEMM-friendly
+ * value of Sec. 4.1.1; smaller for tiny batches).
+ */
+int nf_plan_nanobatches(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch,
+                        int max_nano, int granule, nf_plan **out);
+
+/*
+ * Explicit pipeline structure (tests and the ablation of Sec. 6.4):
+ * n_nano nano-batches with token boundaries bounds[0..n_nano] (host; bounds[0]
+ * = 0, bounds[n_nano] = n_tokens, strictly increasing).
+ * overlap = 0: every nano-operation on the caller's stream, in order
+ *              (nano-batching only).
+ * overlap = 1: GEMM nano-operations on one lane (stream), attention
+ *              nano-operations on a second lane.  attn_cus / gemm_cus give the
+ *              number of compute units each lane's stream is restricted to
+ *              (0 = unrestricted).  The attention lane takes the first attn_cus
+ *              bits of the CU mask; the GEMM lane the gemm_cus bits after them
+ *              when attn_cus + gemm_cus fits the device, else the first gemm_cus.
+ */
+int nf_plan_manual(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch, int n_nano,
+                   const int32_t *bounds, int overlap, int attn_cus, int gemm_cus, nf_plan **out);
+
+/* Writes a JSON description of the plan into buf (host); returns the number of
+ * bytes needed (excluding the terminator), or a negative status. */
+int nf_plan_describe(const nf_plan *plan, char *buf, size_t buf_len);
+void nf_plan_destroy(nf_plan *plan);
+
+/* ---- the layer ------------------------------------------------------------------------------ */
+
+/* Upper bound of the device workspace nf_layer_forward needs for any batch of up to
+ * max_tokens tokens whose requests hold at most max_context tokens (0 on a bad model). */
+size_t nf_workspace_bytes(const nf_model_desc *model, int max_tokens, int max_context);
+/* Exact workspace requirement of nf_layer_forward with this plan. */
+size_t nf_plan_workspace_bytes(const nf_plan *plan);
+
+/*
+ * One decoder-layer iteration (Sec. 2.1):
+ *   h = RMSNorm(x); [Q|K|V] = h W_qkv^T; rotary embedding on Q, K; K, V appended
+ *   to the pages; attention of every token over its request's cached tokens,
+ *   the earlier tokens of its chunk and itself; y = x + attn W_o^T;
+ *   z = y + FFN(RMSNorm(y)) with FFN = SwiGLU (dense) or top-k routed experts.
+ * plan = NULL runs unsplit on hip_stream (a temporary plan is built and
+ * destroyed inside the call, which then synchronises hip_stream).
+ * x_in  : bf16 [n_tokens, D]; must not alias x_out.
+ * x_out : bf16 [n_tokens, D].
+ * Mutates the KV pages and x_out.  Returns NF_EWORKSPACE / NF_EPAGES /
+ * NF_ESHAPE / NF_EPLAN before launching anything when arguments are inconsistent.
+ */
+int nf_layer_forward(nf_ctx *ctx, const nf_model_desc *model, const nf_layer_weights *weights,
+                     nf_kv_cache *kv, const nf_batch *batch, const nf_plan *plan,
+                     const void *x_in, void *x_out, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/* ---- single operations (kernel-level parity tests and profiling) ---------------------------- */
+
+/* RMSNorm rows ("other operations", Sec. 2.2): out[t] = x[t] * rsqrt(mean(x[t]^2) + eps) * g. */
+int nf_op_rmsnorm(const void *x, const void *g, void *out, int n_tokens, int hidden, float eps,
+                  void *hip_stream);
+
+/* Dense operation (Sec. 2.2): out[M, N] = epilogue(x[M, K] w[N, K]^T).
+ *   NF_EPI_NONE    : plain bf16 store
+ *   NF_EPI_RESIDUAL: out = residual[M, N] + product
+ *   NF_EPI_SWIGLU  : w is [2*N, K] (gate rows then up rows); out[M, N] = silu(gate) * up
+ * Requires K % 64 == 0 and N % 64 == 0. */
+enum { NF_EPI_NONE = 0, NF_EPI_RESIDUAL = 1, NF_EPI_SWIGLU = 2 };
+int nf_op_gemm(const void *x, const void *w, void *out, const void *residual, int M, int N, int K,
+               int epilogue, void *hip_stream);
+
+/* Rotary embedding of the Q and K heads of qkv[n_tokens, (Hq+2Hkv)*dh] (Q rotated
+ * in place) and append of K, V into the pages, for tokens [tok_begin, tok_end). */
+int nf_op_rope_append(nf_ctx *ctx, const nf_model_desc *model, nf_kv_cache *kv, const nf_batch *batch,
+                      const nf_plan *plan, void *qkv, int tok_begin, int tok_end, void *hip_stream);
+
+/* Attention (decode and prefill rows) of tokens [tok_begin, tok_end) of the
+ * plan's batch: reads rotated Q from qkv and K, V from the pages; writes
+ * attn_out[n_tokens, Hq*dh].  tok_begin/tok_end must be nano-batch boundaries
+ * of the plan. */
+int nf_op_attention(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *kv,
+                    const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
+                    void *workspace, size_t workspace_bytes, int nano_index, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NF_H_ */

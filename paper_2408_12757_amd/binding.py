@@ -1,0 +1,262 @@
+"""Thin ctypes binding of libnanoflow.so (the C ABI declared in include/nf.h).
+
+Argument marshalling only: every step of the layer runs in the library's HIP
+kernels.  PyTorch is used by callers for device memory and streams; this module
+takes raw device pointers (``tensor.data_ptr()``) and ``hipStream_t`` handles.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import json
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnanoflow.so")
+
+NF_OK, NF_EINVAL, NF_ESHAPE, NF_EWORKSPACE, NF_EPAGES, NF_EHIP, NF_EPLAN, NF_ENOMEM, NF_EIO = 0, -1, -2, -3, -4, -5, -6, -7, -8
+NF_EPI_NONE, NF_EPI_RESIDUAL, NF_EPI_SWIGLU = 0, 1, 2
+
+EXPORTS = [
+    "nf_ctx_create", "nf_ctx_destroy", "nf_last_hip_error", "nf_strerror", "nf_ctx_num_cus", "nf_check_batch",
+    "nf_profile", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
+    "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_layer_forward",
+    "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention",
+]
+
+
+class nf_model_desc(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn_inner", C.c_int32), ("n_experts", C.c_int32),
+                ("top_k", C.c_int32), ("page_size", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float)]
+
+
+class nf_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn_norm", "w_qkv", "w_o", "g_ffn_norm", "w_gate_up",
+                                          "w_down", "w_router")]
+
+
+class nf_kv_cache(C.Structure):
+    _fields_ = [("pages", C.c_void_p), ("num_pages", C.c_int64)]
+
+
+class nf_batch(C.Structure):
+    _fields_ = [("n_tokens", C.c_int32), ("n_prefill_reqs", C.c_int32), ("n_decode_reqs", C.c_int32),
+                ("q_indptr", C.c_void_p), ("ctx_len", C.c_void_p), ("page_indptr", C.c_void_p),
+                ("page_ids", C.c_void_p), ("host_q_indptr", C.c_void_p), ("host_ctx_len", C.c_void_p),
+                ("host_page_indptr", C.c_void_p), ("host_page_ids", C.c_void_p)]
+
+
+class NfError(RuntimeError):
+    def __init__(self, status: int, where: str, hip: int = 0):
+        self.status = status
+        self.hip = hip
+        msg = lib().nf_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hipError {hip})" if hip else ")"))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -c 'import __graft_entry__ as g; g.build()'` (there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+    P = C.POINTER
+    L.nf_ctx_create.argtypes = [i32, P(vp)]
+    L.nf_ctx_destroy.argtypes = [vp]
+    L.nf_ctx_destroy.restype = None
+    L.nf_last_hip_error.argtypes = [vp]
+    L.nf_strerror.argtypes = [i32]
+    L.nf_strerror.restype = C.c_char_p
+    L.nf_ctx_num_cus.argtypes = [vp]
+    L.nf_check_batch.argtypes = [P(nf_model_desc), P(nf_batch), C.c_int64]
+    L.nf_profile.argtypes = [vp, P(nf_model_desc), i32, i32, C.c_char_p]
+    L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
+    L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, P(vp)]
+    L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
+    L.nf_plan_destroy.argtypes = [vp]
+    L.nf_plan_destroy.restype = None
+    L.nf_workspace_bytes.argtypes = [P(nf_model_desc), i32, i32]
+    L.nf_workspace_bytes.restype = sz
+    L.nf_plan_workspace_bytes.argtypes = [vp]
+    L.nf_plan_workspace_bytes.restype = sz
+    L.nf_layer_forward.argtypes = [vp, P(nf_model_desc), P(nf_layer_weights), P(nf_kv_cache), P(nf_batch), vp,
+                                   vp, vp, vp, sz, vp]
+    L.nf_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp]
+    L.nf_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.nf_op_rope_append.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, i32, i32, vp]
+    L.nf_op_attention.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, vp, vp, sz, i32, vp]
+    _lib = L
+    return L
+
+
+def model_desc(m) -> nf_model_desc:
+    return nf_model_desc(m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn_inner, m.n_experts, m.top_k,
+                         m.page_size, m.rms_eps, m.rope_theta)
+
+
+def _check(status: int, where: str, ctx: "Optional[Context]" = None):
+    if status != NF_OK:
+        raise NfError(status, where, lib().nf_last_hip_error(ctx.handle) if ctx is not None else 0)
+
+
+def _np_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Context:
+    def __init__(self, device: int = 0):
+        h = C.c_void_p()
+        _check(lib().nf_ctx_create(device, C.byref(h)), "nf_ctx_create")
+        self.handle = h
+
+    @property
+    def num_cus(self) -> int:
+        return lib().nf_ctx_num_cus(self.handle)
+
+    def close(self):
+        if self.handle:
+            lib().nf_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class BatchArgs:
+    """nf_batch plus the arrays it points to (kept alive here).
+
+    ``dev`` maps q_indptr / ctx_len / page_indptr / page_ids to device pointers
+    (ints); the host mirrors are numpy int32 arrays.
+    """
+
+    def __init__(self, n_tokens, n_prefill_reqs, n_decode_reqs, host_q_indptr, host_ctx_len,
+                 host_page_indptr, host_page_ids, dev: dict, keepalive=None):
+        self.h_q = _np_i32(host_q_indptr)
+        self.h_c = _np_i32(host_ctx_len)
+        self.h_pi = _np_i32(host_page_indptr)
+        self.h_pid = _np_i32(host_page_ids) if host_page_ids is not None else None
+        self.keepalive = keepalive
+        self.struct = nf_batch(
+            int(n_tokens), int(n_prefill_reqs), int(n_decode_reqs),
+            dev["q_indptr"], dev["ctx_len"], dev["page_indptr"], dev["page_ids"],
+            self.h_q.ctypes.data, self.h_c.ctypes.data, self.h_pi.ctypes.data,
+            self.h_pid.ctypes.data if self.h_pid is not None else None)
+
+
+class Plan:
+    def __init__(self, ctx: Context, handle):
+        self.ctx = ctx
+        self.handle = handle
+
+    def describe(self) -> dict:
+        n = lib().nf_plan_describe(self.handle, None, 0)
+        _check(min(n, 0), "nf_plan_describe")
+        buf = C.create_string_buffer(n + 1)
+        lib().nf_plan_describe(self.handle, buf, n + 1)
+        return json.loads(buf.value.decode())
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().nf_plan_workspace_bytes(self.handle))
+
+    def close(self):
+        if self.handle:
+            lib().nf_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def nf_plan_manual(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int], overlap: bool = False,
+                   attn_cus: int = 0, gemm_cus: int = 0) -> Plan:
+    b = _np_i32(bounds)
+    h = C.c_void_p()
+    md = model_desc(model)
+    _check(lib().nf_plan_manual(ctx.handle, C.byref(md), C.byref(batch.struct), len(b) - 1,
+                                b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)), int(attn_cus),
+                                int(gemm_cus), C.byref(h)), "nf_plan_manual", ctx)
+    return Plan(ctx, h)
+
+
+def nf_plan_nanobatches(ctx: Context, model, batch: BatchArgs, max_nano: int = 0, granule: int = 128) -> Plan:
+    h = C.c_void_p()
+    md = model_desc(model)
+    _check(lib().nf_plan_nanobatches(ctx.handle, C.byref(md), C.byref(batch.struct), int(max_nano), int(granule),
+                                     C.byref(h)), "nf_plan_nanobatches", ctx)
+    return Plan(ctx, h)
+
+
+def nf_profile(ctx: Context, model, max_tokens: int, granule: int = 128, cache_path: Optional[str] = None):
+    md = model_desc(model)
+    _check(lib().nf_profile(ctx.handle, C.byref(md), int(max_tokens), int(granule),
+                            cache_path.encode() if cache_path else None), "nf_profile", ctx)
+
+
+def nf_check_batch(model, batch: BatchArgs, num_pages: int) -> int:
+    """Returns the status code (no exception): host-only validation."""
+    md = model_desc(model)
+    return int(lib().nf_check_batch(C.byref(md), C.byref(batch.struct), int(num_pages)))
+
+
+def nf_workspace_bytes(model, max_tokens: int, max_context: int) -> int:
+    md = model_desc(model)
+    return int(lib().nf_workspace_bytes(C.byref(md), int(max_tokens), int(max_context)))
+
+
+def weights_struct(ptrs: dict) -> nf_layer_weights:
+    return nf_layer_weights(*[ptrs.get(n) for n, _ in nf_layer_weights._fields_])
+
+
+def nf_layer_forward(ctx: Context, model, weights: nf_layer_weights, pages_ptr: int, num_pages: int,
+                     batch: BatchArgs, plan: Optional[Plan], x_in_ptr: int, x_out_ptr: int, workspace_ptr: int,
+                     workspace_bytes: int, stream: int = 0):
+    md = model_desc(model)
+    kv = nf_kv_cache(pages_ptr, int(num_pages))
+    _check(lib().nf_layer_forward(ctx.handle, C.byref(md), C.byref(weights), C.byref(kv), C.byref(batch.struct),
+                                  plan.handle if plan is not None else None, x_in_ptr, x_out_ptr, workspace_ptr,
+                                  int(workspace_bytes), stream), "nf_layer_forward", ctx)
+
+
+def nf_op_rmsnorm(x_ptr, g_ptr, out_ptr, n_tokens, hidden, eps, stream=0):
+    _check(lib().nf_op_rmsnorm(x_ptr, g_ptr, out_ptr, int(n_tokens), int(hidden), float(eps), stream), "nf_op_rmsnorm")
+
+
+def nf_op_gemm(x_ptr, w_ptr, out_ptr, residual_ptr, M, N, K, epilogue=NF_EPI_NONE, stream=0):
+    _check(lib().nf_op_gemm(x_ptr, w_ptr, out_ptr, residual_ptr, int(M), int(N), int(K), int(epilogue), stream),
+           "nf_op_gemm")
+
+
+def nf_op_rope_append(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Plan, qkv_ptr, tok_begin, tok_end,
+                      stream=0):
+    md = model_desc(model)
+    kv = nf_kv_cache(pages_ptr, int(num_pages))
+    _check(lib().nf_op_rope_append(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle, qkv_ptr,
+                                   int(tok_begin), int(tok_end), stream), "nf_op_rope_append", ctx)
+
+
+def nf_op_attention(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Plan, qkv_ptr, attn_out_ptr,
+                    workspace_ptr, workspace_bytes, nano_index=0, stream=0):
+    md = model_desc(model)
+    kv = nf_kv_cache(pages_ptr, int(num_pages))
+    _check(lib().nf_op_attention(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle, qkv_ptr,
+                                 attn_out_ptr, workspace_ptr, int(workspace_bytes), int(nano_index), stream),
+           "nf_op_attention", ctx)

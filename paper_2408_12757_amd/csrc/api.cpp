@@ -1,0 +1,325 @@
+// C ABI: context management, workspace layout, and the nano-operation executor that
+// enqueues the layer's kernels on the caller's stream or on the two lane streams
+// (paper Sec. 5: nano-operations are launched in the searched order and their
+// dependencies are enforced with events).
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "nf_internal.h"
+
+// ------------------------------------------------------------------ context ---
+
+extern "C" int nf_ctx_create(int device, nf_ctx** out) {
+  if (!out) return NF_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return NF_EHIP;
+  nf_ctx* c = new (std::nothrow) nf_ctx();
+  if (!c) return NF_ENOMEM;
+  c->device = device;
+  hipError_t e = hipSetDevice(device);
+  hipDeviceProp_t prop;
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+  if (e != hipSuccess) {
+    delete c;
+    return NF_EHIP;
+  }
+  c->num_cus = prop.multiProcessorCount;
+  *out = c;
+  return NF_OK;
+}
+
+extern "C" void nf_ctx_destroy(nf_ctx* ctx) {
+  if (!ctx) return;
+  for (auto& kv : ctx->streams) (void)hipStreamDestroy(kv.second);
+  nf_profile_free(ctx);
+  delete ctx;
+}
+
+extern "C" int nf_last_hip_error(const nf_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+extern "C" int nf_ctx_num_cus(const nf_ctx* ctx) { return ctx ? ctx->num_cus : 0; }
+
+extern "C" const char* nf_strerror(int status) {
+  switch (status) {
+    case NF_OK: return "ok";
+    case NF_EINVAL: return "invalid argument";
+    case NF_ESHAPE: return "unsupported model or batch shape";
+    case NF_EWORKSPACE: return "workspace too small";
+    case NF_EPAGES: return "page table does not cover the batch";
+    case NF_EHIP: return "HIP call failed";
+    case NF_EPLAN: return "plan does not match the batch or is malformed";
+    case NF_ENOMEM: return "host allocation failed";
+    case NF_EIO: return "profile cache i/o failed";
+    default: return "unknown status";
+  }
+}
+
+// Lane streams, one per (lane, CU range).  n_cus = 0: an ordinary non-blocking stream.
+// Otherwise a stream whose kernels may only run on CU bits [first_cu, first_cu + n_cus)
+// of the device's CU mask.
+int nf_get_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, hipStream_t* out) {
+  if (n_cus < 0 || first_cu < 0 || first_cu + n_cus > ctx->num_cus) return NF_EINVAL;
+  const long key = ((long)lane << 40) | ((long)first_cu << 20) | (long)n_cus;
+  auto it = ctx->streams.find(key);
+  if (it != ctx->streams.end()) {
+    *out = it->second;
+    return NF_OK;
+  }
+  hipStream_t s = nullptr;
+  if (n_cus == 0) {
+    NF_HIP(ctx, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+  } else {
+    const int words = (ctx->num_cus + 31) / 32;
+    std::vector<uint32_t> mask((size_t)words, 0u);
+    for (int b = first_cu; b < first_cu + n_cus; ++b) mask[b >> 5] |= 1u << (b & 31);
+    NF_HIP(ctx, hipExtStreamCreateWithCUMask(&s, (uint32_t)words, mask.data()));
+  }
+  ctx->streams[key] = s;
+  *out = s;
+  return NF_OK;
+}
+
+// ---------------------------------------------------------------- workspace ---
+
+namespace {
+
+struct Workspace {
+  char* h;     // [B, D]   normalised activations (both norms)
+  char* qkv;   // [B, Nqkv]
+  char* attn;  // [B, Hq*dh]
+  char* y;     // [B, D]   x + attention block
+  char* f;     // [B, I]   silu(gate) * up
+  float* parts;
+  size_t total;
+};
+
+Workspace layout_workspace(const nf_model_desc* m, int n_tokens, size_t n_parts, char* base) {
+  Workspace w;
+  const size_t B = (size_t)std::max(1, n_tokens);
+  const size_t nqkv = (size_t)(m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base + off;
+    off += nf_align256(bytes);
+    return p;
+  };
+  w.h = take(B * m->hidden * 2);
+  w.qkv = take(B * nqkv * 2);
+  w.attn = take(B * (size_t)m->n_q_heads * m->head_dim * 2);
+  w.y = take(B * m->hidden * 2);
+  w.f = take(B * (size_t)m->ffn_inner * 2);
+  w.parts = (float*)take(n_parts * m->n_kv_heads * nf_attn_part_floats(m->head_dim) * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+size_t max_parts_bound(const nf_model_desc* m, int max_tokens, int max_context) {
+  const size_t per_group = ((size_t)std::max(0, max_context) + 16 + NF_ATTN_CHUNK - 1) / NF_ATTN_CHUNK + 1;
+  return (size_t)std::max(1, max_tokens) * per_group;
+}
+
+}  // namespace
+
+extern "C" size_t nf_workspace_bytes(const nf_model_desc* model, int max_tokens, int max_context) {
+  if (nf_validate_model(model) != NF_OK || max_tokens < 0) return 0;
+  return layout_workspace(model, max_tokens, max_parts_bound(model, max_tokens, max_context), nullptr).total;
+}
+
+extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan) {
+  if (!plan) return 0;
+  return layout_workspace(&plan->model, plan->n_tokens, (size_t)std::max(1, plan->total_parts), nullptr).total;
+}
+
+// ----------------------------------------------------------------- executor ---
+
+namespace {
+
+struct LayerArgs {
+  const nf_model_desc* m;
+  const nf_layer_weights* w;
+  nf_kv_cache* kv;
+  const nf_batch* b;
+  const char* x_in;
+  char* x_out;
+  Workspace ws;
+};
+
+hipError_t launch_nano_op(const nf_plan* p, const NfNanoOp& op, const LayerArgs& a, hipStream_t s) {
+  const nf_model_desc* m = a.m;
+  const int t0 = op.tok_begin, M = op.tok_end - op.tok_begin;
+  if (M <= 0) return hipSuccess;
+  const size_t D = m->hidden, I = m->ffn_inner;
+  const size_t nqkv = (size_t)(m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  const size_t qdim = (size_t)m->n_q_heads * m->head_dim;
+  hipError_t e = hipSuccess;
+  switch (op.kind) {
+    case NF_OP_KQV:
+      e = nf_launch_rmsnorm(a.x_in + t0 * D * 2, a.w->g_attn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      if (e != hipSuccess) return e;
+      e = nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_qkv, a.ws.qkv + t0 * nqkv * 2, nullptr, M, (int)nqkv, (int)D,
+                         NF_EPI_NONE, s);
+      if (e != hipSuccess) return e;
+      return nf_launch_rope_append(a.ws.qkv, a.kv->pages, p->d_tok_req, a.b->q_indptr, a.b->ctx_len,
+                                   a.b->page_indptr, a.b->page_ids, t0, op.tok_end, m->n_q_heads, m->n_kv_heads,
+                                   m->head_dim, m->rope_theta, s);
+    case NF_OP_ATTN: {
+      const NfAttnShape shp{m->n_q_heads, m->n_kv_heads, m->head_dim, (int32_t)nqkv};
+      e = nf_launch_attention(a.ws.qkv, a.kv->pages, a.b->page_indptr, a.b->page_ids,
+                              p->d_items + p->item_off[op.nano], p->item_cnt[op.nano], shp, a.ws.parts, s);
+      if (e != hipSuccess) return e;
+      return nf_launch_attention_merge(a.ws.parts, p->d_groups + p->group_off[op.nano], p->group_cnt[op.nano], shp,
+                                       a.ws.attn, s);
+    }
+    case NF_OP_O:
+      return nf_launch_gemm(a.ws.attn + t0 * qdim * 2, a.w->w_o, a.ws.y + t0 * D * 2, a.x_in + t0 * D * 2, M, (int)D,
+                            (int)qdim, NF_EPI_RESIDUAL, s);
+    case NF_OP_UG:
+      e = nf_launch_rmsnorm(a.ws.y + t0 * D * 2, a.w->g_ffn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      if (e != hipSuccess) return e;
+      return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_gate_up, a.ws.f + t0 * I * 2, nullptr, M, (int)I, (int)D,
+                            NF_EPI_SWIGLU, s);
+    case NF_OP_D:
+      return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
+                            (int)I, NF_EPI_RESIDUAL, s);
+    default:
+      return hipErrorInvalidValue;
+  }
+}
+
+int run_plan(nf_ctx* ctx, const nf_plan* p, const LayerArgs& a, hipStream_t user) {
+  if (!p->overlap) {
+    for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(p, op, a, user));
+    return NF_OK;
+  }
+  // fork: the lane streams start after everything already enqueued on the caller's stream
+  NF_HIP(ctx, hipEventRecord(p->ev_fork, user));
+  for (int l = 0; l < NF_LANES; ++l) NF_HIP(ctx, hipStreamWaitEvent(p->lane_stream[l], p->ev_fork, 0));
+  for (size_t i = 0; i < p->ops.size(); ++i) {
+    const NfNanoOp& op = p->ops[i];
+    hipStream_t s = p->lane_stream[op.lane];
+    for (int d : op.deps) NF_HIP(ctx, hipStreamWaitEvent(s, p->events[d], 0));
+    NF_HIP(ctx, launch_nano_op(p, op, a, s));
+    if (op.record) NF_HIP(ctx, hipEventRecord(p->events[i], s));
+  }
+  // join: the caller's stream continues after both lanes have drained
+  for (int l = 0; l < NF_LANES; ++l) {
+    NF_HIP(ctx, hipEventRecord(p->ev_join[l], p->lane_stream[l]));
+    NF_HIP(ctx, hipStreamWaitEvent(user, p->ev_join[l], 0));
+  }
+  return NF_OK;
+}
+
+}  // namespace
+
+extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const nf_layer_weights* weights,
+                                nf_kv_cache* kv, const nf_batch* batch, const nf_plan* plan, const void* x_in,
+                                void* x_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx || !weights || !kv || !batch) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  if (model->n_experts > 1) return NF_ESHAPE;  // mixture-of-experts layers are not built yet
+  if (!kv->pages || kv->num_pages < 0) return NF_EINVAL;
+  rc = nf_validate_batch(model, batch, kv->num_pages);
+  if (rc) return rc;
+  if (batch->n_tokens == 0) return NF_OK;
+  if (!x_in || !x_out || x_in == x_out || !workspace) return NF_EINVAL;
+  if (!weights->g_attn_norm || !weights->w_qkv || !weights->w_o || !weights->g_ffn_norm || !weights->w_gate_up ||
+      !weights->w_down)
+    return NF_EINVAL;
+  hipStream_t user = (hipStream_t)hip_stream;
+
+  nf_plan* tmp = nullptr;
+  if (!plan) {
+    const int32_t bounds[2] = {0, batch->n_tokens};
+    rc = nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, &tmp);
+    if (rc) return rc;
+    plan = tmp;
+  }
+  rc = NF_OK;
+  if (plan->n_tokens != batch->n_tokens || plan->batch_sig != nf_batch_signature(batch) ||
+      memcmp(&plan->model, model, sizeof(nf_model_desc)) != 0)
+    rc = NF_EPLAN;
+  if (rc == NF_OK && workspace_bytes < nf_plan_workspace_bytes(plan)) rc = NF_EWORKSPACE;
+  if (rc == NF_OK) {
+    LayerArgs a;
+    a.m = model;
+    a.w = weights;
+    a.kv = kv;
+    a.b = batch;
+    a.x_in = (const char*)x_in;
+    a.x_out = (char*)x_out;
+    a.ws = layout_workspace(model, batch->n_tokens, (size_t)std::max(1, plan->total_parts), (char*)workspace);
+    rc = run_plan(ctx, plan, a, user);
+  }
+  if (tmp) {
+    // the temporary plan owns device work lists the kernels are reading: drain first
+    hipError_t e = hipStreamSynchronize(user);
+    nf_plan_destroy(tmp);
+    if (e != hipSuccess && rc == NF_OK) {
+      ctx->last_hip = (int)e;
+      rc = NF_EHIP;
+    }
+  }
+  return rc;
+}
+
+// --------------------------------------------------------- single operations ---
+
+extern "C" int nf_op_rmsnorm(const void* x, const void* g, void* out, int n_tokens, int hidden, float eps,
+                             void* hip_stream) {
+  if (!x || !g || !out || n_tokens < 0 || hidden <= 0) return NF_EINVAL;
+  if (hidden % 8) return NF_ESHAPE;
+  return nf_launch_rmsnorm(x, g, out, n_tokens, hidden, eps, (hipStream_t)hip_stream) == hipSuccess ? NF_OK : NF_EHIP;
+}
+
+extern "C" int nf_op_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                          int epilogue, void* hip_stream) {
+  if (!x || !w || !out || M < 0 || N <= 0 || K <= 0) return NF_EINVAL;
+  if (epilogue < NF_EPI_NONE || epilogue > NF_EPI_SWIGLU) return NF_EINVAL;
+  if (epilogue == NF_EPI_RESIDUAL && !residual) return NF_EINVAL;
+  if (K % 64 || N % 64) return NF_ESHAPE;
+  return nf_launch_gemm(x, w, out, residual, M, N, K, epilogue, (hipStream_t)hip_stream) == hipSuccess ? NF_OK
+                                                                                                         : NF_EHIP;
+}
+
+extern "C" int nf_op_rope_append(nf_ctx* ctx, const nf_model_desc* model, nf_kv_cache* kv, const nf_batch* batch,
+                                 const nf_plan* plan, void* qkv, int tok_begin, int tok_end, void* hip_stream) {
+  if (!ctx || !kv || !batch || !plan || !qkv) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, kv->num_pages);
+  if (rc) return rc;
+  if (plan->batch_sig != nf_batch_signature(batch)) return NF_EPLAN;
+  if (tok_begin < 0 || tok_end > batch->n_tokens || tok_begin > tok_end) return NF_EINVAL;
+  NF_HIP(ctx, nf_launch_rope_append(qkv, kv->pages, plan->d_tok_req, batch->q_indptr, batch->ctx_len,
+                                    batch->page_indptr, batch->page_ids, tok_begin, tok_end, model->n_q_heads,
+                                    model->n_kv_heads, model->head_dim, model->rope_theta, (hipStream_t)hip_stream));
+  return NF_OK;
+}
+
+extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv, const nf_batch* batch,
+                               const nf_plan* plan, const void* qkv, void* attn_out, void* workspace,
+                               size_t workspace_bytes, int nano_index, void* hip_stream) {
+  if (!ctx || !kv || !batch || !plan || !qkv || !attn_out || !workspace) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, kv->num_pages);
+  if (rc) return rc;
+  if (plan->batch_sig != nf_batch_signature(batch)) return NF_EPLAN;
+  if (nano_index < 0 || nano_index + 1 >= (int)plan->bounds.size()) return NF_EINVAL;
+  const size_t need = nf_align256((size_t)std::max(1, plan->total_parts) * model->n_kv_heads *
+                                  nf_attn_part_floats(model->head_dim) * sizeof(float));
+  if (workspace_bytes < need) return NF_EWORKSPACE;
+  const int32_t nqkv = (model->n_q_heads + 2 * model->n_kv_heads) * model->head_dim;
+  const NfAttnShape shp{model->n_q_heads, model->n_kv_heads, model->head_dim, nqkv};
+  hipStream_t s = (hipStream_t)hip_stream;
+  NF_HIP(ctx, nf_launch_attention(qkv, kv->pages, batch->page_indptr, batch->page_ids,
+                                  plan->d_items + plan->item_off[nano_index], plan->item_cnt[nano_index], shp,
+                                  (float*)workspace, s));
+  NF_HIP(ctx, nf_launch_attention_merge((const float*)workspace, plan->d_groups + plan->group_off[nano_index],
+                                        plan->group_cnt[nano_index], shp, attn_out, s));
+  return NF_OK;
+}

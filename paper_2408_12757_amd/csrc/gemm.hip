@@ -1,0 +1,214 @@
+// Dense operations (paper Sec. 2.2): out[M, N] = epilogue(x[M, K] . w[N, K]^T), bf16 in,
+// fp32 accumulation on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16).
+//
+// Tiling: one workgroup of 4 wavefronts computes a BM x BN output tile and walks K in
+// steps of 64.  The x and w tiles are staged through LDS (register-staged double
+// buffering: the global loads of step k+1 are in flight while step k is multiplied).
+// The product is formed transposed - w rows feed the A operand, x rows the B operand -
+// so that each lane ends up with 4 consecutive output columns of one token row and can
+// store 8 bytes at a time.
+//
+// The K loop order and the MFMA instruction are the same for every M, so an output row
+// is bit-identical no matter which token range (nano-batch) it was computed in.
+#include "nf_device.h"
+#include "nf_kernels.h"
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row: 144 B keeps ds_read_b128 conflict-free
+
+enum { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+// Workgroup index -> tile index so that the tiles one XCD works on are consecutive
+// (workgroups are dealt round-robin to the 8 XCDs; each XCD has its own L2).
+__device__ __forceinline__ int xcd_remap(int b, int nblocks) {
+  const int q = nblocks >> 3, r = nblocks & 7;
+  const int xcd = b & 7, idx = b >> 3;
+  return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
+__device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
+
+// BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
+                                                      bf16_t* __restrict__ Y, const bf16_t* __restrict__ R, int M,
+                                                      int N, int K, int tiles_m, int tiles_n) {
+  constexpr int WM = BM / 2, WN = BN / 2;   // wavefront tile
+  constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wavefront
+  constexpr int A_CHUNKS = BM * 8 / 256;    // 16-byte chunks per thread per stage
+  constexpr int B_CHUNKS = BN * 8 / 256;
+  __shared__ __attribute__((aligned(16))) bf16_t sX[2][BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[2][BN * LDS_STRIDE];
+
+  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int tm = tile % tiles_m, tn = tile / tiles_m;
+  const int m0 = tm * BM;
+  const int n0 = tn * BN;  // first output column of this tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // global -> register staging
+  const bf16_t* xg[A_CHUNKS];
+  const bf16_t* wg[B_CHUNKS];
+  int xs[A_CHUNKS], ws[B_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) {
+    const int q = i * 256 + tid, row = q >> 3, c = q & 7;
+    int gm = m0 + row;
+    gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+    xg[i] = X + (size_t)gm * K + c * 8;
+    xs[i] = row * LDS_STRIDE + c * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_CHUNKS; ++i) {
+    const int q = i * 256 + tid, row = q >> 3, c = q & 7;
+    int gn;
+    if (EPI == EPI_SWIGLU) {
+      // tile rows alternate in 32-row groups: gate rows of 32 output columns, then their up rows
+      const int grp = row >> 5, within = row & 31;
+      const int col = (n0 >> 1) + (grp >> 1) * 32 + within;  // output column (N = ffn inner)
+      gn = (grp & 1) * N + col;
+    } else {
+      gn = n0 + row;
+    }
+    wg[i] = W + (size_t)gn * K + c * 8;
+    ws[i] = row * LDS_STRIDE + c * 8;
+  }
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  u32x4 xr[A_CHUNKS], wr[B_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) xr[i] = *reinterpret_cast<const u32x4*>(xg[i]);
+#pragma unroll
+  for (int i = 0; i < B_CHUNKS; ++i) wr[i] = *reinterpret_cast<const u32x4*>(wg[i]);
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[0][xs[i]]) = xr[i];
+#pragma unroll
+  for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[0][ws[i]]) = wr[i];
+  __syncthreads();
+
+  const int KT = K / BK;
+  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < KT) {
+      const int koff = (kt + 1) * BK;
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) xr[i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) wr[i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
+    }
+    const bf16_t* cx = &sX[cur][(wm * WM + frag_row) * LDS_STRIDE + frag_k];
+    const bf16_t* cw = &sW[cur][(wn * WN + frag_row) * LDS_STRIDE + frag_k];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fw[TN], fx[TM];
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(cw + i * 32 * LDS_STRIDE + kk * 16);
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fx[j] = *reinterpret_cast<const bf16x8*>(cx + j * 32 * LDS_STRIDE + kk * 16);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) {
+      const int nxt = cur ^ 1;
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[nxt][xs[i]]) = xr[i];
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[nxt][ws[i]]) = wr[i];
+    }
+    __syncthreads();
+  }
+
+  // Epilogue.  acc[i][j][v]: token row m = m0 + wm*WM + j*32 + (lane & 31);
+  // tile column c = wn*WN + i*32 + 8*(v/4) + 4*(lane >> 5) + (v & 3).
+  const int col4 = 4 * (lane >> 5);
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm * WM + j * 32 + (lane & 31);
+    if (m >= M) continue;
+    if (EPI == EPI_SWIGLU) {
+      // 32-column groups come in (gate, up) pairs: acc[2p] is gate, acc[2p+1] is up
+#pragma unroll
+      for (int p = 0; p < TN / 2; ++p) {
+        const int ocol0 = (n0 >> 1) + (wn * (TN / 2) + p) * 32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = silu_f(acc[2 * p][j][q * 4 + e]) * acc[2 * p + 1][j][q * 4 + e];
+          u32x2 pk = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
+          *reinterpret_cast<u32x2*>(Y + (size_t)m * N + ocol0 + q * 8 + col4) = pk;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const size_t off = (size_t)m * N + n0 + wn * WN + i * 32 + q * 8 + col4;
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][q * 4 + e];
+          if (EPI == EPI_RESIDUAL) {
+            const u32x2 r = *reinterpret_cast<const u32x2*>(R + off);
+            o[0] += __uint_as_float(r[0] << 16);
+            o[1] += __uint_as_float(r[0] & 0xffff0000u);
+            o[2] += __uint_as_float(r[1] << 16);
+            o[3] += __uint_as_float(r[1] & 0xffff0000u);
+          }
+          u32x2 pk = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
+          *reinterpret_cast<u32x2*>(Y + off) = pk;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN>
+hipError_t launch(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
+                  hipStream_t s) {
+  const int tiles_m = (M + BM - 1) / BM;
+  // SwiGLU: a BN-wide tile of the stacked [2N, K] weight yields BN/2 output columns
+  const int tiles_n = epilogue == EPI_SWIGLU ? (2 * N) / BN : N / BN;
+  const dim3 grid(tiles_m * tiles_n), block(256);
+  const bf16_t* X = (const bf16_t*)x;
+  const bf16_t* W = (const bf16_t*)w;
+  bf16_t* Y = (bf16_t*)out;
+  const bf16_t* R = (const bf16_t*)residual;
+  switch (epilogue) {
+    case EPI_NONE:
+      gemm_kernel<BM, BN, EPI_NONE><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      break;
+    case EPI_RESIDUAL:
+      gemm_kernel<BM, BN, EPI_RESIDUAL><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      break;
+    default:
+      gemm_kernel<BM, BN, EPI_SWIGLU><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Requires K % 64 == 0 and N % 64 == 0 (checked by the caller on the host).
+hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                          int epilogue, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+  if (n_eff % 128 == 0) return launch<128, 128>(x, w, out, residual, M, N, K, epilogue, s);
+  return launch<128, 64>(x, w, out, residual, M, N, K, epilogue, s);
+}

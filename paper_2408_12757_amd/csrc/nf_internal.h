@@ -1,0 +1,89 @@
+// Host-side internals of the library: context, plan, and the helpers shared by
+// the planner and the executor.  Nothing here crosses the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/nf.h"
+#include "nf_kernels.h"
+
+// Keys per attention work item.  Part of the numerics contract: a request's keys are
+// always cut at multiples of this length, whatever the batch split or CU share.
+constexpr int NF_ATTN_CHUNK = 1024;
+
+enum NfOpKind { NF_OP_KQV = 0, NF_OP_ATTN = 1, NF_OP_O = 2, NF_OP_UG = 3, NF_OP_D = 4, NF_OP_KINDS = 5 };
+enum NfLane { NF_LANE_GEMM = 0, NF_LANE_ATTN = 1, NF_LANES = 2 };
+
+// One nano-operation (paper Sec. 3.7): a parent operation restricted to the token
+// range [tok_begin, tok_end) of the dense batch.
+struct NfNanoOp {
+  int kind;
+  int nano;  // index of the nano-batch the range belongs to
+  int tok_begin, tok_end;
+  int lane;
+  std::vector<int> deps;  // indices of earlier nano-ops this one waits for (other lane only)
+  bool record = false;    // some later nano-op on another lane waits for this one
+};
+
+struct NfProfile;  // kernel timing tables (planner input)
+
+struct nf_ctx {
+  int device = 0;
+  int num_cus = 0;
+  int last_hip = 0;
+  // lane streams keyed by (lane, first CU bit, CU count); count 0 = unmasked stream
+  std::map<long, hipStream_t> streams;
+  NfProfile* profile = nullptr;
+};
+
+struct nf_plan {
+  nf_model_desc model;
+  int n_tokens = 0, n_reqs = 0, n_prefill_reqs = 0;
+  uint64_t batch_sig = 0;
+  std::vector<int> bounds;  // nano-batch token boundaries, size n_nano + 1
+  std::vector<NfNanoOp> ops;  // launch order
+  int overlap = 0;
+  int lane_cus[NF_LANES] = {0, 0};        // CU count per lane (0 = whole chip, no mask)
+  int lane_cu_first[NF_LANES] = {0, 0};   // first CU bit of the lane's mask
+  hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
+  std::vector<hipEvent_t> events;  // one per nano-op that records
+  hipEvent_t ev_fork = nullptr, ev_join[NF_LANES] = {nullptr, nullptr};
+  // device work lists
+  void* dev_blob = nullptr;
+  int32_t* d_tok_req = nullptr;
+  NfAttnItem* d_items = nullptr;
+  NfAttnGroup* d_groups = nullptr;
+  std::vector<int> item_off, item_cnt, group_off, group_cnt;  // per nano-batch
+  int total_parts = 0;
+  double est_time_us = 0.0;  // planner's estimate of the pipeline length
+  std::string origin;        // "manual" | "search"
+};
+
+#define NF_HIP(ctx, call)                         \
+  do {                                            \
+    hipError_t e__ = (call);                      \
+    if (e__ != hipSuccess) {                      \
+      if (ctx) (ctx)->last_hip = (int)e__;        \
+      return NF_EHIP;                             \
+    }                                             \
+  } while (0)
+
+int nf_validate_model(const nf_model_desc* m);
+int nf_validate_batch(const nf_model_desc* m, const nf_batch* b, int64_t num_pages);
+uint64_t nf_batch_signature(const nf_batch* b);
+int nf_get_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, hipStream_t* out);
+void nf_profile_free(nf_ctx* ctx);
+extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan);
+
+// Builds the device work lists, dependencies and events of a plan whose bounds, ops
+// order, lanes and CU shares are already filled in.
+int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch);
+// Default launch order for given nano-batch bounds (used by nf_plan_manual and as the
+// search's starting point).
+void nf_plan_default_order(nf_plan* p, int overlap);
+
+size_t nf_align256(size_t v);

@@ -1,0 +1,49 @@
+// Host-callable launchers of the HIP kernels and the work-list records shared
+// between the planner (host) and the attention kernels (device).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// One attention work item: the rows of up to 16/G consecutive tokens of one
+// request (G = q heads per kv head) against keys [key_begin, key_end) of that
+// request.  Token tok0 + j sits at position pos0 + j and may read keys
+// 0 .. pos0 + j.  key_begin is a multiple of the page size.
+struct NfAttnItem {
+  int32_t req;
+  int32_t tok0;
+  int32_t n_tok;
+  int32_t pos0;
+  int32_t key_begin;
+  int32_t key_end;
+  int32_t part;   // slot of the partial result in the workspace
+  int32_t pad;
+};
+
+// One group of query rows whose partial results (part0 .. part0 + n_parts)
+// are merged into the final attention output.
+struct NfAttnGroup {
+  int32_t tok0;
+  int32_t n_tok;
+  int32_t part0;
+  int32_t n_parts;
+};
+
+struct NfAttnShape {
+  int32_t n_q_heads, n_kv_heads, head_dim, n_qkv;  // n_qkv = row stride of the qkv buffer
+};
+
+static inline size_t nf_attn_part_floats(int head_dim) { return (size_t)16 * head_dim + 32; }
+
+hipError_t nf_launch_rmsnorm(const void* x, const void* g, void* out, int n_tokens, int hidden, float eps,
+                             hipStream_t s);
+hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req, const int32_t* q_indptr,
+                                 const int32_t* ctx_len, const int32_t* page_indptr, const int32_t* page_ids,
+                                 int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
+                                 float rope_theta, hipStream_t s);
+hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                          int epilogue, hipStream_t s);
+hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
+                               const int32_t* page_ids, const NfAttnItem* items, int n_items,
+                               const NfAttnShape& shp, float* parts, hipStream_t s);
+hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
+                                     const NfAttnShape& shp, void* attn_out, hipStream_t s);

@@ -1,0 +1,83 @@
+"""Helpers for the GPU parity tests: build a case from the seeded generators, run the
+HIP path through the C-ABI binding and the CPU oracle on the same inputs."""
+import numpy as np
+import torch
+
+from oracle import decoder_layer as orc
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import harness as hz
+from paper_2408_12757_amd import workloads as wl
+
+# the benchmark spec tolerance for bf16 with fp32 accumulation: max |gpu - ref| / max |ref| per tensor
+REL_TOL = 2e-2
+DEV = "cuda:0"
+
+
+def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.max(np.abs(gpu.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def f64(bits: np.ndarray) -> np.ndarray:
+    return orc.widen(bits)
+
+
+class Case:
+    """One synthetic layer problem resident on the GPU, with host copies for the oracle."""
+
+    def __init__(self, model, batch: wl.Batch, seed: int, weights=None, ctx=None):
+        self.model = model
+        self.batch = batch
+        self.weights = weights if weights is not None else wl.make_weights(model, seed)
+        self.x_bits = wl.make_x(batch.n_tokens, model.hidden, seed + 1)
+        self.pages_bits = wl.make_kv_pages_host(model, batch.num_pages, seed + 3)
+        self.pages = hz.bf16_tensor(self.pages_bits, DEV)
+        self.runner = hz.LayerRunner(model, self.weights, self.pages, DEV, ctx=ctx)
+        self.ctx = self.runner.ctx
+        self.args = hz.upload_batch(batch, DEV)
+        self.x = hz.bf16_tensor(self.x_bits, DEV)
+
+    def reset_pages(self):
+        self.pages.copy_(hz.bf16_tensor(self.pages_bits, DEV))
+
+    def run(self, plan=None):
+        """Returns (z bits [B, D], pages bits after the call)."""
+        self.reset_pages()
+        out = self.runner.forward(self.args, self.x, plan)
+        torch.cuda.synchronize()
+        return hz.bf16_bits(out), hz.bf16_bits(self.pages)
+
+    def oracle(self, reqs=None):
+        b, x, pages = self.batch, self.x_bits, self.pages_bits
+        tok = np.arange(b.n_tokens)
+        if reqs is not None:
+            b, tok, phys = wl.subset_batch(self.batch, reqs)
+            x, pages = x[tok], pages[phys]
+        z, k, v = orc.layer_forward(self.model, self.weights, pages, b, x)
+        return z, k, v, tok
+
+    def check(self, z_bits, pages_bits, reqs=None, tol=REL_TOL):
+        z, k, v, tok = self.oracle(reqs)
+        e_z = rel_err(f64(z_bits[tok]), z)
+        kg, vg = hz.read_kv_rows(pages_bits, self.model, self.batch, tok)
+        e_k = rel_err(f64(kg), k)
+        e_v = rel_err(f64(vg), v)
+        assert np.all(np.isfinite(f64(z_bits))), "non-finite output"
+        assert e_z <= tol and e_k <= tol and e_v <= tol, (e_z, e_k, e_v)
+        return e_z, e_k, e_v
+
+
+def untouched_pages_equal(case: Case, pages_after: np.ndarray) -> bool:
+    """Every page slot not written by the append must be unchanged."""
+    m, b = case.model, case.batch
+    P, Hkv, dh = m.page_size, m.n_kv_heads, m.head_dim
+    before = case.pages_bits.reshape(-1, 2, Hkv, P * dh).copy()
+    after = pages_after.reshape(-1, 2, Hkv, P * dh).copy()
+    tok_req = np.repeat(np.arange(b.n_reqs), np.diff(b.q_indptr))
+    for t in range(b.n_tokens):
+        r = int(tok_req[t])
+        pos = int(b.ctx_len[r]) + int(t - b.q_indptr[r])
+        page, slot = int(b.page_ids[int(b.page_indptr[r]) + pos // P]), pos % P
+        for arr in (before, after):
+            arr[page, 0].reshape(Hkv, P, dh)[:, slot, :] = 0
+            arr[page, 1].reshape(Hkv, dh, P)[:, :, slot] = 0
+    return bool(np.array_equal(before, after))

@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Run with -m gpu on an MI355X."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_layer as orc
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import harness as hz
+from paper_2408_12757_amd import workloads as wl
+
+from gpu_util import DEV, REL_TOL, Case, f64, rel_err, untouched_pages_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = nf.Context(0)
+    yield c
+    c.close()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------ single operations ---
+
+@pytest.mark.parametrize("T,D", [(1, 512), (37, 4096), (64, 8192)])
+def test_rmsnorm_kernel(T, D):
+    say("rmsnorm", T, D)
+    r = np.random.default_rng(T * 7 + D)
+    x = wl.f32_to_bf16_bits(r.standard_normal((T, D)).astype(np.float32) * 3)
+    g = wl.f32_to_bf16_bits(1 + 0.1 * r.standard_normal(D).astype(np.float32))
+    xt, gt = hz.bf16_tensor(x, DEV), hz.bf16_tensor(g, DEV)
+    out = torch.empty_like(xt)
+    nf.nf_op_rmsnorm(xt.data_ptr(), gt.data_ptr(), out.data_ptr(), T, D, 1e-5)
+    torch.cuda.synchronize()
+    ref = orc.rmsnorm(f64(x), f64(g), 1e-5)
+    assert rel_err(f64(hz.bf16_bits(out)), ref) <= 1e-2
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (64, 1536, 512), (200, 192, 1408), (333, 512, 4096), (128, 6144, 4096)])
+def test_gemm_kernel_plain_and_residual(M, N, K):
+    say("gemm", M, N, K)
+    r = np.random.default_rng(M + N + K)
+    x = wl.f32_to_bf16_bits(r.standard_normal((M, K)).astype(np.float32))
+    w = wl.f32_to_bf16_bits(0.05 * r.standard_normal((N, K)).astype(np.float32))
+    res = wl.f32_to_bf16_bits(r.standard_normal((M, N)).astype(np.float32))
+    xt, wt, rt = hz.bf16_tensor(x, DEV), hz.bf16_tensor(w, DEV), hz.bf16_tensor(res, DEV)
+    # rows past M in the output buffer must stay untouched
+    out = torch.full((M + 3, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), None, M, N, K, nf.NF_EPI_NONE)
+    torch.cuda.synchronize()
+    ref = orc.dense(f64(x), f64(w))
+    got = f64(hz.bf16_bits(out))
+    assert rel_err(got[:M], ref) <= REL_TOL / 2
+    assert np.all(got[M:] == 7.0)
+    nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), rt.data_ptr(), M, N, K, nf.NF_EPI_RESIDUAL)
+    torch.cuda.synchronize()
+    assert rel_err(f64(hz.bf16_bits(out))[:M], ref + f64(res)) <= REL_TOL / 2
+
+
+@pytest.mark.parametrize("M,I,K", [(64, 1408, 512), (130, 256, 1024), (77, 14336, 4096)])
+def test_gemm_kernel_swiglu(M, I, K):
+    say("gemm swiglu", M, I, K)
+    r = np.random.default_rng(M + I + K)
+    x = wl.f32_to_bf16_bits(r.standard_normal((M, K)).astype(np.float32))
+    w = wl.f32_to_bf16_bits(0.05 * r.standard_normal((2 * I, K)).astype(np.float32))
+    xt, wt = hz.bf16_tensor(x, DEV), hz.bf16_tensor(w, DEV)
+    out = torch.empty((M, I), dtype=torch.bfloat16, device=DEV)
+    nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), None, M, I, K, nf.NF_EPI_SWIGLU)
+    torch.cuda.synchronize()
+    wf = f64(w)
+    ref = orc.silu(orc.dense(f64(x), wf[:I])) * orc.dense(f64(x), wf[I:])
+    assert rel_err(f64(hz.bf16_bits(out)), ref) <= REL_TOL / 2
+
+
+def test_gemm_rejects_bad_shapes():
+    t = torch.zeros(64 * 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_gemm(t.data_ptr(), t.data_ptr(), t.data_ptr(), None, 8, 64, 48)
+    assert e.value.status == nf.NF_ESHAPE
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_gemm(t.data_ptr(), t.data_ptr(), t.data_ptr(), None, 8, 64, 64, nf.NF_EPI_RESIDUAL)
+    assert e.value.status == nf.NF_EINVAL
+
+
+# ------------------------------------------------------------------ whole layer ---
+
+def test_c1_layer_matches_oracle_and_appends_kv(ctx):
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2, spare_pages=7)
+    say("C1 layer", b.n_tokens, "tokens", b.num_pages, "pages")
+    case = Case(cfg.model, b, cfg.seed, ctx=ctx)
+    z, pages = case.run(None)
+    errs = case.check(z, pages)
+    say("C1 rel err z/k/v", errs)
+    assert untouched_pages_equal(case, pages)
+
+
+def small_gqa_model(**kw):
+    base = dict(hidden=256, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_inner=512, rope_theta=5e5)
+    base.update(kw)
+    return wl.ModelDesc(**base)
+
+
+@pytest.mark.parametrize("name,model,q_lens,ctx_lens,n_pf", [
+    # contexts around page boundaries, single-token batch pieces
+    ("page_edges", small_gqa_model(), [1] * 8, [0, 1, 14, 15, 16, 17, 31, 32], 0),
+    # several attention chunks per request (chunk = 1024 keys) incl. exact multiples
+    ("long_ctx", small_gqa_model(), [1] * 5, [1023, 1024, 1025, 2047, 3000], 0),
+    # chunked prefill with cached prefix, chunk crossing pages and the 1024-key chunk edge
+    ("prefill_prior", small_gqa_model(), [37, 5, 1, 1], [1000, 0, 77, 200], 2),
+    # G = 8 (two tokens per row group), dh = 128
+    ("gqa8", small_gqa_model(n_q_heads=16, n_kv_heads=2), [19, 1, 1, 1], [3, 40, 129, 16], 1),
+    # G = 1, dh = 64 (sixteen tokens per row group)
+    ("mha64", small_gqa_model(n_q_heads=4, n_kv_heads=4, head_dim=64), [33, 1, 1], [0, 65, 300], 1),
+    # prefill only, ragged lengths; 3 kv heads exercise the partial head group of a workgroup
+    ("prefill_only", small_gqa_model(n_q_heads=6, n_kv_heads=3), [1, 16, 17, 50], [0, 0, 0, 0], 4),
+    # decode only, one request
+    ("one_decode", small_gqa_model(), [1], [500], 0),
+])
+def test_layer_edge_cases(ctx, name, model, q_lens, ctx_lens, n_pf):
+    say("edge case", name)
+    b = wl.batch_from_lengths(q_lens, ctx_lens, n_pf, np.random.default_rng(5), spare_pages=3)
+    case = Case(model, b, 900 + len(q_lens), ctx=ctx)
+    z, pages = case.run(None)
+    say(name, case.check(z, pages))
+    assert untouched_pages_equal(case, pages)
+
+
+def test_empty_batch_is_a_no_op(ctx):
+    m = small_gqa_model()
+    b = wl.batch_from_lengths([], [], 0, np.random.default_rng(0), spare_pages=2)
+    args = hz.upload_batch(b, DEV)
+    pages = torch.zeros((2, m.page_elems), dtype=torch.bfloat16, device=DEV)
+    runner = hz.LayerRunner(m, wl.make_weights(m, 1), pages, DEV, ctx=ctx)
+    x = torch.zeros((0, m.hidden), dtype=torch.bfloat16, device=DEV)
+    out = runner.forward(args, x, None)
+    torch.cuda.synchronize()
+    assert out.shape[0] == 0
+
+
+# ---------------------------------------------------- nano-batching is bit-exact ---
+
+def test_nano_batched_and_overlapped_are_bit_exact_with_unsplit(ctx):
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    case = Case(cfg.model, b, cfg.seed, ctx=ctx)
+    z0, p0 = case.run(None)
+    for bounds in ([0, 32, 64], [0, 16, 64], [0, 20, 41, 64], [0, 4, 64]):   # 20/41/4 cut prefill requests
+        for overlap, acu, gcu in ((False, 0, 0), (True, 0, 0), (True, 64, 192), (True, 96, 0)):
+            say("plan", bounds, overlap, acu, gcu)
+            plan = nf.nf_plan_manual(case.ctx, cfg.model, case.args, bounds, overlap, acu, gcu)
+            d = plan.describe()
+            assert d["bounds"] == bounds
+            for rep in range(2):
+                z, p = case.run(plan)
+                assert np.array_equal(z, z0), (bounds, overlap, acu)
+                assert np.array_equal(p, p0)
+            plan.close()
+
+
+def test_plan_mismatch_and_workspace_errors(ctx):
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    case = Case(cfg.model, b, cfg.seed, ctx=ctx)
+    plan = nf.nf_plan_manual(case.ctx, cfg.model, case.args, [0, 32, 64])
+    b2 = wl.make_batch(cfg.batch, cfg.seed + 99)
+    args2 = hz.upload_batch(b2, DEV)
+    with pytest.raises(nf.NfError) as e:
+        case.runner.forward(args2, case.x, plan)
+    assert e.value.status == nf.NF_EPLAN
+    out = torch.empty_like(case.x)
+    ws = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_layer_forward(case.ctx, cfg.model, case.runner.w.struct, case.pages.data_ptr(), b.num_pages, case.args,
+                            plan, case.x.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), 0)
+    assert e.value.status == nf.NF_EWORKSPACE
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_plan_manual(case.ctx, cfg.model, case.args, [0, 40, 30, 64])
+    assert e.value.status == nf.NF_EPLAN
+    plan.close()
