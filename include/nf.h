@@ -129,6 +129,43 @@ int nf_ctx_num_cus(const nf_ctx *ctx);
  * the checks nf_layer_forward performs before launching anything.  Needs no GPU. */
 int nf_check_batch(const nf_model_desc *model, const nf_batch *batch, int64_t num_pages);
 
+/*
+ * Kernel trace: when enabled, nf_layer_forward brackets kernel launches with timing
+ * events on the stream they run on.  level 0 = off, 1 = the attention kernel only,
+ * 2 = every kernel.  nf_ctx_read_trace waits for the recorded events, writes up to
+ * max_recs records (host array) in launch order, clears the trace and returns the
+ * number of records that were pending (or a negative status).
+ */
+typedef struct nf_trace_rec {
+  int32_t kernel;    /* NF_K_* below                                               */
+  int32_t op;        /* parent operation: 0 KQV, 1 ATTN, 2 O, 3 UG, 4 D            */
+  int32_t nano;      /* nano-batch index                                           */
+  int32_t tok_begin, tok_end;
+  float start_ms;    /* start relative to the first record of the trace            */
+  float ms;          /* duration                                                   */
+} nf_trace_rec;
+enum { NF_K_RMSNORM = 0, NF_K_GEMM = 1, NF_K_ROPE_APPEND = 2, NF_K_ATTENTION = 3, NF_K_ATTN_MERGE = 4 };
+int nf_ctx_set_trace(nf_ctx *ctx, int level);
+int nf_ctx_read_trace(nf_ctx *ctx, nf_trace_rec *recs, int max_recs);
+
+/*
+ * A library-owned stream restricted to n_cus compute units starting at bit first_cu of the
+ * device's CU mask (n_cus = 0: unrestricted).  lane (0 or 1) distinguishes streams with the
+ * same mask.  Used by the profiler and by tests to run single operations on a CU share;
+ * the stream lives until nf_ctx_destroy.  *out receives a hipStream_t.
+ */
+int nf_ctx_lane_stream(nf_ctx *ctx, int lane, int first_cu, int n_cus, void **out);
+/* Same, with an explicit CU mask (host array of `words` 32-bit words, bit i = CU i of the
+ * runtime's CU numbering).  Each call creates a new stream owned by ctx. */
+int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out);
+
+/*
+ * Process-wide kernel-variant knobs for tuning runs (Sec. 4.1.1: several implementations
+ * per kernel are profiled).  key "attention.variant": 0..4 = pages in flight / occupancy
+ * trade-off of the attention kernel.  Variants never change results.
+ */
+int nf_tune_set(const char *key, int value);
+
 /* ---- planning (Sec. 4.1: automated pipeline search) ---------------------------------------- */
 
 /*
@@ -168,9 +205,14 @@ int nf_plan_nanobatches(nf_ctx *ctx, const nf_model_desc *model, const nf_batch 
  *              (0 = unrestricted).  The attention lane takes the first attn_cus
  *              bits of the CU mask; the GEMM lane the gemm_cus bits after them
  *              when attn_cus + gemm_cus fits the device, else the first gemm_cus.
+ * attn_wgs   : number of persistent workgroups (4 wavefronts each) the attention kernel is
+ *              launched with; 0 = one per work unit.  This is the resource share R of the
+ *              memory-bound kernel (Sec. 4.1.1): fewer workgroups leave more of every
+ *              compute unit to the GEMMs running beside it.  It never changes results.
  */
 int nf_plan_manual(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch, int n_nano,
-                   const int32_t *bounds, int overlap, int attn_cus, int gemm_cus, nf_plan **out);
+                   const int32_t *bounds, int overlap, int attn_cus, int gemm_cus, int attn_wgs,
+                   nf_plan **out);
 
 /* Writes a JSON description of the plan into buf (host); returns the number of
  * bytes needed (excluding the terminator), or a negative status. */

@@ -22,6 +22,7 @@ NF_EPI_NONE, NF_EPI_RESIDUAL, NF_EPI_SWIGLU = 0, 1, 2
 
 EXPORTS = [
     "nf_ctx_create", "nf_ctx_destroy", "nf_last_hip_error", "nf_strerror", "nf_ctx_num_cus", "nf_check_batch",
+    "nf_ctx_set_trace", "nf_ctx_read_trace", "nf_ctx_lane_stream", "nf_ctx_mask_stream", "nf_tune_set",
     "nf_profile", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
     "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_layer_forward",
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention",
@@ -49,6 +50,15 @@ class nf_batch(C.Structure):
                 ("q_indptr", C.c_void_p), ("ctx_len", C.c_void_p), ("page_indptr", C.c_void_p),
                 ("page_ids", C.c_void_p), ("host_q_indptr", C.c_void_p), ("host_ctx_len", C.c_void_p),
                 ("host_page_indptr", C.c_void_p), ("host_page_ids", C.c_void_p)]
+
+
+class nf_trace_rec(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("op", C.c_int32), ("nano", C.c_int32), ("tok_begin", C.c_int32),
+                ("tok_end", C.c_int32), ("start_ms", C.c_float), ("ms", C.c_float)]
+
+
+KERNEL_NAMES = ["rmsnorm", "gemm", "rope_append", "attention", "attn_merge"]
+OP_NAMES = ["KQV", "ATTN", "O", "UG", "D"]
 
 
 class NfError(RuntimeError):
@@ -80,10 +90,15 @@ def lib() -> C.CDLL:
     L.nf_strerror.argtypes = [i32]
     L.nf_strerror.restype = C.c_char_p
     L.nf_ctx_num_cus.argtypes = [vp]
+    L.nf_ctx_set_trace.argtypes = [vp, i32]
+    L.nf_ctx_read_trace.argtypes = [vp, P(nf_trace_rec), i32]
+    L.nf_ctx_lane_stream.argtypes = [vp, i32, i32, i32, P(vp)]
+    L.nf_ctx_mask_stream.argtypes = [vp, P(C.c_uint32), i32, P(vp)]
+    L.nf_tune_set.argtypes = [C.c_char_p, i32]
     L.nf_check_batch.argtypes = [P(nf_model_desc), P(nf_batch), C.c_int64]
     L.nf_profile.argtypes = [vp, P(nf_model_desc), i32, i32, C.c_char_p]
     L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
-    L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, P(vp)]
+    L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
     L.nf_plan_destroy.argtypes = [vp]
     L.nf_plan_destroy.restype = None
@@ -124,6 +139,32 @@ class Context:
     @property
     def num_cus(self) -> int:
         return lib().nf_ctx_num_cus(self.handle)
+
+    def lane_stream(self, lane: int, first_cu: int, n_cus: int) -> int:
+        h = C.c_void_p()
+        _check(lib().nf_ctx_lane_stream(self.handle, lane, first_cu, n_cus, C.byref(h)), "nf_ctx_lane_stream", self)
+        return h.value or 0
+
+    def mask_stream(self, cu_bits) -> int:
+        """Stream restricted to the listed CU bit indices."""
+        words = (self.num_cus + 31) // 32
+        mask = (C.c_uint32 * words)()
+        for b in cu_bits:
+            mask[b >> 5] |= 1 << (b & 31)
+        h = C.c_void_p()
+        _check(lib().nf_ctx_mask_stream(self.handle, mask, words, C.byref(h)), "nf_ctx_mask_stream", self)
+        return h.value or 0
+
+    def set_trace(self, level: int):
+        _check(lib().nf_ctx_set_trace(self.handle, int(level)), "nf_ctx_set_trace", self)
+
+    def read_trace(self, max_recs: int = 4096):
+        """Waits for the traced kernels and returns a list of dict records."""
+        arr = (nf_trace_rec * max_recs)()
+        n = lib().nf_ctx_read_trace(self.handle, arr, max_recs)
+        _check(min(n, 0), "nf_ctx_read_trace", self)
+        return [dict(kernel=KERNEL_NAMES[r.kernel], op=OP_NAMES[r.op], nano=r.nano, tok_begin=r.tok_begin,
+                     tok_end=r.tok_end, start_ms=r.start_ms, ms=r.ms) for r in arr[:min(n, max_recs)]]
 
     def close(self):
         if self.handle:
@@ -187,13 +228,13 @@ class Plan:
 
 
 def nf_plan_manual(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int], overlap: bool = False,
-                   attn_cus: int = 0, gemm_cus: int = 0) -> Plan:
+                   attn_cus: int = 0, gemm_cus: int = 0, attn_wgs: int = 0) -> Plan:
     b = _np_i32(bounds)
     h = C.c_void_p()
     md = model_desc(model)
     _check(lib().nf_plan_manual(ctx.handle, C.byref(md), C.byref(batch.struct), len(b) - 1,
                                 b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)), int(attn_cus),
-                                int(gemm_cus), C.byref(h)), "nf_plan_manual", ctx)
+                                int(gemm_cus), int(attn_wgs), C.byref(h)), "nf_plan_manual", ctx)
     return Plan(ctx, h)
 
 
@@ -209,6 +250,10 @@ def nf_profile(ctx: Context, model, max_tokens: int, granule: int = 128, cache_p
     md = model_desc(model)
     _check(lib().nf_profile(ctx.handle, C.byref(md), int(max_tokens), int(granule),
                             cache_path.encode() if cache_path else None), "nf_profile", ctx)
+
+
+def nf_tune_set(key: str, value: int):
+    _check(lib().nf_tune_set(key.encode(), int(value)), "nf_tune_set")
 
 
 def nf_check_batch(model, batch: BatchArgs, num_pages: int) -> int:

@@ -34,6 +34,11 @@ extern "C" int nf_ctx_create(int device, nf_ctx** out) {
 
 extern "C" void nf_ctx_destroy(nf_ctx* ctx) {
   if (!ctx) return;
+  for (auto& t : ctx->trace) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
   for (auto& kv : ctx->streams) (void)hipStreamDestroy(kv.second);
   nf_profile_free(ctx);
   delete ctx;
@@ -80,6 +85,38 @@ int nf_get_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, hipStream
   ctx->streams[key] = s;
   *out = s;
   return NF_OK;
+}
+
+extern "C" int nf_ctx_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, void** out) {
+  if (!ctx || !out || lane < 0 || lane >= NF_LANES) return NF_EINVAL;
+  hipStream_t s = nullptr;
+  int rc = nf_get_lane_stream(ctx, lane, first_cu, n_cus, &s);
+  *out = (void*)s;
+  return rc;
+}
+
+extern "C" int nf_ctx_mask_stream(nf_ctx* ctx, const uint32_t* mask, int words, void** out) {
+  if (!ctx || !out || !mask || words < 1 || words > 32) return NF_EINVAL;
+  hipStream_t s = nullptr;
+  NF_HIP(ctx, hipExtStreamCreateWithCUMask(&s, (uint32_t)words, mask));
+  ctx->streams[(7L << 40) + (long)ctx->streams.size()] = s;
+  *out = (void*)s;
+  return NF_OK;
+}
+
+extern "C" int nf_tune_set(const char* key, int value) {
+  if (!key) return NF_EINVAL;
+  if (!strcmp(key, "attention.variant")) {
+    if (value < 0 || value > 4) return NF_EINVAL;
+    nf_set_attention_variant(value);
+    return NF_OK;
+  }
+  if (!strcmp(key, "gemm.tile")) {
+    if (value < 0 || value > 4) return NF_EINVAL;
+    nf_set_gemm_tile(value);
+    return NF_OK;
+  }
+  return NF_EINVAL;
 }
 
 // ---------------------------------------------------------------- workspace ---
@@ -133,9 +170,65 @@ extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan) {
   return layout_workspace(&plan->model, plan->n_tokens, (size_t)std::max(1, plan->total_parts), nullptr).total;
 }
 
+// -------------------------------------------------------------------- trace ---
+
+extern "C" int nf_ctx_set_trace(nf_ctx* ctx, int level) {
+  if (!ctx || level < 0 || level > 2) return NF_EINVAL;
+  ctx->trace_level = level;
+  return NF_OK;
+}
+
+extern "C" int nf_ctx_read_trace(nf_ctx* ctx, nf_trace_rec* recs, int max_recs) {
+  if (!ctx || max_recs < 0 || (max_recs > 0 && !recs)) return NF_EINVAL;
+  const int n = (int)ctx->trace.size();
+  for (int i = 0; i < n; ++i) {
+    NfTraceSlot& t = ctx->trace[i];
+    NF_HIP(ctx, hipEventSynchronize(t.stop));
+    NF_HIP(ctx, hipEventElapsedTime(&t.rec.ms, t.start, t.stop));
+    NF_HIP(ctx, hipEventSynchronize(t.start));
+    NF_HIP(ctx, hipEventElapsedTime(&t.rec.start_ms, ctx->trace[0].start, t.start));
+    if (i < max_recs) recs[i] = t.rec;
+  }
+  for (auto& t : ctx->trace) {
+    ctx->event_pool.push_back(t.start);
+    ctx->event_pool.push_back(t.stop);
+  }
+  ctx->trace.clear();
+  return n;
+}
+
 // ----------------------------------------------------------------- executor ---
 
 namespace {
+
+hipError_t trace_event(nf_ctx* ctx, hipEvent_t* e) {
+  if (!ctx->event_pool.empty()) {
+    *e = ctx->event_pool.back();
+    ctx->event_pool.pop_back();
+    return hipSuccess;
+  }
+  return hipEventCreate(e);
+}
+
+// Brackets the kernels launched by `fn` with timing events when the trace level asks for it.
+template <typename F>
+hipError_t traced(nf_ctx* ctx, int kernel, const NfNanoOp& op, hipStream_t s, F fn) {
+  const bool on = ctx->trace_level >= 2 || (ctx->trace_level == 1 && kernel == NF_K_ATTENTION);
+  if (!on) return fn();
+  NfTraceSlot t;
+  t.rec = nf_trace_rec{kernel, op.kind, op.nano, op.tok_begin, op.tok_end, 0.f, 0.f};
+  hipError_t e = trace_event(ctx, &t.start);
+  if (e != hipSuccess) return e;
+  e = trace_event(ctx, &t.stop);
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(t.start, s);
+  if (e != hipSuccess) return e;
+  e = fn();
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(t.stop, s);
+  ctx->trace.push_back(t);
+  return e;
+}
 
 struct LayerArgs {
   const nf_model_desc* m;
@@ -147,7 +240,7 @@ struct LayerArgs {
   Workspace ws;
 };
 
-hipError_t launch_nano_op(const nf_plan* p, const NfNanoOp& op, const LayerArgs& a, hipStream_t s) {
+hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, const LayerArgs& a, hipStream_t s) {
   const nf_model_desc* m = a.m;
   const int t0 = op.tok_begin, M = op.tok_end - op.tok_begin;
   if (M <= 0) return hipSuccess;
@@ -157,33 +250,52 @@ hipError_t launch_nano_op(const nf_plan* p, const NfNanoOp& op, const LayerArgs&
   hipError_t e = hipSuccess;
   switch (op.kind) {
     case NF_OP_KQV:
-      e = nf_launch_rmsnorm(a.x_in + t0 * D * 2, a.w->g_attn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      e = traced(ctx, NF_K_RMSNORM, op, s, [&] {
+        return nf_launch_rmsnorm(a.x_in + t0 * D * 2, a.w->g_attn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      });
       if (e != hipSuccess) return e;
-      e = nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_qkv, a.ws.qkv + t0 * nqkv * 2, nullptr, M, (int)nqkv, (int)D,
-                         NF_EPI_NONE, s);
+      e = traced(ctx, NF_K_GEMM, op, s, [&] {
+        return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_qkv, a.ws.qkv + t0 * nqkv * 2, nullptr, M, (int)nqkv, (int)D,
+                              NF_EPI_NONE, s);
+      });
       if (e != hipSuccess) return e;
-      return nf_launch_rope_append(a.ws.qkv, a.kv->pages, p->d_tok_req, a.b->q_indptr, a.b->ctx_len,
-                                   a.b->page_indptr, a.b->page_ids, t0, op.tok_end, m->n_q_heads, m->n_kv_heads,
-                                   m->head_dim, m->rope_theta, s);
+      return traced(ctx, NF_K_ROPE_APPEND, op, s, [&] {
+        return nf_launch_rope_append(a.ws.qkv, a.kv->pages, p->d_tok_req, a.b->q_indptr, a.b->ctx_len,
+                                     a.b->page_indptr, a.b->page_ids, t0, op.tok_end, m->n_q_heads, m->n_kv_heads,
+                                     m->head_dim, m->rope_theta, s);
+      });
     case NF_OP_ATTN: {
       const NfAttnShape shp{m->n_q_heads, m->n_kv_heads, m->head_dim, (int32_t)nqkv};
-      e = nf_launch_attention(a.ws.qkv, a.kv->pages, a.b->page_indptr, a.b->page_ids,
-                              p->d_items + p->item_off[op.nano], p->item_cnt[op.nano], shp, a.ws.parts, s);
+      e = traced(ctx, NF_K_ATTENTION, op, s, [&] {
+        return nf_launch_attention(a.ws.qkv, a.kv->pages, a.b->page_indptr, a.b->page_ids,
+                                   p->d_items + p->item_off[op.nano], p->item_cnt[op.nano], shp, a.ws.parts,
+                                   p->attn_wgs, s);
+      });
       if (e != hipSuccess) return e;
-      return nf_launch_attention_merge(a.ws.parts, p->d_groups + p->group_off[op.nano], p->group_cnt[op.nano], shp,
-                                       a.ws.attn, s);
+      return traced(ctx, NF_K_ATTN_MERGE, op, s, [&] {
+        return nf_launch_attention_merge(a.ws.parts, p->d_groups + p->group_off[op.nano], p->group_cnt[op.nano], shp,
+                                         a.ws.attn, s);
+      });
     }
     case NF_OP_O:
-      return nf_launch_gemm(a.ws.attn + t0 * qdim * 2, a.w->w_o, a.ws.y + t0 * D * 2, a.x_in + t0 * D * 2, M, (int)D,
-                            (int)qdim, NF_EPI_RESIDUAL, s);
+      return traced(ctx, NF_K_GEMM, op, s, [&] {
+        return nf_launch_gemm(a.ws.attn + t0 * qdim * 2, a.w->w_o, a.ws.y + t0 * D * 2, a.x_in + t0 * D * 2, M, (int)D,
+                              (int)qdim, NF_EPI_RESIDUAL, s);
+      });
     case NF_OP_UG:
-      e = nf_launch_rmsnorm(a.ws.y + t0 * D * 2, a.w->g_ffn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      e = traced(ctx, NF_K_RMSNORM, op, s, [&] {
+        return nf_launch_rmsnorm(a.ws.y + t0 * D * 2, a.w->g_ffn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
+      });
       if (e != hipSuccess) return e;
-      return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_gate_up, a.ws.f + t0 * I * 2, nullptr, M, (int)I, (int)D,
-                            NF_EPI_SWIGLU, s);
+      return traced(ctx, NF_K_GEMM, op, s, [&] {
+        return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_gate_up, a.ws.f + t0 * I * 2, nullptr, M, (int)I, (int)D,
+                              NF_EPI_SWIGLU, s);
+      });
     case NF_OP_D:
-      return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
-                            (int)I, NF_EPI_RESIDUAL, s);
+      return traced(ctx, NF_K_GEMM, op, s, [&] {
+        return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
+                              (int)I, NF_EPI_RESIDUAL, s);
+      });
     default:
       return hipErrorInvalidValue;
   }
@@ -191,7 +303,7 @@ hipError_t launch_nano_op(const nf_plan* p, const NfNanoOp& op, const LayerArgs&
 
 int run_plan(nf_ctx* ctx, const nf_plan* p, const LayerArgs& a, hipStream_t user) {
   if (!p->overlap) {
-    for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(p, op, a, user));
+    for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(ctx, p, op, a, user));
     return NF_OK;
   }
   // fork: the lane streams start after everything already enqueued on the caller's stream
@@ -201,7 +313,7 @@ int run_plan(nf_ctx* ctx, const nf_plan* p, const LayerArgs& a, hipStream_t user
     const NfNanoOp& op = p->ops[i];
     hipStream_t s = p->lane_stream[op.lane];
     for (int d : op.deps) NF_HIP(ctx, hipStreamWaitEvent(s, p->events[d], 0));
-    NF_HIP(ctx, launch_nano_op(p, op, a, s));
+    NF_HIP(ctx, launch_nano_op(ctx, p, op, a, s));
     if (op.record) NF_HIP(ctx, hipEventRecord(p->events[i], s));
   }
   // join: the caller's stream continues after both lanes have drained
@@ -234,7 +346,7 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
   nf_plan* tmp = nullptr;
   if (!plan) {
     const int32_t bounds[2] = {0, batch->n_tokens};
-    rc = nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, &tmp);
+    rc = nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, 0, &tmp);
     if (rc) return rc;
     plan = tmp;
   }
@@ -318,7 +430,7 @@ extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf
   hipStream_t s = (hipStream_t)hip_stream;
   NF_HIP(ctx, nf_launch_attention(qkv, kv->pages, batch->page_indptr, batch->page_ids,
                                   plan->d_items + plan->item_off[nano_index], plan->item_cnt[nano_index], shp,
-                                  (float*)workspace, s));
+                                  (float*)workspace, plan->attn_wgs, s));
   NF_HIP(ctx, nf_launch_attention_merge((const float*)workspace, plan->d_groups + plan->group_off[nano_index],
                                         plan->group_cnt[nano_index], shp, attn_out, s));
   return NF_OK;

@@ -32,36 +32,106 @@ struct PageRegs {
   s16x4 v[DH / 16];
 };
 
-template <int DH>
-__device__ __forceinline__ void load_page(PageRegs<DH>& r, const bf16_t* __restrict__ pages, int page_id, int Hkv,
-                                          int kvh, int lane) {
-  const int c = lane & 15, g = lane >> 4;
-  const bf16_t* kb = pages + (((size_t)page_id * 2 + 0) * Hkv + kvh) * (16 * DH);
-  const bf16_t* vb = pages + (((size_t)page_id * 2 + 1) * Hkv + kvh) * (16 * DH);
+// Issues the loads of one page.  `page_base` is wave-uniform, so the loads take the
+// scalar-base + 32-bit lane offset form; a lane reads 16 bytes of one key per K step
+// (the 4 lanes of a key cover 64 contiguous bytes) and 8 bytes (4 keys of one
+// dimension) per V block (the wavefront covers 512 contiguous bytes).
+template <int DH, bool NT = false>
+__device__ __forceinline__ void load_page(PageRegs<DH>& r, const char* __restrict__ page_base, uint32_t v_block_off,
+                                          uint32_t koff, uint32_t voff) {
+  const char* vb = page_base + v_block_off;
+  if (NT) {  // streaming hint: the KV cache is read once per iteration
 #pragma unroll
-  for (int s = 0; s < DH / 32; ++s)
-    r.k[s] = *reinterpret_cast<const bf16x8*>(kb + c * DH + (4 * s + g) * 8);
+    for (int s = 0; s < DH / 32; ++s)
+      r.k[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(page_base + koff + s * 64));
 #pragma unroll
-  for (int b = 0; b < DH / 16; ++b)
-    r.v[b] = *reinterpret_cast<const s16x4*>(vb + (b * 16 + c) * 16 + 4 * g);
+    for (int b = 0; b < DH / 16; ++b)
+      r.v[b] = __builtin_nontemporal_load(reinterpret_cast<const s16x4*>(vb + voff + b * 512));
+  } else {
+#pragma unroll
+    for (int s = 0; s < DH / 32; ++s) r.k[s] = *reinterpret_cast<const bf16x8*>(page_base + koff + s * 64);
+#pragma unroll
+    for (int b = 0; b < DH / 16; ++b) r.v[b] = *reinterpret_cast<const s16x4*>(vb + voff + b * 512);
+  }
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ qkv,
+struct AttnState {
+  f32x4 o[DH / 16];
+  float m_run, l_run;
+};
+
+// One page (16 keys) of online softmax.  p = page index within the request.
+template <int DH>
+__device__ __forceinline__ void attend_page(AttnState<DH>& st, PageRegs<DH>& pg, const bf16x8 (&qf)[DH / 32], int p,
+                                            int g, int lim, int key_end, float scale_log2) {
+  // scores S^T: lane (row c, g) gets keys 16p + 4g + i
+  f32x4 sc4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < DH / 32; ++s) sc4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pg.k[s], qf[s], sc4, 0, 0, 0);
+  const int key0 = p * 16 + 4 * g;
+  float sc[4];
+  float pm = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sc[i] = (key0 + i <= lim) ? sc4[i] * scale_log2 : -INFINITY;
+    pm = fmaxf(pm, sc[i]);
+  }
+  pm = fmaxf(pm, __shfl_xor(pm, 16, 64));
+  pm = fmaxf(pm, __shfl_xor(pm, 32, 64));
+  const float m_new = fmaxf(st.m_run, pm);
+  const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_use);
+  float pr[4];
+  float ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    pr[i] = __builtin_amdgcn_exp2f(sc[i] - m_use);
+    ps += pr[i];
+  }
+  st.l_run = st.l_run * alpha + ps;
+  st.m_run = m_new;
+  bf16x4 pb = {(__bf16)pr[0], (__bf16)pr[1], (__bf16)pr[2], (__bf16)pr[3]};
+  const s16x4 pf = __builtin_bit_cast(s16x4, pb);
+  // a page that reaches past the chunk's last key: clear V beyond it so that
+  // 0 * (uninitialised slot) cannot produce NaN
+  if (p * 16 + 16 > key_end) {
+#pragma unroll
+    for (int b = 0; b < DH / 16; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (key0 + i >= key_end) pg.v[b][i] = 0;
+  }
+  // the running maximum moves on few pages only: skip the rescale when no lane needs it
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+    for (int b = 0; b < DH / 16; ++b) st.o[b] *= alpha;
+  }
+#pragma unroll
+  for (int b = 0; b < DH / 16; ++b)
+    st.o[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pg.v[b], pf, st.o[b], 0, 0, 0);
+}
+
+template <int DH, int NBUF, int WAVES_PER_SIMD, bool NT = false>
+__global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf16_t* __restrict__ qkv,
                                                         const bf16_t* __restrict__ pages,
                                                         const int32_t* __restrict__ page_indptr,
                                                         const int32_t* __restrict__ page_ids,
-                                                        const NfAttnItem* __restrict__ items, int head_groups,
-                                                        int Hq, int Hkv, int n_qkv, float scale_log2,
-                                                        float* __restrict__ parts) {
+                                                        const NfAttnItem* __restrict__ items, int n_work,
+                                                        int head_groups, int Hq, int Hkv, int n_qkv,
+                                                        float scale_log2, float* __restrict__ parts) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int item_idx = blockIdx.x / head_groups;
-  const int kvh = (blockIdx.x % head_groups) * 4 + wave;
-  if (kvh >= Hkv) return;  // no workgroup barriers in this kernel
-  const NfAttnItem it = items[item_idx];
   const int G = Hq / Hkv;
   const int c = lane & 15, g = lane >> 4;
+  // Persistent workgroups: workgroup b takes work units b, b + gridDim.x, ...  The list is
+  // sorted longest first, so every workgroup gets a similar mix.  There are no workgroup
+  // barriers: the four wavefronts (four kv heads of one item) run independently.
+  for (int work = blockIdx.x; work < n_work; work += gridDim.x) {
+  const int item_idx = work / head_groups;
+  const int kvh = (work % head_groups) * 4 + wave;
+  if (kvh >= Hkv) continue;
+  const NfAttnItem it = items[item_idx];
   const int n_rows = it.n_tok * G;
 
   // Q^T operand: lane (row c, k-group g) holds Q[row c][(4s+g)*8 .. +8] for step s
@@ -82,78 +152,58 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
   // last key this lane's row may read (rows past n_rows read nothing)
   const int lim = c < n_rows ? it.pos0 + c / G : -1;
 
-  f32x4 o[DH / 16];
+  AttnState<DH> st;
 #pragma unroll
-  for (int b = 0; b < DH / 16; ++b) o[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int b = 0; b < DH / 16; ++b) st.o[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
 
-  const int32_t* plist = page_ids + page_indptr[it.req];
+  // The chunk spans at most 64 pages: lane i keeps the physical id of page p_begin + i, so
+  // the id of any page is one cross-lane read away and no load waits on the page table.
   const int p_begin = it.key_begin >> 4;
-  const int p_end = (it.key_end + 15) >> 4;
+  const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
+  const int32_t* plist = page_ids + page_indptr[it.req] + p_begin;
+  const int ids = lane < n_pages ? plist[lane] : 0;
 
-  PageRegs<DH> cur, nxt;
-  load_page<DH>(cur, pages, plist[p_begin], Hkv, kvh, lane);
-  for (int p = p_begin; p < p_end; ++p) {
-    if (p + 1 < p_end) load_page<DH>(nxt, pages, plist[p + 1], Hkv, kvh, lane);
+  const size_t blk_bytes = (size_t)16 * DH * 2;
+  const size_t page_bytes = 2 * (size_t)Hkv * blk_bytes;
+  const uint32_t v_block_off = (uint32_t)((size_t)Hkv * blk_bytes);
+  const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
+  const uint32_t koff = (uint32_t)((c * DH + g * 8) * 2);
+  const uint32_t voff = (uint32_t)((c * 16 + 4 * g) * 2);
+#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)__builtin_amdgcn_readlane(ids, (i)) * page_bytes)
 
-    // scores S^T: lane (row c, g) gets keys 16p + 4g + i
-    f32x4 st = (f32x4){0.f, 0.f, 0.f, 0.f};
+  // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
+  // page has been consumed
+  PageRegs<DH> buf[NBUF];
 #pragma unroll
-    for (int s = 0; s < DH / 32; ++s) st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[s], qf[s], st, 0, 0, 0);
-    const int key0 = p * 16 + 4 * g;
-    float sc[4];
-    float pm = -INFINITY;
+  for (int j = 0; j < NBUF; ++j)
+    if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+  for (int i = 0; i < n_pages; i += NBUF) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      sc[i] = (key0 + i <= lim) ? st[i] * scale_log2 : -INFINITY;
-      pm = fmaxf(pm, sc[i]);
+    for (int j = 0; j < NBUF; ++j) {
+      if (i + j < n_pages) {
+        attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
+        if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+      }
     }
-    pm = fmaxf(pm, __shfl_xor(pm, 16, 64));
-    pm = fmaxf(pm, __shfl_xor(pm, 32, 64));
-    const float m_new = fmaxf(m_run, pm);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    float pr[4];
-    float ps = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      pr[i] = __builtin_amdgcn_exp2f(sc[i] - m_use);
-      ps += pr[i];
-    }
-    l_run = l_run * alpha + ps;
-    m_run = m_new;
-    bf16x4 pb = {(__bf16)pr[0], (__bf16)pr[1], (__bf16)pr[2], (__bf16)pr[3]};
-    const s16x4 pf = __builtin_bit_cast(s16x4, pb);
-
-    // a page that reaches past the chunk's last key: clear V beyond it so that
-    // 0 * (uninitialised slot) cannot produce NaN
-    if (p * 16 + 16 > it.key_end) {
-#pragma unroll
-      for (int b = 0; b < DH / 16; ++b)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (key0 + i >= it.key_end) cur.v[b][i] = 0;
-    }
-#pragma unroll
-    for (int b = 0; b < DH / 16; ++b) {
-      o[b] *= alpha;
-      o[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(cur.v[b], pf, o[b], 0, 0, 0);
-    }
-    cur = nxt;
   }
+#undef NF_PAGE_BASE
 
   // partial result: [16 rows][DH] floats, then m[16], l[16]
+  float l_run = st.l_run;
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   float* part = parts + ((size_t)it.part * Hkv + kvh) * (16 * DH + 32);
   if (c < n_rows) {
 #pragma unroll
-    for (int b = 0; b < DH / 16; ++b) *reinterpret_cast<f32x4*>(part + c * DH + b * 16 + 4 * g) = o[b];
+    for (int b = 0; b < DH / 16; ++b) *reinterpret_cast<f32x4*>(part + c * DH + b * 16 + 4 * g) = st.o[b];
     if (g == 0) {
-      part[16 * DH + c] = m_run;
+      part[16 * DH + c] = st.m_run;
       part[16 * DH + 16 + c] = l_run;
     }
   }
+  }  // work loop
 }
 
 // Merge the partial results of one row group in chunk order and write bf16 output.
@@ -187,25 +237,47 @@ __global__ __launch_bounds__(DH) void attention_merge_kernel(const float* __rest
 
 }  // namespace
 
+// Kernel variant: pages in flight per wavefront (more pages = more bytes in flight per
+// wavefront but fewer resident wavefronts).
+static int g_attn_variant = 4;
+void nf_set_attention_variant(int v) { g_attn_variant = v; }
+
+template <int DH>
+static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* pages,
+                                      const int32_t* page_indptr, const int32_t* page_ids, const NfAttnItem* items,
+                                      int n_work, int head_groups, const NfAttnShape& shp, float scale_log2,
+                                      float* parts) {
+#define NF_ATTN_LAUNCH(NB, W, NT)                                                                                  \
+  attention_kernel<DH, NB, W, NT><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
+                                                         head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,     \
+                                                         scale_log2, parts)
+  switch (variant) {
+    case 0: NF_ATTN_LAUNCH(2, 3, false); break;
+    case 1: NF_ATTN_LAUNCH(3, 2, false); break;
+    case 2: NF_ATTN_LAUNCH(4, 2, false); break;
+    case 3: NF_ATTN_LAUNCH(5, 2, false); break;
+    case 4: NF_ATTN_LAUNCH(3, 2, true); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef NF_ATTN_LAUNCH
+  return hipGetLastError();
+}
+
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
-                               const NfAttnShape& shp, float* parts, hipStream_t s) {
+                               const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
-  const dim3 grid((unsigned)n_items * head_groups), block(256);
-  if (shp.head_dim == 128) {
-    attention_kernel<128><<<grid, block, 0, s>>>((const bf16_t*)qkv, (const bf16_t*)pages, page_indptr, page_ids,
-                                                 items, head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,
-                                                 scale_log2, parts);
-  } else if (shp.head_dim == 64) {
-    attention_kernel<64><<<grid, block, 0, s>>>((const bf16_t*)qkv, (const bf16_t*)pages, page_indptr, page_ids,
-                                                items, head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,
-                                                scale_log2, parts);
-  } else {
-    return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+  const int n_work = n_items * head_groups;
+  const dim3 grid((unsigned)(max_workgroups > 0 && max_workgroups < n_work ? max_workgroups : n_work));
+  if (shp.head_dim == 128)
+    return launch_attention_dh<128>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
+                                    page_ids, items, n_work, head_groups, shp, scale_log2, parts);
+  if (shp.head_dim == 64)
+    return launch_attention_dh<64>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
+                                   page_ids, items, n_work, head_groups, shp, scale_log2, parts);
+  return hipErrorInvalidValue;
 }
 
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,

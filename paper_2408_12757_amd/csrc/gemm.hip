@@ -32,7 +32,7 @@ __device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)
 
 // BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
 template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ Y, const bf16_t* __restrict__ R, int M,
                                                       int N, int K, int tiles_m, int tiles_n) {
   constexpr int WM = BM / 2, WN = BN / 2;   // wavefront tile
@@ -204,11 +204,25 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 
 }  // namespace
 
+// Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256.
+// Every tile shape walks K in the same order with the same MFMA, so the choice never
+// changes an output bit.
+static int g_gemm_tile = 0;
+void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
+
 // Requires K % 64 == 0 and N % 64 == 0 (checked by the caller on the host).
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                           int epilogue, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
-  if (n_eff % 128 == 0) return launch<128, 128>(x, w, out, residual, M, N, K, epilogue, s);
-  return launch<128, 64>(x, w, out, residual, M, N, K, epilogue, s);
+  if (n_eff % 128 != 0) return launch<128, 64>(x, w, out, residual, M, N, K, epilogue, s);
+  int tile = g_gemm_tile;
+  if (tile == 0) tile = 1;
+  if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;
+  switch (tile) {
+    case 2: return launch<256, 128>(x, w, out, residual, M, N, K, epilogue, s);
+    case 3: return launch<128, 256>(x, w, out, residual, M, N, K, epilogue, s);
+    case 4: return launch<256, 256>(x, w, out, residual, M, N, K, epilogue, s);
+    default: return launch<128, 128>(x, w, out, residual, M, N, K, epilogue, s);
+  }
 }

@@ -31,7 +31,15 @@ struct NfNanoOp {
 
 struct NfProfile;  // kernel timing tables (planner input)
 
+struct NfTraceSlot {
+  nf_trace_rec rec;
+  hipEvent_t start, stop;
+};
+
 struct nf_ctx {
+  int trace_level = 0;
+  std::vector<NfTraceSlot> trace;       // pending records
+  std::vector<hipEvent_t> event_pool;   // timing events ready for reuse
   int device = 0;
   int num_cus = 0;
   int last_hip = 0;
@@ -49,6 +57,7 @@ struct nf_plan {
   int overlap = 0;
   int lane_cus[NF_LANES] = {0, 0};        // CU count per lane (0 = whole chip, no mask)
   int lane_cu_first[NF_LANES] = {0, 0};   // first CU bit of the lane's mask
+  int attn_wgs = 0;                       // persistent attention workgroups (0 = as many as there is work)
   hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
   std::vector<hipEvent_t> events;  // one per nano-op that records
   hipEvent_t ev_fork = nullptr, ev_join[NF_LANES] = {nullptr, nullptr};

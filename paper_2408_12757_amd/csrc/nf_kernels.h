@@ -44,6 +44,8 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
                           int epilogue, hipStream_t s);
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
-                               const NfAttnShape& shp, float* parts, hipStream_t s);
+                               const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s);
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
+void nf_set_attention_variant(int v);
+void nf_set_gemm_tile(int v);

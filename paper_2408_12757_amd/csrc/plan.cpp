@@ -248,7 +248,8 @@ static int check_bounds(const nf_batch* batch, int n_nano, const int32_t* bounds
 }
 
 extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int n_nano,
-                              const int32_t* bounds, int overlap, int attn_cus, int gemm_cus, nf_plan** out) {
+                              const int32_t* bounds, int overlap, int attn_cus, int gemm_cus, int attn_wgs,
+                              nf_plan** out) {
   if (!ctx || !out) return NF_EINVAL;
   *out = nullptr;
   int rc = nf_validate_model(model);
@@ -257,12 +258,14 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
   if (rc) return rc;
   rc = check_bounds(batch, n_nano, bounds);
   if (rc) return rc;
-  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus) return NF_EINVAL;
+  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus || attn_wgs < 0)
+    return NF_EINVAL;
   nf_plan* p = new (std::nothrow) nf_plan();
   if (!p) return NF_ENOMEM;
   p->model = *model;
   p->bounds.assign(bounds, bounds + n_nano + 1);
   p->origin = "manual";
+  p->attn_wgs = attn_wgs;
   nf_plan_default_order(p, overlap ? 1 : 0);
   // attention lane owns CU bits [0, attn_cus); the GEMM lane the gemm_cus bits that follow
   // (or the whole chip when gemm_cus = 0)
@@ -302,7 +305,7 @@ extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) {
   for (size_t i = 0; i < p->bounds.size(); ++i) s += (i ? ", " : "") + std::to_string(p->bounds[i]);
   s += "], \"attn_cus\": " + std::to_string(p->lane_cus[NF_LANE_ATTN]) +
        ", \"gemm_cus\": " + std::to_string(p->lane_cus[NF_LANE_GEMM]) +
-       ", \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
+       ", \"attn_wgs\": " + std::to_string(p->attn_wgs) + ", \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
        ", \"ops\": [";
   for (size_t a = 0; a < p->ops.size(); ++a) {
     const NfNanoOp& o = p->ops[a];

@@ -22,7 +22,7 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   (void)granule;
   if (max_nano == 1 || batch->n_tokens == 0) {
     const int32_t bounds[2] = {0, batch->n_tokens};
-    return nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, out);
+    return nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, 0, out);
   }
   return NF_EINVAL;
 }

@@ -88,3 +88,66 @@ def read_kv_rows(pages_bits: np.ndarray, model: wl.ModelDesc, batch: wl.Batch, t
         K[i] = pg[page, 0].reshape(Hkv, P, dh)[:, slot, :]
         V[i] = pg[page, 1].reshape(Hkv, dh, P)[:, :, slot]
     return K, V
+
+
+class DeviceCase:
+    """A full-size synthetic layer problem on the GPU: weights (several copies, so that
+    consecutive steps read cold weights), a seeded KV pool generated on the device,
+    the uploaded batch and the layer input."""
+
+    def __init__(self, cfg: wl.Config, n_weight_copies: int = 1, device="cuda:0", sort_decode: bool = False,
+                 keep_host_weights: bool = True):
+        self.cfg = cfg
+        self.model = cfg.model
+        self.device = torch.device(device)
+        self.batch = wl.make_batch(cfg.batch, cfg.seed + 2, sort_decode=sort_decode)
+        self.host_weights = []
+        self.runners = []
+        gen = torch.Generator(device=self.device)
+        gen.manual_seed(cfg.seed + 3)
+        # KV pool ~ N(0,1) in bf16, every slot filled (also the slots past each context)
+        self.pages = torch.empty((self.batch.num_pages, self.model.page_elems), dtype=torch.bfloat16,
+                                 device=self.device)
+        step = 1 << 14
+        for s in range(0, self.batch.num_pages, step):
+            self.pages[s:s + step].normal_(0.0, 1.0, generator=gen)
+        self.ctx = nf.Context(self.device.index or 0)
+        for c in range(n_weight_copies):
+            w = wl.make_weights(self.model, cfg.seed + 100 * c)
+            self.runners.append(LayerRunner(self.model, w, self.pages, device, ctx=self.ctx))
+            if keep_host_weights and c == 0:
+                self.host_weights.append(w)
+        self.x_bits = wl.make_x(self.batch.n_tokens, self.model.hidden, cfg.seed + 1)
+        self.x = bf16_tensor(self.x_bits, device)
+        self.args = upload_batch(self.batch, device)
+        self.out = torch.empty_like(self.x)
+        self._ws = None
+
+    def forward(self, plan: Optional[nf.Plan], copy: int = 0) -> torch.Tensor:
+        r = self.runners[copy % len(self.runners)]
+        if self._ws is not None:
+            r.workspace = self._ws
+        out = r.forward(self.args, self.x, plan, out=self.out)
+        self._ws = r.workspace
+        return out
+
+    def pages_of_requests(self, reqs) -> np.ndarray:
+        """bf16 bits of the physical pages of the listed requests (device -> host)."""
+        b = self.batch
+        phys = np.concatenate([b.page_ids[b.page_indptr[r]:b.page_indptr[r + 1]] for r in reqs]).astype(np.int64)
+        idx = torch.from_numpy(phys).to(self.device)
+        return bf16_bits(self.pages.index_select(0, idx))
+
+
+def time_plan(case: DeviceCase, plan: Optional[nf.Plan], warmup: int, steps: int) -> float:
+    """Average milliseconds per nf_layer_forward over `steps` calls (weights rotate)."""
+    for i in range(warmup):
+        case.forward(plan, i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        case.forward(plan, warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
