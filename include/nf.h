@@ -171,11 +171,13 @@ int nf_tune_set(const char *key, int value);
 /*
  * Kernel profiling for the auto-search (Sec. 4.1.1): times every dense
  * operation of `model` alone for batch sizes granule, 2*granule, ... max_tokens
- * and on every CU share in the search set, times decode attention alone on
- * those CU shares, and times GEMM || attention pairs to obtain the
- * R -> P resource-mapping table.  Results are kept in ctx and, if cache_path
- * (host string) is not NULL, written to / read from that text file.
- * Synchronous; allocates and frees its own scratch device memory.
+ * with every GEMM tile shape (keeping the best: the kernel -> implementation map),
+ * times decode attention alone for every persistent-workgroup count in the search
+ * set, and times GEMM || attention pairs to obtain the R -> P resource-mapping
+ * table (dominated pairs are dropped).  Results are kept in ctx and, if cache_path
+ * (host string) is not NULL, read from that text file when it matches, else
+ * written to it.  Synchronous; allocates and frees its own scratch device memory
+ * (weights of one layer plus a few GB of synthetic KV cache).
  */
 int nf_profile(nf_ctx *ctx, const nf_model_desc *model, int max_tokens, int granule,
                const char *cache_path);
@@ -192,6 +194,35 @@ int nf_profile(nf_ctx *ctx, const nf_model_desc *model, int max_tokens, int gran
  */
 int nf_plan_nanobatches(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch,
                         int max_nano, int granule, nf_plan **out);
+
+/*
+ * Host-only forms of the search (no GPU needed; used by CPU tests and offline planning).
+ * profile_path: text file written by nf_profile, or NULL for built-in analytic estimates.
+ * nf_search_pipeline returns the structure nf_plan_nanobatches would pick from that profile.
+ * nf_simulate_pipeline returns the modelled makespan (microseconds) of a given structure:
+ * overlap = 0 runs every nano-operation back to back; overlap = 1 runs the GEMM lane and the
+ * attention lane concurrently, with rp_row = -1 for no interference (Stage I) or the index
+ * of a row of the profile's R -> P table (Stage II: overlapped kernels run at p_gemm and
+ * p_attn of their stand-alone speed, so a nano-operation takes D_best / P, Sec. 4.1.3).
+ */
+typedef struct nf_pipeline_desc {
+  int32_t n_nano;
+  int32_t bounds[9];      /* n_nano + 1 token boundaries                                */
+  int32_t overlap;        /* 0 = unsplit / sequential, 1 = two lanes                     */
+  int32_t attn_wgs;       /* attention kernel's persistent workgroups (its share R)      */
+  double est_us;          /* modelled makespan with interference                         */
+  double est_us_stage1;   /* same structure without interference                         */
+  double est_us_unsplit;  /* the unsplit sequential layer                                */
+} nf_pipeline_desc;
+int nf_search_pipeline(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
+                       int max_nano, int granule, nf_pipeline_desc *out);
+int nf_simulate_pipeline(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
+                         int n_nano, const int32_t *bounds, int overlap, int rp_row, double *est_us);
+
+/* Dependency rule of Sec. 4.1.2: 1 iff the parent operations are dependent (kinds: 0 KQV,
+ * 1 ATTN, 2 O, 3 UG, 4 D; KQV -> ATTN -> O -> UG -> D) and the token ranges [b0,e0) and
+ * [b1,e1) intersect.  Host only. */
+int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b1, int e1);
 
 /*
  * Explicit pipeline structure (tests and the ablation of Sec. 6.4):

@@ -1,0 +1,109 @@
+"""CPU oracle of the nano-operation pipeline model used by the auto-search
+(paper Sec. 4.1.2 - 4.1.3).  TEST INFRASTRUCTURE ONLY: imported by tests, never by the
+product, and sharing no code with the C++ planner.
+
+The model, in the paper's terms: every operation of the layer is duplicated into one
+nano-operation per nano-batch (a token range); two nano-operations are dependent iff their
+parent operations are dependent and their ranges intersect; compute-bound nano-operations
+(KQV, then O + Up/Gate + Down) run one at a time on the compute resource in launch order,
+memory-bound ones (decode attention) one at a time on the memory resource; operations bound
+by different resources may overlap.  A nano-operation's duration is D_best / P, where D_best
+is its interference-free time and P its normalised performance: while a GEMM and an
+attention kernel overlap, the GEMM runs at P = R_gemm and attention at P = P_attn(1 - R_gemm)
+(the R -> P table, with the R of overlapping kernels summing to 1); a kernel that runs alone
+runs at its stand-alone speed.
+
+It is written as a fixed-step time integration - slow and plain - so that it can check the
+event-driven C++ implementation.
+"""
+from __future__ import annotations
+
+import itertools
+from typing import List, Optional, Sequence
+
+
+def interp_dense(table: Sequence[float], granule: int, m: int) -> float:
+    """Interference-free time of a dense op on m tokens from times at granule, 2*granule, ..."""
+    x = m / granule
+    if x <= 1:
+        return table[0]
+    i = int(x) - 1
+    if i + 1 >= len(table):
+        return table[-1] * x / len(table)
+    f = x - int(x)
+    return table[i] + f * (table[i + 1] - table[i])
+
+
+def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, overlap,
+             row: Optional[dict], dt: float = 0.02) -> float:
+    """dense: dict op -> table; row: dict(p_gemm, p_attn, p_attn_solo) or None."""
+    n = len(bounds) - 1
+    kqv, att, rest = [], [], []
+    for i in range(n):
+        m = bounds[i + 1] - bounds[i]
+        kqv.append(interp_dense(dense["KQV"], granule, m))
+        rest.append(sum(interp_dense(dense[o], granule, m) for o in ("O", "UG", "D")))
+        att.append(attn_fixed + attn_per_mb * (attn_mb_prefix[bounds[i + 1]] - attn_mb_prefix[bounds[i]]))
+    if not overlap:
+        return sum(kqv) + sum(att) + sum(rest)
+    # launch order on the compute resource: all KQV nano-ops, then O+UG+D per nano-batch
+    compute = [("kqv", i) for i in range(n)] + [("rest", i) for i in range(n)]
+    memory = [("att", i) for i in range(n)]
+    work = {("kqv", i): kqv[i] for i in range(n)}
+    work.update({("att", i): att[i] for i in range(n)})
+    work.update({("rest", i): rest[i] for i in range(n)})
+    done = set()
+
+    def ready(op):
+        kind, i = op
+        if kind == "kqv":
+            return True
+        if kind == "rest":
+            return ("att", i) in done
+        lo = req_start[bounds[i]]           # attention also reads K/V appended by earlier ranges
+        return all(("kqv", j) in done for j in range(i + 1) if bounds[j + 1] > lo)
+
+    t = 0.0
+    ci = mi = 0
+    left = dict(work)
+    while ci < len(compute) or mi < len(memory):
+        c = compute[ci] if ci < len(compute) and ready(compute[ci]) else None
+        m = memory[mi] if mi < len(memory) and ready(memory[mi]) else None
+        assert c is not None or m is not None, "deadlock"
+        sc = sm = 1.0
+        if row is not None:
+            if c is not None and m is not None:
+                sc, sm = row["p_gemm"], row["p_attn"]
+            elif m is not None:
+                sm = row["p_attn_solo"]
+        if c is not None:
+            left[c] -= sc * dt
+            if left[c] <= 0:
+                done.add(c)
+                ci += 1
+        if m is not None:
+            left[m] -= sm * dt
+            if left[m] <= 0:
+                done.add(m)
+                mi += 1
+        t += dt
+    return t
+
+
+def all_bounds(n_tokens: int, granule: int, n_nano: int) -> List[List[int]]:
+    cuts = list(range(granule, n_tokens, granule))
+    return [[0, *c, n_tokens] for c in itertools.combinations(cuts, n_nano - 1)]
+
+
+def brute_force(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, n_tokens, rows, max_nano,
+                dt: float = 0.02):
+    """Minimum makespan over every structure and every table row, and the unsplit time."""
+    unsplit = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, [0, n_tokens], False, None)
+    best = (unsplit, [0, n_tokens], None)
+    for n in range(2, max_nano + 1):
+        for b in all_bounds(n_tokens, granule, n):
+            for r in (rows or [None]):
+                t = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, b, True, r, dt)
+                if t < best[0]:
+                    best = (t, b, r)
+    return best, unsplit

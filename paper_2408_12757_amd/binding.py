@@ -23,7 +23,7 @@ NF_EPI_NONE, NF_EPI_RESIDUAL, NF_EPI_SWIGLU = 0, 1, 2
 EXPORTS = [
     "nf_ctx_create", "nf_ctx_destroy", "nf_last_hip_error", "nf_strerror", "nf_ctx_num_cus", "nf_check_batch",
     "nf_ctx_set_trace", "nf_ctx_read_trace", "nf_ctx_lane_stream", "nf_ctx_mask_stream", "nf_tune_set",
-    "nf_profile", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
+    "nf_nano_ops_dependent", "nf_profile", "nf_search_pipeline", "nf_simulate_pipeline", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
     "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_layer_forward",
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention",
 ]
@@ -50,6 +50,11 @@ class nf_batch(C.Structure):
                 ("q_indptr", C.c_void_p), ("ctx_len", C.c_void_p), ("page_indptr", C.c_void_p),
                 ("page_ids", C.c_void_p), ("host_q_indptr", C.c_void_p), ("host_ctx_len", C.c_void_p),
                 ("host_page_indptr", C.c_void_p), ("host_page_ids", C.c_void_p)]
+
+
+class nf_pipeline_desc(C.Structure):
+    _fields_ = [("n_nano", C.c_int32), ("bounds", C.c_int32 * 9), ("overlap", C.c_int32), ("attn_wgs", C.c_int32),
+                ("est_us", C.c_double), ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
 
 
 class nf_trace_rec(C.Structure):
@@ -97,6 +102,10 @@ def lib() -> C.CDLL:
     L.nf_tune_set.argtypes = [C.c_char_p, i32]
     L.nf_check_batch.argtypes = [P(nf_model_desc), P(nf_batch), C.c_int64]
     L.nf_profile.argtypes = [vp, P(nf_model_desc), i32, i32, C.c_char_p]
+    L.nf_nano_ops_dependent.argtypes = [i32] * 6
+    L.nf_search_pipeline.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, i32, P(nf_pipeline_desc)]
+    L.nf_simulate_pipeline.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, P(C.c_int32), i32, i32,
+                                       P(C.c_double)]
     L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
@@ -244,6 +253,28 @@ def nf_plan_nanobatches(ctx: Context, model, batch: BatchArgs, max_nano: int = 0
     _check(lib().nf_plan_nanobatches(ctx.handle, C.byref(md), C.byref(batch.struct), int(max_nano), int(granule),
                                      C.byref(h)), "nf_plan_nanobatches", ctx)
     return Plan(ctx, h)
+
+
+def nf_search_pipeline(model, batch: BatchArgs, profile_path: Optional[str] = None, max_nano: int = 0,
+                       granule: int = 128) -> dict:
+    md = model_desc(model)
+    out = nf_pipeline_desc()
+    _check(lib().nf_search_pipeline(C.byref(md), C.byref(batch.struct), profile_path.encode() if profile_path else None,
+                                    int(max_nano), int(granule), C.byref(out)), "nf_search_pipeline")
+    return dict(bounds=[int(out.bounds[i]) for i in range(out.n_nano + 1)], overlap=int(out.overlap),
+                attn_wgs=int(out.attn_wgs), est_us=out.est_us, est_us_stage1=out.est_us_stage1,
+                est_us_unsplit=out.est_us_unsplit)
+
+
+def nf_simulate_pipeline(model, batch: BatchArgs, bounds: Sequence[int], overlap: bool, rp_row: int = -1,
+                         profile_path: Optional[str] = None) -> float:
+    md = model_desc(model)
+    b = _np_i32(bounds)
+    est = C.c_double()
+    _check(lib().nf_simulate_pipeline(C.byref(md), C.byref(batch.struct), profile_path.encode() if profile_path else None,
+                                      len(b) - 1, b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)),
+                                      int(rp_row), C.byref(est)), "nf_simulate_pipeline")
+    return est.value
 
 
 def nf_profile(ctx: Context, model, max_tokens: int, granule: int = 128, cache_path: Optional[str] = None):

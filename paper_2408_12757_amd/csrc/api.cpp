@@ -256,7 +256,7 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       if (e != hipSuccess) return e;
       e = traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_qkv, a.ws.qkv + t0 * nqkv * 2, nullptr, M, (int)nqkv, (int)D,
-                              NF_EPI_NONE, s);
+                              NF_EPI_NONE, op.gemm_tile, s);
       });
       if (e != hipSuccess) return e;
       return traced(ctx, NF_K_ROPE_APPEND, op, s, [&] {
@@ -280,7 +280,7 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
     case NF_OP_O:
       return traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.attn + t0 * qdim * 2, a.w->w_o, a.ws.y + t0 * D * 2, a.x_in + t0 * D * 2, M, (int)D,
-                              (int)qdim, NF_EPI_RESIDUAL, s);
+                              (int)qdim, NF_EPI_RESIDUAL, op.gemm_tile, s);
       });
     case NF_OP_UG:
       e = traced(ctx, NF_K_RMSNORM, op, s, [&] {
@@ -289,12 +289,12 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       if (e != hipSuccess) return e;
       return traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_gate_up, a.ws.f + t0 * I * 2, nullptr, M, (int)I, (int)D,
-                              NF_EPI_SWIGLU, s);
+                              NF_EPI_SWIGLU, op.gemm_tile, s);
       });
     case NF_OP_D:
       return traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
-                              (int)I, NF_EPI_RESIDUAL, s);
+                              (int)I, NF_EPI_RESIDUAL, op.gemm_tile, s);
       });
     default:
       return hipErrorInvalidValue;
@@ -393,7 +393,7 @@ extern "C" int nf_op_gemm(const void* x, const void* w, void* out, const void* r
   if (epilogue < NF_EPI_NONE || epilogue > NF_EPI_SWIGLU) return NF_EINVAL;
   if (epilogue == NF_EPI_RESIDUAL && !residual) return NF_EINVAL;
   if (K % 64 || N % 64) return NF_ESHAPE;
-  return nf_launch_gemm(x, w, out, residual, M, N, K, epilogue, (hipStream_t)hip_stream) == hipSuccess ? NF_OK
+  return nf_launch_gemm(x, w, out, residual, M, N, K, epilogue, 0, (hipStream_t)hip_stream) == hipSuccess ? NF_OK
                                                                                                          : NF_EHIP;
 }
 

@@ -212,11 +212,11 @@ void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
 
 // Requires K % 64 == 0 and N % 64 == 0 (checked by the caller on the host).
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
-                          int epilogue, hipStream_t s) {
+                          int epilogue, int tile, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (n_eff % 128 != 0) return launch<128, 64>(x, w, out, residual, M, N, K, epilogue, s);
-  int tile = g_gemm_tile;
+  if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) tile = 1;
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;
   switch (tile) {

@@ -27,6 +27,7 @@ struct NfNanoOp {
   int lane;
   std::vector<int> deps;  // indices of earlier nano-ops this one waits for (other lane only)
   bool record = false;    // some later nano-op on another lane waits for this one
+  int gemm_tile = 0;      // GEMM implementation chosen by the profile (0 = default)
 };
 
 struct NfProfile;  // kernel timing tables (planner input)
@@ -86,6 +87,7 @@ int nf_validate_batch(const nf_model_desc* m, const nf_batch* b, int64_t num_pag
 uint64_t nf_batch_signature(const nf_batch* b);
 int nf_get_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, hipStream_t* out);
 void nf_profile_free(nf_ctx* ctx);
+extern "C" int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b1, int e1);
 extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan);
 
 // Builds the device work lists, dependencies and events of a plan whose bounds, ops

@@ -40,8 +40,9 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
                                  const int32_t* ctx_len, const int32_t* page_indptr, const int32_t* page_ids,
                                  int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
                                  float rope_theta, hipStream_t s);
+// tile: 0 = default, 1..4 = tile shape (see gemm.hip); all shapes give identical bits
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
-                          int epilogue, hipStream_t s);
+                          int epilogue, int tile, hipStream_t s);
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s);

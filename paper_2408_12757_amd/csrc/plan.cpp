@@ -80,6 +80,13 @@ static bool is_parent(int parent, int child) {
          (parent == NF_OP_O && child == NF_OP_UG) || (parent == NF_OP_UG && child == NF_OP_D);
 }
 
+// Dependency rule of Sec. 4.1.2: two nano-operations are dependent iff their parent
+// operations are dependent and their token ranges intersect.
+extern "C" int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b1, int e1) {
+  if (!is_parent(parent_kind, child_kind)) return 0;
+  return std::max(b0, b1) < std::min(e0, e1) ? 1 : 0;
+}
+
 void nf_plan_default_order(nf_plan* p, int overlap) {
   const int n = (int)p->bounds.size() - 1;
   p->ops.clear();
@@ -135,10 +142,9 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
     if (oa.kind == NF_OP_ATTN && oa.tok_begin < oa.tok_end) eb = batch->host_q_indptr[tok_req[oa.tok_begin]];
     for (size_t b = 0; b < a; ++b) {
       NfNanoOp& ob = p->ops[b];
-      if (!is_parent(ob.kind, oa.kind)) continue;
-      const int lo = std::max(oa.kind == NF_OP_ATTN ? eb : oa.tok_begin, ob.tok_begin);
-      const int hi = std::min(oa.tok_end, ob.tok_end);
-      if (lo >= hi) continue;
+      if (!nf_nano_ops_dependent(ob.kind, oa.kind, ob.tok_begin, ob.tok_end,
+                                 oa.kind == NF_OP_ATTN ? eb : oa.tok_begin, oa.tok_end))
+        continue;
       if (ob.lane != oa.lane) {
         oa.deps.push_back((int)b);
         ob.record = true;

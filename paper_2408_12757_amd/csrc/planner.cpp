@@ -1,28 +1,279 @@
-// Auto-search (paper Sec. 4.1): kernel profiles and the pipeline search.
-#include "nf_internal.h"
+// Auto-search, host part (paper Sec. 4.1.2 - 4.1.3): a discrete-event model of the two-lane
+// nano-operation pipeline and the two-stage search over its structure and resource share.
+//
+// Stage I enumerates the number and the boundaries of the nano-batches (multiples of the
+// granule) and ranks the structures by their makespan WITHOUT interference, using the
+// interference-free kernel times.  Stage II keeps the best structures and, for each row of
+// the R -> P table, recomputes the makespan with the overlapped kernels slowed to p_gemm and
+// p_attn; the fastest (structure, row) wins, unless running unsplit is estimated faster.
+// The instance has no network operations, so exhaustive enumeration replaces the MILP.
+#include "planner.h"
 
-struct NfProfile {
-  int dummy;
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+double nf_profile_dense_us(const NfProfile& p, int op, int m) {
+  const std::vector<double>& t = p.dense_us[op];
+  if (t.empty() || m <= 0) return 0.0;
+  const double x = (double)m / p.granule;  // table index + 1
+  if (x <= 1.0) return t[0];               // a partial tile costs a whole one
+  const int i = (int)floor(x) - 1;
+  if (i + 1 >= (int)t.size()) return t.back() * (x / (double)t.size());
+  const double f = x - floor(x);
+  return t[i] + f * (t[i + 1] - t[i]);
+}
+
+void nf_profile_analytic(NfProfile* p, const nf_model_desc* m, int max_tokens, int granule) {
+  p->model = *m;
+  p->granule = granule;
+  p->max_tokens = max_tokens;
+  p->measured = false;
+  const double nqkv = (double)(m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  const double qd = (double)m->n_q_heads * m->head_dim;
+  const double NK[NF_DENSE_OPS][2] = {{nqkv, (double)m->hidden},
+                                      {(double)m->hidden, qd},
+                                      {2.0 * m->ffn_inner, (double)m->hidden},
+                                      {(double)m->hidden, (double)m->ffn_inner}};
+  const int steps = std::max(1, (max_tokens + granule - 1) / granule);
+  for (int o = 0; o < NF_DENSE_OPS; ++o) {
+    p->dense_us[o].assign(steps, 0.0);
+    p->dense_tile[o].assign(steps, 1);
+    for (int i = 0; i < steps; ++i) {
+      const double M = (double)(i + 1) * granule;
+      const double flops = 2.0 * M * NK[o][0] * NK[o][1];
+      const double bytes = 2.0 * (NK[o][0] * NK[o][1] + M * NK[o][1] + M * NK[o][0]);
+      p->dense_us[o][i] = 8.0 + std::max(flops / 0.85e15, bytes / 3.0e12) * 1e6;
+    }
+  }
+  p->attn_fixed_us = 8.0;
+  p->attn_us_per_mb = 1.0 / 5.8;
+  p->rp.clear();
+}
+
+int nf_profile_save(const NfProfile& p, const char* path) {
+  FILE* f = fopen(path, "w");
+  if (!f) return NF_EIO;
+  const nf_model_desc& m = p.model;
+  fprintf(f, "nfprofile 1\n");
+  fprintf(f, "model %d %d %d %d %d %d %d\n", m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn_inner,
+          m.n_experts, m.top_k);
+  fprintf(f, "granule %d max_tokens %d measured %d\n", p.granule, p.max_tokens, p.measured ? 1 : 0);
+  for (int o = 0; o < NF_DENSE_OPS; ++o)
+    for (size_t i = 0; i < p.dense_us[o].size(); ++i)
+      fprintf(f, "dense %d %d %.4f %d\n", o, (int)(i + 1) * p.granule, p.dense_us[o][i], p.dense_tile[o][i]);
+  fprintf(f, "attn %.6f %.8f\n", p.attn_fixed_us, p.attn_us_per_mb);
+  for (const NfRpRow& r : p.rp) fprintf(f, "rp %d %.6f %.6f %.6f\n", r.attn_wgs, r.p_gemm, r.p_attn, r.p_attn_solo);
+  return fclose(f) == 0 ? NF_OK : NF_EIO;
+}
+
+int nf_profile_load(NfProfile* p, const char* path) {
+  FILE* f = fopen(path, "r");
+  if (!f) return NF_EIO;
+  char line[512];
+  int version = 0;
+  if (!fgets(line, sizeof line, f) || sscanf(line, "nfprofile %d", &version) != 1 || version != 1) {
+    fclose(f);
+    return NF_EIO;
+  }
+  NfProfile q;
+  int ok = 1;
+  while (fgets(line, sizeof line, f)) {
+    int a, b, c, d;
+    double x, y, z;
+    nf_model_desc& m = q.model;
+    if (sscanf(line, "model %d %d %d %d %d %d %d", &m.hidden, &m.n_q_heads, &m.n_kv_heads, &m.head_dim, &m.ffn_inner,
+               &m.n_experts, &m.top_k) == 7) {
+      continue;
+    } else if (sscanf(line, "granule %d max_tokens %d measured %d", &a, &b, &c) == 3) {
+      q.granule = a;
+      q.max_tokens = b;
+      q.measured = c != 0;
+    } else if (sscanf(line, "dense %d %d %lf %d", &a, &b, &x, &d) == 4) {
+      if (a < 0 || a >= NF_DENSE_OPS || q.granule <= 0 || b != (int)(q.dense_us[a].size() + 1) * q.granule) {
+        ok = 0;
+        break;
+      }
+      q.dense_us[a].push_back(x);
+      q.dense_tile[a].push_back(d);
+    } else if (sscanf(line, "attn %lf %lf", &x, &y) == 2) {
+      q.attn_fixed_us = x;
+      q.attn_us_per_mb = y;
+    } else if (sscanf(line, "rp %d %lf %lf %lf", &a, &x, &y, &z) == 4) {
+      q.rp.push_back(NfRpRow{a, x, y, z});
+    } else if (line[0] != '#' && line[0] != '\n') {
+      ok = 0;
+      break;
+    }
+  }
+  fclose(f);
+  if (!ok || q.granule <= 0) return NF_EIO;
+  for (int o = 0; o < NF_DENSE_OPS; ++o)
+    if (q.dense_us[o].empty()) return NF_EIO;
+  q.model.page_size = 16;
+  *p = q;
+  return NF_OK;
+}
+
+// ------------------------------------------------------------------ simulation ---
+
+namespace {
+
+struct SimOp {
+  int lane;  // 0 GEMM, 1 attention
+  double work;  // stand-alone microseconds
+  std::vector<int> deps;
 };
 
-void nf_profile_free(nf_ctx* ctx) {
-  delete ctx->profile;
-  ctx->profile = nullptr;
-}
+}  // namespace
 
-extern "C" int nf_profile(nf_ctx* ctx, const nf_model_desc* model, int max_tokens, int granule,
-                          const char* cache_path) {
-  (void)ctx; (void)model; (void)max_tokens; (void)granule; (void)cache_path;
-  return NF_EINVAL;
-}
-
-extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
-                                   int granule, nf_plan** out) {
-  if (!ctx || !batch || !out) return NF_EINVAL;
-  (void)granule;
-  if (max_nano == 1 || batch->n_tokens == 0) {
-    const int32_t bounds[2] = {0, batch->n_tokens};
-    return nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, 0, out);
+double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
+                   const NfRpRow* row) {
+  const int n = (int)bounds.size() - 1;
+  std::vector<double> kqv(n), att(n), rest(n);
+  for (int i = 0; i < n; ++i) {
+    const int m = bounds[i + 1] - bounds[i];
+    kqv[i] = nf_profile_dense_us(prof, NF_DENSE_KQV, m);
+    rest[i] = nf_profile_dense_us(prof, NF_DENSE_O, m) + nf_profile_dense_us(prof, NF_DENSE_UG, m) +
+              nf_profile_dense_us(prof, NF_DENSE_D, m);
+    const double mb = in.attn_mb_prefix[bounds[i + 1]] - in.attn_mb_prefix[bounds[i]];
+    att[i] = prof.attn_fixed_us + prof.attn_us_per_mb * mb;
   }
-  return NF_EINVAL;
+  if (!overlap) {
+    double t = 0;
+    for (int i = 0; i < n; ++i) t += kqv[i] + att[i] + rest[i];
+    return t;
+  }
+  // ops: KQV_i = i, ATTN_i = n + i, REST_i (O, Up/Gate, Down) = 2n + i
+  std::vector<SimOp> ops(3 * n);
+  for (int i = 0; i < n; ++i) {
+    ops[i] = SimOp{0, kqv[i], {}};
+    ops[n + i] = SimOp{1, att[i], {}};
+    ops[2 * n + i] = SimOp{0, rest[i], {n + i}};
+    // attention needs the K/V of its own tokens and of the earlier tokens of a prefill
+    // request it starts inside of
+    const int lo = in.req_start_of_tok.empty() ? bounds[i] : in.req_start_of_tok[bounds[i]];
+    for (int j = 0; j <= i; ++j)
+      if (bounds[j + 1] > lo) ops[n + i].deps.push_back(j);
+  }
+  std::vector<int> q[2];
+  for (int i = 0; i < n; ++i) q[0].push_back(i);
+  for (int i = 0; i < n; ++i) q[0].push_back(2 * n + i);
+  for (int i = 0; i < n; ++i) q[1].push_back(n + i);
+  std::vector<char> done(3 * n, 0);
+  size_t head[2] = {0, 0};
+  double rem[2] = {0, 0};
+  bool running[2] = {false, false};
+  double t = 0;
+  for (;;) {
+    for (int l = 0; l < 2; ++l) {
+      if (running[l] || head[l] >= q[l].size()) continue;
+      const SimOp& o = ops[q[l][head[l]]];
+      bool ready = true;
+      for (int d : o.deps) ready = ready && done[d];
+      if (ready) {
+        running[l] = true;
+        rem[l] = o.work;
+      }
+    }
+    if (!running[0] && !running[1]) break;  // all done (a valid structure cannot deadlock)
+    double sp[2] = {1.0, 1.0};
+    if (row) {
+      if (running[0] && running[1]) {
+        sp[0] = row->p_gemm;
+        sp[1] = row->p_attn;
+      } else if (running[1]) {
+        sp[1] = row->p_attn_solo;
+      }
+    }
+    double dt = 1e300;
+    for (int l = 0; l < 2; ++l)
+      if (running[l]) dt = std::min(dt, rem[l] / std::max(sp[l], 1e-6));
+    t += dt;
+    for (int l = 0; l < 2; ++l) {
+      if (!running[l]) continue;
+      rem[l] -= dt * std::max(sp[l], 1e-6);
+      if (rem[l] <= 1e-9) {
+        running[l] = false;
+        done[q[l][head[l]]] = 1;
+        ++head[l];
+      }
+    }
+  }
+  return t;
+}
+
+// ---------------------------------------------------------------------- search ---
+
+namespace {
+
+void enumerate(int n_left, int pos, int n_tokens, int granule, std::vector<int>& cur,
+               std::vector<std::vector<int>>& out) {
+  if (n_left == 1) {
+    cur.push_back(n_tokens);
+    out.push_back(cur);
+    cur.pop_back();
+    return;
+  }
+  for (int b = pos + granule; b < n_tokens; b += granule) {
+    cur.push_back(b);
+    enumerate(n_left - 1, b, n_tokens, granule, cur, out);
+    cur.pop_back();
+  }
+}
+
+}  // namespace
+
+int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
+  if (in.n_tokens < 0 || in.granule <= 0 || (int)in.attn_mb_prefix.size() != in.n_tokens + 1) return NF_EINVAL;
+  const std::vector<int> whole = {0, in.n_tokens};
+  out->bounds = whole;
+  out->overlap = 0;
+  out->attn_wgs = 0;
+  out->est_us_unsplit = in.n_tokens ? nf_simulate(prof, in, whole, 0, nullptr) : 0.0;
+  out->est_us = out->est_us_stage1 = out->est_us_unsplit;
+  const int max_n = in.max_nano > 0 ? std::min(in.max_nano, NF_MAX_NANO) : NF_MAX_NANO;
+  if (max_n < 2 || in.n_tokens < 2 * in.granule) return NF_OK;
+
+  // Stage I: structures ranked without interference
+  struct Cand {
+    std::vector<int> bounds;
+    double t1;
+  };
+  std::vector<Cand> cands;
+  for (int n = 2; n <= max_n; ++n) {
+    std::vector<std::vector<int>> all;
+    std::vector<int> cur = {0};
+    enumerate(n, 0, in.n_tokens, in.granule, cur, all);
+    for (auto& b : all) cands.push_back(Cand{b, nf_simulate(prof, in, b, 1, nullptr)});
+  }
+  if (cands.empty()) return NF_OK;
+  // fewer nano-operations win ties: splitting costs batching efficiency (Sec. 4.1.2)
+  std::stable_sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) {
+    if (fabs(a.t1 - b.t1) > 1e-9) return a.t1 < b.t1;
+    return a.bounds.size() < b.bounds.size();
+  });
+  const size_t keep = std::min<size_t>(cands.size(), 64);
+
+  // Stage II: resource share per structure, with interference
+  double best = out->est_us_unsplit;
+  const NfRpRow ideal{0, 1.0, 1.0, 1.0};
+  for (size_t c = 0; c < keep; ++c) {
+    const size_t n_rows = prof.rp.empty() ? 1 : prof.rp.size();
+    for (size_t r = 0; r < n_rows; ++r) {
+      const NfRpRow& row = prof.rp.empty() ? ideal : prof.rp[r];
+      const double t2 = nf_simulate(prof, in, cands[c].bounds, 1, &row);
+      if (t2 < best - 1e-9) {
+        best = t2;
+        out->bounds = cands[c].bounds;
+        out->overlap = 1;
+        out->attn_wgs = row.attn_wgs;
+        out->est_us = t2;
+        out->est_us_stage1 = cands[c].t1;
+      }
+    }
+  }
+  return NF_OK;
 }

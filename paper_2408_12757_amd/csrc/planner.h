@@ -1,0 +1,72 @@
+// Auto-search (paper Sec. 4.1): profile tables and the two-stage pipeline search.
+// Pure host code; the GPU measurements that fill the tables live in profile.cpp.
+#pragma once
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/nf.h"
+
+enum { NF_DENSE_KQV = 0, NF_DENSE_O = 1, NF_DENSE_UG = 2, NF_DENSE_D = 3, NF_DENSE_OPS = 4 };
+
+// One row of the resource-mapping table (Sec. 4.1.1, Table 3) for the memory-bound kernel:
+// when decode attention runs with `attn_wgs` persistent workgroups beside a GEMM, the GEMM
+// keeps p_gemm of its stand-alone performance (this is R of the GEMM by definition, so the
+// attention kernel's share is R = 1 - p_gemm) and attention reaches p_attn of its best
+// stand-alone performance.  p_attn_solo is its performance with that workgroup count when
+// nothing runs beside it.
+struct NfRpRow {
+  int attn_wgs;
+  double p_gemm, p_attn, p_attn_solo;
+};
+
+struct NfProfile {
+  nf_model_desc model{};
+  int granule = 128;
+  int max_tokens = 0;
+  bool measured = false;
+  // interference-free execution time (microseconds) of dense op `o` at batch size
+  // (i + 1) * granule, best over the GEMM tile shapes, and the tile that achieved it
+  std::vector<double> dense_us[NF_DENSE_OPS];
+  std::vector<int> dense_tile[NF_DENSE_OPS];
+  // stand-alone attention: fixed cost + cost per byte of K/V read, at the best configuration
+  double attn_fixed_us = 5.0;
+  double attn_us_per_mb = 1.0 / 5.7;  // 5.7 TB/s
+  std::vector<NfRpRow> rp;            // sorted by attn_wgs ascending; last row = "as many as there is work"
+};
+
+// Interpolated interference-free time of a dense op on m tokens (0 < m).
+double nf_profile_dense_us(const NfProfile& p, int op, int m);
+// Analytic stand-in used when nothing was measured (no GPU, or nf_profile never called).
+void nf_profile_analytic(NfProfile* p, const nf_model_desc* model, int max_tokens, int granule);
+int nf_profile_save(const NfProfile& p, const char* path);
+int nf_profile_load(NfProfile* p, const char* path);
+
+// Input of the search: per-token-range attention work, in bytes of K/V read.
+struct NfSearchInput {
+  int n_tokens = 0;
+  int granule = 128;
+  int max_nano = 0;                  // 0 = search up to NF_MAX_NANO
+  std::vector<double> attn_mb_prefix;  // [n_tokens + 1] prefix sums of attention megabytes per token
+  std::vector<int> req_start_of_tok;   // [n_tokens] first token of the request that owns token t
+};
+
+struct NfPipeline {
+  std::vector<int> bounds;   // nano-batch boundaries
+  int overlap = 0;
+  int attn_wgs = 0;          // chosen row of the R -> P table (0 = unrestricted)
+  double est_us = 0.0;       // simulated makespan
+  double est_us_stage1 = 0.0;  // makespan of the same structure without interference
+  double est_us_unsplit = 0.0;
+};
+
+constexpr int NF_MAX_NANO = 4;
+
+// Simulated makespan (microseconds) of a pipeline structure.  row = nullptr: no
+// interference (Stage I); otherwise overlapped GEMM and attention progress at p_gemm and
+// p_attn of their stand-alone speeds and attention alone at p_attn_solo (Stage II).
+double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
+                   const NfRpRow* row);
+// Two-stage search.  Returns NF_OK and fills `out`.
+int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out);

@@ -1,0 +1,440 @@
+// Auto-search, GPU part (paper Sec. 4.1.1): interference-free kernel profiling over batch
+// sizes and implementations, pairwise GEMM || attention interference profiling that yields
+// the R -> P table, and the entry points that turn a search result into a plan.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "nf_internal.h"
+#include "planner.h"
+
+void nf_profile_free(nf_ctx* ctx) {
+  delete ctx->profile;
+  ctx->profile = nullptr;
+}
+
+namespace {
+
+constexpr int kTiles[] = {1, 2, 3, 4};
+constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 384, 512, 768, 0};  // 0 = one per work unit
+
+struct Scratch {
+  std::vector<void*> ptrs;
+  nf_ctx* ctx;
+  explicit Scratch(nf_ctx* c) : ctx(c) {}
+  ~Scratch() {
+    for (void* p : ptrs) (void)hipFree(p);
+  }
+  void* get(size_t bytes, int fill) {
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+    ptrs.push_back(p);
+    if (hipMemset(p, fill, bytes) != hipSuccess) return nullptr;
+    return p;
+  }
+};
+
+// Average milliseconds of `reps` calls of fn on stream s (one untimed call first).
+template <typename F>
+int time_ms(nf_ctx* ctx, hipStream_t s, int reps, F fn, double* out_ms) {
+  hipEvent_t e0, e1;
+  NF_HIP(ctx, hipEventCreate(&e0));
+  NF_HIP(ctx, hipEventCreate(&e1));
+  int rc = fn();
+  if (rc == NF_OK && hipStreamSynchronize(s) != hipSuccess) rc = NF_EHIP;
+  if (rc == NF_OK && hipEventRecord(e0, s) != hipSuccess) rc = NF_EHIP;
+  for (int i = 0; i < reps && rc == NF_OK; ++i) rc = fn();
+  if (rc == NF_OK && hipEventRecord(e1, s) != hipSuccess) rc = NF_EHIP;
+  if (rc == NF_OK && hipEventSynchronize(e1) != hipSuccess) rc = NF_EHIP;
+  float ms = 0.f;
+  if (rc == NF_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = NF_EHIP;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *out_ms = ms / reps;
+  return rc;
+}
+
+struct DenseShape {
+  int N, K, epi;
+};
+
+void dense_shapes(const nf_model_desc* m, DenseShape* s) {
+  const int nqkv = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  const int qd = m->n_q_heads * m->head_dim;
+  s[NF_DENSE_KQV] = DenseShape{nqkv, m->hidden, NF_EPI_NONE};
+  s[NF_DENSE_O] = DenseShape{m->hidden, qd, NF_EPI_RESIDUAL};
+  s[NF_DENSE_UG] = DenseShape{m->ffn_inner, m->hidden, NF_EPI_SWIGLU};
+  s[NF_DENSE_D] = DenseShape{m->hidden, m->ffn_inner, NF_EPI_RESIDUAL};
+}
+
+// Synthetic decode-only batch for attention profiling: n_req requests of ctx cached tokens,
+// pages numbered consecutively.
+struct SynthBatch {
+  std::vector<int32_t> q_indptr, ctx_len, page_indptr, page_ids;
+  int32_t *d_q = nullptr, *d_c = nullptr, *d_pi = nullptr, *d_pid = nullptr;
+  nf_batch b{};
+  int64_t num_pages = 0;
+};
+
+int make_synth_batch(nf_ctx* ctx, Scratch& sc, int n_req, int ctx_tokens, SynthBatch* sb) {
+  sb->q_indptr.resize(n_req + 1);
+  sb->ctx_len.assign(n_req, ctx_tokens);
+  sb->page_indptr.resize(n_req + 1);
+  const int ppr = (ctx_tokens + 1 + 15) / 16;
+  for (int r = 0; r <= n_req; ++r) {
+    sb->q_indptr[r] = r;
+    sb->page_indptr[r] = r * ppr;
+  }
+  sb->page_ids.resize((size_t)n_req * ppr);
+  for (size_t i = 0; i < sb->page_ids.size(); ++i) sb->page_ids[i] = (int32_t)i;
+  sb->num_pages = (int64_t)sb->page_ids.size();
+  auto up = [&](const std::vector<int32_t>& v, int32_t** d) {
+    *d = (int32_t*)sc.get(std::max<size_t>(4, v.size() * 4), 0);
+    if (!*d) return NF_EHIP;
+    return hipMemcpy(*d, v.data(), v.size() * 4, hipMemcpyHostToDevice) == hipSuccess ? NF_OK : NF_EHIP;
+  };
+  int rc = up(sb->q_indptr, &sb->d_q);
+  if (!rc) rc = up(sb->ctx_len, &sb->d_c);
+  if (!rc) rc = up(sb->page_indptr, &sb->d_pi);
+  if (!rc) rc = up(sb->page_ids, &sb->d_pid);
+  if (rc) {
+    ctx->last_hip = (int)hipGetLastError();
+    return rc;
+  }
+  sb->b = nf_batch{n_req, 0, n_req, sb->d_q, sb->d_c, sb->d_pi, sb->d_pid,
+                   sb->q_indptr.data(), sb->ctx_len.data(), sb->page_indptr.data(), sb->page_ids.data()};
+  return NF_OK;
+}
+
+int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, NfProfile* p) {
+  NF_HIP(ctx, hipSetDevice(ctx->device));
+  Scratch sc(ctx);
+  hipStream_t sg = nullptr, sa = nullptr;
+  int rc = nf_get_lane_stream(ctx, NF_LANE_GEMM, 0, 0, &sg);
+  if (!rc) rc = nf_get_lane_stream(ctx, NF_LANE_ATTN, 0, 0, &sa);
+  if (rc) return rc;
+  nf_profile_analytic(p, m, max_tokens, granule);
+  DenseShape shp[NF_DENSE_OPS];
+  dense_shapes(m, shp);
+  const int steps = (int)p->dense_us[0].size();
+  const size_t Mmax = (size_t)steps * granule;
+
+  // ---- interference-free dense operations: every batch size x every tile shape ----
+  size_t max_in = 0, max_out = 0, max_w = 0;
+  for (int o = 0; o < NF_DENSE_OPS; ++o) {
+    max_in = std::max(max_in, Mmax * shp[o].K * 2);
+    max_out = std::max(max_out, Mmax * shp[o].N * 2);
+    max_w = std::max(max_w, (size_t)shp[o].N * (shp[o].epi == NF_EPI_SWIGLU ? 2 : 1) * shp[o].K * 2);
+  }
+  // 0x3c3c as bf16 is about 0.0115: finite inputs, timing does not depend on values
+  void* x = sc.get(max_in, 0x3c);
+  void* y = sc.get(max_out, 0x3c);
+  void* res = sc.get(max_out, 0x3c);
+  void* w[2] = {sc.get(max_w, 0x3c), sc.get(max_w, 0x3c)};  // alternate so weights are not cache-warm
+  if (!x || !y || !res || !w[0] || !w[1]) {
+    ctx->last_hip = (int)hipErrorOutOfMemory;
+    return NF_EHIP;
+  }
+  for (int o = 0; o < NF_DENSE_OPS; ++o) {
+    for (int i = 0; i < steps; ++i) {
+      const int M = (i + 1) * granule;
+      double best = 1e300;
+      int best_tile = 1;
+      for (int tile : kTiles) {
+        int flip = 0;
+        double ms = 0;
+        rc = time_ms(ctx, sg, 3, [&] {
+          flip ^= 1;
+          return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg) == hipSuccess
+                     ? NF_OK
+                     : NF_EHIP;
+        }, &ms);
+        if (rc) return rc;
+        if (ms < best) {
+          best = ms;
+          best_tile = tile;
+        }
+      }
+      p->dense_us[o][i] = best * 1e3;
+      p->dense_tile[o][i] = best_tile;
+    }
+  }
+
+  // ---- interference-free attention: long contexts for the per-byte cost, short for the fixed cost ----
+  const int n_req = std::max(16, std::min(max_tokens, 512));
+  const size_t page_bytes = (size_t)2 * m->n_kv_heads * 16 * m->head_dim * 2;
+  const int32_t nqkv = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  void* qkv = sc.get((size_t)n_req * nqkv * 2, 0x3c);
+  void* aout = sc.get((size_t)n_req * m->n_q_heads * m->head_dim * 2, 0);
+  if (!qkv || !aout) return NF_EHIP;
+  const NfAttnShape ash{m->n_q_heads, m->n_kv_heads, m->head_dim, nqkv};
+  double t_short_ms = 0, t_long_ms[sizeof(kAttnWgSettings) / sizeof(int)] = {0};
+  double long_mb = 0;
+  nf_plan* plans[2] = {nullptr, nullptr};
+  SynthBatch sb[2];
+  void* pool = nullptr;
+  float* parts = nullptr;
+  const int ctx_tokens[2] = {48, 2047};
+  for (int v = 1; v >= 0 && !rc; --v) {
+    rc = make_synth_batch(ctx, sc, n_req, ctx_tokens[v], &sb[v]);
+    if (rc) break;
+    if (v == 1) {
+      pool = sc.get((size_t)sb[1].num_pages * page_bytes, 0x3c);
+      if (!pool) return NF_EHIP;
+    }
+    const int32_t bounds[2] = {0, n_req};
+    rc = nf_plan_manual(ctx, m, &sb[v].b, 1, bounds, 0, 0, 0, 0, &plans[v]);
+    if (rc) break;
+    if (v == 1) {
+      parts = (float*)sc.get((size_t)plans[1]->total_parts * m->n_kv_heads * nf_attn_part_floats(m->head_dim) * 4, 0);
+      if (!parts) rc = NF_EHIP;
+    }
+  }
+  auto attn_call = [&](int v, int wgs, hipStream_t s) {
+    hipError_t e = nf_launch_attention(qkv, pool, sb[v].d_pi, sb[v].d_pid, plans[v]->d_items, plans[v]->item_cnt[0],
+                                       ash, parts, wgs, s);
+    if (e == hipSuccess)
+      e = nf_launch_attention_merge(parts, plans[v]->d_groups, plans[v]->group_cnt[0], ash, aout, s);
+    return e == hipSuccess ? NF_OK : NF_EHIP;
+  };
+  const int n_set = (int)(sizeof(kAttnWgSettings) / sizeof(int));
+  double best_long = 1e300;
+  if (!rc) rc = time_ms(ctx, sa, 5, [&] { return attn_call(0, 0, sa); }, &t_short_ms);
+  for (int k = 0; k < n_set && !rc; ++k) {
+    rc = time_ms(ctx, sa, 3, [&] { return attn_call(1, kAttnWgSettings[k], sa); }, &t_long_ms[k]);
+    best_long = std::min(best_long, t_long_ms[k]);
+  }
+  if (!rc) {
+    long_mb = (double)n_req * (ctx_tokens[1] + 1) * (page_bytes / 16) / 1e6;
+    const double short_mb = (double)n_req * (ctx_tokens[0] + 1) * (page_bytes / 16) / 1e6;
+    p->attn_us_per_mb = std::max(1e-6, (best_long - t_short_ms) * 1e3 / (long_mb - short_mb));
+    p->attn_fixed_us = std::max(1.0, t_short_ms * 1e3 - p->attn_us_per_mb * short_mb);
+  }
+
+  // ---- pairwise interference: Up/Gate GEMM at the full batch || attention with k workgroups ----
+  if (!rc) {
+    const int o = NF_DENSE_UG, M = (int)Mmax;
+    const int tile = p->dense_tile[o][steps - 1];
+    const double g_solo_ms = p->dense_us[o][steps - 1] / 1e3;
+    const int n_gemm = std::min(64, (int)ceil(3.0 * best_long / g_solo_ms) + 2);
+    std::vector<hipEvent_t> ev((size_t)n_gemm + 4);
+    for (auto& e : ev)
+      if (hipEventCreate(&e) != hipSuccess) rc = NF_EHIP;
+    hipEvent_t fork = ev[n_gemm], a0 = ev[n_gemm + 1], a1 = ev[n_gemm + 2];
+    p->rp.clear();
+    for (int k = 0; k < n_set && !rc; ++k) {
+      (void)hipDeviceSynchronize();
+      hipError_t e = hipEventRecord(fork, sg);
+      if (e == hipSuccess) e = hipStreamWaitEvent(sa, fork, 0);
+      // GEMMs first in issue order; attention joins right behind
+      int flip = 0;
+      for (int i = 0; i < n_gemm && e == hipSuccess; ++i) {
+        flip ^= 1;
+        e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
+        if (e == hipSuccess) e = hipEventRecord(ev[i], sg);
+        if (i == 0 && e == hipSuccess) {
+          e = hipEventRecord(a0, sa);
+          if (e == hipSuccess && attn_call(1, kAttnWgSettings[k], sa) != NF_OK) e = hipErrorUnknown;
+          if (e == hipSuccess) e = hipEventRecord(a1, sa);
+        }
+      }
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+      if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        rc = NF_EHIP;
+        break;
+      }
+      float t_a0 = 0, t_a1 = 0;
+      (void)hipEventElapsedTime(&t_a0, fork, a0);
+      (void)hipEventElapsedTime(&t_a1, fork, a1);
+      // GEMM work (in units of one GEMM) finished inside the attention window [t_a0, t_a1]
+      auto progress_at = [&](float t) {
+        float prev = 0.f;
+        for (int i = 0; i < n_gemm; ++i) {
+          float ti = 0;
+          (void)hipEventElapsedTime(&ti, fork, ev[i]);
+          if (t <= ti) return (double)i + (double)(t - prev) / std::max(1e-6f, ti - prev);
+          prev = ti;
+        }
+        return (double)n_gemm;
+      };
+      const double done = progress_at(t_a1) - progress_at(t_a0);
+      const double window = std::max(1e-6, (double)(t_a1 - t_a0));
+      NfRpRow row;
+      row.attn_wgs = kAttnWgSettings[k];
+      row.p_gemm = std::min(1.0, done * g_solo_ms / window);
+      row.p_attn = std::min(1.0, best_long / window);
+      row.p_attn_solo = std::min(1.0, best_long / t_long_ms[k]);
+      p->rp.push_back(row);
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    // discard dominated rows: lower GEMM performance and lower attention performance than
+    // another row (Sec. 4.1.1, the greyed-out pairs)
+    std::vector<NfRpRow> keep;
+    for (const NfRpRow& r : p->rp) {
+      bool dominated = false;
+      for (const NfRpRow& q : p->rp)
+        if (&q != &r && q.p_gemm >= r.p_gemm && q.p_attn >= r.p_attn && (q.p_gemm > r.p_gemm || q.p_attn > r.p_attn))
+          dominated = true;
+      if (!dominated) keep.push_back(r);
+    }
+    p->rp = keep;
+  }
+  for (nf_plan* pl : plans) nf_plan_destroy(pl);
+  (void)hipDeviceSynchronize();
+  if (!rc) p->measured = true;
+  return rc;
+}
+
+bool same_shape(const nf_model_desc& a, const nf_model_desc& b) {
+  return a.hidden == b.hidden && a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads &&
+         a.head_dim == b.head_dim && a.ffn_inner == b.ffn_inner;
+}
+
+void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano, int granule, NfSearchInput* in) {
+  const int n_reqs = b->n_prefill_reqs + b->n_decode_reqs;
+  in->n_tokens = b->n_tokens;
+  in->granule = granule;
+  in->max_nano = max_nano;
+  in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
+  in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
+  const double tok_mb = 2.0 * m->n_kv_heads * m->head_dim * 2 / 1e6;
+  const int T = std::max(1, 16 / (m->n_q_heads / m->n_kv_heads));
+  for (int r = 0; r < n_reqs; ++r) {
+    const int q0 = b->host_q_indptr[r], q1 = b->host_q_indptr[r + 1];
+    for (int t = q0; t < q1; ++t) {
+      const double keys = (double)b->host_ctx_len[r] + (t - q0) + 1;
+      // the rows of one group (T tokens of a prefill chunk) share one pass over the keys
+      const double share = (q1 - q0 > 1) ? 1.0 / T : 1.0;
+      in->attn_mb_prefix[t + 1] = in->attn_mb_prefix[t] + keys * tok_mb * share;
+      in->req_start_of_tok[t] = q0;
+    }
+  }
+}
+
+const NfProfile* pick_profile(const nf_ctx* ctx, const nf_model_desc* m, int n_tokens, int granule, NfProfile* tmp) {
+  if (ctx && ctx->profile && same_shape(ctx->profile->model, *m) && ctx->profile->granule == granule &&
+      ctx->profile->max_tokens >= n_tokens)
+    return ctx->profile;
+  nf_profile_analytic(tmp, m, std::max(n_tokens, granule), granule);
+  return tmp;
+}
+
+}  // namespace
+
+extern "C" int nf_profile(nf_ctx* ctx, const nf_model_desc* model, int max_tokens, int granule,
+                          const char* cache_path) {
+  if (!ctx || max_tokens < 1 || granule < 1) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  NfProfile* p = new (std::nothrow) NfProfile();
+  if (!p) return NF_ENOMEM;
+  if (cache_path && nf_profile_load(p, cache_path) == NF_OK && same_shape(p->model, *model) &&
+      p->granule == granule && p->max_tokens >= max_tokens) {
+    nf_profile_free(ctx);
+    ctx->profile = p;
+    return NF_OK;
+  }
+  rc = measure(ctx, model, max_tokens, granule, p);
+  if (rc) {
+    delete p;
+    return rc;
+  }
+  nf_profile_free(ctx);
+  ctx->profile = p;
+  if (cache_path) return nf_profile_save(*p, cache_path);
+  return NF_OK;
+}
+
+extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
+                                  int max_nano, int granule, nf_pipeline_desc* out) {
+  if (!out || granule < 1 || max_nano < 0) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  NfProfile prof;
+  if (profile_path) {
+    rc = nf_profile_load(&prof, profile_path);
+    if (rc) return rc;
+  } else {
+    nf_profile_analytic(&prof, model, std::max(batch->n_tokens, granule), granule);
+  }
+  NfSearchInput in;
+  build_search_input(model, batch, max_nano, granule, &in);
+  NfPipeline pl;
+  rc = nf_search(prof, in, &pl);
+  if (rc) return rc;
+  memset(out, 0, sizeof *out);
+  out->n_nano = (int32_t)pl.bounds.size() - 1;
+  for (size_t i = 0; i < pl.bounds.size() && i < 9; ++i) out->bounds[i] = pl.bounds[i];
+  out->overlap = pl.overlap;
+  out->attn_wgs = pl.attn_wgs;
+  out->est_us = pl.est_us;
+  out->est_us_stage1 = pl.est_us_stage1;
+  out->est_us_unsplit = pl.est_us_unsplit;
+  return NF_OK;
+}
+
+extern "C" int nf_simulate_pipeline(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
+                                    int n_nano, const int32_t* bounds, int overlap, int rp_row, double* est_us) {
+  if (!est_us || !bounds || n_nano < 1) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  NfProfile prof;
+  if (profile_path) {
+    rc = nf_profile_load(&prof, profile_path);
+    if (rc) return rc;
+  } else {
+    nf_profile_analytic(&prof, model, std::max(batch->n_tokens, 128), 128);
+  }
+  if (bounds[0] != 0 || bounds[n_nano] != batch->n_tokens) return NF_EPLAN;
+  for (int i = 0; i < n_nano; ++i)
+    if (bounds[i + 1] <= bounds[i]) return NF_EPLAN;
+  if (rp_row >= (int)prof.rp.size()) return NF_EINVAL;
+  NfSearchInput in;
+  build_search_input(model, batch, 0, prof.granule, &in);
+  *est_us = nf_simulate(prof, in, std::vector<int>(bounds, bounds + n_nano + 1), overlap,
+                        rp_row < 0 ? nullptr : &prof.rp[rp_row]);
+  return NF_OK;
+}
+
+extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
+                                   int granule, nf_plan** out) {
+  if (!ctx || !out || granule < 1 || max_nano < 0) return NF_EINVAL;
+  *out = nullptr;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  NfProfile tmp;
+  const NfProfile* prof = pick_profile(ctx, model, batch->n_tokens, granule, &tmp);
+  NfSearchInput in;
+  build_search_input(model, batch, max_nano, granule, &in);
+  NfPipeline pl;
+  rc = nf_search(*prof, in, &pl);
+  if (rc) return rc;
+  std::vector<int32_t> b32(pl.bounds.begin(), pl.bounds.end());
+  rc = nf_plan_manual(ctx, model, batch, (int)b32.size() - 1, b32.data(), pl.overlap, 0, 0, pl.attn_wgs, out);
+  if (rc) return rc;
+  (*out)->origin = prof->measured ? "search(measured profile)" : "search(analytic profile)";
+  (*out)->est_time_us = pl.est_us;
+  // implementation map (Sec. 4.1.1): best GEMM tile per (operation, batch size)
+  for (NfNanoOp& op : (*out)->ops) {
+    const int dense = op.kind == NF_OP_KQV ? NF_DENSE_KQV
+                      : op.kind == NF_OP_O ? NF_DENSE_O
+                      : op.kind == NF_OP_UG ? NF_DENSE_UG
+                      : op.kind == NF_OP_D ? NF_DENSE_D
+                                           : -1;
+    if (dense < 0 || prof->dense_tile[dense].empty()) continue;
+    const int m = op.tok_end - op.tok_begin;
+    const int idx = std::min((int)prof->dense_tile[dense].size() - 1, std::max(0, (m + granule - 1) / granule - 1));
+    op.gemm_tile = prof->dense_tile[dense][idx];
+  }
+  return NF_OK;
+}

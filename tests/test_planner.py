@@ -1,0 +1,170 @@
+"""Auto-search (host logic, CPU only): the C++ planner, called through the C ABI, against
+the paper's rules and a brute-force Python model of the pipeline."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pipeline_model as pm
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "table3_resource_mapping.txt")
+OPS = ["KQV", "O", "UG", "D"]
+
+
+def host_batch(b: wl.Batch) -> nf.BatchArgs:
+    dev = {"q_indptr": 1, "ctx_len": 1, "page_indptr": 1, "page_ids": 1}   # never dereferenced on the host
+    return nf.BatchArgs(b.n_tokens, b.n_prefill_reqs, b.n_decode_reqs, b.q_indptr, b.ctx_len, b.page_indptr,
+                        b.page_ids, dev)
+
+
+def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_mb, rows):
+    with open(path, "w") as f:
+        f.write("nfprofile 1\n")
+        f.write(f"model {model.hidden} {model.n_q_heads} {model.n_kv_heads} {model.head_dim} {model.ffn_inner} 0 0\n")
+        f.write(f"granule {granule} max_tokens {max_tokens} measured 1\n")
+        for o, name in enumerate(OPS):
+            for i, us in enumerate(dense[name]):
+                f.write(f"dense {o} {(i + 1) * granule} {us:.4f} 1\n")
+        f.write(f"attn {attn_fixed:.6f} {attn_per_mb:.8f}\n")
+        for r in rows:
+            f.write(f"rp {r['attn_wgs']} {r['p_gemm']:.6f} {r['p_attn']:.6f} {r['p_attn_solo']:.6f}\n")
+
+
+def attn_prefix(model, b: wl.Batch):
+    """Megabytes of K/V a token's attention reads (prefix sums) and each token's request start."""
+    tok_mb = 2 * model.n_kv_heads * model.head_dim * 2 / 1e6
+    T = max(1, 16 // model.gqa)
+    pre = [0.0]
+    start = []
+    for r in range(b.n_reqs):
+        q0, q1 = int(b.q_indptr[r]), int(b.q_indptr[r + 1])
+        for t in range(q0, q1):
+            share = 1.0 / T if q1 - q0 > 1 else 1.0
+            pre.append(pre[-1] + (int(b.ctx_len[r]) + (t - q0) + 1) * tok_mb * share)
+            start.append(q0)
+    return pre, start
+
+
+MODEL = wl.ModelDesc(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_inner=1024)
+
+
+def table3_rows():
+    rows = []
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        R, p_gemm, p_gemv, _ = [float(v) for v in line.split()]
+        if 0 < R < 1:
+            # attention gets share R, the GEMM beside it keeps 1 - R (the shares sum to 1)
+            rows.append(dict(attn_wgs=int(round(R * 1000)), p_gemm=1 - R, p_attn=p_gemv, p_attn_solo=1.0))
+    return rows
+
+
+def test_dependency_rule_example_from_the_paper():
+    dep = nf.lib().nf_nano_ops_dependent
+    # O projection depends on attention; ranges 0-255 and 128-383 intersect
+    assert dep(1, 2, 0, 256, 128, 384) == 1
+    assert dep(1, 2, 0, 128, 128, 384) == 0          # disjoint ranges
+    assert dep(0, 2, 0, 256, 128, 384) == 0          # KQV is not a parent of O
+    assert dep(2, 1, 0, 256, 128, 384) == 0          # direction matters
+    for parent, child in ((0, 1), (1, 2), (2, 3), (3, 4)):
+        assert dep(parent, child, 0, 10, 9, 20) == 1
+
+
+def test_one_nano_batch_equals_the_sequential_sum(tmp_path):
+    g = 16
+    b = wl.batch_from_lengths([1] * 64, np.full(64, 100), 0, np.random.default_rng(0))
+    dense = {o: [10.0 * (i + 1) + k for i in range(4)] for k, o in enumerate(OPS)}
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, 64, dense, 3.0, 2.0, [])
+    pre, _ = attn_prefix(MODEL, b)
+    expect = sum(dense[o][3] for o in OPS) + 3.0 + 2.0 * pre[-1]
+    got = nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 64], False, -1, path)
+    assert got == pytest.approx(expect, rel=1e-9)
+    # nano-batching without overlap only adds: same ops on smaller batches, run back to back
+    got2 = nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 32, 64], False, -1, path)
+    expect2 = 2 * sum(dense[o][1] for o in OPS) + 2 * 3.0 + 2.0 * pre[-1]
+    assert got2 == pytest.approx(expect2, rel=1e-9)
+
+
+def test_duration_is_d_best_over_p_and_shares_sum_to_one(tmp_path):
+    # The paper's 70B operating point: attention at R = 0.4 reaches P = 0.8 while the GEMM keeps 0.6.
+    g = 16
+    b = wl.batch_from_lengths([1] * 32, np.full(32, 1000), 0, np.random.default_rng(0))
+    dense = {"KQV": [0.0, 0.0], "O": [0.0, 0.0], "UG": [60.0, 120.0], "D": [0.0, 0.0]}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = 80.0 / (pre[16] - pre[0])             # attention of one half takes 80 us alone
+    row = dict(attn_wgs=400, p_gemm=0.6, p_attn=0.8, p_attn_solo=1.0)
+    assert row["p_gemm"] + 0.4 == pytest.approx(1.0)
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, 32, dense, 0.0, per_mb, [row])
+    # lanes: ATTN_0 alone (80), then ATTN_1 || UG_0: attention needs 80/0.8 = 100 us, the GEMM
+    # 60/0.6 = 100 us; then UG_1 alone (60).  Makespan 80 + 100 + 60.
+    got = nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 16, 32], True, 0, path)
+    assert got == pytest.approx(240.0, rel=1e-6)
+    # Stage I (no interference) sees 80 + 80 + 60
+    assert nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 16, 32], True, -1, path) == pytest.approx(220.0, rel=1e-6)
+    slow = pm.makespan(dense, g, 0.0, per_mb, pre, start, [0, 16, 32], True, row, dt=0.01)
+    assert slow == pytest.approx(240.0, abs=0.1)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_search_matches_brute_force_on_tiny_instances(tmp_path, seed):
+    r = np.random.default_rng(seed)
+    g, n_gran = 8, 5
+    n_tok = g * n_gran
+    n_pf = int(r.integers(0, 2))
+    q_lens = ([int(r.integers(3, 14))] if n_pf else [])
+    q_lens += [1] * (n_tok - sum(q_lens))
+    ctxs = [0] * n_pf + list(r.integers(50, 3000, size=len(q_lens) - n_pf))
+    b = wl.batch_from_lengths(q_lens, ctxs, n_pf, r)
+    # interference-free times: roughly affine in the batch size, with random efficiency loss for small batches
+    dense = {o: list(np.cumsum(r.uniform(4, 12, size=n_gran)) * s + r.uniform(2, 6))
+             for o, s in zip(OPS, (1.0, 0.7, 3.0, 1.5))}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = r.uniform(0.5, 2.0) * sum(sum(v) for v in dense.values()) / n_gran / pre[-1]
+    rows = table3_rows()
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows)
+    got = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=3, granule=g)
+    (best_t, best_b, best_row), unsplit = pm.brute_force(dense, g, 2.0, per_mb, pre, start, n_tok, rows, 3, dt=0.01)
+    assert got["est_us_unsplit"] == pytest.approx(unsplit, rel=1e-6)
+    assert got["est_us"] == pytest.approx(best_t, rel=2e-3, abs=0.2)
+    assert got["est_us"] <= got["est_us_unsplit"] + 1e-9
+    # the reported estimate is what the model gives for the reported structure
+    if got["overlap"]:
+        row_idx = [x["attn_wgs"] for x in rows].index(got["attn_wgs"])
+        again = nf.nf_simulate_pipeline(MODEL, host_batch(b), got["bounds"], True, row_idx, path)
+        assert again == pytest.approx(got["est_us"], rel=1e-9)
+        assert all(x % g == 0 for x in got["bounds"][:-1])
+
+
+def test_search_never_returns_a_pipeline_slower_than_unsplit(tmp_path):
+    # heavy interference: overlapping is useless, the search must fall back to the unsplit layer
+    g = 16
+    b = wl.batch_from_lengths([1] * 64, np.full(64, 500), 0, np.random.default_rng(0))
+    dense = {o: [20.0 + 5 * i for i in range(4)] for o in OPS}      # poor batching: splitting is expensive
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, 64, dense, 1.0, 0.5, [dict(attn_wgs=256, p_gemm=0.3, p_attn=0.3, p_attn_solo=0.9)])
+    got = nf.nf_search_pipeline(MODEL, host_batch(b), path, 0, g)
+    assert got["bounds"] == [0, 64] and got["overlap"] == 0
+    assert got["est_us"] == pytest.approx(got["est_us_unsplit"])
+
+
+def test_search_uses_analytic_profile_without_a_file():
+    cfg = wl.CONFIGS["C2"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    got = nf.nf_search_pipeline(cfg.model, host_batch(b), None, 0, 128)
+    assert got["bounds"][0] == 0 and got["bounds"][-1] == 2048
+    assert 1000 < got["est_us_unsplit"] < 10000
+
+
+def test_bad_profile_file_is_an_io_error(tmp_path):
+    p = tmp_path / "bad.txt"
+    p.write_text("not a profile\n")
+    b = wl.batch_from_lengths([1] * 32, np.full(32, 10), 0, np.random.default_rng(0))
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_search_pipeline(MODEL, host_batch(b), str(p), 0, 16)
+    assert e.value.status == nf.NF_EIO
