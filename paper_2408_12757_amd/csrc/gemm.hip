@@ -31,7 +31,7 @@ __device__ __forceinline__ int xcd_remap(int b, int nblocks) {
 __device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 
 // BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int PF>
 __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
                                                       bf16_t* __restrict__ Y, const bf16_t* __restrict__ R, int M,
                                                       int N, int K, int tiles_m, int tiles_n) {
@@ -85,51 +85,74 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  u32x4 xr[A_CHUNKS], wr[B_CHUNKS];
+  // Global -> LDS pipeline.  Tile kt is multiplied out of LDS stage kt & 1 while tile kt + 1
+  // is written into the other stage from registers and tiles kt + 2 .. kt + 1 + PF are in
+  // flight from global memory into a ring of PF register sets, so a load has PF K-steps
+  // to arrive before anything waits on it.
+  u32x4 xr[PF][A_CHUNKS], wr[PF][B_CHUNKS];
+  const int KT = K / BK;
+  {
+    u32x4 x0[A_CHUNKS], w0[B_CHUNKS];
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) xr[i] = *reinterpret_cast<const u32x4*>(xg[i]);
+    for (int i = 0; i < A_CHUNKS; ++i) x0[i] = *reinterpret_cast<const u32x4*>(xg[i]);
 #pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) wr[i] = *reinterpret_cast<const u32x4*>(wg[i]);
+    for (int i = 0; i < B_CHUNKS; ++i) w0[i] = *reinterpret_cast<const u32x4*>(wg[i]);
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[0][xs[i]]) = xr[i];
+    for (int d = 0; d < PF; ++d) {
+      if (d + 1 < KT) {
+        const int koff = (d + 1) * BK;
 #pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[0][ws[i]]) = wr[i];
+        for (int i = 0; i < A_CHUNKS; ++i) xr[d][i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) wr[d][i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[0][xs[i]]) = x0[i];
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[0][ws[i]]) = w0[i];
+  }
   __syncthreads();
 
-  const int KT = K / BK;
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      const int koff = (kt + 1) * BK;
+  for (int kt0 = 0; kt0 < KT; kt0 += PF) {
 #pragma unroll
-      for (int i = 0; i < A_CHUNKS; ++i) xr[i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
+    for (int d = 0; d < PF; ++d) {
+      const int kt = kt0 + d;
+      if (kt < KT) {
+        const int cur = kt & 1;
+        const bf16_t* cx = &sX[cur][(wm * WM + frag_row) * LDS_STRIDE + frag_k];
+        const bf16_t* cw = &sW[cur][(wn * WN + frag_row) * LDS_STRIDE + frag_k];
 #pragma unroll
-      for (int i = 0; i < B_CHUNKS; ++i) wr[i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          bf16x8 fw[TN], fx[TM];
+#pragma unroll
+          for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(cw + i * 32 * LDS_STRIDE + kk * 16);
+#pragma unroll
+          for (int j = 0; j < TM; ++j) fx[j] = *reinterpret_cast<const bf16x8*>(cx + j * 32 * LDS_STRIDE + kk * 16);
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < KT) {
+          const int nxt = cur ^ 1;
+#pragma unroll
+          for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[nxt][xs[i]]) = xr[d][i];
+#pragma unroll
+          for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[nxt][ws[i]]) = wr[d][i];
+        }
+        if (kt + 1 + PF < KT) {
+          const int koff = (kt + 1 + PF) * BK;
+#pragma unroll
+          for (int i = 0; i < A_CHUNKS; ++i) xr[d][i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
+#pragma unroll
+          for (int i = 0; i < B_CHUNKS; ++i) wr[d][i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
+        }
+        __syncthreads();
+      }
     }
-    const bf16_t* cx = &sX[cur][(wm * WM + frag_row) * LDS_STRIDE + frag_k];
-    const bf16_t* cw = &sW[cur][(wn * WN + frag_row) * LDS_STRIDE + frag_k];
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fw[TN], fx[TM];
-#pragma unroll
-      for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(cw + i * 32 * LDS_STRIDE + kk * 16);
-#pragma unroll
-      for (int j = 0; j < TM; ++j) fx[j] = *reinterpret_cast<const bf16x8*>(cx + j * 32 * LDS_STRIDE + kk * 16);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      const int nxt = cur ^ 1;
-#pragma unroll
-      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[nxt][xs[i]]) = xr[i];
-#pragma unroll
-      for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[nxt][ws[i]]) = wr[i];
-    }
-    __syncthreads();
   }
 
   // Epilogue.  acc[i][j][v]: token row m = m0 + wm*WM + j*32 + (lane & 31);
@@ -177,7 +200,7 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
   }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int PF>
 hipError_t launch(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
                   hipStream_t s) {
   const int tiles_m = (M + BM - 1) / BM;
@@ -190,13 +213,13 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
   const bf16_t* R = (const bf16_t*)residual;
   switch (epilogue) {
     case EPI_NONE:
-      gemm_kernel<BM, BN, EPI_NONE><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_NONE, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
       break;
     case EPI_RESIDUAL:
-      gemm_kernel<BM, BN, EPI_RESIDUAL><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_RESIDUAL, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
       break;
     default:
-      gemm_kernel<BM, BN, EPI_SWIGLU><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_SWIGLU, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
       break;
   }
   return hipGetLastError();
@@ -204,9 +227,9 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 
 }  // namespace
 
-// Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256.
-// Every tile shape walks K in the same order with the same MFMA, so the choice never
-// changes an output bit.
+// Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
+// 5 / 6 = 128x128 with 2 / 3 K-steps of global loads in flight.  Every variant walks K in the
+// same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
 
@@ -215,14 +238,16 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
                           int epilogue, int tile, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
-  if (n_eff % 128 != 0) return launch<128, 64>(x, w, out, residual, M, N, K, epilogue, s);
+  if (n_eff % 128 != 0) return launch<128, 64, 1>(x, w, out, residual, M, N, K, epilogue, s);
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) tile = 1;
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;
   switch (tile) {
-    case 2: return launch<256, 128>(x, w, out, residual, M, N, K, epilogue, s);
-    case 3: return launch<128, 256>(x, w, out, residual, M, N, K, epilogue, s);
-    case 4: return launch<256, 256>(x, w, out, residual, M, N, K, epilogue, s);
-    default: return launch<128, 128>(x, w, out, residual, M, N, K, epilogue, s);
+    case 2: return launch<256, 128, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 3: return launch<128, 256, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 4: return launch<256, 256, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 5: return launch<128, 128, 2>(x, w, out, residual, M, N, K, epilogue, s);
+    case 6: return launch<128, 128, 3>(x, w, out, residual, M, N, K, epilogue, s);
+    default: return launch<128, 128, 1>(x, w, out, residual, M, N, K, epilogue, s);
   }
 }
