@@ -144,7 +144,8 @@ typedef struct nf_trace_rec {
   float start_ms;    /* start relative to the first record of the trace            */
   float ms;          /* duration                                                   */
 } nf_trace_rec;
-enum { NF_K_RMSNORM = 0, NF_K_GEMM = 1, NF_K_ROPE_APPEND = 2, NF_K_ATTENTION = 3, NF_K_ATTN_MERGE = 4 };
+enum { NF_K_RMSNORM = 0, NF_K_GEMM = 1, NF_K_ROPE_APPEND = 2, NF_K_ATTENTION = 3, NF_K_ATTN_MERGE = 4,
+       NF_K_MOE_ROUTE = 5, NF_K_MOE_COMBINE = 6 };
 int nf_ctx_set_trace(nf_ctx *ctx, int level);
 int nf_ctx_read_trace(nf_ctx *ctx, nf_trace_rec *recs, int max_recs);
 
@@ -257,6 +258,10 @@ void nf_plan_destroy(nf_plan *plan);
 size_t nf_workspace_bytes(const nf_model_desc *model, int max_tokens, int max_context);
 /* Exact workspace requirement of nf_layer_forward with this plan. */
 size_t nf_plan_workspace_bytes(const nf_plan *plan);
+/* Where nf_layer_forward keeps an intermediate inside the caller's workspace, for
+ * inspection after a call: name = "h", "qkv", "attn", "y", "f", "moe.expert_ids"
+ * (int32 [B, top_k]), "moe.expert_w" (float [B, top_k]), "moe.slot_of". */
+int nf_workspace_region(const nf_plan *plan, const char *name, size_t *offset, size_t *bytes);
 
 /*
  * One decoder-layer iteration (Sec. 2.1):

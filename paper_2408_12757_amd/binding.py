@@ -24,7 +24,7 @@ EXPORTS = [
     "nf_ctx_create", "nf_ctx_destroy", "nf_last_hip_error", "nf_strerror", "nf_ctx_num_cus", "nf_check_batch",
     "nf_ctx_set_trace", "nf_ctx_read_trace", "nf_ctx_lane_stream", "nf_ctx_mask_stream", "nf_tune_set",
     "nf_nano_ops_dependent", "nf_profile", "nf_search_pipeline", "nf_simulate_pipeline", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
-    "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_layer_forward",
+    "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_workspace_region", "nf_layer_forward",
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention",
 ]
 
@@ -62,7 +62,7 @@ class nf_trace_rec(C.Structure):
                 ("tok_end", C.c_int32), ("start_ms", C.c_float), ("ms", C.c_float)]
 
 
-KERNEL_NAMES = ["rmsnorm", "gemm", "rope_append", "attention", "attn_merge"]
+KERNEL_NAMES = ["rmsnorm", "gemm", "rope_append", "attention", "attn_merge", "moe_route", "moe_combine"]
 OP_NAMES = ["KQV", "ATTN", "O", "UG", "D"]
 
 
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
     L.nf_workspace_bytes.restype = sz
     L.nf_plan_workspace_bytes.argtypes = [vp]
     L.nf_plan_workspace_bytes.restype = sz
+    L.nf_workspace_region.argtypes = [vp, C.c_char_p, P(sz), P(sz)]
     L.nf_layer_forward.argtypes = [vp, P(nf_model_desc), P(nf_layer_weights), P(nf_kv_cache), P(nf_batch), vp,
                                    vp, vp, vp, sz, vp]
     L.nf_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp]
@@ -223,6 +224,12 @@ class Plan:
     @property
     def workspace_bytes(self) -> int:
         return int(lib().nf_plan_workspace_bytes(self.handle))
+
+    def workspace_region(self, name: str):
+        """(offset, bytes) of a named intermediate inside the workspace."""
+        off, nb = C.c_size_t(), C.c_size_t()
+        _check(lib().nf_workspace_region(self.handle, name.encode(), C.byref(off), C.byref(nb)), "nf_workspace_region")
+        return off.value, nb.value
 
     def close(self):
         if self.handle:

@@ -128,10 +128,19 @@ struct Workspace {
   char* qkv;   // [B, Nqkv]
   char* attn;  // [B, Hq*dh]
   char* y;     // [B, D]   x + attention block
-  char* f;     // [B, I]   silu(gate) * up
+  char* f;     // [B*k, I] silu(gate) * up  (k = 1 dense, top_k for experts: rows sorted by expert)
   float* parts;
+  // mixture of experts only
+  int32_t* expert_ids;     // [B, k]
+  float* expert_w;         // [B, k]
+  int32_t* slot_of;        // [B, k] sorted row of (token, k)
+  int32_t* row_token;      // [B*k]  token of a sorted row
+  int32_t* expert_offset;  // [NF_MAX_NANO_OFFSETS][E + 1] per nano-batch
+  char* expert_out;        // [B*k, D]
   size_t total;
 };
+
+constexpr int kMaxNanoOffsets = 64;
 
 Workspace layout_workspace(const nf_model_desc* m, int n_tokens, size_t n_parts, char* base) {
   Workspace w;
@@ -147,8 +156,16 @@ Workspace layout_workspace(const nf_model_desc* m, int n_tokens, size_t n_parts,
   w.qkv = take(B * nqkv * 2);
   w.attn = take(B * (size_t)m->n_q_heads * m->head_dim * 2);
   w.y = take(B * m->hidden * 2);
-  w.f = take(B * (size_t)m->ffn_inner * 2);
+  const bool moe = m->n_experts > 1;
+  const size_t k = moe ? (size_t)m->top_k : 1;
+  w.f = take(B * k * (size_t)m->ffn_inner * 2);
   w.parts = (float*)take(n_parts * m->n_kv_heads * nf_attn_part_floats(m->head_dim) * sizeof(float));
+  w.expert_ids = (int32_t*)take(moe ? B * k * 4 : 0);
+  w.expert_w = (float*)take(moe ? B * k * 4 : 0);
+  w.slot_of = (int32_t*)take(moe ? B * k * 4 : 0);
+  w.row_token = (int32_t*)take(moe ? B * k * 4 : 0);
+  w.expert_offset = (int32_t*)take(moe ? (size_t)kMaxNanoOffsets * (m->n_experts + 1) * 4 : 0);
+  w.expert_out = take(moe ? B * k * (size_t)m->hidden * 2 : 0);
   w.total = off;
   return w;
 }
@@ -168,6 +185,34 @@ extern "C" size_t nf_workspace_bytes(const nf_model_desc* model, int max_tokens,
 extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan) {
   if (!plan) return 0;
   return layout_workspace(&plan->model, plan->n_tokens, (size_t)std::max(1, plan->total_parts), nullptr).total;
+}
+
+extern "C" int nf_workspace_region(const nf_plan* plan, const char* name, size_t* offset, size_t* bytes) {
+  if (!plan || !name || !offset || !bytes) return NF_EINVAL;
+  const nf_model_desc* m = &plan->model;
+  const Workspace w = layout_workspace(m, plan->n_tokens, (size_t)std::max(1, plan->total_parts), nullptr);
+  const size_t B = (size_t)plan->n_tokens, k = m->n_experts > 1 ? (size_t)m->top_k : 1;
+  const size_t nqkv = (size_t)(m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+  struct {
+    const char* n;
+    const void* p;
+    size_t b;
+  } tab[] = {{"h", w.h, B * m->hidden * 2},
+             {"qkv", w.qkv, B * nqkv * 2},
+             {"attn", w.attn, B * (size_t)m->n_q_heads * m->head_dim * 2},
+             {"y", w.y, B * m->hidden * 2},
+             {"f", w.f, B * k * m->ffn_inner * 2},
+             {"moe.expert_ids", w.expert_ids, m->n_experts > 1 ? B * k * 4 : 0},
+             {"moe.expert_w", w.expert_w, m->n_experts > 1 ? B * k * 4 : 0},
+             {"moe.slot_of", w.slot_of, m->n_experts > 1 ? B * k * 4 : 0}};
+  for (auto& t : tab) {
+    if (!strcmp(t.n, name)) {
+      *offset = (size_t)((const char*)t.p - (const char*)nullptr);
+      *bytes = t.b;
+      return NF_OK;
+    }
+  }
+  return NF_EINVAL;
 }
 
 // -------------------------------------------------------------------- trace ---
@@ -287,11 +332,40 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
         return nf_launch_rmsnorm(a.ws.y + t0 * D * 2, a.w->g_ffn_norm, a.ws.h + t0 * D * 2, M, (int)D, m->rms_eps, s);
       });
       if (e != hipSuccess) return e;
+      if (m->n_experts > 1) {
+        // gate routing, grouping of the (token, expert) rows, grouped Up/Gate GEMM
+        const int E = m->n_experts, k = m->top_k;
+        int32_t* eoff = a.ws.expert_offset + (size_t)op.nano * (E + 1);
+        e = traced(ctx, NF_K_MOE_ROUTE, op, s, [&] {
+          hipError_t r = nf_launch_moe_router(a.ws.h, a.w->w_router, a.ws.expert_ids, a.ws.expert_w, t0, op.tok_end,
+                                              (int)D, E, k, s);
+          if (r != hipSuccess) return r;
+          return nf_launch_moe_scatter(a.ws.expert_ids, t0, op.tok_end, E, k, eoff, a.ws.row_token, a.ws.slot_of, s);
+        });
+        if (e != hipSuccess) return e;
+        return traced(ctx, NF_K_GEMM, op, s, [&] {
+          return nf_launch_grouped_gemm(a.ws.h, a.w->w_gate_up, a.ws.f, M * k, (int)I, (int)D, NF_EPI_SWIGLU, eoff,
+                                        a.ws.row_token, E, (long long)(2 * I * D), s);
+        });
+      }
       return traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.h + t0 * D * 2, a.w->w_gate_up, a.ws.f + t0 * I * 2, nullptr, M, (int)I, (int)D,
                               NF_EPI_SWIGLU, op.gemm_tile, s);
       });
     case NF_OP_D:
+      if (m->n_experts > 1) {
+        const int E = m->n_experts, k = m->top_k;
+        const int32_t* eoff = a.ws.expert_offset + (size_t)op.nano * (E + 1);
+        e = traced(ctx, NF_K_GEMM, op, s, [&] {
+          return nf_launch_grouped_gemm(a.ws.f, a.w->w_down, a.ws.expert_out, M * k, (int)D, (int)I, NF_EPI_NONE, eoff,
+                                        nullptr, E, (long long)(D * I), s);
+        });
+        if (e != hipSuccess) return e;
+        return traced(ctx, NF_K_MOE_COMBINE, op, s, [&] {
+          return nf_launch_moe_combine(a.ws.y, a.ws.expert_out, a.ws.slot_of, a.ws.expert_w, a.x_out, t0, op.tok_end,
+                                       (int)D, k, s);
+        });
+      }
       return traced(ctx, NF_K_GEMM, op, s, [&] {
         return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
                               (int)I, NF_EPI_RESIDUAL, op.gemm_tile, s);
@@ -332,14 +406,13 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
   if (!ctx || !weights || !kv || !batch) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
-  if (model->n_experts > 1) return NF_ESHAPE;  // mixture-of-experts layers are not built yet
   if (!kv->pages || kv->num_pages < 0) return NF_EINVAL;
   rc = nf_validate_batch(model, batch, kv->num_pages);
   if (rc) return rc;
   if (batch->n_tokens == 0) return NF_OK;
   if (!x_in || !x_out || x_in == x_out || !workspace) return NF_EINVAL;
   if (!weights->g_attn_norm || !weights->w_qkv || !weights->w_o || !weights->g_ffn_norm || !weights->w_gate_up ||
-      !weights->w_down)
+      !weights->w_down || (model->n_experts > 1 && !weights->w_router))
     return NF_EINVAL;
   hipStream_t user = (hipStream_t)hip_stream;
 
@@ -351,6 +424,7 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
     plan = tmp;
   }
   rc = NF_OK;
+  if ((int)plan->bounds.size() - 1 > kMaxNanoOffsets) rc = NF_EPLAN;
   if (plan->n_tokens != batch->n_tokens || plan->batch_sig != nf_batch_signature(batch) ||
       memcmp(&plan->model, model, sizeof(nf_model_desc)) != 0)
     rc = NF_EPLAN;

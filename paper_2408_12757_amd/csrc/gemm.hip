@@ -31,10 +31,23 @@ __device__ __forceinline__ int xcd_remap(int b, int nblocks) {
 __device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 
 // BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
-template <int BM, int BN, int EPI, int PF>
-__global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
-                                                      bf16_t* __restrict__ Y, const bf16_t* __restrict__ R, int M,
-                                                      int N, int K, int tiles_m, int tiles_n) {
+// Grouped mode (mixture-of-experts FFN as a grouped GEMM): the M rows are the routed
+// (token, expert) pairs sorted by expert; expert e owns rows [expert_offset[e],
+// expert_offset[e+1]) and multiplies them with its own weight W + e * w_stride.  The row
+// counts live on the device, so the grid covers the worst case and a workgroup whose
+// M-tile index is past the last expert's tiles exits.  row_index (optional) gathers the
+// input rows; outputs are written at the sorted row position.
+struct GroupedArgs {
+  const int32_t* expert_offset;
+  const int32_t* row_index;
+  int n_experts;
+  long long w_stride;
+};
+
+template <int BM, int BN, int EPI, int PF, bool GROUPED>
+__global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
   constexpr int WM = BM / 2, WN = BN / 2;   // wavefront tile
   constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wavefront
   constexpr int A_CHUNKS = BM * 8 / 256;    // 16-byte chunks per thread per stage
@@ -44,8 +57,24 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
 
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
   const int tm = tile % tiles_m, tn = tile / tiles_m;
-  const int m0 = tm * BM;
+  int m0 = tm * BM;
   const int n0 = tn * BN;  // first output column of this tile
+  if (GROUPED) {
+    int acc_tiles = 0, found = 0;
+    for (int e = 0; e < grp.n_experts; ++e) {
+      const int lo = grp.expert_offset[e], hi = grp.expert_offset[e + 1];
+      const int nt = (hi - lo + BM - 1) / BM;
+      if (tm < acc_tiles + nt) {
+        m0 = lo + (tm - acc_tiles) * BM;
+        M = hi;  // this expert's rows end here
+        W += (size_t)e * (size_t)grp.w_stride;
+        found = 1;
+        break;
+      }
+      acc_tiles += nt;
+    }
+    if (!found) return;  // uniform for the whole workgroup, before any barrier
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
 
@@ -58,6 +87,7 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
     const int q = i * 256 + tid, row = q >> 3, c = q & 7;
     int gm = m0 + row;
     gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+    if (GROUPED && grp.row_index) gm = grp.row_index[gm];
     xg[i] = X + (size_t)gm * K + c * 8;
     xs[i] = row * LDS_STRIDE + c * 8;
   }
@@ -200,10 +230,11 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
   }
 }
 
-template <int BM, int BN, int PF>
+template <int BM, int BN, int PF, bool GROUPED = false>
 hipError_t launch(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
-                  hipStream_t s) {
-  const int tiles_m = (M + BM - 1) / BM;
+                  hipStream_t s, GroupedArgs grp = GroupedArgs{nullptr, nullptr, 0, 0}) {
+  // grouped: M is the total row count; every expert may add one partial tile
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
   // SwiGLU: a BN-wide tile of the stacked [2N, K] weight yields BN/2 output columns
   const int tiles_n = epilogue == EPI_SWIGLU ? (2 * N) / BN : N / BN;
   const dim3 grid(tiles_m * tiles_n), block(256);
@@ -213,13 +244,13 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
   const bf16_t* R = (const bf16_t*)residual;
   switch (epilogue) {
     case EPI_NONE:
-      gemm_kernel<BM, BN, EPI_NONE, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_NONE, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
     case EPI_RESIDUAL:
-      gemm_kernel<BM, BN, EPI_RESIDUAL, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_RESIDUAL, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
     default:
-      gemm_kernel<BM, BN, EPI_SWIGLU, PF><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n);
+      gemm_kernel<BM, BN, EPI_SWIGLU, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
   }
   return hipGetLastError();
@@ -250,4 +281,16 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     case 6: return launch<128, 128, 3>(x, w, out, residual, M, N, K, epilogue, s);
     default: return launch<128, 128, 1>(x, w, out, residual, M, N, K, epilogue, s);
   }
+}
+
+// Grouped GEMM over experts (see GroupedArgs).  rows = total routed rows; N % 64 == 0
+// (N % 128 == 0 for SwiGLU counts the stacked 2N rows), K % 64 == 0.
+hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
+                                  const int32_t* expert_offset, const int32_t* row_index, int n_experts,
+                                  long long w_stride, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
+  const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+  if (n_eff % 128 != 0) return launch<128, 64, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+  return launch<128, 128, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
 }

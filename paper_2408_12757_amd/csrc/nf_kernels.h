@@ -50,3 +50,13 @@ hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* grou
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
 void nf_set_attention_variant(int v);
 void nf_set_gemm_tile(int v);
+hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
+                                  const int32_t* expert_offset, const int32_t* row_index, int n_experts,
+                                  long long w_stride, hipStream_t s);
+// Mixture-of-experts helpers (moe.hip)
+hipError_t nf_launch_moe_router(const void* h, const void* w_router, int32_t* expert_ids, float* expert_w,
+                                int tok_begin, int tok_end, int hidden, int n_experts, int top_k, hipStream_t s);
+hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int tok_end, int n_experts, int top_k,
+                                 int32_t* expert_offset, int32_t* row_token, int32_t* slot_of, hipStream_t s);
+hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
+                                 void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s);

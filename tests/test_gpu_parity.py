@@ -185,3 +185,95 @@ def test_plan_mismatch_and_workspace_errors(ctx):
         nf.nf_plan_manual(case.ctx, cfg.model, case.args, [0, 40, 30, 64])
     assert e.value.status == nf.NF_EPLAN
     plan.close()
+
+
+# ------------------------------------------------------------ mixture of experts ---
+
+def moe_model(**kw):
+    base = dict(hidden=256, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_inner=384, n_experts=8, top_k=2,
+                rope_theta=1e6)
+    base.update(kw)
+    return wl.ModelDesc(**base)
+
+
+def read_routing(case, plan, B, k):
+    off, nb = plan.workspace_region("moe.expert_ids")
+    ws = case.runner.workspace
+    ids = ws[off:off + nb].view(torch.int32).cpu().numpy().reshape(B, k)
+    off, nb = plan.workspace_region("moe.expert_w")
+    w = ws[off:off + nb].view(torch.float32).cpu().numpy().reshape(B, k)
+    return ids, w
+
+
+def check_moe_case(case, plan):
+    m, b = case.model, case.batch
+    z_bits, pages = case.run(plan)
+    ids, wts = read_routing(case, plan, b.n_tokens, m.top_k)
+    # The argmax decision is taken in the kernel's precision (fp32): the oracle is given the
+    # GPU's choice, and the choice itself is checked against the oracle's float64 logits.
+    z, k, v, parts = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, expert_choice=ids,
+                                       return_parts=True)
+    idx64, w64, logits = parts["route"]
+    _, _, _, parts_free = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, return_parts=True)
+    top64 = parts_free["route"][0]
+    scale = np.max(np.abs(logits))
+    n_diff = 0
+    for t in range(b.n_tokens):
+        if list(ids[t]) != list(top64[t]):
+            n_diff += 1
+            # a different choice is valid only at a near-tie of the float64 logits
+            lg = logits[t]
+            kth = np.sort(lg)[::-1][m.top_k - 1]
+            assert all(lg[e] >= kth - 2e-2 * scale for e in ids[t]), (t, ids[t], top64[t])
+        assert len(set(ids[t])) == m.top_k
+    assert n_diff <= max(2, b.n_tokens // 20), n_diff
+    assert rel_err(wts, w64) <= 2e-2
+    e = rel_err(f64(z_bits), z)
+    assert np.all(np.isfinite(f64(z_bits))) and e <= REL_TOL, e
+    return z_bits, pages, e
+
+
+def test_moe_layer_matches_oracle_and_is_split_invariant(ctx):
+    m = moe_model()
+    b = wl.batch_from_lengths([40, 9] + [1] * 79, [0, 30] + list(np.random.default_rng(3).integers(5, 400, 79)), 2,
+                              np.random.default_rng(4), spare_pages=2)
+    say("moe layer", b.n_tokens, "tokens")
+    case = Case(m, b, 4000, ctx=ctx)
+    plan1 = nf.nf_plan_manual(case.ctx, m, case.args, [0, b.n_tokens])
+    z0, p0, e = check_moe_case(case, plan1)
+    say("moe rel err", e)
+    for bounds, overlap in (([0, 48, 128], False), ([0, 64, 128], True), ([0, 16, 50, 128], True)):
+        plan = nf.nf_plan_manual(case.ctx, m, case.args, bounds, overlap)
+        z, p = case.run(plan)
+        assert np.array_equal(z, z0) and np.array_equal(p, p0), bounds
+        plan.close()
+    plan1.close()
+
+
+def test_moe_skewed_routing_and_empty_experts(ctx):
+    # a router that sends every token to experts 5 and 1: six experts get no rows
+    m = moe_model(n_experts=8, top_k=2)
+    b = wl.batch_from_lengths([1] * 37, list(range(3, 40)), 0, np.random.default_rng(8))
+    w = wl.make_weights(m, 4100)
+    wr = np.zeros((8, m.hidden), np.float32)
+    case_x = wl.bf16_bits_to_f32(wl.make_x(b.n_tokens, m.hidden, 4101))
+    wr[5] = 0.05
+    wr[1] = 0.02
+    w["w_router"] = wl.f32_to_bf16_bits(wr)
+    w["g_ffn_norm"] = wl.f32_to_bf16_bits(np.ones(m.hidden, np.float32))
+    case = Case(m, b, 4100, weights=w, ctx=ctx)
+    plan = nf.nf_plan_manual(case.ctx, m, case.args, [0, b.n_tokens])
+    z_bits, pages, e = check_moe_case(case, plan)
+    ids, _ = read_routing(case, plan, b.n_tokens, 2)
+    say("skewed moe rel err", e, "experts used", sorted(set(ids.ravel().tolist())))
+    plan.close()
+
+
+def test_moe_top1_and_four_experts(ctx):
+    m = moe_model(n_experts=4, top_k=1, ffn_inner=256)
+    b = wl.batch_from_lengths([12] + [1] * 20, [5] + list(range(10, 30)), 1, np.random.default_rng(9))
+    case = Case(m, b, 4200, ctx=ctx)
+    plan = nf.nf_plan_manual(case.ctx, m, case.args, [0, 16, b.n_tokens], True)
+    _, _, e = check_moe_case(case, plan)
+    say("top-1 moe rel err", e)
+    plan.close()
