@@ -32,23 +32,25 @@ def parse_args():
     ap.add_argument("--config", default="C2", help="workload: C1..C3 (C2 = the headline configuration)")
     ap.add_argument("--weight-copies", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--plans", default="auto", help="'auto' or a JSON list of candidate plans "
-                    "[{bounds:[...], overlap:0|1, attn_cus:int, gemm_cus:int}, ...]")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy, the yardstick for rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--profile-cache", default=None, help="file to keep the kernel profile in (default: re-measure)")
+    ap.add_argument("--ablation-attn-wgs", type=int, default=256,
+                    help="persistent attention workgroups of the overlapped ablation run")
     return ap.parse_args()
 
 
-def candidate_plans(B: int, granule: int):
-    """Pipeline structures tried before the timed run; the fastest is timed."""
-    g = granule
-    half = (B // 2) // g * g
-    c = [dict(bounds=[0, B], overlap=0, attn_cus=0, gemm_cus=0)]
-    if half <= 0 or half >= B:
-        return c
-    q = max(g, (B // 4) // g * g)
-    for bounds in ([0, half, B], [0, q, B], [0, B - q, B], [0, q, half + q // 2, B]):
-        if all(b1 > b0 for b0, b1 in zip(bounds, bounds[1:])):
-            c.append(dict(bounds=bounds, overlap=1, attn_cus=0, gemm_cus=0))
-    return c
+def measured_traffic(kernel_tag: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
+    summary (profiles/), or None when no summary for this kernel/workload is there."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg, case, n_decode_sample: int = 448):
@@ -108,16 +110,28 @@ def main():
     costs = cm.layer_costs(m, b)
     roof = cm.iteration_roofline(costs)
 
-    # ---- choose the pipeline: time each candidate briefly, keep the fastest ----
-    cands = candidate_plans(B, cfg.granule) if args.plans == "auto" else json.loads(args.plans)
-    timings = []
-    for c in cands:
-        plan = nf.nf_plan_manual(case.ctx, m, case.args, c["bounds"], bool(c["overlap"]), c["attn_cus"], c["gemm_cus"])
-        ms = hz.time_plan(case, plan, 3, 10)
-        timings.append((ms, c, plan))
-    unsplit_ms = timings[0][0] if timings[0][1]["bounds"] == [0, B] else None
-    best_ms, best_c, best_plan = min(timings, key=lambda t: t[0])
-    seq_plan = nf.nf_plan_manual(case.ctx, m, case.args, best_c["bounds"], False, 0, 0)
+    if args.pmc_calibration:
+        a = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")
+        bcopy = torch.empty_like(a)
+        bcopy.copy_(a)
+        torch.cuda.synchronize()
+        del a, bcopy
+
+    # ---- auto-search (Sec. 4.1): profile the kernels on this GPU, then search the pipeline ----
+    t0 = time.perf_counter()
+    nf.nf_profile(case.ctx, m, B, cfg.granule, args.profile_cache)
+    t_profile = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    best_plan = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
+    t_search = time.perf_counter() - t0
+    best_desc = best_plan.describe()
+    best_c = {k: best_desc[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
+    # the ablation of Sec. 6.4 on a fixed two-nano-batch structure
+    half = max(cfg.granule, (B // 2) // cfg.granule * cfg.granule)
+    abl_bounds = [0, half, B] if half < B else [0, B]
+    unsplit_plan = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
+    seq_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, False, 0, 0, 0)
+    ovl_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, True, 0, 0, args.ablation_attn_wgs)
 
     def timed(plan, steps, warmup, trace=0):
         for i in range(warmup):
@@ -144,11 +158,10 @@ def main():
     attn_ms_step = sum(attn_ms) / args.steps
     achieved = attn_bytes_step / (attn_ms_step * 1e-3) / 1e9
     # ---- ablation (Sec. 6.4): unsplit, nano-batched sequential, nano-batched overlapped ----
-    seq_ms, _ = timed(seq_plan, max(10, args.steps // 4), 3)
-    if unsplit_ms is None:
-        unsplit_ms = seq_ms
-    else:
-        unsplit_ms, _ = timed(timings[0][2], max(10, args.steps // 4), 3)
+    n_abl = max(10, args.steps // 4)
+    unsplit_ms, _ = timed(unsplit_plan, n_abl, 3)
+    seq_ms, _ = timed(seq_plan, n_abl, 3)
+    ovl_ms, _ = timed(ovl_plan, n_abl, 3)
 
     out = {
         "metric": METRIC,
@@ -172,12 +185,15 @@ def main():
                                "frac": roof["t_roofline"] * 1e3 / ms_step,
                                "peaks": {"bf16_mfma_flops": cm.MI355X_PEAK_BF16_FLOPS,
                                          "hbm_bytes_per_s": cm.MI355X_PEAK_HBM_BPS}},
-        "ablation_ms": {"unsplit": unsplit_ms, "nano_sequential": seq_ms, "nano_overlapped": ms_step,
-                        "speedup_overlapped_vs_sequential": seq_ms / ms_step,
-                        "speedup_vs_unsplit": unsplit_ms / ms_step},
+        "ablation_ms": {"structure": abl_bounds, "unsplit": unsplit_ms, "nano_sequential": seq_ms,
+                        "nano_overlapped": ovl_ms, "overlapped_attn_wgs": args.ablation_attn_wgs,
+                        "speedup_overlapped_vs_sequential": seq_ms / ovl_ms,
+                        "nano_batching_overhead": seq_ms / unsplit_ms - 1.0},
+        "auto_search": {"profile_s": t_profile, "search_s": t_search},
         "roofline": {"bound": "hbm", "kernel": "attention_kernel<128>", "achieved": achieved,
                      "peak": cm.MI355X_PEAK_HBM_BPS / 1e9, "unit": "GB/s",
-                     "frac": achieved / (cm.MI355X_PEAK_HBM_BPS / 1e9), "traffic": None,
+                     "frac": achieved / (cm.MI355X_PEAK_HBM_BPS / 1e9),
+                     "traffic": measured_traffic(f"attention_{cfg.name.lower()}"),
                      "launches_per_step": launches_per_step, "avg_launch_ms": attn_ms_step / launches_per_step,
                      "algorithmic_bytes_per_step": attn_bytes_step},
     }

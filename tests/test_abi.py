@@ -1,0 +1,65 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/nf.h declares;
+host-side validation returns the documented status codes (CPU only)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import workloads as wl
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "nf.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(nf_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = nf.lib()
+    names = declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(nf.EXPORTS) <= set(names)
+
+
+def test_strerror_and_context_without_gpu():
+    L = nf.lib()
+    assert L.nf_strerror(0) == b"ok"
+    assert b"workspace" in L.nf_strerror(nf.NF_EWORKSPACE)
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(nf.NfError) as e:
+            nf.Context(0)
+        assert e.value.status == nf.NF_EHIP
+
+
+def host_args(b):
+    dev = {"q_indptr": 1, "ctx_len": 1, "page_indptr": 1, "page_ids": 1}
+    return nf.BatchArgs(b.n_tokens, b.n_prefill_reqs, b.n_decode_reqs, b.q_indptr, b.ctx_len, b.page_indptr,
+                        b.page_ids, dev)
+
+
+def test_host_validation_status_codes():
+    m = wl.CONFIGS["C1"].model
+    b = wl.make_batch(wl.CONFIGS["C1"].batch, 5)
+    assert nf.nf_check_batch(m, host_args(b), b.num_pages) == nf.NF_OK
+    # page id out of range
+    assert nf.nf_check_batch(m, host_args(b), int(b.page_ids.max())) == nf.NF_EPAGES
+    # page list too short for ctx_len + q_len
+    import dataclasses
+    short = dataclasses.replace(b, ctx_len=b.ctx_len + 64)
+    assert nf.nf_check_batch(m, host_args(short), b.num_pages) == nf.NF_EPAGES
+    # a decode request must carry exactly one token
+    bad = dataclasses.replace(b, n_prefill_reqs=b.n_prefill_reqs - 1, n_decode_reqs=b.n_decode_reqs + 1)
+    assert nf.nf_check_batch(m, host_args(bad), b.num_pages) == nf.NF_ESHAPE
+    # unsupported shapes
+    assert nf.nf_check_batch(dataclasses.replace(m, head_dim=96), host_args(b), b.num_pages) == nf.NF_ESHAPE
+    assert nf.nf_check_batch(dataclasses.replace(m, page_size=32), host_args(b), b.num_pages) == nf.NF_ESHAPE
+    assert nf.nf_check_batch(dataclasses.replace(m, n_q_heads=7), host_args(b), b.num_pages) == nf.NF_ESHAPE
+    assert nf.nf_workspace_bytes(dataclasses.replace(m, head_dim=96), 64, 128) == 0
+    assert nf.nf_workspace_bytes(m, 64, 128) > 64 * m.hidden * 2 * 3

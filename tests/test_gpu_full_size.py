@@ -1,0 +1,107 @@
+"""Full-size parity: the LLaMA-3-8B layer at dense batch 2048 (the configuration the bench
+times), in the launch configurations the bench uses, checked against the CPU oracle on a
+sample of requests (requests are independent, so the oracle on a sub-batch gives the exact
+reference rows), plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_layer as orc
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import harness as hz
+from paper_2408_12757_amd import workloads as wl
+
+from gpu_util import REL_TOL, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def c2():
+    cfg = wl.CONFIGS["C2"]
+    case = hz.DeviceCase(cfg, n_weight_copies=1)
+    yield cfg, case
+    case.ctx.close()
+
+
+def sample_check(cfg, case, out_bits, pages_before, reqs):
+    b, m = case.batch, cfg.model
+    sub, tok, phys = wl.subset_batch(b, reqs)
+    z, k, v = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok])
+    e_z = rel_err(f64(out_bits[tok]), z)
+    # appended K/V rows, read back from the device pool
+    pages_after = case.pages_of_requests(reqs)
+    kg, vg = hz.read_kv_rows(pages_after, m, sub, np.arange(sub.n_tokens))
+    e_k, e_v = rel_err(f64(kg), k), rel_err(f64(vg), v)
+    assert e_z <= REL_TOL and e_k <= REL_TOL and e_v <= REL_TOL, (e_z, e_k, e_v)
+    return e_z, e_k, e_v
+
+
+def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
+    cfg, case = c2
+    b, m = case.batch, cfg.model
+    assert b.n_tokens == 2048 and b.n_decode_reqs == 1792
+    rng = np.random.default_rng(11)
+    dec = np.sort(rng.choice(np.arange(b.n_prefill_reqs, b.n_reqs), size=20, replace=False))
+    longest = b.n_prefill_reqs + int(np.argmax(b.ctx_len[b.n_prefill_reqs:]))
+    reqs = np.unique(np.concatenate([[0], dec, [longest]]))
+    say("sampled requests", len(reqs), "longest ctx", int(b.ctx_len[longest]))
+    pages_before = case.pages_of_requests(reqs)
+
+    say("unsplit run")
+    plan1 = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
+    out1 = hz.bf16_bits(case.forward(plan1))
+    torch.cuda.synchronize()
+    say("oracle on the sample")
+    errs = sample_check(cfg, case, out1, pages_before, reqs)
+    say("C2 sampled rel err z/k/v", errs)
+    assert np.all(np.isfinite(f64(out1)))
+
+    # the searched pipeline (measured profile) and explicit overlapped structures give the same bits
+    say("profile + search")
+    nf.nf_profile(case.ctx, m, b.n_tokens, cfg.granule, str(tmp_path / "profile.txt"))
+    plans = [nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule),
+             nf.nf_plan_manual(case.ctx, m, case.args, [0, 1024, 2048], True, 0, 0, 256),
+             nf.nf_plan_manual(case.ctx, m, case.args, [0, 128, 1152, 2048], True, 0, 0, 0),
+             nf.nf_plan_manual(case.ctx, m, case.args, [0, 100, 2048], False)]     # cuts the prefill request
+    for p in plans:
+        d = p.describe()
+        say("plan", d["origin"], d["bounds"], "overlap", d["overlap"], "attn_wgs", d["attn_wgs"])
+        out = hz.bf16_bits(case.forward(p))
+        torch.cuda.synchronize()
+        assert np.array_equal(out, out1), d["bounds"]
+    # the profile file round-trips through the host-only search
+    got = nf.nf_search_pipeline(m, case.args, str(tmp_path / "profile.txt"), 0, cfg.granule)
+    assert got["bounds"] == plans[0].describe()["bounds"]
+    assert got["est_us"] <= got["est_us_unsplit"] + 1e-6
+
+
+def test_c2_attention_rows_are_convex_combinations(c2):
+    """A property that holds at any size: every attention output lies within the range of
+    the values it averaged; checked here through the op entry point on all 2048 rows with
+    V pages set to a constant per kv head (so the output must equal that constant)."""
+    cfg, case = c2
+    b, m = case.batch, cfg.model
+    plan = nf.nf_plan_manual(case.ctx, m, case.args, [0, b.n_tokens])
+    pages = case.pages.view(b.num_pages, 2, m.n_kv_heads, 16 * m.head_dim)
+    saved = pages[:, 1].clone()
+    for h in range(m.n_kv_heads):
+        pages[:, 1, h] = 0.25 * (h + 1)
+    qkv = torch.randn((b.n_tokens, m.n_qkv), device="cuda:0", dtype=torch.bfloat16)
+    attn = torch.empty((b.n_tokens, m.q_dim), device="cuda:0", dtype=torch.bfloat16)
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+    nf.nf_op_attention(case.ctx, m, case.pages.data_ptr(), b.num_pages, case.args, plan, qkv.data_ptr(),
+                       attn.data_ptr(), ws.data_ptr(), ws.numel(), 0, 0)
+    torch.cuda.synchronize()
+    got = attn.float().view(b.n_tokens, m.n_q_heads, m.head_dim).cpu().numpy()
+    G = m.gqa
+    # decode rows read only cached + appended slots; the append did not run here, so restrict
+    # the check to decode requests whose own slot also holds the constant (all slots do)
+    for hq in range(m.n_q_heads):
+        expect = 0.25 * (hq // G + 1)
+        assert np.max(np.abs(got[:, hq, :] - expect)) <= 2e-2 * expect, hq
+    pages[:, 1] = saved
