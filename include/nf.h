@@ -211,6 +211,8 @@ typedef struct nf_pipeline_desc {
   int32_t bounds[9];      /* n_nano + 1 token boundaries                                */
   int32_t overlap;        /* 0 = unsplit / sequential, 1 = two lanes                     */
   int32_t attn_wgs;       /* attention kernel's persistent workgroups (its share R)      */
+  int32_t gemm_tile;      /* GEMM implementation of the chosen R -> P pair (0 = per-op best) */
+  int32_t reserved;
   double est_us;          /* modelled makespan with interference                         */
   double est_us_stage1;   /* same structure without interference                         */
   double est_us_unsplit;  /* the unsplit sequential layer                                */

@@ -11,7 +11,7 @@ by different resources may overlap.  A nano-operation's duration is D_best / P, 
 is its interference-free time and P its normalised performance: while a GEMM and an
 attention kernel overlap, the GEMM runs at P = R_gemm and attention at P = P_attn(1 - R_gemm)
 (the R -> P table, with the R of overlapping kernels summing to 1); a kernel that runs alone
-runs at its stand-alone speed.
+runs at the stand-alone speed of the implementation the table row names.
 
 It is written as a fixed-step time integration - slow and plain - so that it can check the
 event-driven C++ implementation.
@@ -76,6 +76,8 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
                 sc, sm = row["p_gemm"], row["p_attn"]
             elif m is not None:
                 sm = row["p_attn_solo"]
+            else:
+                sc = row.get("p_gemm_solo", 1.0)
         if c is not None:
             left[c] -= sc * dt
             if left[c] <= 0:

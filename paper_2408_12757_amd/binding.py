@@ -54,7 +54,7 @@ class nf_batch(C.Structure):
 
 class nf_pipeline_desc(C.Structure):
     _fields_ = [("n_nano", C.c_int32), ("bounds", C.c_int32 * 9), ("overlap", C.c_int32), ("attn_wgs", C.c_int32),
-                ("est_us", C.c_double), ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
+                ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("est_us", C.c_double), ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
 
 
 class nf_trace_rec(C.Structure):
@@ -269,7 +269,7 @@ def nf_search_pipeline(model, batch: BatchArgs, profile_path: Optional[str] = No
     _check(lib().nf_search_pipeline(C.byref(md), C.byref(batch.struct), profile_path.encode() if profile_path else None,
                                     int(max_nano), int(granule), C.byref(out)), "nf_search_pipeline")
     return dict(bounds=[int(out.bounds[i]) for i in range(out.n_nano + 1)], overlap=int(out.overlap),
-                attn_wgs=int(out.attn_wgs), est_us=out.est_us, est_us_stage1=out.est_us_stage1,
+                attn_wgs=int(out.attn_wgs), gemm_tile=int(out.gemm_tile), est_us=out.est_us, est_us_stage1=out.est_us_stage1,
                 est_us_unsplit=out.est_us_unsplit)
 
 

@@ -111,6 +111,11 @@ extern "C" int nf_tune_set(const char* key, int value) {
     nf_set_attention_variant(value);
     return NF_OK;
   }
+  if (!strcmp(key, "gemm.debug")) {
+    if (value < 0 || value > 3) return NF_EINVAL;
+    nf_set_gemm_debug(value);
+    return NF_OK;
+  }
   if (!strcmp(key, "gemm.tile")) {
     if (value < 0 || value > 6) return NF_EINVAL;
     nf_set_gemm_tile(value);

@@ -44,14 +44,15 @@ struct GroupedArgs {
   long long w_stride;
 };
 
-template <int BM, int BN, int EPI, int PF, bool GROUPED>
-__global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kernel(
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int PF, bool GROUPED, int DBG = 0>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WAVES_M * WAVES_N) / 4 : 2) void gemm_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
-  constexpr int WM = BM / 2, WN = BN / 2;   // wavefront tile
-  constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wavefront
-  constexpr int A_CHUNKS = BM * 8 / 256;    // 16-byte chunks per thread per stage
-  constexpr int B_CHUNKS = BN * 8 / 256;
+  constexpr int NT = 64 * WAVES_M * WAVES_N;        // threads per workgroup
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
+  constexpr int TM = WM / 32, TN = WN / 32;          // 32x32 MFMA tiles per wavefront
+  constexpr int A_CHUNKS = BM * 8 / NT;              // 16-byte chunks per thread per stage
+  constexpr int B_CHUNKS = BN * 8 / NT;
   __shared__ __attribute__((aligned(16))) bf16_t sX[2][BM * LDS_STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t sW[2][BN * LDS_STRIDE];
 
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
     if (!found) return;  // uniform for the whole workgroup, before any barrier
   }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
   // global -> register staging
   const bf16_t* xg[A_CHUNKS];
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
   int xs[A_CHUNKS], ws[B_CHUNKS];
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
-    const int q = i * 256 + tid, row = q >> 3, c = q & 7;
+    const int q = i * NT + tid, row = q >> 3, c = q & 7;
     int gm = m0 + row;
     gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
     if (GROUPED && grp.row_index) gm = grp.row_index[gm];
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
   }
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
-    const int q = i * 256 + tid, row = q >> 3, c = q & 7;
+    const int q = i * NT + tid, row = q >> 3, c = q & 7;
     int gn;
     if (EPI == EPI_SWIGLU) {
       // tile rows alternate in 32-row groups: gate rows of 32 output columns, then their up rows
@@ -166,21 +167,21 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
             for (int j = 0; j < TM; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) {
+        if (kt + 1 < KT && DBG < 2) {
           const int nxt = cur ^ 1;
 #pragma unroll
           for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[nxt][xs[i]]) = xr[d][i];
 #pragma unroll
           for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[nxt][ws[i]]) = wr[d][i];
         }
-        if (kt + 1 + PF < KT) {
+        if (kt + 1 + PF < KT && DBG < 1) {
           const int koff = (kt + 1 + PF) * BK;
 #pragma unroll
           for (int i = 0; i < A_CHUNKS; ++i) xr[d][i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
 #pragma unroll
           for (int i = 0; i < B_CHUNKS; ++i) wr[d][i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
         }
-        __syncthreads();
+        if (DBG < 3) __syncthreads();
       }
     }
   }
@@ -230,27 +231,27 @@ __global__ __launch_bounds__(256, (BM * BN > 128 * 128) ? 1 : 2) void gemm_kerne
   }
 }
 
-template <int BM, int BN, int PF, bool GROUPED = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool GROUPED = false>
 hipError_t launch(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
                   hipStream_t s, GroupedArgs grp = GroupedArgs{nullptr, nullptr, 0, 0}) {
   // grouped: M is the total row count; every expert may add one partial tile
   const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
   // SwiGLU: a BN-wide tile of the stacked [2N, K] weight yields BN/2 output columns
   const int tiles_n = epilogue == EPI_SWIGLU ? (2 * N) / BN : N / BN;
-  const dim3 grid(tiles_m * tiles_n), block(256);
+  const dim3 grid(tiles_m * tiles_n), block(64 * WAVES_M * WAVES_N);
   const bf16_t* X = (const bf16_t*)x;
   const bf16_t* W = (const bf16_t*)w;
   bf16_t* Y = (bf16_t*)out;
   const bf16_t* R = (const bf16_t*)residual;
   switch (epilogue) {
     case EPI_NONE:
-      gemm_kernel<BM, BN, EPI_NONE, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
+      gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_NONE, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
     case EPI_RESIDUAL:
-      gemm_kernel<BM, BN, EPI_RESIDUAL, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
+      gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_RESIDUAL, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
     default:
-      gemm_kernel<BM, BN, EPI_SWIGLU, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
+      gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_SWIGLU, PF, GROUPED><<<grid, block, 0, s>>>(X, W, Y, R, M, N, K, tiles_m, tiles_n, grp);
       break;
   }
   return hipGetLastError();
@@ -259,27 +260,46 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 }  // namespace
 
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
-// 5 / 6 = 128x128 with 2 / 3 K-steps of global loads in flight.  Every variant walks K in the
+// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads).  Every variant walks K in the
 // same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
+
+// Timing-only ablations of the 128x128 kernel (results are wrong): 1 = no global loads in
+// the main loop, 2 = also no LDS writes, 3 = also no barriers.
+static int g_gemm_debug = 0;
+void nf_set_gemm_debug(int v) { g_gemm_debug = v; }
+
+template <int DBG>
+static hipError_t launch_debug(const void* x, const void* w, void* out, int M, int N, int K, hipStream_t s) {
+  const int tiles_m = (M + 127) / 128, tiles_n = N / 128;
+  gemm_kernel<128, 128, 2, 2, EPI_NONE, 1, false, DBG><<<dim3(tiles_m * tiles_n), dim3(256), 0, s>>>(
+      (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out, nullptr, M, N, K, tiles_m, tiles_n,
+      GroupedArgs{nullptr, nullptr, 0, 0});
+  return hipGetLastError();
+}
 
 // Requires K % 64 == 0 and N % 64 == 0 (checked by the caller on the host).
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                           int epilogue, int tile, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
-  if (n_eff % 128 != 0) return launch<128, 64, 1>(x, w, out, residual, M, N, K, epilogue, s);
+  if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
+  if (g_gemm_debug && epilogue == EPI_NONE && n_eff % 128 == 0) {
+    if (g_gemm_debug == 1) return launch_debug<1>(x, w, out, M, N, K, s);
+    if (g_gemm_debug == 2) return launch_debug<2>(x, w, out, M, N, K, s);
+    return launch_debug<3>(x, w, out, M, N, K, s);
+  }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) tile = 1;
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;
   switch (tile) {
-    case 2: return launch<256, 128, 1>(x, w, out, residual, M, N, K, epilogue, s);
-    case 3: return launch<128, 256, 1>(x, w, out, residual, M, N, K, epilogue, s);
-    case 4: return launch<256, 256, 1>(x, w, out, residual, M, N, K, epilogue, s);
-    case 5: return launch<128, 128, 2>(x, w, out, residual, M, N, K, epilogue, s);
-    case 6: return launch<128, 128, 3>(x, w, out, residual, M, N, K, epilogue, s);
-    default: return launch<128, 128, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 2: return launch<256, 128, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 3: return launch<128, 256, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 4: return launch<256, 256, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 5: return launch<256, 256, 2, 4, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    case 6: return launch<256, 128, 4, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
+    default: return launch<128, 128, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
   }
 }
 
@@ -291,6 +311,6 @@ hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int r
   if (rows <= 0) return hipSuccess;
   const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
-  if (n_eff % 128 != 0) return launch<128, 64, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
-  return launch<128, 128, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+  if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+  return launch<128, 128, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
 }

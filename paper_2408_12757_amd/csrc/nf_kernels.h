@@ -60,3 +60,4 @@ hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int t
                                  int32_t* expert_offset, int32_t* row_token, int32_t* slot_of, hipStream_t s);
 hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
                                  void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s);
+void nf_set_gemm_debug(int v);

@@ -65,7 +65,9 @@ int nf_profile_save(const NfProfile& p, const char* path) {
     for (size_t i = 0; i < p.dense_us[o].size(); ++i)
       fprintf(f, "dense %d %d %.4f %d\n", o, (int)(i + 1) * p.granule, p.dense_us[o][i], p.dense_tile[o][i]);
   fprintf(f, "attn %.6f %.8f\n", p.attn_fixed_us, p.attn_us_per_mb);
-  for (const NfRpRow& r : p.rp) fprintf(f, "rp %d %.6f %.6f %.6f\n", r.attn_wgs, r.p_gemm, r.p_attn, r.p_attn_solo);
+  for (const NfRpRow& r : p.rp)
+    fprintf(f, "rp %d %.6f %.6f %.6f %d %.6f\n", r.attn_wgs, r.p_gemm, r.p_attn, r.p_attn_solo, r.gemm_tile,
+            r.p_gemm_solo);
   return fclose(f) == 0 ? NF_OK : NF_EIO;
 }
 
@@ -82,7 +84,7 @@ int nf_profile_load(NfProfile* p, const char* path) {
   int ok = 1;
   while (fgets(line, sizeof line, f)) {
     int a, b, c, d;
-    double x, y, z;
+    double x, y;
     nf_model_desc& m = q.model;
     if (sscanf(line, "model %d %d %d %d %d %d %d", &m.hidden, &m.n_q_heads, &m.n_kv_heads, &m.head_dim, &m.ffn_inner,
                &m.n_experts, &m.top_k) == 7) {
@@ -101,8 +103,19 @@ int nf_profile_load(NfProfile* p, const char* path) {
     } else if (sscanf(line, "attn %lf %lf", &x, &y) == 2) {
       q.attn_fixed_us = x;
       q.attn_us_per_mb = y;
-    } else if (sscanf(line, "rp %d %lf %lf %lf", &a, &x, &y, &z) == 4) {
-      q.rp.push_back(NfRpRow{a, x, y, z});
+    } else if (!strncmp(line, "rp ", 3)) {
+      NfRpRow r{};
+      const int nf = sscanf(line, "rp %d %lf %lf %lf %d %lf", &r.attn_wgs, &r.p_gemm, &r.p_attn, &r.p_attn_solo,
+                            &r.gemm_tile, &r.p_gemm_solo);
+      if (nf != 4 && nf != 6) {
+        ok = 0;
+        break;
+      }
+      if (nf == 4) {
+        r.gemm_tile = 0;
+        r.p_gemm_solo = 1.0;
+      }
+      q.rp.push_back(r);
     } else if (line[0] != '#' && line[0] != '\n') {
       ok = 0;
       break;
@@ -186,6 +199,8 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
         sp[1] = row->p_attn;
       } else if (running[1]) {
         sp[1] = row->p_attn_solo;
+      } else {
+        sp[0] = row->p_gemm_solo;
       }
     }
     double dt = 1e300;
@@ -259,7 +274,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
 
   // Stage II: resource share per structure, with interference
   double best = out->est_us_unsplit;
-  const NfRpRow ideal{0, 1.0, 1.0, 1.0};
+  const NfRpRow ideal{0, 1.0, 1.0, 1.0, 0, 1.0};
   for (size_t c = 0; c < keep; ++c) {
     const size_t n_rows = prof.rp.empty() ? 1 : prof.rp.size();
     for (size_t r = 0; r < n_rows; ++r) {
@@ -270,6 +285,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
         out->bounds = cands[c].bounds;
         out->overlap = 1;
         out->attn_wgs = row.attn_wgs;
+        out->gemm_tile = row.gemm_tile;
         out->est_us = t2;
         out->est_us_stage1 = cands[c].t1;
       }

@@ -19,6 +19,10 @@ enum { NF_DENSE_KQV = 0, NF_DENSE_O = 1, NF_DENSE_UG = 2, NF_DENSE_D = 3, NF_DEN
 struct NfRpRow {
   int attn_wgs;
   double p_gemm, p_attn, p_attn_solo;
+  // GEMM implementation (tile shape) of this pair, and the performance of that
+  // implementation when it runs alone, relative to the best implementation (<= 1)
+  int gemm_tile = 0;
+  double p_gemm_solo = 1.0;
 };
 
 struct NfProfile {
@@ -56,6 +60,7 @@ struct NfPipeline {
   std::vector<int> bounds;   // nano-batch boundaries
   int overlap = 0;
   int attn_wgs = 0;          // chosen row of the R -> P table (0 = unrestricted)
+  int gemm_tile = 0;         // GEMM implementation of the chosen row (0 = per-op best)
   double est_us = 0.0;       // simulated makespan
   double est_us_stage1 = 0.0;  // makespan of the same structure without interference
   double est_us_unsplit = 0.0;

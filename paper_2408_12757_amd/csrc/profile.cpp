@@ -18,7 +18,7 @@ void nf_profile_free(nf_ctx* ctx) {
 
 namespace {
 
-constexpr int kTiles[] = {1, 2, 3, 4};
+constexpr int kTiles[] = {1, 2, 3, 4, 5, 6};
 constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 384, 512, 768, 0};  // 0 = one per work unit
 
 struct Scratch {
@@ -214,65 +214,80 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     p->attn_fixed_us = std::max(1.0, t_short_ms * 1e3 - p->attn_us_per_mb * short_mb);
   }
 
-  // ---- pairwise interference: Up/Gate GEMM at the full batch || attention with k workgroups ----
+  // ---- pairwise interference: Up/Gate GEMM at the full batch (every tile shape) || attention
+  // with k persistent workgroups.  Performance is normalised to the best stand-alone
+  // implementation of each kernel. ----
   if (!rc) {
     const int o = NF_DENSE_UG, M = (int)Mmax;
-    const int tile = p->dense_tile[o][steps - 1];
-    const double g_solo_ms = p->dense_us[o][steps - 1] / 1e3;
-    const int n_gemm = std::min(64, (int)ceil(3.0 * best_long / g_solo_ms) + 2);
-    std::vector<hipEvent_t> ev((size_t)n_gemm + 4);
-    for (auto& e : ev)
-      if (hipEventCreate(&e) != hipSuccess) rc = NF_EHIP;
-    hipEvent_t fork = ev[n_gemm], a0 = ev[n_gemm + 1], a1 = ev[n_gemm + 2];
+    const double g_best_ms = p->dense_us[o][steps - 1] / 1e3;
+    const int kPairTiles[] = {1, 2, 5, 6};
     p->rp.clear();
-    for (int k = 0; k < n_set && !rc; ++k) {
-      (void)hipDeviceSynchronize();
-      hipError_t e = hipEventRecord(fork, sg);
-      if (e == hipSuccess) e = hipStreamWaitEvent(sa, fork, 0);
-      // GEMMs first in issue order; attention joins right behind
+    for (int tile : kPairTiles) {
+      if (rc) break;
       int flip = 0;
-      for (int i = 0; i < n_gemm && e == hipSuccess; ++i) {
+      double g_solo_ms = 0;
+      rc = time_ms(ctx, sg, 3, [&] {
         flip ^= 1;
-        e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
-        if (e == hipSuccess) e = hipEventRecord(ev[i], sg);
-        if (i == 0 && e == hipSuccess) {
-          e = hipEventRecord(a0, sa);
-          if (e == hipSuccess && attn_call(1, kAttnWgSettings[k], sa) != NF_OK) e = hipErrorUnknown;
-          if (e == hipSuccess) e = hipEventRecord(a1, sa);
+        return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg) == hipSuccess ? NF_OK
+                                                                                                             : NF_EHIP;
+      }, &g_solo_ms);
+      if (rc) break;
+      const int n_gemm = std::min(64, (int)ceil(3.0 * best_long / g_solo_ms) + 2);
+      std::vector<hipEvent_t> ev((size_t)n_gemm + 3);
+      for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) rc = NF_EHIP;
+      hipEvent_t fork = ev[n_gemm], a0 = ev[n_gemm + 1], a1 = ev[n_gemm + 2];
+      for (int k = 0; k < n_set && !rc; ++k) {
+        (void)hipDeviceSynchronize();
+        hipError_t e = hipEventRecord(fork, sg);
+        if (e == hipSuccess) e = hipStreamWaitEvent(sa, fork, 0);
+        // GEMMs first in issue order; attention joins right behind
+        for (int i = 0; i < n_gemm && e == hipSuccess; ++i) {
+          flip ^= 1;
+          e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
+          if (e == hipSuccess) e = hipEventRecord(ev[i], sg);
+          if (i == 0 && e == hipSuccess) {
+            e = hipEventRecord(a0, sa);
+            if (e == hipSuccess && attn_call(1, kAttnWgSettings[k], sa) != NF_OK) e = hipErrorUnknown;
+            if (e == hipSuccess) e = hipEventRecord(a1, sa);
+          }
         }
-      }
-      if (e == hipSuccess) e = hipDeviceSynchronize();
-      if (e != hipSuccess) {
-        ctx->last_hip = (int)e;
-        rc = NF_EHIP;
-        break;
-      }
-      float t_a0 = 0, t_a1 = 0;
-      (void)hipEventElapsedTime(&t_a0, fork, a0);
-      (void)hipEventElapsedTime(&t_a1, fork, a1);
-      // GEMM work (in units of one GEMM) finished inside the attention window [t_a0, t_a1]
-      auto progress_at = [&](float t) {
-        float prev = 0.f;
-        for (int i = 0; i < n_gemm; ++i) {
-          float ti = 0;
-          (void)hipEventElapsedTime(&ti, fork, ev[i]);
-          if (t <= ti) return (double)i + (double)(t - prev) / std::max(1e-6f, ti - prev);
-          prev = ti;
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+          ctx->last_hip = (int)e;
+          rc = NF_EHIP;
+          break;
         }
-        return (double)n_gemm;
-      };
-      const double done = progress_at(t_a1) - progress_at(t_a0);
-      const double window = std::max(1e-6, (double)(t_a1 - t_a0));
-      NfRpRow row;
-      row.attn_wgs = kAttnWgSettings[k];
-      row.p_gemm = std::min(1.0, done * g_solo_ms / window);
-      row.p_attn = std::min(1.0, best_long / window);
-      row.p_attn_solo = std::min(1.0, best_long / t_long_ms[k]);
-      p->rp.push_back(row);
+        float t_a0 = 0, t_a1 = 0;
+        (void)hipEventElapsedTime(&t_a0, fork, a0);
+        (void)hipEventElapsedTime(&t_a1, fork, a1);
+        // GEMM work (in units of one GEMM) finished inside the attention window [t_a0, t_a1]
+        auto progress_at = [&](float t) {
+          float prev = 0.f;
+          for (int i = 0; i < n_gemm; ++i) {
+            float ti = 0;
+            (void)hipEventElapsedTime(&ti, fork, ev[i]);
+            if (t <= ti) return (double)i + (double)(t - prev) / std::max(1e-6f, ti - prev);
+            prev = ti;
+          }
+          return (double)n_gemm;
+        };
+        const double done = progress_at(t_a1) - progress_at(t_a0);
+        const double window = std::max(1e-6, (double)(t_a1 - t_a0));
+        NfRpRow row;
+        row.attn_wgs = kAttnWgSettings[k];
+        row.gemm_tile = tile;
+        // one GEMM of this tile is worth g_best_ms of the best implementation's time
+        row.p_gemm = std::min(1.0, done * g_best_ms / window);
+        row.p_attn = std::min(1.0, best_long / window);
+        row.p_attn_solo = std::min(1.0, best_long / t_long_ms[k]);
+        row.p_gemm_solo = std::min(1.0, g_best_ms / g_solo_ms);
+        p->rp.push_back(row);
+      }
+      for (auto& e : ev) (void)hipEventDestroy(e);
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
-    // discard dominated rows: lower GEMM performance and lower attention performance than
-    // another row (Sec. 4.1.1, the greyed-out pairs)
+    // discard dominated pairs: another pair is at least as good for both kernels
+    // (Sec. 4.1.1, the greyed-out pairs)
     std::vector<NfRpRow> keep;
     for (const NfRpRow& r : p->rp) {
       bool dominated = false;
@@ -373,6 +388,7 @@ extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* ba
   for (size_t i = 0; i < pl.bounds.size() && i < 9; ++i) out->bounds[i] = pl.bounds[i];
   out->overlap = pl.overlap;
   out->attn_wgs = pl.attn_wgs;
+  out->gemm_tile = pl.gemm_tile;
   out->est_us = pl.est_us;
   out->est_us_stage1 = pl.est_us_stage1;
   out->est_us_unsplit = pl.est_us_unsplit;
@@ -434,7 +450,7 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
     if (dense < 0 || prof->dense_tile[dense].empty()) continue;
     const int m = op.tok_end - op.tok_begin;
     const int idx = std::min((int)prof->dense_tile[dense].size() - 1, std::max(0, (m + granule - 1) / granule - 1));
-    op.gemm_tile = prof->dense_tile[dense][idx];
+    op.gemm_tile = (pl.overlap && pl.gemm_tile) ? pl.gemm_tile : prof->dense_tile[dense][idx];
   }
   return NF_OK;
 }
