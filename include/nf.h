@@ -240,7 +240,8 @@ int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b
  *              bits of the CU mask; the GEMM lane the gemm_cus bits after them
  *              when attn_cus + gemm_cus fits the device, else the first gemm_cus.
  * attn_wgs   : number of persistent workgroups (4 wavefronts each) the attention kernel is
- *              launched with; 0 = one per work unit.  This is the resource share R of the
+ *              launched with; 0 = one per compute unit (the stand-alone optimum), -1 = one per
+ *              work unit.  This is the resource share R of the
  *              memory-bound kernel (Sec. 4.1.1): fewer workgroups leave more of every
  *              compute unit to the GEMMs running beside it.  It never changes results.
  */

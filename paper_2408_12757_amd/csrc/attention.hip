@@ -239,7 +239,7 @@ __global__ __launch_bounds__(DH) void attention_merge_kernel(const float* __rest
 
 // Kernel variant: pages in flight per wavefront (more pages = more bytes in flight per
 // wavefront but fewer resident wavefronts).
-static int g_attn_variant = 4;
+static int g_attn_variant = 5;
 void nf_set_attention_variant(int v) { g_attn_variant = v; }
 
 template <int DH>
@@ -257,6 +257,9 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
     case 2: NF_ATTN_LAUNCH(4, 2, false); break;
     case 3: NF_ATTN_LAUNCH(5, 2, false); break;
     case 4: NF_ATTN_LAUNCH(3, 2, true); break;
+    case 5: NF_ATTN_LAUNCH(2, 3, true); break;
+    case 6: NF_ATTN_LAUNCH(4, 2, true); break;
+    case 7: NF_ATTN_LAUNCH(5, 2, true); break;
     default: return hipErrorInvalidValue;
   }
 #undef NF_ATTN_LAUNCH
@@ -270,7 +273,20 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
   const int n_work = n_items * head_groups;
-  const dim3 grid((unsigned)(max_workgroups > 0 && max_workgroups < n_work ? max_workgroups : n_work));
+  // Default: one persistent workgroup per compute unit.  Measured on MI355X: 4 wavefronts per
+  // CU already saturate HBM, a grid that is a multiple of the CU count keeps every CU equally
+  // loaded (320 workgroups on 256 CUs lose 25 %), and short grids end with a shorter tail.
+  static int n_cus = 0;
+  if (n_cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n_cus = prop.multiProcessorCount;
+    if (n_cus <= 0) n_cus = 256;
+  }
+  int wgs = max_workgroups > 0 ? max_workgroups : (max_workgroups < 0 ? n_work : n_cus);
+  if (wgs > n_work) wgs = n_work;
+  const dim3 grid((unsigned)wgs);
   if (shp.head_dim == 128)
     return launch_attention_dh<128>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
                                     page_ids, items, n_work, head_groups, shp, scale_log2, parts);

@@ -58,7 +58,7 @@ struct nf_plan {
   int overlap = 0;
   int lane_cus[NF_LANES] = {0, 0};        // CU count per lane (0 = whole chip, no mask)
   int lane_cu_first[NF_LANES] = {0, 0};   // first CU bit of the lane's mask
-  int attn_wgs = 0;                       // persistent attention workgroups (0 = as many as there is work)
+  int attn_wgs = 0;                       // persistent attention workgroups (0 = one per CU, -1 = one per work unit)
   hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
   std::vector<hipEvent_t> events;  // one per nano-op that records
   hipEvent_t ev_fork = nullptr, ev_join[NF_LANES] = {nullptr, nullptr};

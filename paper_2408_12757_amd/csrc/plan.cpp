@@ -264,7 +264,7 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
   if (rc) return rc;
   rc = check_bounds(batch, n_nano, bounds);
   if (rc) return rc;
-  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus || attn_wgs < 0)
+  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus || attn_wgs < -1)
     return NF_EINVAL;
   nf_plan* p = new (std::nothrow) nf_plan();
   if (!p) return NF_ENOMEM;

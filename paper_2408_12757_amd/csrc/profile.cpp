@@ -19,7 +19,7 @@ void nf_profile_free(nf_ctx* ctx) {
 namespace {
 
 constexpr int kTiles[] = {1, 2, 3, 4, 5, 6};
-constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 384, 512, 768, 0};  // 0 = one per work unit
+constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 512, 768};
 
 struct Scratch {
   std::vector<void*> ptrs;
