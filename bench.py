@@ -126,12 +126,27 @@ def main():
     t_search = time.perf_counter() - t0
     best_desc = best_plan.describe()
     best_c = {k: best_desc[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
+    searched_c = dict(best_c)
     # the ablation of Sec. 6.4 on a fixed two-nano-batch structure
     half = max(cfg.granule, (B // 2) // cfg.granule * cfg.granule)
     abl_bounds = [0, half, B] if half < B else [0, B]
     unsplit_plan = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
     seq_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, False, 0, 0, 0)
     ovl_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, True, 0, 0, args.ablation_attn_wgs)
+
+    # A searched pipeline that splits the batch is kept only if a short trial run on this batch
+    # confirms the model (Sec. 4.1.3 refines the pipeline with measured interference); else the
+    # unsplit pipeline is timed.
+    verify = None
+    if len(best_desc["bounds"]) > 2:
+        t_s = hz.time_plan(case, best_plan, 3, 8)
+        t_u = hz.time_plan(case, unsplit_plan, 3, 8)
+        verify = {"searched_ms": t_s, "unsplit_ms": t_u}
+        if t_u < t_s:
+            best_plan = unsplit_plan
+            d = unsplit_plan.describe()
+            best_c = {k: d[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
+            best_c["origin"] += "; searched pipeline rejected by the trial run"
 
     def timed(plan, steps, warmup, trace=0):
         for i in range(warmup):
@@ -189,7 +204,7 @@ def main():
                         "nano_overlapped": ovl_ms, "overlapped_attn_wgs": args.ablation_attn_wgs,
                         "speedup_overlapped_vs_sequential": seq_ms / ovl_ms,
                         "nano_batching_overhead": seq_ms / unsplit_ms - 1.0},
-        "auto_search": {"profile_s": t_profile, "search_s": t_search},
+        "auto_search": {"profile_s": t_profile, "search_s": t_search, "searched": searched_c, "trial_run": verify},
         "roofline": {"bound": "hbm", "kernel": "attention_kernel<128>", "achieved": achieved,
                      "peak": cm.MI355X_PEAK_HBM_BPS / 1e9, "unit": "GB/s",
                      "frac": achieved / (cm.MI355X_PEAK_HBM_BPS / 1e9),

@@ -35,8 +35,18 @@ def interp_dense(table: Sequence[float], granule: int, m: int) -> float:
 
 
 def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, overlap,
-             row: Optional[dict], dt: float = 0.02) -> float:
-    """dense: dict op -> table; row: dict(p_gemm, p_attn, p_attn_solo) or None."""
+             row: Optional[dict], dt: float = 0.02, misc=None) -> float:
+    """dense: dict op -> table of the best implementation; row: dict(p_gemm, p_attn,
+    p_attn_solo[, p_gemm_solo][, dense]) or None.  A row that carries its own "dense" tables
+    (the times of the GEMM implementation it was measured with) makes every GEMM of an
+    overlapped pipeline run in that implementation: its table gives D, and the overlapped
+    speed p_gemm (normalised to the best implementation) is re-expressed relative to it.
+    misc: ((a, b), (a, b), (a, b)) fixed + per-token cost of the small kernels added to the KQV
+    stage, the O/Up/Gate/Down stage and the attention stage."""
+    if overlap and row is not None and row.get("dense") is not None:
+        dense = row["dense"]
+        solo = row.get("p_gemm_solo", 1.0)
+        row = dict(row, p_gemm=row["p_gemm"] / solo, p_gemm_solo=1.0)
     n = len(bounds) - 1
     kqv, att, rest = [], [], []
     for i in range(n):
@@ -44,6 +54,10 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
         kqv.append(interp_dense(dense["KQV"], granule, m))
         rest.append(sum(interp_dense(dense[o], granule, m) for o in ("O", "UG", "D")))
         att.append(attn_fixed + attn_per_mb * (attn_mb_prefix[bounds[i + 1]] - attn_mb_prefix[bounds[i]]))
+        if misc is not None:
+            kqv[-1] += misc[0][0] + misc[0][1] * m
+            rest[-1] += misc[1][0] + misc[1][1] * m
+            att[-1] += misc[2][0] + misc[2][1] * m
     if not overlap:
         return sum(kqv) + sum(att) + sum(rest)
     # launch order on the compute resource: all KQV nano-ops, then O+UG+D per nano-batch
@@ -98,14 +112,15 @@ def all_bounds(n_tokens: int, granule: int, n_nano: int) -> List[List[int]]:
 
 
 def brute_force(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, n_tokens, rows, max_nano,
-                dt: float = 0.02):
+                dt: float = 0.02, misc=None):
     """Minimum makespan over every structure and every table row, and the unsplit time."""
-    unsplit = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, [0, n_tokens], False, None)
+    unsplit = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, [0, n_tokens], False, None,
+                       misc=misc)
     best = (unsplit, [0, n_tokens], None)
     for n in range(2, max_nano + 1):
         for b in all_bounds(n_tokens, granule, n):
             for r in (rows or [None]):
-                t = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, b, True, r, dt)
+                t = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, b, True, r, dt, misc)
                 if t < best[0]:
                     best = (t, b, r)
     return best, unsplit

@@ -15,10 +15,19 @@
 
 #include <algorithm>
 
-double nf_profile_dense_us(const NfProfile& p, int op, int m) {
-  const std::vector<double>& t = p.dense_us[op];
+static double interp_table(const std::vector<double>& t, int granule, int m);
+
+double nf_profile_dense_us(const NfProfile& p, int op, int m) { return interp_table(p.dense_us[op], p.granule, m); }
+
+double nf_profile_tile_us(const NfProfile& p, int tile, double p_solo, int op, int m) {
+  if (tile >= 1 && tile <= NF_MAX_TILE && !p.tile_us[tile][op].empty())
+    return interp_table(p.tile_us[tile][op], p.granule, m);
+  return nf_profile_dense_us(p, op, m) / std::max(p_solo, 1e-6);
+}
+
+static double interp_table(const std::vector<double>& t, int granule, int m) {
   if (t.empty() || m <= 0) return 0.0;
-  const double x = (double)m / p.granule;  // table index + 1
+  const double x = (double)m / granule;  // table index + 1
   if (x <= 1.0) return t[0];               // a partial tile costs a whole one
   const int i = (int)floor(x) - 1;
   if (i + 1 >= (int)t.size()) return t.back() * (x / (double)t.size());
@@ -50,6 +59,8 @@ void nf_profile_analytic(NfProfile* p, const nf_model_desc* m, int max_tokens, i
   }
   p->attn_fixed_us = 8.0;
   p->attn_us_per_mb = 1.0 / 5.8;
+  for (int t = 0; t <= NF_MAX_TILE; ++t)
+    for (int o = 0; o < NF_DENSE_OPS; ++o) p->tile_us[t][o].clear();
   p->rp.clear();
 }
 
@@ -64,6 +75,12 @@ int nf_profile_save(const NfProfile& p, const char* path) {
   for (int o = 0; o < NF_DENSE_OPS; ++o)
     for (size_t i = 0; i < p.dense_us[o].size(); ++i)
       fprintf(f, "dense %d %d %.4f %d\n", o, (int)(i + 1) * p.granule, p.dense_us[o][i], p.dense_tile[o][i]);
+  for (int t = 1; t <= NF_MAX_TILE; ++t)
+    for (int o = 0; o < NF_DENSE_OPS; ++o)
+      for (size_t i = 0; i < p.tile_us[t][o].size(); ++i)
+        fprintf(f, "tile_us %d %d %d %.4f\n", t, o, (int)(i + 1) * p.granule, p.tile_us[t][o][i]);
+  fprintf(f, "misc %.4f %.6f %.4f %.6f %.4f %.6f\n", p.misc_kqv[0], p.misc_kqv[1], p.misc_rest[0], p.misc_rest[1],
+          p.misc_attn[0], p.misc_attn[1]);
   fprintf(f, "attn %.6f %.8f\n", p.attn_fixed_us, p.attn_us_per_mb);
   for (const NfRpRow& r : p.rp)
     fprintf(f, "rp %d %.6f %.6f %.6f %d %.6f\n", r.attn_wgs, r.p_gemm, r.p_attn, r.p_attn_solo, r.gemm_tile,
@@ -100,6 +117,19 @@ int nf_profile_load(NfProfile* p, const char* path) {
       }
       q.dense_us[a].push_back(x);
       q.dense_tile[a].push_back(d);
+    } else if (sscanf(line, "tile_us %d %d %d %lf", &a, &b, &c, &x) == 4) {
+      if (a < 1 || a > NF_MAX_TILE || b < 0 || b >= NF_DENSE_OPS ||
+          c != (int)(q.tile_us[a][b].size() + 1) * q.granule) {
+        ok = 0;
+        break;
+      }
+      q.tile_us[a][b].push_back(x);
+    } else if (!strncmp(line, "misc ", 5)) {
+      if (sscanf(line, "misc %lf %lf %lf %lf %lf %lf", &q.misc_kqv[0], &q.misc_kqv[1], &q.misc_rest[0],
+                 &q.misc_rest[1], &q.misc_attn[0], &q.misc_attn[1]) != 6) {
+        ok = 0;
+        break;
+      }
     } else if (sscanf(line, "attn %lf %lf", &x, &y) == 2) {
       q.attn_fixed_us = x;
       q.attn_us_per_mb = y;
@@ -146,13 +176,20 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
                    const NfRpRow* row) {
   const int n = (int)bounds.size() - 1;
   std::vector<double> kqv(n), att(n), rest(n);
+  // With a table row, every GEMM runs in the row's implementation: its own interference-free
+  // time is the work, and its overlapped speed is relative to that implementation alone.
+  const bool use_row_tile = overlap && row && row->gemm_tile > 0;
+  auto dense = [&](int op, int m) {
+    return use_row_tile ? nf_profile_tile_us(prof, row->gemm_tile, row->p_gemm_solo, op, m)
+                        : nf_profile_dense_us(prof, op, m);
+  };
   for (int i = 0; i < n; ++i) {
     const int m = bounds[i + 1] - bounds[i];
-    kqv[i] = nf_profile_dense_us(prof, NF_DENSE_KQV, m);
-    rest[i] = nf_profile_dense_us(prof, NF_DENSE_O, m) + nf_profile_dense_us(prof, NF_DENSE_UG, m) +
-              nf_profile_dense_us(prof, NF_DENSE_D, m);
+    kqv[i] = dense(NF_DENSE_KQV, m) + prof.misc_kqv[0] + prof.misc_kqv[1] * m;
+    rest[i] = dense(NF_DENSE_O, m) + dense(NF_DENSE_UG, m) + dense(NF_DENSE_D, m) + prof.misc_rest[0] +
+              prof.misc_rest[1] * m;
     const double mb = in.attn_mb_prefix[bounds[i + 1]] - in.attn_mb_prefix[bounds[i]];
-    att[i] = prof.attn_fixed_us + prof.attn_us_per_mb * mb;
+    att[i] = prof.attn_fixed_us + prof.attn_us_per_mb * mb + prof.misc_attn[0] + prof.misc_attn[1] * m;
   }
   if (!overlap) {
     double t = 0;
@@ -194,13 +231,15 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
     if (!running[0] && !running[1]) break;  // all done (a valid structure cannot deadlock)
     double sp[2] = {1.0, 1.0};
     if (row) {
+      // GEMM work is in units of the row's implementation when its table is used
+      const double g_solo = use_row_tile ? 1.0 : row->p_gemm_solo;
       if (running[0] && running[1]) {
-        sp[0] = row->p_gemm;
+        sp[0] = use_row_tile ? row->p_gemm / std::max(row->p_gemm_solo, 1e-6) : row->p_gemm;
         sp[1] = row->p_attn;
       } else if (running[1]) {
         sp[1] = row->p_attn_solo;
       } else {
-        sp[0] = row->p_gemm_solo;
+        sp[0] = g_solo;
       }
     }
     double dt = 1e300;

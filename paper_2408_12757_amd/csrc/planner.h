@@ -8,6 +8,7 @@
 
 #include "../../include/nf.h"
 
+constexpr int NF_MAX_TILE = 6;
 enum { NF_DENSE_KQV = 0, NF_DENSE_O = 1, NF_DENSE_UG = 2, NF_DENSE_D = 3, NF_DENSE_OPS = 4 };
 
 // One row of the resource-mapping table (Sec. 4.1.1, Table 3) for the memory-bound kernel:
@@ -34,6 +35,11 @@ struct NfProfile {
   // (i + 1) * granule, best over the GEMM tile shapes, and the tile that achieved it
   std::vector<double> dense_us[NF_DENSE_OPS];
   std::vector<int> dense_tile[NF_DENSE_OPS];
+  // the same times per implementation (GEMM tile shape 1..NF_MAX_TILE); empty when unknown
+  std::vector<double> tile_us[NF_MAX_TILE + 1][NF_DENSE_OPS];
+  // the small row-wise kernels, as fixed + per-token microseconds: norm + rotary/append before
+  // the KQV GEMM's consumers, norm before Up/Gate, merge after attention
+  double misc_kqv[2] = {8.0, 0.02}, misc_rest[2] = {4.0, 0.005}, misc_attn[2] = {4.0, 0.02};
   // stand-alone attention: fixed cost + cost per byte of K/V read, at the best configuration
   double attn_fixed_us = 5.0;
   double attn_us_per_mb = 1.0 / 5.7;  // 5.7 TB/s
@@ -42,6 +48,8 @@ struct NfProfile {
 
 // Interpolated interference-free time of a dense op on m tokens (0 < m).
 double nf_profile_dense_us(const NfProfile& p, int op, int m);
+// Same for one implementation; falls back to best / p_solo when that table is missing.
+double nf_profile_tile_us(const NfProfile& p, int tile, double p_solo, int op, int m);
 // Analytic stand-in used when nothing was measured (no GPU, or nf_profile never called).
 void nf_profile_analytic(NfProfile* p, const nf_model_desc* model, int max_tokens, int granule);
 int nf_profile_save(const NfProfile& p, const char* path);

@@ -153,6 +153,8 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
                      : NF_EHIP;
         }, &ms);
         if (rc) return rc;
+        if (i == 0) p->tile_us[tile][o].assign(steps, 0.0);
+        p->tile_us[tile][o][i] = ms * 1e3;
         if (ms < best) {
           best = ms;
           best_tile = tile;
@@ -212,6 +214,37 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     const double short_mb = (double)n_req * (ctx_tokens[0] + 1) * (page_bytes / 16) / 1e6;
     p->attn_us_per_mb = std::max(1e-6, (best_long - t_short_ms) * 1e3 / (long_mb - short_mb));
     p->attn_fixed_us = std::max(1.0, t_short_ms * 1e3 - p->attn_us_per_mb * short_mb);
+  }
+
+  // ---- the small row-wise kernels at n_req tokens: per-token cost, launch cost assumed 4 us each ----
+  if (!rc) {
+    double t_rms = 0, t_rope = 0, t_merge = 0;
+    rc = time_ms(ctx, sg, 5, [&] {
+      return nf_launch_rmsnorm(x, res, y, n_req, m->hidden, m->rms_eps, sg) == hipSuccess ? NF_OK : NF_EHIP;
+    }, &t_rms);
+    if (!rc)
+      rc = time_ms(ctx, sg, 5, [&] {
+        return nf_launch_rope_append(qkv, pool, plans[1]->d_tok_req, sb[1].d_q, sb[1].d_c, sb[1].d_pi, sb[1].d_pid, 0,
+                                     n_req, m->n_q_heads, m->n_kv_heads, m->head_dim, m->rope_theta, sg) == hipSuccess
+                   ? NF_OK
+                   : NF_EHIP;
+      }, &t_rope);
+    if (!rc)
+      rc = time_ms(ctx, sg, 5, [&] {
+        return nf_launch_attention_merge(parts, plans[0]->d_groups, plans[0]->group_cnt[0], ash, aout, sg) == hipSuccess
+                   ? NF_OK
+                   : NF_EHIP;
+      }, &t_merge);
+    if (!rc) {
+      const double fixed = 4.0;
+      auto per_tok = [&](double ms) { return std::max(0.0, ms * 1e3 - fixed) / n_req; };
+      p->misc_kqv[0] = 2 * fixed;
+      p->misc_kqv[1] = per_tok(t_rms) + per_tok(t_rope);
+      p->misc_rest[0] = fixed;
+      p->misc_rest[1] = per_tok(t_rms);
+      p->misc_attn[0] = fixed;
+      p->misc_attn[1] = per_tok(t_merge);
+    }
   }
 
   // ---- pairwise interference: Up/Gate GEMM at the full batch (every tile shape) || attention

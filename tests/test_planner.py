@@ -19,7 +19,9 @@ def host_batch(b: wl.Batch) -> nf.BatchArgs:
                         b.page_ids, dev)
 
 
-def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_mb, rows):
+def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_mb, rows, misc=None, tiles=None):
+    """tiles: {tile id: {op name: table}} interference-free times per GEMM implementation."""
+    misc = misc or ((0, 0), (0, 0), (0, 0))
     with open(path, "w") as f:
         f.write("nfprofile 1\n")
         f.write(f"model {model.hidden} {model.n_q_heads} {model.n_kv_heads} {model.head_dim} {model.ffn_inner} 0 0\n")
@@ -27,9 +29,15 @@ def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_
         for o, name in enumerate(OPS):
             for i, us in enumerate(dense[name]):
                 f.write(f"dense {o} {(i + 1) * granule} {us:.4f} 1\n")
+        for t, tabs in (tiles or {}).items():
+            for o, name in enumerate(OPS):
+                for i, us in enumerate(tabs[name]):
+                    f.write(f"tile_us {t} {o} {(i + 1) * granule} {us:.4f}\n")
+        f.write("misc " + " ".join(f"{v:.6f}" for pair in misc for v in pair) + "\n")
         f.write(f"attn {attn_fixed:.6f} {attn_per_mb:.8f}\n")
         for r in rows:
-            f.write(f"rp {r['attn_wgs']} {r['p_gemm']:.6f} {r['p_attn']:.6f} {r['p_attn_solo']:.6f}\n")
+            f.write(f"rp {r['attn_wgs']} {r['p_gemm']:.6f} {r['p_attn']:.6f} {r['p_attn_solo']:.6f} "
+                    f"{r.get('gemm_tile', 0)} {r.get('p_gemm_solo', 1.0):.6f}\n")
 
 
 def attn_prefix(model, b: wl.Batch):
@@ -139,6 +147,38 @@ def test_search_matches_brute_force_on_tiny_instances(tmp_path, seed):
         again = nf.nf_simulate_pipeline(MODEL, host_batch(b), got["bounds"], True, row_idx, path)
         assert again == pytest.approx(got["est_us"], rel=1e-9)
         assert all(x % g == 0 for x in got["bounds"][:-1])
+
+
+def test_rows_carry_their_gemm_implementation_and_small_kernels_are_counted(tmp_path):
+    # Two table rows measured with different GEMM implementations.  Tile 2 is slower alone
+    # (p_gemm_solo 0.8 at the profiled batch size) but interferes less.  Its own table says
+    # how slow it is at every batch size, so the model must use that table, not the best one.
+    g = 16
+    r = np.random.default_rng(5)
+    b = wl.batch_from_lengths([1] * 64, r.integers(200, 2000, 64), 0, r)
+    best = {o: [10.0 * (i + 1) * s for i in range(4)] for o, s in zip(OPS, (1, 0.6, 3, 1.5))}
+    tile2 = {o: [v * (2.0 if i == 0 else 1.25) for i, v in enumerate(tab)] for o, tab in best.items()}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = 150.0 / pre[-1]
+    rows = [dict(attn_wgs=256, p_gemm=0.45, p_attn=0.6, p_attn_solo=1.0, gemm_tile=1, p_gemm_solo=1.0),
+            dict(attn_wgs=256, p_gemm=0.56, p_attn=0.8, p_attn_solo=1.0, gemm_tile=2, p_gemm_solo=0.8)]
+    misc = ((3.0, 0.05), (1.0, 0.02), (2.0, 0.1))
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, 64, best, 1.0, per_mb, rows, misc=misc, tiles={1: best, 2: tile2})
+    orows = [dict(rows[0], dense=best), dict(rows[1], dense=tile2)]
+    for bounds in ([0, 32, 64], [0, 16, 64], [0, 16, 48, 64]):
+        for i in (0, 1):
+            got = nf.nf_simulate_pipeline(MODEL, host_batch(b), bounds, True, i, path)
+            ref = pm.makespan(best, g, 1.0, per_mb, pre, start, bounds, True, orows[i], dt=0.005, misc=misc)
+            assert got == pytest.approx(ref, rel=2e-3, abs=0.1), (bounds, i)
+    seq = nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 64], False, -1, path)
+    assert seq == pytest.approx(pm.makespan(best, g, 1.0, per_mb, pre, start, [0, 64], False, None, misc=misc), rel=1e-9)
+    got = nf.nf_search_pipeline(MODEL, host_batch(b), path, 3, g)
+    (best_t, best_b, best_row), unsplit = pm.brute_force(best, g, 1.0, per_mb, pre, start, 64, orows, 3, dt=0.005,
+                                                         misc=misc)
+    assert got["est_us"] == pytest.approx(best_t, rel=2e-3, abs=0.2)
+    if got["overlap"]:
+        assert got["gemm_tile"] == best_row["gemm_tile"]
 
 
 def test_search_never_returns_a_pipeline_slower_than_unsplit(tmp_path):
