@@ -36,11 +36,23 @@ struct PageRegs {
 // scalar-base + 32-bit lane offset form; a lane reads 16 bytes of one key per K step
 // (the 4 lanes of a key cover 64 contiguous bytes) and 8 bytes (4 keys of one
 // dimension) per V block (the wavefront covers 512 contiguous bytes).
-template <int DH, bool NT = false>
+template <int DH, bool NT = false, bool COAL = false>
 __device__ __forceinline__ void load_page(PageRegs<DH>& r, const char* __restrict__ page_base, uint32_t v_block_off,
                                           uint32_t koff, uint32_t voff) {
   const char* vb = page_base + v_block_off;
-  if (NT) {  // streaming hint: the KV cache is read once per iteration
+  if (COAL) {
+    // timing-only ablation: the same bytes fetched as fully coalesced 1 KiB wavefront loads
+    const uint32_t lo = (threadIdx.x & 63) * 16;
+#pragma unroll
+    for (int s = 0; s < DH / 32; ++s)
+      r.k[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(page_base + lo + s * 1024));
+#pragma unroll
+    for (int b2 = 0; b2 < DH / 32; ++b2) {
+      const bf16x8 t = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(vb + lo + b2 * 1024));
+      r.v[2 * b2] = __builtin_bit_cast(s16x4, (bf16x4){t[0], t[1], t[2], t[3]});
+      r.v[2 * b2 + 1] = __builtin_bit_cast(s16x4, (bf16x4){t[4], t[5], t[6], t[7]});
+    }
+  } else if (NT) {  // streaming hint: the KV cache is read once per iteration
 #pragma unroll
     for (int s = 0; s < DH / 32; ++s)
       r.k[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(page_base + koff + s * 64));
@@ -112,7 +124,7 @@ __device__ __forceinline__ void attend_page(AttnState<DH>& st, PageRegs<DH>& pg,
     st.o[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pg.v[b], pf, st.o[b], 0, 0, 0);
 }
 
-template <int DH, int NBUF, int WAVES_PER_SIMD, bool NT = false>
+template <int DH, int NBUF, int WAVES_PER_SIMD, bool NT = false, bool COAL = false>
 __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf16_t* __restrict__ qkv,
                                                         const bf16_t* __restrict__ pages,
                                                         const int32_t* __restrict__ page_indptr,
@@ -178,13 +190,13 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   PageRegs<DH> buf[NBUF];
 #pragma unroll
   for (int j = 0; j < NBUF; ++j)
-    if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+    if (j < n_pages) load_page<DH, NT, COAL>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
   for (int i = 0; i < n_pages; i += NBUF) {
 #pragma unroll
     for (int j = 0; j < NBUF; ++j) {
       if (i + j < n_pages) {
         attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
-        if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+        if (i + j + NBUF < n_pages) load_page<DH, NT, COAL>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
       }
     }
   }
@@ -247,8 +259,8 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
                                       const int32_t* page_indptr, const int32_t* page_ids, const NfAttnItem* items,
                                       int n_work, int head_groups, const NfAttnShape& shp, float scale_log2,
                                       float* parts) {
-#define NF_ATTN_LAUNCH(NB, W, NT)                                                                                  \
-  attention_kernel<DH, NB, W, NT><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
+#define NF_ATTN_LAUNCH(NB, W, NT, ...)                                                                             \
+  attention_kernel<DH, NB, W, NT, ##__VA_ARGS__><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
                                                          head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,     \
                                                          scale_log2, parts)
   switch (variant) {
@@ -260,6 +272,8 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
     case 5: NF_ATTN_LAUNCH(2, 3, true); break;
     case 6: NF_ATTN_LAUNCH(4, 2, true); break;
     case 7: NF_ATTN_LAUNCH(5, 2, true); break;
+    case 8: NF_ATTN_LAUNCH(2, 3, true, true); break;  // timing-only: coalesced loads
+    case 9: NF_ATTN_LAUNCH(3, 2, true, true); break;
     default: return hipErrorInvalidValue;
   }
 #undef NF_ATTN_LAUNCH

@@ -10,40 +10,14 @@
 //
 // The K loop order and the MFMA instruction are the same for every M, so an output row
 // is bit-identical no matter which token range (nano-batch) it was computed in.
-#include "nf_device.h"
+#include "gemm_common.h"
 #include "nf_kernels.h"
 
 namespace {
 
-constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row: 144 B keeps ds_read_b128 conflict-free
-
-enum { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
-
-// Workgroup index -> tile index so that the tiles one XCD works on are consecutive
-// (workgroups are dealt round-robin to the 8 XCDs; each XCD has its own L2).
-__device__ __forceinline__ int xcd_remap(int b, int nblocks) {
-  const int q = nblocks >> 3, r = nblocks & 7;
-  const int xcd = b & 7, idx = b >> 3;
-  return xcd * q + (xcd < r ? xcd : r) + idx;
-}
-
-__device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
+using namespace nfgemm;
 
 // BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
-// Grouped mode (mixture-of-experts FFN as a grouped GEMM): the M rows are the routed
-// (token, expert) pairs sorted by expert; expert e owns rows [expert_offset[e],
-// expert_offset[e+1]) and multiplies them with its own weight W + e * w_stride.  The row
-// counts live on the device, so the grid covers the worst case and a workgroup whose
-// M-tile index is past the last expert's tiles exits.  row_index (optional) gathers the
-// input rows; outputs are written at the sorted row position.
-struct GroupedArgs {
-  const int32_t* expert_offset;
-  const int32_t* row_index;
-  int n_experts;
-  long long w_stride;
-};
-
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int PF, bool GROUPED, int DBG = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WAVES_M * WAVES_N) / 4 : 2) void gemm_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
@@ -56,26 +30,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WA
   __shared__ __attribute__((aligned(16))) bf16_t sX[2][BM * LDS_STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t sW[2][BN * LDS_STRIDE];
 
-  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tm = tile % tiles_m, tn = tile / tiles_m;
-  int m0 = tm * BM;
-  const int n0 = tn * BN;  // first output column of this tile
-  if (GROUPED) {
-    int acc_tiles = 0, found = 0;
-    for (int e = 0; e < grp.n_experts; ++e) {
-      const int lo = grp.expert_offset[e], hi = grp.expert_offset[e + 1];
-      const int nt = (hi - lo + BM - 1) / BM;
-      if (tm < acc_tiles + nt) {
-        m0 = lo + (tm - acc_tiles) * BM;
-        M = hi;  // this expert's rows end here
-        W += (size_t)e * (size_t)grp.w_stride;
-        found = 1;
-        break;
-      }
-      acc_tiles += nt;
-    }
-    if (!found) return;  // uniform for the whole workgroup, before any barrier
-  }
+  int m0, n0;
+  size_t w_off;
+  if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
+  W += w_off;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
@@ -95,15 +53,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WA
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
     const int q = i * NT + tid, row = q >> 3, c = q & 7;
-    int gn;
-    if (EPI == EPI_SWIGLU) {
-      // tile rows alternate in 32-row groups: gate rows of 32 output columns, then their up rows
-      const int grp = row >> 5, within = row & 31;
-      const int col = (n0 >> 1) + (grp >> 1) * 32 + within;  // output column (N = ffn inner)
-      gn = (grp & 1) * N + col;
-    } else {
-      gn = n0 + row;
-    }
+    const int gn = weight_row<EPI>(row, n0, N);
     wg[i] = W + (size_t)gn * K + c * 8;
     ws[i] = row * LDS_STRIDE + c * 8;
   }
@@ -186,49 +136,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WA
     }
   }
 
-  // Epilogue.  acc[i][j][v]: token row m = m0 + wm*WM + j*32 + (lane & 31);
-  // tile column c = wn*WN + i*32 + 8*(v/4) + 4*(lane >> 5) + (v & 3).
-  const int col4 = 4 * (lane >> 5);
-#pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wm * WM + j * 32 + (lane & 31);
-    if (m >= M) continue;
-    if (EPI == EPI_SWIGLU) {
-      // 32-column groups come in (gate, up) pairs: acc[2p] is gate, acc[2p+1] is up
-#pragma unroll
-      for (int p = 0; p < TN / 2; ++p) {
-        const int ocol0 = (n0 >> 1) + (wn * (TN / 2) + p) * 32;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float o[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = silu_f(acc[2 * p][j][q * 4 + e]) * acc[2 * p + 1][j][q * 4 + e];
-          u32x2 pk = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
-          *reinterpret_cast<u32x2*>(Y + (size_t)m * N + ocol0 + q * 8 + col4) = pk;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const size_t off = (size_t)m * N + n0 + wn * WN + i * 32 + q * 8 + col4;
-          float o[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][q * 4 + e];
-          if (EPI == EPI_RESIDUAL) {
-            const u32x2 r = *reinterpret_cast<const u32x2*>(R + off);
-            o[0] += __uint_as_float(r[0] << 16);
-            o[1] += __uint_as_float(r[0] & 0xffff0000u);
-            o[2] += __uint_as_float(r[1] << 16);
-            o[3] += __uint_as_float(r[1] & 0xffff0000u);
-          }
-          u32x2 pk = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
-          *reinterpret_cast<u32x2*>(Y + off) = pk;
-        }
-      }
-    }
-  }
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int PF, bool GROUPED = false>
@@ -260,7 +168,8 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 }  // namespace
 
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
-// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads).  Every variant walks K in the
+// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..10 = the direct-to-LDS
+// kernels of gemm_dl.hip.  Every variant walks K in the
 // same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
@@ -292,6 +201,10 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
   }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) tile = 1;
+  if (tile >= 7 && tile <= 10) {
+    if (tile == 10 && n_eff % 256 != 0) tile = 9;
+    return nf_launch_gemm_dl(x, w, out, residual, M, N, K, epilogue, tile, s);
+  }
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;
   switch (tile) {
     case 2: return launch<256, 128, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);

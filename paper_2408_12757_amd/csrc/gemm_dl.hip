@@ -1,0 +1,179 @@
+// Dense operations with direct global -> LDS loads (global_load_lds_dwordx4 on gfx950).
+//
+// Same contract and the same arithmetic as gemm.hip (v_mfma_f32_32x32x16_bf16, K walked in
+// steps of 64 in ascending order, transposed product, shared epilogues), hence the same
+// output bits.  What differs is how the x and w tiles reach LDS: each wavefront instruction
+// moves 64 x 16 bytes from global memory straight into 1 KiB of LDS (the destination is
+// wave-uniform base + 16 * lane), so no VGPR holds data in flight, there is no ds_write
+// burst before the barrier, and an LDS ring of STAGES tiles keeps STAGES - 1 K-steps of
+// loads in flight.
+//
+// LDS layout: a tile row is 128 contiguous bytes (8 chunks of 16 bytes), rows are not padded
+// (a wavefront instruction fills 8 whole rows); bank conflicts are avoided by storing global
+// chunk c of row r in slot c ^ (r & 7) - the lane picks its global address accordingly - and
+// reading fragments through the same XOR.
+#include "gemm_common.h"
+#include "nf_kernels.h"
+
+namespace {
+
+using namespace nfgemm;
+
+typedef const void __attribute__((address_space(1))) * gptr_t;
+typedef void __attribute__((address_space(3))) * lptr_t;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  if (N == 0)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
+  constexpr int NW = WAVES_M * WAVES_N;              // wavefronts per workgroup
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
+  constexpr int TM = WM / 32, TN = WN / 32;          // 32x32 MFMA tiles per wavefront
+  constexpr int ROWS = BM + BN;                      // tile rows per stage: x rows, then w rows
+  constexpr int LOADS = ROWS / 8 / NW;               // wavefront load instructions per stage
+  constexpr int STAGE_BYTES = ROWS * 128;
+  static_assert(ROWS % (8 * NW) == 0, "rows must split evenly over the wavefronts");
+  static_assert(STAGES >= 2 && STAGES <= 4, "LDS ring depth");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  int m0, n0;
+  size_t w_off;
+  if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
+  W += w_off;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+  // Loader: instruction i of this wavefront fills LDS rows (i*NW + wave)*8 .. +8 of the stage;
+  // this lane supplies row +lane/8, slot lane%8, i.e. global chunk (lane%8) ^ (row & 7).
+  const bf16_t* src[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int row = (i * NW + wave) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ (row & 7);
+    if (row < BM) {
+      int gm = m0 + row;
+      gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+      if (GROUPED && grp.row_index) gm = grp.row_index[gm];
+      src[i] = X + (size_t)gm * K + chunk * 8;
+    } else {
+      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * K + chunk * 8;
+    }
+  }
+  auto issue_stage = [&](int stage, int kt) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BK),
+                                       (lptr_t)(lds + stage * STAGE_BYTES + (i * NW + wave) * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int KT = K / BK;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < KT) issue_stage(s, s);
+
+  // fragment addressing: row = wave tile base + i*32 + (lane & 31); the k-chunk of slice kk is
+  // 2*kk + (lane >> 5), found in slot chunk ^ (row & 7); wave tile bases are multiples of 32
+  const int frag_row = lane & 31, swz = lane & 7, g = lane >> 5;
+  const int x_off = (wm * WM + frag_row) * 128;
+  const int w_off_lds = (BM + wn * WN + frag_row) * 128;
+
+  int stage = 0;
+  for (int kt = 0; kt < KT; ++kt) {
+    // tile kt has landed once at most (STAGES - 2) younger stages of loads are outstanding
+    if (kt + STAGES - 2 < KT)
+      wait_vmcnt<(STAGES - 2) * LOADS>();
+    else
+      wait_vmcnt<0>();
+    __syncthreads();  // every wavefront's part of tile kt is in LDS; stage (kt - 1) % STAGES is free
+    if (kt + STAGES - 1 < KT) {
+      int fill = stage + STAGES - 1;
+      if (fill >= STAGES) fill -= STAGES;
+      issue_stage(fill, kt + STAGES - 1);
+    }
+    const char* base = lds + stage * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int slot = ((2 * kk + g) ^ swz) * 16;
+      bf16x8 fw[TN], fx[TM];
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(base + w_off_lds + i * 32 * 128 + slot);
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fx[j] = *reinterpret_cast<const bf16x8*>(base + x_off + j * 32 * 128 + slot);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
+    }
+    if (++stage == STAGES) stage = 0;
+  }
+
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED>
+hipError_t launch_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
+                     hipStream_t s, GroupedArgs grp) {
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
+  const int tiles_n = epilogue == EPI_SWIGLU ? (2 * N) / BN : N / BN;
+  const dim3 grid(tiles_m * tiles_n), block(64 * WAVES_M * WAVES_N);
+  const size_t lds_bytes = (size_t)STAGES * (BM + BN) * 128;
+  const bf16_t* X = (const bf16_t*)x;
+  const bf16_t* Wp = (const bf16_t*)w;
+  bf16_t* Y = (bf16_t*)out;
+  const bf16_t* R = (const bf16_t*)residual;
+#define NF_DL_LAUNCH(E)                                                                                            \
+  do {                                                                                                             \
+    auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, E, STAGES, GROUPED>;                                      \
+    static bool attr_set = false;                                                                                  \
+    if (lds_bytes > 64 * 1024 && !attr_set) {                                                                      \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,            \
+                                         (int)lds_bytes);                                                          \
+      if (e != hipSuccess) return e;                                                                               \
+      attr_set = true;                                                                                             \
+    }                                                                                                              \
+    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp);                              \
+  } while (0)
+  switch (epilogue) {
+    case EPI_NONE: NF_DL_LAUNCH(EPI_NONE); break;
+    case EPI_RESIDUAL: NF_DL_LAUNCH(EPI_RESIDUAL); break;
+    default: NF_DL_LAUNCH(EPI_SWIGLU); break;
+  }
+#undef NF_DL_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Variants: 7 = 128x128 tile, 4 wavefronts, 2 stages (two workgroups per CU);
+//           8 = 128x128, 4 wavefronts, 4 stages (one workgroup per CU);
+//           9 = 256x128, 8 wavefronts, 3 stages; 10 = 256x256, 8 wavefronts, 2 stages.
+// Requires K % 64 == 0 and the (stacked) N % 128 == 0 (% 256 for variant 10).
+hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                             int epilogue, int variant, hipStream_t s) {
+  const GroupedArgs none{nullptr, nullptr, 0, 0};
+  switch (variant) {
+    case 7: return launch_dl<128, 128, 2, 2, 2, false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 8: return launch_dl<128, 128, 2, 2, 4, false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 9: return launch_dl<256, 128, 4, 2, 3, false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 10: return launch_dl<256, 256, 2, 4, 2, false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    default: return hipErrorInvalidValue;
+  }
+}

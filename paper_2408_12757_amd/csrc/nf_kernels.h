@@ -61,3 +61,5 @@ hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int t
 hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
                                  void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s);
 void nf_set_gemm_debug(int v);
+hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                             int epilogue, int variant, hipStream_t s);
