@@ -75,11 +75,14 @@ typedef struct nf_layer_weights {
 
 /*
  * Paged KV cache of this layer (Sec. 4.2.2: pages are scattered in device
- * memory).  One page holds page_size = 16 tokens:
- *   pages[p][0][h] = K block of kv head h, [16 tokens][dh]   (token-major)
- *   pages[p][1][h] = V block of kv head h, [dh][16 tokens]   (dimension-major)
- * i.e. bf16 [num_pages][2][Hkv][16*dh].  The dimension-major V block lets the
- * attention kernel feed V to the matrix cores without a transpose.
+ * memory).  One page holds page_size = 16 tokens and is bf16 [2][Hkv][16*dh]:
+ * pages[p][0][h] is the K block and pages[p][1][h] the V block of kv head h.
+ * Inside a block the 16 x dh elements are stored in the order the matrix cores
+ * consume them, so that the attention kernel reads every block with fully
+ * coalesced 1 KiB wavefront loads and no transpose:
+ *   K block: [dh/8][16 tokens][8]            element (t, d) at ((d/8)*16 + t)*8 + d%8
+ *   V block: [dh/32][16][4][2][4]            element (t, d) at
+ *            ((((d/32)*16 + d%16)*4 + t/4)*2 + (d/16)%2)*4 + t%4
  * nf_layer_forward WRITES the K/V of the batch's tokens into their slots.
  */
 typedef struct nf_kv_cache {

@@ -32,10 +32,11 @@ notes of the repository):
   * MoE feed-forward (Sec. 4.1.4): router logits W_r.h, the top_k largest
     logits (ties to the lower expert index), softmax over the selected
     logits, weighted sum of the selected experts' SwiGLU outputs;
-  * KV pages hold page_size tokens; a page stores, for every kv head, a K block
-    [page_size, head_dim] (token-major) followed by the V blocks
-    [head_dim, page_size] (dimension-major): pages[p, 0, h] is K, pages[p, 1, h]
-    is V.
+  * KV pages hold page_size = 16 tokens; pages[p, 0, h] is the K block and
+    pages[p, 1, h] the V block of kv head h.  The paper gives no layout; the one
+    read here is the library's interface: K block [dh/8][16 tokens][8], V block
+    [dh/32][16][4][2][4] with element (t, d) at index
+    ((((d//32)*16 + d%16)*4 + t//4)*2 + (d//16)%2)*4 + t%4  (see unpack_page_blocks).
 
 Inputs are bf16 bit patterns (uint16) or float arrays; every bf16 value is
 widened exactly and all arithmetic is float64.  Values produced in this
@@ -158,6 +159,18 @@ def moe_ffn(h, w_router, w_gate_up, w_down, top_k, expert_choice=None):
 # paged KV cache access
 # ----------------------------------------------------------------------------
 
+def unpack_page_blocks(kblk, vblk, head_dim: int, page_size: int):
+    """K and V of one page and kv head as [page_size, head_dim] arrays.
+
+    kblk: [head_dim/8, 16, 8]          kblk[c, t, e]       = K[t, 8c + e]
+    vblk: [head_dim/32, 16, 4, 2, 4]   vblk[q, c, g, h, j] = V[4g + j, 32q + 16h + c]
+    """
+    assert page_size == 16
+    K = kblk.reshape(head_dim // 8, 16, 8).transpose(1, 0, 2).reshape(16, head_dim)
+    V = vblk.reshape(head_dim // 32, 16, 4, 2, 4).transpose(2, 4, 0, 3, 1).reshape(16, head_dim)
+    return K, V
+
+
 def gather_kv(pages, page_list, n_tokens: int, n_kv_heads: int, head_dim: int, page_size: int):
     """Read the first n_tokens cached tokens of a request from its pages.
 
@@ -168,11 +181,11 @@ def gather_kv(pages, page_list, n_tokens: int, n_kv_heads: int, head_dim: int, p
     V = np.zeros((n_tokens, n_kv_heads, head_dim))
     for pi in range((n_tokens + page_size - 1) // page_size):
         page = widen(pages[page_list[pi]]).reshape(2, n_kv_heads, page_size * head_dim)
-        for slot in range(min(page_size, n_tokens - pi * page_size)):
-            j = pi * page_size + slot
-            for h in range(n_kv_heads):
-                K[j, h] = page[0, h].reshape(page_size, head_dim)[slot]
-                V[j, h] = page[1, h].reshape(head_dim, page_size)[:, slot]
+        n_here = min(page_size, n_tokens - pi * page_size)
+        for h in range(n_kv_heads):
+            Kp, Vp = unpack_page_blocks(page[0, h], page[1, h], head_dim, page_size)
+            K[pi * page_size: pi * page_size + n_here, h] = Kp[:n_here]
+            V[pi * page_size: pi * page_size + n_here, h] = Vp[:n_here]
     return K, V
 
 

@@ -107,7 +107,7 @@ extern "C" int nf_ctx_mask_stream(nf_ctx* ctx, const uint32_t* mask, int words, 
 extern "C" int nf_tune_set(const char* key, int value) {
   if (!key) return NF_EINVAL;
   if (!strcmp(key, "attention.variant")) {
-    if (value < 0 || value > 9) return NF_EINVAL;
+    if (value < 0 || value > 7) return NF_EINVAL;
     nf_set_attention_variant(value);
     return NF_OK;
   }
@@ -117,7 +117,7 @@ extern "C" int nf_tune_set(const char* key, int value) {
     return NF_OK;
   }
   if (!strcmp(key, "gemm.tile")) {
-    if (value < 0 || value > 10) return NF_EINVAL;
+    if (value < 0 || value > 14) return NF_EINVAL;
     nf_set_gemm_tile(value);
     return NF_OK;
   }

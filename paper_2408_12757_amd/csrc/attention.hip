@@ -14,11 +14,11 @@
 // Matrix-core mapping (all wave64, 16 query rows padded with zeros):
 //   S^T[16 keys x 16 rows]  = K_page[16 x dh] . Q^T[dh x 16]   v_mfma_f32_16x16x32_bf16, dh/32 steps
 //   O^T[dh x 16 rows]      += V_page^T[dh x 16 keys] . P^T      v_mfma_f32_16x16x16_bf16, dh/16 blocks
-// The K block of a page is token-major, so a lane reads 16 contiguous bytes of one key;
-// the V block is dimension-major, so a lane reads 8 contiguous bytes (4 keys of one
-// dimension) - both straight from global memory into MFMA operand registers.  The
-// accumulator layout of S^T (lane = row, 4 consecutive keys) is exactly the B-operand
-// layout the second product needs, so P never leaves registers.
+// The K and V blocks of a page are stored in MFMA operand order, so every wavefront load is
+// 1 KiB of contiguous memory that lands straight in operand registers: K as [dh/8 chunks]
+// [16 keys][8], V as [dh/32][16 dims][4 key groups][2 blocks][4 keys].  The accumulator
+// layout of S^T (lane = row, 4 consecutive keys) is exactly the B-operand layout the second
+// product needs, so P never leaves registers.
 #include <math.h>
 
 #include "nf_device.h"
@@ -36,34 +36,26 @@ struct PageRegs {
 // scalar-base + 32-bit lane offset form; a lane reads 16 bytes of one key per K step
 // (the 4 lanes of a key cover 64 contiguous bytes) and 8 bytes (4 keys of one
 // dimension) per V block (the wavefront covers 512 contiguous bytes).
-template <int DH, bool NT = false, bool COAL = false>
+// Issues the loads of one page.  `page_base` is wave-uniform, so the loads take the
+// scalar-base + 32-bit lane offset form.  The page blocks are stored in MFMA operand order
+// (see the layout note in the C header), so every wavefront instruction reads 1 KiB of
+// contiguous memory: K step s is lanes x 16 bytes at s * 1024; V pair q (blocks 2q, 2q+1)
+// is lanes x 16 bytes at q * 1024.
+template <int DH, bool NT = false>
 __device__ __forceinline__ void load_page(PageRegs<DH>& r, const char* __restrict__ page_base, uint32_t v_block_off,
                                           uint32_t koff, uint32_t voff) {
   const char* vb = page_base + v_block_off;
-  if (COAL) {
-    // timing-only ablation: the same bytes fetched as fully coalesced 1 KiB wavefront loads
-    const uint32_t lo = (threadIdx.x & 63) * 16;
 #pragma unroll
-    for (int s = 0; s < DH / 32; ++s)
-      r.k[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(page_base + lo + s * 1024));
+  for (int s = 0; s < DH / 32; ++s) {
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(page_base + koff + s * 1024);
+    r.k[s] = NT ? __builtin_nontemporal_load(p) : *p;  // NT: streaming hint, the cache is read once
+  }
 #pragma unroll
-    for (int b2 = 0; b2 < DH / 32; ++b2) {
-      const bf16x8 t = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(vb + lo + b2 * 1024));
-      r.v[2 * b2] = __builtin_bit_cast(s16x4, (bf16x4){t[0], t[1], t[2], t[3]});
-      r.v[2 * b2 + 1] = __builtin_bit_cast(s16x4, (bf16x4){t[4], t[5], t[6], t[7]});
-    }
-  } else if (NT) {  // streaming hint: the KV cache is read once per iteration
-#pragma unroll
-    for (int s = 0; s < DH / 32; ++s)
-      r.k[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(page_base + koff + s * 64));
-#pragma unroll
-    for (int b = 0; b < DH / 16; ++b)
-      r.v[b] = __builtin_nontemporal_load(reinterpret_cast<const s16x4*>(vb + voff + b * 512));
-  } else {
-#pragma unroll
-    for (int s = 0; s < DH / 32; ++s) r.k[s] = *reinterpret_cast<const bf16x8*>(page_base + koff + s * 64);
-#pragma unroll
-    for (int b = 0; b < DH / 16; ++b) r.v[b] = *reinterpret_cast<const s16x4*>(vb + voff + b * 512);
+  for (int q = 0; q < DH / 32; ++q) {
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(vb + voff + q * 1024);
+    const bf16x8 t = NT ? __builtin_nontemporal_load(p) : *p;
+    r.v[2 * q] = __builtin_bit_cast(s16x4, (bf16x4){t[0], t[1], t[2], t[3]});
+    r.v[2 * q + 1] = __builtin_bit_cast(s16x4, (bf16x4){t[4], t[5], t[6], t[7]});
   }
 }
 
@@ -124,7 +116,7 @@ __device__ __forceinline__ void attend_page(AttnState<DH>& st, PageRegs<DH>& pg,
     st.o[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pg.v[b], pf, st.o[b], 0, 0, 0);
 }
 
-template <int DH, int NBUF, int WAVES_PER_SIMD, bool NT = false, bool COAL = false>
+template <int DH, int NBUF, int WAVES_PER_SIMD, bool NT = false>
 __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf16_t* __restrict__ qkv,
                                                         const bf16_t* __restrict__ pages,
                                                         const int32_t* __restrict__ page_indptr,
@@ -181,8 +173,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   const size_t page_bytes = 2 * (size_t)Hkv * blk_bytes;
   const uint32_t v_block_off = (uint32_t)((size_t)Hkv * blk_bytes);
   const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
-  const uint32_t koff = (uint32_t)((c * DH + g * 8) * 2);
-  const uint32_t voff = (uint32_t)((c * 16 + 4 * g) * 2);
+  const uint32_t koff = (uint32_t)(lane * 16);         // K: [dh/8 chunks][16 keys][8]; chunk 4s+g, key c
+  const uint32_t voff = (uint32_t)((c * 4 + g) * 16);  // V: [dh/32][16 c][4 g][2][4 keys]
 #define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)__builtin_amdgcn_readlane(ids, (i)) * page_bytes)
 
   // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
@@ -190,13 +182,13 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   PageRegs<DH> buf[NBUF];
 #pragma unroll
   for (int j = 0; j < NBUF; ++j)
-    if (j < n_pages) load_page<DH, NT, COAL>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+    if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
   for (int i = 0; i < n_pages; i += NBUF) {
 #pragma unroll
     for (int j = 0; j < NBUF; ++j) {
       if (i + j < n_pages) {
         attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
-        if (i + j + NBUF < n_pages) load_page<DH, NT, COAL>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+        if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
       }
     }
   }
@@ -259,8 +251,8 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
                                       const int32_t* page_indptr, const int32_t* page_ids, const NfAttnItem* items,
                                       int n_work, int head_groups, const NfAttnShape& shp, float scale_log2,
                                       float* parts) {
-#define NF_ATTN_LAUNCH(NB, W, NT, ...)                                                                             \
-  attention_kernel<DH, NB, W, NT, ##__VA_ARGS__><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
+#define NF_ATTN_LAUNCH(NB, W, NT)                                                                                  \
+  attention_kernel<DH, NB, W, NT><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
                                                          head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,     \
                                                          scale_log2, parts)
   switch (variant) {
@@ -272,8 +264,6 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
     case 5: NF_ATTN_LAUNCH(2, 3, true); break;
     case 6: NF_ATTN_LAUNCH(4, 2, true); break;
     case 7: NF_ATTN_LAUNCH(5, 2, true); break;
-    case 8: NF_ATTN_LAUNCH(2, 3, true, true); break;  // timing-only: coalesced loads
-    case 9: NF_ATTN_LAUNCH(3, 2, true, true); break;
     default: return hipErrorInvalidValue;
   }
 #undef NF_ATTN_LAUNCH

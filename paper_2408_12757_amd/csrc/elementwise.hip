@@ -52,8 +52,8 @@ hipError_t nf_launch_rmsnorm(const void* x, const void* g, void* out, int n_toke
 // ------------------------------------------------- rotary embedding + append ---
 // One workgroup per token.  The pair (i, i + dh/2) of every Q and K head is
 // rotated by pos * theta^(-2i/dh); the angle is formed in double so that large
-// positions lose no accuracy.  Q is rotated in place in the qkv buffer; K goes
-// to the token-major K block of its page slot, V to the dimension-major V block.
+// positions lose no accuracy.  Q is rotated in place in the qkv buffer; K and V go to
+// their page slot in the operand-ordered block layouts.
 __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ qkv, bf16_t* __restrict__ pages,
                                                           const int32_t* __restrict__ tok_req,
                                                           const int32_t* __restrict__ q_indptr,
@@ -90,15 +90,20 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
       hv[i] = ra;
       hv[i + half] = rb;
     } else {
-      bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh + slot * dh;
-      kb[i] = ra;
-      kb[i + half] = rb;
+      // K block [dh/8][16 keys][8]
+      bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh;
+      const int j = i + half;
+      kb[((i >> 3) * 16 + slot) * 8 + (i & 7)] = ra;
+      kb[((j >> 3) * 16 + slot) * 8 + (j & 7)] = rb;
     }
   }
   const bf16_t* vrow = row + (Hq + Hkv) * dh;
   for (int e = threadIdx.x; e < Hkv * dh; e += 256) {
     const int h = e / dh, d = e - h * dh;
-    vpage[(size_t)h * 16 * dh + d * 16 + slot] = vrow[e];
+    // V block [dh/32][16 c][4 g][2][4 keys]: dimension d = (2*quad + hb)*16 + c, key = 4*g + j
+    const int b = d >> 4, c = d & 15;
+    const int off = ((((b >> 1) * 16 + c) * 4 + (slot >> 2)) * 2 + (b & 1)) * 4 + (slot & 3);
+    vpage[(size_t)h * 16 * dh + off] = vrow[e];
   }
 }
 

@@ -201,8 +201,9 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
   }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) tile = 1;
-  if (tile >= 7 && tile <= 10) {
+  if (tile >= 7 && tile <= 14) {
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
+    if (tile == 13 && n_eff % 256 != 0) tile = 12;
     return nf_launch_gemm_dl(x, w, out, residual, M, N, K, epilogue, tile, s);
   }
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;

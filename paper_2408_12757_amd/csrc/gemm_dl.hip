@@ -30,7 +30,27 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED>
+// LDS fragment read the compiler does not see as a memory access: it then adds no wait of
+// its own for the LDS-DMA loads still in flight into OTHER stages of the ring (it cannot
+// tell the stages apart and would wait for all of them).  Completion is awaited explicitly.
+__device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Waits until at most N LDS operations of this wavefront are outstanding; the fragments are
+// passed through so that their uses are ordered after the wait.
+template <int N, int TN, int TM>
+__device__ __forceinline__ void wait_frags(bf16x8 (&fw)[TN], bf16x8 (&fx)[TM]) {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+#pragma unroll
+  for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fw[i]));
+#pragma unroll
+  for (int j = 0; j < TM; ++j) asm volatile("" : "+v"(fx[j]));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED, bool PIPE = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
@@ -95,6 +115,52 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
   const int w_off_lds = (BM + wn * WN + frag_row) * 128;
 
   int stage = 0;
+  if (PIPE) {
+    // Explicitly scheduled loop: bare barrier, explicit waits, fragments of K-slice kk + 1 read
+    // from LDS while the MFMAs of slice kk issue.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+    for (int kt = 0; kt < KT; ++kt) {
+      if (kt + STAGES - 2 < KT)
+        wait_vmcnt<(STAGES - 2) * LOADS>();
+      else
+        wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (kt + STAGES - 1 < KT) {
+        int fill = stage + STAGES - 1;
+        if (fill >= STAGES) fill -= STAGES;
+        issue_stage(fill, kt + STAGES - 1);
+      }
+      const uint32_t base = lds_base + stage * STAGE_BYTES;
+      bf16x8 fw[2][TN], fx[2][TM];
+      {
+        const uint32_t slot = ((uint32_t)(g ^ swz)) * 16;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) fw[0][i] = lds_read_frag(base + w_off_lds + i * 32 * 128 + slot);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) fx[0][j] = lds_read_frag(base + x_off + j * 32 * 128 + slot);
+      }
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const int cb = kk & 1, nb = cb ^ 1;
+        if (kk + 1 < BK / 16) {
+          const uint32_t slot = ((uint32_t)((2 * (kk + 1) + g) ^ swz)) * 16;
+#pragma unroll
+          for (int i = 0; i < TN; ++i) fw[nb][i] = lds_read_frag(base + w_off_lds + i * 32 * 128 + slot);
+#pragma unroll
+          for (int j = 0; j < TM; ++j) fx[nb][j] = lds_read_frag(base + x_off + j * 32 * 128 + slot);
+          wait_frags<TN + TM, TN, TM>(fw[cb], fx[cb]);  // slice kk has arrived; kk + 1 may be in flight
+        } else {
+          wait_frags<0, TN, TM>(fw[cb], fx[cb]);
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int j = 0; j < TM; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cb][i], fx[cb][j], acc[i][j], 0, 0, 0);
+      }
+      if (++stage == STAGES) stage = 0;
+    }
+  } else {
   for (int kt = 0; kt < KT; ++kt) {
     // tile kt has landed once at most (STAGES - 2) younger stages of loads are outstanding
     if (kt + STAGES - 2 < KT)
@@ -125,10 +191,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
     if (++stage == STAGES) stage = 0;
   }
 
+  }
+
   store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, bool PIPE = false>
 hipError_t launch_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
                      hipStream_t s, GroupedArgs grp) {
   const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
@@ -141,7 +209,7 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
   const bf16_t* R = (const bf16_t*)residual;
 #define NF_DL_LAUNCH(E)                                                                                            \
   do {                                                                                                             \
-    auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, E, STAGES, GROUPED>;                                      \
+    auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, E, STAGES, GROUPED, PIPE>;                                      \
     static bool attr_set = false;                                                                                  \
     if (lds_bytes > 64 * 1024 && !attr_set) {                                                                      \
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,            \
@@ -164,7 +232,8 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
 
 // Variants: 7 = 128x128 tile, 4 wavefronts, 2 stages (two workgroups per CU);
 //           8 = 128x128, 4 wavefronts, 4 stages (one workgroup per CU);
-//           9 = 256x128, 8 wavefronts, 3 stages; 10 = 256x256, 8 wavefronts, 2 stages.
+//           9 = 256x128, 8 wavefronts, 3 stages; 10 = 256x256, 8 wavefronts, 2 stages;
+//           11..14 = 7, 9, 10, 8 with the explicitly scheduled main loop.
 // Requires K % 64 == 0 and the (stacked) N % 128 == 0 (% 256 for variant 10).
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s) {
@@ -174,6 +243,10 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     case 8: return launch_dl<128, 128, 2, 2, 4, false>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 9: return launch_dl<256, 128, 4, 2, 3, false>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 10: return launch_dl<256, 256, 2, 4, 2, false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 11: return launch_dl<128, 128, 2, 2, 2, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 12: return launch_dl<256, 128, 4, 2, 3, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 13: return launch_dl<256, 256, 2, 4, 2, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 14: return launch_dl<128, 128, 2, 2, 4, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
     default: return hipErrorInvalidValue;
   }
 }

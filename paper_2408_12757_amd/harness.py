@@ -80,13 +80,14 @@ def read_kv_rows(pages_bits: np.ndarray, model: wl.ModelDesc, batch: wl.Batch, t
     tok_req = np.repeat(np.arange(batch.n_reqs), np.diff(batch.q_indptr))
     K = np.zeros((len(tokens), Hkv, dh), np.uint16)
     V = np.zeros((len(tokens), Hkv, dh), np.uint16)
+    kidx, vidx = wl.page_block_index(dh, P)
     for i, t in enumerate(tokens):
         r = int(tok_req[t])
         pos = int(batch.ctx_len[r]) + int(t - batch.q_indptr[r])
         page = int(batch.page_ids[int(batch.page_indptr[r]) + pos // P])
         slot = pos % P
-        K[i] = pg[page, 0].reshape(Hkv, P, dh)[:, slot, :]
-        V[i] = pg[page, 1].reshape(Hkv, dh, P)[:, :, slot]
+        K[i] = pg[page, 0][:, kidx[slot]]
+        V[i] = pg[page, 1][:, vidx[slot]]
     return K, V
 
 

@@ -260,6 +260,18 @@ def make_kv_pages_host(m: ModelDesc, num_pages: int, seed: int) -> np.ndarray:
     return _normal_bf16(np.random.default_rng(seed), (num_pages, m.page_elems), 1.0)
 
 
+def page_block_index(head_dim: int, page_size: int = PAGE_SIZE):
+    """Index maps of the page block layouts of the library's interface: kidx[t, d] and
+    vidx[t, d] give the position of element (token slot t, dimension d) inside the K block
+    ([dh/8][16][8]) and the V block ([dh/32][16][4][2][4]).  Data formatting only."""
+    assert page_size == 16
+    t = np.arange(page_size)[:, None]
+    d = np.arange(head_dim)[None, :]
+    kidx = ((d // 8) * 16 + t) * 8 + d % 8
+    vidx = ((((d // 32) * 16 + d % 16) * 4 + t // 4) * 2 + (d // 16) % 2) * 4 + t % 4
+    return kidx, vidx
+
+
 def subset_batch(b: Batch, reqs) -> "tuple[Batch, np.ndarray, np.ndarray]":
     """Restrict a batch to the listed requests (order kept as given).
 

@@ -73,11 +73,12 @@ def untouched_pages_equal(case: Case, pages_after: np.ndarray) -> bool:
     before = case.pages_bits.reshape(-1, 2, Hkv, P * dh).copy()
     after = pages_after.reshape(-1, 2, Hkv, P * dh).copy()
     tok_req = np.repeat(np.arange(b.n_reqs), np.diff(b.q_indptr))
+    kidx, vidx = wl.page_block_index(dh, P)
     for t in range(b.n_tokens):
         r = int(tok_req[t])
         pos = int(b.ctx_len[r]) + int(t - b.q_indptr[r])
         page, slot = int(b.page_ids[int(b.page_indptr[r]) + pos // P]), pos % P
         for arr in (before, after):
-            arr[page, 0].reshape(Hkv, P, dh)[:, slot, :] = 0
-            arr[page, 1].reshape(Hkv, dh, P)[:, :, slot] = 0
+            arr[page, 0][:, kidx[slot]] = 0
+            arr[page, 1][:, vidx[slot]] = 0
     return bool(np.array_equal(before, after))

@@ -17,7 +17,7 @@ from paper_2408_12757_amd import workloads as wl
 
 
 def small_model(**kw):
-    base = dict(hidden=32, n_q_heads=4, n_kv_heads=2, head_dim=8, ffn_inner=24, page_size=4,
+    base = dict(hidden=32, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn_inner=24, page_size=16,
                 rope_theta=1e4, rms_eps=1e-5)
     base.update(kw)
     return wl.ModelDesc(**base)
@@ -117,11 +117,12 @@ def write_rows_to_pages(m, pages, batch, r, k_rows, v_rows, start_pos=0):
     """Store K/V rows of request r at positions start_pos.. (append rule)."""
     P, Hkv, dh = m.page_size, m.n_kv_heads, m.head_dim
     pg = pages.reshape(pages.shape[0], 2, Hkv, P * dh)
+    kidx, vidx = wl.page_block_index(dh, P)
     for i in range(k_rows.shape[0]):
         page, slot = orc.kv_slot(batch, m, r, start_pos + i)
         for h in range(Hkv):
-            pg[page, 0, h].reshape(P, dh)[slot] = k_rows[i, h]
-            pg[page, 1, h].reshape(dh, P)[:, slot] = v_rows[i, h]
+            pg[page, 0, h][kidx[slot]] = k_rows[i, h]
+            pg[page, 1, h][vidx[slot]] = v_rows[i, h]
 
 
 def test_decode_equals_last_row_of_prefill():
@@ -213,7 +214,7 @@ def test_new_kv_rows_and_positions():
     # rotary embedding is the identity, so k_new is the plain K projection
     m = small_model()
     w = float_weights(m, 71)
-    b = mk_batch([3, 1], [0, 4], 1, m.page_size)
+    b = mk_batch([3, 1], [0, 20], 1, m.page_size)
     x = np.random.default_rng(72).standard_normal((b.n_tokens, m.hidden))
     pages = random_pages(m, b.num_pages, 73)
     z, k, v, parts = orc.layer_forward(m, w, pages, b, x, return_parts=True)
@@ -221,12 +222,12 @@ def test_new_kv_rows_and_positions():
     plain = parts["h"] @ w["w_qkv"].T
     np.testing.assert_allclose(k[0].ravel(), plain[0, Hq * dh:(Hq + Hkv) * dh], rtol=1e-12)
     np.testing.assert_allclose(v.reshape(b.n_tokens, -1), plain[:, (Hq + Hkv) * dh:], rtol=1e-12)
-    # decode token (row 3) sits at position 4: its K differs from the plain projection
-    # by a rotation of exactly 4 rad in the first pair of every head
+    # decode token (row 3) sits at position 20: its K differs from the plain projection
+    # by a rotation of exactly 20 rad in the first pair of every head
     kp = plain[3, Hq * dh:(Hq + Hkv) * dh].reshape(Hkv, dh)
     a, bb = kp[:, 0], kp[:, dh // 2]
-    np.testing.assert_allclose(k[3, :, 0], a * np.cos(4.0) - bb * np.sin(4.0), rtol=1e-12)
-    assert orc.kv_slot(b, m, 1, 4) == (int(b.page_ids[b.page_indptr[1] + 1]), 0)
+    np.testing.assert_allclose(k[3, :, 0], a * np.cos(20.0) - bb * np.sin(20.0), rtol=1e-11)
+    assert orc.kv_slot(b, m, 1, 20) == (int(b.page_ids[b.page_indptr[1] + 1]), 4)
 
 
 def test_moe_layer_identical_experts_equals_dense_layer():

@@ -244,24 +244,30 @@ def test_moe_selects_the_routed_expert_only():
 # ------------------------------------------------------------- paged read ---
 
 def test_gather_kv_layout():
-    # page block layout: K [slot, d] token-major, V [d, slot] dimension-major
-    Hkv, dh, P = 2, 4, 4
+    # The page block layouts, pinned element by element with the index formulas of the
+    # interface: K (t, d) at ((d//8)*16 + t)*8 + d%8;
+    # V (t, d) at ((((d//32)*16 + d%16)*4 + t//4)*2 + (d//16)%2)*4 + t%4.
+    Hkv, dh, P = 2, 64, 16
     n_pages = 3
     pages = np.zeros((n_pages, 2, Hkv, P * dh))
+    val = lambda p, h, t, d: 10000 * p + 1000 * h + 64 * t + d          # noqa: E731
     for p in range(n_pages):
         for h in range(Hkv):
-            for s in range(P):
+            for t in range(P):
                 for d in range(dh):
-                    pages[p, 0, h, s * dh + d] = 1000 * p + 100 * h + 10 * s + d          # K
-                    pages[p, 1, h, d * P + s] = -(1000 * p + 100 * h + 10 * s + d)       # V
-    K, V = orc.gather_kv(pages.reshape(n_pages, -1), [2, 0], 6, Hkv, dh, P)
-    assert K.shape == (6, Hkv, dh)
-    for j in range(6):
+                    pages[p, 0, h, ((d // 8) * 16 + t) * 8 + d % 8] = val(p, h, t, d)
+                    pages[p, 1, h, ((((d // 32) * 16 + d % 16) * 4 + t // 4) * 2 + (d // 16) % 2) * 4 + t % 4] = \
+                        -val(p, h, t, d)
+    # every position of a block is used exactly once
+    assert len(np.unique(pages[0, 0, 0])) == P * dh and len(np.unique(pages[0, 1, 0])) == P * dh
+    K, V = orc.gather_kv(pages.reshape(n_pages, -1), [2, 0], 21, Hkv, dh, P)
+    assert K.shape == (21, Hkv, dh)
+    for j in range(21):
         p = [2, 0][j // P]
         for h in range(Hkv):
             for d in range(dh):
-                assert K[j, h, d] == 1000 * p + 100 * h + 10 * (j % P) + d
-                assert V[j, h, d] == -K[j, h, d]
+                assert K[j, h, d] == val(p, h, j % P, d)
+                assert V[j, h, d] == -val(p, h, j % P, d)
 
 
 def test_widen_bf16_exact():
