@@ -200,7 +200,18 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     return launch_debug<3>(x, w, out, M, N, K, s);
   }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
-  if (tile == 0) tile = 1;
+  if (tile == 0) {
+    // No profile: pick the tile shape with the best (fill of the last round of workgroups on
+    // 256 CUs) x (measured relative speed of the shape): 256x256, 256x128, 128x128.
+    auto score = [&](int bm, int bn, double speed) {
+      if (n_eff % bn) return 0.0;
+      const long tiles = (long)((M + bm - 1) / bm) * (n_eff / bn);
+      const long rounds = (tiles + 255) / 256;
+      return speed * (double)tiles / (double)(rounds * 256);
+    };
+    const double s10 = score(256, 256, 1.0), s9 = score(256, 128, 0.95), s7 = score(128, 128, 0.87);
+    tile = (s10 >= s9 && s10 >= s7) ? 10 : (s9 >= s7 ? 9 : 7);
+  }
   if (tile >= 7 && tile <= 14) {
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
     if (tile == 13 && n_eff % 256 != 0) tile = 12;
