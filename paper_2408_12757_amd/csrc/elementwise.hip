@@ -117,3 +117,34 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
       n_kv_heads, head_dim, rope_theta);
   return hipGetLastError();
 }
+
+namespace {
+
+// Pseudo-random bf16 values, roughly normal with the given standard deviation: the sum of
+// the four bytes of a hashed counter.  Only for timing buffers: dense kernels on this chip
+// run measurably slower on varied data than on constant data, so profiling inputs must
+// look like activations and weights.
+__global__ __launch_bounds__(256) void fill_random_kernel(bf16_t* __restrict__ p, size_t n, uint32_t seed,
+                                                          float stddev) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    uint32_t h = (uint32_t)i * 0x9E3779B9u + (uint32_t)(i >> 32) + seed;
+    h ^= h >> 16;
+    h *= 0x7FEB352Du;
+    h ^= h >> 15;
+    h *= 0x846CA68Bu;
+    h ^= h >> 16;
+    const int sum = (int)(h & 255) + (int)((h >> 8) & 255) + (int)((h >> 16) & 255) + (int)(h >> 24);
+    p[i] = f2bf((float)(sum - 510) * (1.0f / 147.8f) * stddev);
+  }
+}
+
+}  // namespace
+
+hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float stddev, hipStream_t s) {
+  if (n_elems == 0) return hipSuccess;
+  const size_t want = (n_elems + 255) / 256;
+  fill_random_kernel<<<dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, s>>>((bf16_t*)p, n_elems, seed,
+                                                                                        stddev);
+  return hipGetLastError();
+}

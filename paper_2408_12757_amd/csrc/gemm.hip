@@ -10,6 +10,8 @@
 //
 // The K loop order and the MFMA instruction are the same for every M, so an output row
 // is bit-identical no matter which token range (nano-batch) it was computed in.
+#include <math.h>
+
 #include "gemm_common.h"
 #include "nf_kernels.h"
 
@@ -168,7 +170,7 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 }  // namespace
 
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
-// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..10 = the direct-to-LDS
+// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..14 = the direct-to-LDS
 // kernels of gemm_dl.hip.  Every variant walks K in the
 // same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
@@ -201,16 +203,18 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
   }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) {
-    // No profile: pick the tile shape with the best (fill of the last round of workgroups on
-    // 256 CUs) x (measured relative speed of the shape): 256x256, 256x128, 128x128.
+    // No profile: pick among 256x256, 256x128 and 128x128 by (relative speed of the shape on
+    // activation-like data) x sqrt(fill of the 256 CUs over whole rounds of workgroups).  The
+    // square root is empirical: the chip is power-limited on these kernels, and the busy CUs
+    // of a partly filled round run faster than those of a full one.
     auto score = [&](int bm, int bn, double speed) {
       if (n_eff % bn) return 0.0;
       const long tiles = (long)((M + bm - 1) / bm) * (n_eff / bn);
       const long rounds = (tiles + 255) / 256;
-      return speed * (double)tiles / (double)(rounds * 256);
+      return speed * sqrt((double)tiles / (double)(rounds * 256));
     };
-    const double s10 = score(256, 256, 1.0), s9 = score(256, 128, 0.95), s7 = score(128, 128, 0.87);
-    tile = (s10 >= s9 && s10 >= s7) ? 10 : (s9 >= s7 ? 9 : 7);
+    const double s13 = score(256, 256, 1.0), s12 = score(256, 128, 0.92), s7 = score(128, 128, 0.84);
+    tile = (s13 >= s12 && s13 >= s7) ? 13 : (s12 >= s7 ? 12 : 7);
   }
   if (tile >= 7 && tile <= 14) {
     if (tile == 10 && n_eff % 256 != 0) tile = 9;

@@ -48,6 +48,8 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
                                const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s);
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
+// Fills a bf16 buffer with pseudo-random, roughly normal values (timing buffers only).
+hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float stddev, hipStream_t s);
 void nf_set_attention_variant(int v);
 void nf_set_gemm_tile(int v);
 hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,

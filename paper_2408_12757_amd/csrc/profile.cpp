@@ -18,7 +18,7 @@ void nf_profile_free(nf_ctx* ctx) {
 
 namespace {
 
-constexpr int kTiles[] = {1, 2, 5, 6, 7, 9, 10};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
+constexpr int kTiles[] = {1, 6, 7, 9, 10, 11, 12, 13};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
 constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 512, 768};
 
 struct Scratch {
@@ -33,6 +33,16 @@ struct Scratch {
     if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
     ptrs.push_back(p);
     if (hipMemset(p, fill, bytes) != hipSuccess) return nullptr;
+    return p;
+  }
+  // bf16 buffer of pseudo-random values: dense-kernel speed depends on the data (constant
+  // inputs run up to 20 % faster than activations and weights do), so timing buffers are varied
+  void* get_random(size_t bytes, float stddev) {
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+    ptrs.push_back(p);
+    if (nf_launch_fill_random(p, bytes / 2, (uint32_t)ptrs.size() * 7919u, stddev, nullptr) != hipSuccess) return nullptr;
+    if (hipDeviceSynchronize() != hipSuccess) return nullptr;
     return p;
   }
 };
@@ -129,11 +139,11 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     max_out = std::max(max_out, Mmax * shp[o].N * 2);
     max_w = std::max(max_w, (size_t)shp[o].N * (shp[o].epi == NF_EPI_SWIGLU ? 2 : 1) * shp[o].K * 2);
   }
-  // 0x3c3c as bf16 is about 0.0115: finite inputs, timing does not depend on values
-  void* x = sc.get(max_in, 0x3c);
-  void* y = sc.get(max_out, 0x3c);
-  void* res = sc.get(max_out, 0x3c);
-  void* w[2] = {sc.get(max_w, 0x3c), sc.get(max_w, 0x3c)};  // alternate so weights are not cache-warm
+  void* x = sc.get_random(max_in, 1.0f);
+  void* y = sc.get(max_out, 0);
+  void* res = sc.get_random(max_out, 1.0f);
+  // alternate so weights are not cache-warm
+  void* w[2] = {sc.get_random(max_w, 0.02f), sc.get_random(max_w, 0.02f)};
   if (!x || !y || !res || !w[0] || !w[1]) {
     ctx->last_hip = (int)hipErrorOutOfMemory;
     return NF_EHIP;
@@ -169,7 +179,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
   const int n_req = std::max(16, std::min(max_tokens, 512));
   const size_t page_bytes = (size_t)2 * m->n_kv_heads * 16 * m->head_dim * 2;
   const int32_t nqkv = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
-  void* qkv = sc.get((size_t)n_req * nqkv * 2, 0x3c);
+  void* qkv = sc.get_random((size_t)n_req * nqkv * 2, 1.0f);
   void* aout = sc.get((size_t)n_req * m->n_q_heads * m->head_dim * 2, 0);
   if (!qkv || !aout) return NF_EHIP;
   const NfAttnShape ash{m->n_q_heads, m->n_kv_heads, m->head_dim, nqkv};
@@ -184,7 +194,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     rc = make_synth_batch(ctx, sc, n_req, ctx_tokens[v], &sb[v]);
     if (rc) break;
     if (v == 1) {
-      pool = sc.get((size_t)sb[1].num_pages * page_bytes, 0x3c);
+      pool = sc.get_random((size_t)sb[1].num_pages * page_bytes, 1.0f);
       if (!pool) return NF_EHIP;
     }
     const int32_t bounds[2] = {0, n_req};
@@ -253,7 +263,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
   if (!rc) {
     const int o = NF_DENSE_UG, M = (int)Mmax;
     const double g_best_ms = p->dense_us[o][steps - 1] / 1e3;
-    const int kPairTiles[] = {1, 6, 7, 9, 10};
+    const int kPairTiles[] = {6, 7, 9, 10, 12, 13};
     p->rp.clear();
     for (int tile : kPairTiles) {
       if (rc) break;

@@ -79,6 +79,37 @@ def test_gemm_kernel_swiglu(M, I, K):
     assert rel_err(f64(hz.bf16_bits(out)), ref) <= REL_TOL / 2
 
 
+@pytest.mark.parametrize("M,N,K,epi", [(300, 512, 256, "none"), (1100, 1024, 1408, "residual"), (257, 768, 512, "swiglu")])
+def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
+    """All tile shapes and both LDS feeding schemes walk K in the same order with the same
+    MFMA instruction, so the implementation choice (which the profile makes per operation
+    and batch size) must never change an output bit."""
+    say("gemm implementations", M, N, K, epi)
+    r = np.random.default_rng(M * 3 + N + K)
+    rows = 2 * N if epi == "swiglu" else N
+    xt = hz.bf16_tensor(wl.f32_to_bf16_bits(r.standard_normal((M, K)).astype(np.float32)), DEV)
+    wt = hz.bf16_tensor(wl.f32_to_bf16_bits(0.05 * r.standard_normal((rows, K)).astype(np.float32)), DEV)
+    rt = hz.bf16_tensor(wl.f32_to_bf16_bits(r.standard_normal((M, N)).astype(np.float32)), DEV)
+    code = {"none": nf.NF_EPI_NONE, "residual": nf.NF_EPI_RESIDUAL, "swiglu": nf.NF_EPI_SWIGLU}[epi]
+    res_ptr = rt.data_ptr() if epi == "residual" else None
+    outs = {}
+    try:
+        for tile in range(1, 15):
+            nf.nf_tune_set("gemm.tile", tile)
+            out = torch.full((M + 1, N), 7.0, dtype=torch.bfloat16, device=DEV)
+            nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), res_ptr, M, N, K, code)
+            torch.cuda.synchronize()
+            outs[tile] = hz.bf16_bits(out)
+    finally:
+        nf.nf_tune_set("gemm.tile", 0)
+    for tile, got in outs.items():
+        assert np.array_equal(got, outs[1]), f"implementation {tile} differs from implementation 1"
+    assert np.all(f64(outs[1])[M:] == 7.0)
+    nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), res_ptr, M, N, K, code)  # the default choice
+    torch.cuda.synchronize()
+    assert np.array_equal(hz.bf16_bits(out), outs[1])
+
+
 def test_gemm_rejects_bad_shapes():
     t = torch.zeros(64 * 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(nf.NfError) as e:
