@@ -123,91 +123,145 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
                                                         const int32_t* __restrict__ page_ids,
                                                         const NfAttnItem* __restrict__ items, int n_work,
                                                         int head_groups, int Hq, int Hkv, int n_qkv,
-                                                        float scale_log2, float* __restrict__ parts) {
+                                                        float scale_log2, float* __restrict__ parts,
+                                                        bf16_t* __restrict__ out) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = Hq / Hkv;
   const int c = lane & 15, g = lane >> 4;
-  // Persistent workgroups: workgroup b takes work units b, b + gridDim.x, ...  The list is
-  // sorted longest first, so every workgroup gets a similar mix.  There are no workgroup
-  // barriers: the four wavefronts (four kv heads of one item) run independently.
-  for (int work = blockIdx.x; work < n_work; work += gridDim.x) {
-  const int item_idx = work / head_groups;
-  const int kvh = (work % head_groups) * 4 + wave;
-  if (kvh >= Hkv) continue;
-  const NfAttnItem it = items[item_idx];
-  const int n_rows = it.n_tok * G;
+  const int stride = gridDim.x;
 
-  // Q^T operand: lane (row c, k-group g) holds Q[row c][(4s+g)*8 .. +8] for step s
-  bf16x8 qf[DH / 32];
-  {
+  // Descriptor of work unit `w` (clamped past the end: such a unit is fetched but never run).
+  auto item_of = [&](int w) { return items[(w < n_work ? w : n_work - 1) / head_groups]; };
+  // Operands that do not depend on the page data: the Q^T fragments (lane (row c, k-group g)
+  // holds Q[row c][(4s+g)*8 .. +8] for step s; rows past the item's are zero) and the physical
+  // ids of the item's pages.  The chunk spans at most 64 pages: lane i keeps the id of page
+  // p_begin + i, so the id of any page is one cross-lane read away and no page load waits on
+  // the page table.
+  auto load_operands = [&](const NfAttnItem& it, int list_base, int w, bf16x8 (&qf)[DH / 32], int& ids) {
+    int kvh = (w % head_groups) * 4 + wave;
+    kvh = kvh < Hkv ? kvh : Hkv - 1;
+    const int n_rows = it.n_tok * G;
     const int j = c / G, hg = c - j * G;
-    const bf16_t* qrow = qkv + (size_t)(it.tok0 + j) * n_qkv + (size_t)(kvh * G + hg) * DH;
+    const bf16_t* qrow = qkv + (size_t)(it.tok0 + (c < n_rows ? j : 0)) * n_qkv + (size_t)(kvh * G + hg) * DH;
 #pragma unroll
     for (int s = 0; s < DH / 32; ++s) {
-      if (c < n_rows) {
-        qf[s] = *reinterpret_cast<const bf16x8*>(qrow + (4 * s + g) * 8);
-      } else {
+      qf[s] = *reinterpret_cast<const bf16x8*>(qrow + (4 * s + g) * 8);
+      if (c >= n_rows) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[s][e] = (__bf16)0.0f;
       }
     }
-  }
-  // last key this lane's row may read (rows past n_rows read nothing)
-  const int lim = c < n_rows ? it.pos0 + c / G : -1;
+    const int p_begin = it.key_begin >> 4;
+    const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
+    ids = lane < n_pages ? page_ids[list_base + p_begin + lane] : 0;
+  };
 
-  AttnState<DH> st;
-#pragma unroll
-  for (int b = 0; b < DH / 16; ++b) st.o[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  st.m_run = -INFINITY;
-  st.l_run = 0.f;
-
-  // The chunk spans at most 64 pages: lane i keeps the physical id of page p_begin + i, so
-  // the id of any page is one cross-lane read away and no load waits on the page table.
-  const int p_begin = it.key_begin >> 4;
-  const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
-  const int32_t* plist = page_ids + page_indptr[it.req] + p_begin;
-  const int ids = lane < n_pages ? plist[lane] : 0;
+  // Persistent workgroups: workgroup b takes work units b, b + gridDim.x, ...  The list is
+  // sorted longest first, so every workgroup gets a similar mix.  There are no workgroup
+  // barriers: the four wavefronts (four kv heads of one item) run independently.
+  //
+  // The chain descriptor -> page-list base -> page ids / Q -> first page costs three memory
+  // round trips before a unit streams its first byte, and a wavefront runs tens of units.
+  // It is therefore software-pipelined over units: while unit k streams, the operands of
+  // unit k + 1 and the descriptor and page-list base of unit k + 2 are fetched.
+  int work = blockIdx.x;
+  NfAttnItem it = item_of(work);
+  int list_base = page_indptr[it.req];
+  NfAttnItem it1 = item_of(work + stride);
+  int list_base1 = page_indptr[it1.req];
+  bf16x8 qf[DH / 32];
+  int ids;
+  load_operands(it, list_base, work, qf, ids);
 
   const size_t blk_bytes = (size_t)16 * DH * 2;
   const size_t page_bytes = 2 * (size_t)Hkv * blk_bytes;
   const uint32_t v_block_off = (uint32_t)((size_t)Hkv * blk_bytes);
-  const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
   const uint32_t koff = (uint32_t)(lane * 16);         // K: [dh/8 chunks][16 keys][8]; chunk 4s+g, key c
   const uint32_t voff = (uint32_t)((c * 4 + g) * 16);  // V: [dh/32][16 c][4 g][2][4 keys]
-#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)__builtin_amdgcn_readlane(ids, (i)) * page_bytes)
 
-  // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
-  // page has been consumed
-  PageRegs<DH> buf[NBUF];
+  for (;;) {
+    const int kvh = (work % head_groups) * 4 + wave;
+    const int work1 = work + stride;
+    bf16x8 qf1[DH / 32];
+    int ids1;
+    load_operands(it1, list_base1, work1, qf1, ids1);
+    const NfAttnItem it2 = item_of(work1 + stride);
+    int list_base2 = 0;
+
+    if (kvh < Hkv) {
+      const int n_rows = it.n_tok * G;
+      // last key this lane's row may read (rows past n_rows read nothing)
+      const int lim = c < n_rows ? it.pos0 + c / G : -1;
+      AttnState<DH> st;
 #pragma unroll
-  for (int j = 0; j < NBUF; ++j)
-    if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
-  for (int i = 0; i < n_pages; i += NBUF) {
+      for (int b = 0; b < DH / 16; ++b) st.o[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      st.m_run = -INFINITY;
+      st.l_run = 0.f;
+      const int p_begin = it.key_begin >> 4;
+      const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
+      const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
+#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)__builtin_amdgcn_readlane(ids, (i)) * page_bytes)
+      // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
+      // page has been consumed
+      PageRegs<DH> buf[NBUF];
 #pragma unroll
-    for (int j = 0; j < NBUF; ++j) {
-      if (i + j < n_pages) {
-        attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
-        if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+      for (int j = 0; j < NBUF; ++j)
+        if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+      for (int i = 0; i < n_pages; i += NBUF) {
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j) {
+          if (i + j < n_pages) {
+            attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
+            if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+          }
+        }
+        if (i == 0) list_base2 = page_indptr[it2.req];  // its descriptor has arrived by now
       }
-    }
-  }
 #undef NF_PAGE_BASE
 
-  // partial result: [16 rows][DH] floats, then m[16], l[16]
-  float l_run = st.l_run;
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
-  float* part = parts + ((size_t)it.part * Hkv + kvh) * (16 * DH + 32);
-  if (c < n_rows) {
+      float l_run = st.l_run;
+      l_run += __shfl_xor(l_run, 16, 64);
+      l_run += __shfl_xor(l_run, 32, 64);
+      if (it.part < 0) {
+        // the only chunk of its rows: normalise and write the attention output directly
+        if (c < n_rows) {
+          const int tok = it.tok0 + c / G, hq = kvh * G + (c % G);
+          bf16_t* orow = out + ((size_t)tok * Hq + hq) * DH + 4 * g;
 #pragma unroll
-    for (int b = 0; b < DH / 16; ++b) *reinterpret_cast<f32x4*>(part + c * DH + b * 16 + 4 * g) = st.o[b];
-    if (g == 0) {
-      part[16 * DH + c] = st.m_run;
-      part[16 * DH + 16 + c] = l_run;
+          for (int b = 0; b < DH / 16; ++b) {
+            u16x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = f2bf(st.o[b][i] / l_run);
+            *reinterpret_cast<u16x4*>(orow + b * 16) = v;
+          }
+        }
+      } else {
+        // partial result: [16 rows][DH] floats, then m[16], l[16]
+        float* part = parts + ((size_t)it.part * Hkv + kvh) * (16 * DH + 32);
+        if (c < n_rows) {
+#pragma unroll
+          for (int b = 0; b < DH / 16; ++b) *reinterpret_cast<f32x4*>(part + c * DH + b * 16 + 4 * g) = st.o[b];
+          if (g == 0) {
+            part[16 * DH + c] = st.m_run;
+            part[16 * DH + 16 + c] = l_run;
+          }
+        }
+      }
+    } else {
+      list_base2 = page_indptr[it2.req];
     }
+
+    if (work1 >= n_work) break;
+    work = work1;
+    it = it1;
+    list_base = list_base1;
+#pragma unroll
+    for (int s = 0; s < DH / 32; ++s) qf[s] = qf1[s];
+    ids = ids1;
+    it1 = it2;
+    list_base1 = list_base2;
   }
-  }  // work loop
 }
 
 // Merge the partial results of one row group in chunk order and write bf16 output.
@@ -250,11 +304,11 @@ template <int DH>
 static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* pages,
                                       const int32_t* page_indptr, const int32_t* page_ids, const NfAttnItem* items,
                                       int n_work, int head_groups, const NfAttnShape& shp, float scale_log2,
-                                      float* parts) {
+                                      float* parts, bf16_t* out) {
 #define NF_ATTN_LAUNCH(NB, W, NT)                                                                                  \
   attention_kernel<DH, NB, W, NT><<<grid, dim3(256), 0, s>>>(qkv, pages, page_indptr, page_ids, items, n_work,          \
                                                          head_groups, shp.n_q_heads, shp.n_kv_heads, shp.n_qkv,     \
-                                                         scale_log2, parts)
+                                                         scale_log2, parts, out)
   switch (variant) {
     case 0: NF_ATTN_LAUNCH(2, 3, false); break;
     case 1: NF_ATTN_LAUNCH(3, 2, false); break;
@@ -272,7 +326,8 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
 
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
-                               const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s) {
+                               const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
+                               hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
@@ -293,10 +348,10 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
   const dim3 grid((unsigned)wgs);
   if (shp.head_dim == 128)
     return launch_attention_dh<128>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
-                                    page_ids, items, n_work, head_groups, shp, scale_log2, parts);
+                                    page_ids, items, n_work, head_groups, shp, scale_log2, parts, (bf16_t*)attn_out);
   if (shp.head_dim == 64)
     return launch_attention_dh<64>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
-                                   page_ids, items, n_work, head_groups, shp, scale_log2, parts);
+                                   page_ids, items, n_work, head_groups, shp, scale_log2, parts, (bf16_t*)attn_out);
   return hipErrorInvalidValue;
 }
 

@@ -15,7 +15,8 @@ struct NfAttnItem {
   int32_t pos0;
   int32_t key_begin;
   int32_t key_end;
-  int32_t part;   // slot of the partial result in the workspace
+  int32_t part;   // slot of the partial result in the workspace; -1: the item covers all keys of
+                  // its rows and the kernel writes the final attention output itself
   int32_t pad;
 };
 
@@ -45,7 +46,8 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
                           int epilogue, int tile, hipStream_t s);
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
-                               const NfAttnShape& shp, float* parts, int max_workgroups, hipStream_t s);
+                               const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
+                               hipStream_t s);
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
 // Fills a bf16 buffer with pseudo-random, roughly normal values (timing buffers only).

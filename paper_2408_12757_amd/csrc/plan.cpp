@@ -189,7 +189,8 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
       const int pos0 = batch->host_ctx_len[r] + (t - q0);
       const int keys = pos0 + n_tok;
       const int n_parts = (keys + NF_ATTN_CHUNK - 1) / NF_ATTN_CHUNK;
-      groups.push_back(NfAttnGroup{t, n_tok, part, n_parts});
+      // rows whose keys fit one chunk need no merge: the attention kernel finishes them
+      if (n_parts > 1) groups.push_back(NfAttnGroup{t, n_tok, part, n_parts});
       for (int j = 0; j < n_parts; ++j) {
         NfAttnItem it;
         it.req = r;
@@ -198,11 +199,11 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
         it.pos0 = pos0;
         it.key_begin = j * NF_ATTN_CHUNK;
         it.key_end = std::min(keys, (j + 1) * NF_ATTN_CHUNK);
-        it.part = part + j;
+        it.part = n_parts > 1 ? part + j : -1;
         it.pad = 0;
         items.push_back(it);
       }
-      part += n_parts;
+      if (n_parts > 1) part += n_parts;
       t += n_tok;
     }
     p->item_cnt[i] = (int)items.size() - p->item_off[i];
