@@ -241,5 +241,10 @@ hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int r
   const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+  // the process-wide tuning override also selects the grouped implementation (1 = staged through registers)
+  const int tile = g_gemm_tile ? g_gemm_tile : 12;
+  if (tile == 7 || tile == 9 || tile == 11 || tile == 12)
+    return nf_launch_gemm_dl_grouped(x, w, out, rows, N, K, epilogue, expert_offset, row_index, n_experts, w_stride,
+                                     tile, s);
   return launch<128, 128, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
 }

@@ -254,3 +254,17 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     default: return hipErrorInvalidValue;
   }
 }
+
+// Grouped mode (see GroupedArgs): 7 / 11 = 128x128 tiles, 9 / 12 = 256x128 tiles.
+hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
+                                     const int32_t* expert_offset, const int32_t* row_index, int n_experts,
+                                     long long w_stride, int variant, hipStream_t s) {
+  const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
+  switch (variant) {
+    case 7: return launch_dl<128, 128, 2, 2, 2, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 9: return launch_dl<256, 128, 4, 2, 3, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 11: return launch_dl<128, 128, 2, 2, 2, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 12: return launch_dl<256, 128, 4, 2, 3, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    default: return hipErrorInvalidValue;
+  }
+}

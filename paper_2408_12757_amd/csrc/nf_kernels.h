@@ -57,6 +57,9 @@ void nf_set_gemm_tile(int v);
 hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                   const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                   long long w_stride, hipStream_t s);
+hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
+                                     const int32_t* expert_offset, const int32_t* row_index, int n_experts,
+                                     long long w_stride, int variant, hipStream_t s);
 // Mixture-of-experts helpers (moe.hip)
 hipError_t nf_launch_moe_router(const void* h, const void* w_router, int32_t* expert_ids, float* expert_w,
                                 int tok_begin, int tok_end, int hidden, int n_experts, int top_k, hipStream_t s);

@@ -156,7 +156,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
       for (int tile : kTiles) {
         int flip = 0;
         double ms = 0;
-        rc = time_ms(ctx, sg, 3, [&] {
+        rc = time_ms(ctx, sg, 6, [&] {
           flip ^= 1;
           return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg) == hipSuccess
                      ? NF_OK
