@@ -170,7 +170,7 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 }  // namespace
 
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
-// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..14 = the direct-to-LDS
+// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..19 = the direct-to-LDS
 // kernels of gemm_dl.hip.  Every variant walks K in the
 // same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
@@ -214,11 +214,13 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
       return speed * sqrt((double)tiles / (double)(rounds * 256));
     };
     const double s13 = score(256, 256, 1.0), s12 = score(256, 128, 0.92), s7 = score(128, 128, 0.84);
-    tile = (s13 >= s12 && s13 >= s7) ? 13 : (s12 >= s7 ? 12 : 7);
+    tile = (s13 >= s12 && s13 >= s7) ? 13 : (s12 >= s7 ? 19 : 7);
   }
-  if (tile >= 7 && tile <= 14) {
+  if (tile >= 7 && tile <= 19) {
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
     if (tile == 13 && n_eff % 256 != 0) tile = 12;
+    if ((tile == 15 || tile == 16) && n_eff % 256 != 0) tile = 18;
+    if (tile == 17 && n_eff % 256 != 0) tile = 19;
     return nf_launch_gemm_dl(x, w, out, residual, M, N, K, epilogue, tile, s);
   }
   if ((tile == 3 || tile == 4) && n_eff % 256 != 0) tile = tile == 4 ? 2 : 1;

@@ -161,6 +161,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
 #pragma unroll
           for (int j = 0; j < TM; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cb][i], fx[cb][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // keep this slice's MFMAs in front of the next slice's waits
       }
       if (++stage == STAGES) stage = 0;
     }
@@ -200,6 +201,170 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
   store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
 }
 
+// Second main loop: K-step BKT of 32 or 64, an LDS ring of up to 5 stages, and the stage
+// barrier moved in front of the last K-slice's MFMAs: a wavefront finishes its LDS reads of
+// stage k, waits for its own loads of stage k + 1, meets the others at the barrier, issues
+// the fragment reads of stage k + 1 and only then the MFMAs of the last slice of stage k, so
+// the matrix pipe has work queued while the barrier and the first fragment reads complete.
+// With BKT = 32 a tile row is 64 bytes (4 chunks): 16 lanes read 16 consecutive rows, four
+// rows fill the 256-byte bank window, so the slot XOR comes from (row >> 2) & 3.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED, int BKT>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int ROWS = BM + BN;
+  constexpr int RB = BKT * 2;     // bytes per tile row
+  constexpr int CPR = RB / 16;    // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;   // rows filled by one wavefront load instruction
+  constexpr int LOADS = ROWS / RPI / NW;
+  constexpr int STAGE_BYTES = ROWS * RB;
+  constexpr int SLICES = BKT / 16;
+  static_assert(BKT == 32 || BKT == 64, "K-step");
+  static_assert(ROWS % (RPI * NW) == 0, "rows must split evenly over the wavefronts");
+  static_assert(STAGES >= 2 && STAGES <= 6, "LDS ring depth");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  int m0, n0;
+  size_t w_off;
+  if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
+  W += w_off;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  auto slot_xor = [](int row) { return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+
+  const bf16_t* src[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int row = (i * NW + wave) * RPI + lane / CPR;
+    const int chunk = (lane % CPR) ^ slot_xor(row);
+    if (row < BM) {
+      int gm = m0 + row;
+      gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+      if (GROUPED && grp.row_index) gm = grp.row_index[gm];
+      src[i] = X + (size_t)gm * K + chunk * 8;
+    } else {
+      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * K + chunk * 8;
+    }
+  }
+  auto issue_stage = [&](int stage, int kt) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BKT),
+                                       (lptr_t)(lds + stage * STAGE_BYTES + (i * NW + wave) * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int KT = K / BKT;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < KT) issue_stage(s, s);
+
+  const int frag_row = lane & 31, g = lane >> 5;
+  const uint32_t sx = (uint32_t)slot_xor(frag_row);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+  const uint32_t x_off = (uint32_t)((wm * WM + frag_row) * RB);
+  const uint32_t w_off_lds = (uint32_t)((BM + wn * WN + frag_row) * RB);
+  bf16x8 fw[2][TN], fx[2][TM];
+  auto read_slice = [&](uint32_t base, int kk, bf16x8 (&dw)[TN], bf16x8 (&dx)[TM]) {
+    const uint32_t slot = (((uint32_t)(2 * kk + g)) ^ sx) * 16;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) dw[i] = lds_read_frag(base + w_off_lds + i * 32 * RB + slot);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) dx[j] = lds_read_frag(base + x_off + j * 32 * RB + slot);
+  };
+
+  if (KT >= STAGES - 1)
+    wait_vmcnt<(STAGES - 2) * LOADS>();
+  else
+    wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  read_slice(lds_base, 0, fw[0], fx[0]);
+
+  int stage = 0;
+  for (int kt = 0; kt < KT; ++kt) {
+    // every wavefront has passed the barrier that ended stage kt - 1: its buffer is free
+    if (kt + STAGES - 1 < KT) {
+      int fill = stage + STAGES - 1;
+      if (fill >= STAGES) fill -= STAGES;
+      issue_stage(fill, kt + STAGES - 1);
+    }
+    const uint32_t base = lds_base + stage * STAGE_BYTES;
+    int next = stage + 1;
+    if (next == STAGES) next = 0;
+#pragma unroll
+    for (int kk = 0; kk < SLICES; ++kk) {
+      const int cb = kk & 1, nb = cb ^ 1;
+      if (kk + 1 < SLICES) {
+        read_slice(base, kk + 1, fw[nb], fx[nb]);
+        wait_frags<TN + TM, TN, TM>(fw[cb], fx[cb]);  // slice kk has arrived; kk + 1 may be in flight
+      } else {
+        wait_frags<0, TN, TM>(fw[cb], fx[cb]);  // this wavefront's last reads of the stage are done
+        if (kt + 1 < KT) {
+          if (kt + STAGES - 1 < KT)
+            wait_vmcnt<(STAGES - 2) * LOADS>();  // stage kt + 1 has landed; younger stages stay in flight
+          else
+            wait_vmcnt<0>();
+          __builtin_amdgcn_s_barrier();
+          read_slice(lds_base + next * STAGE_BYTES, 0, fw[nb], fx[nb]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cb][i], fx[cb][j], acc[i][j], 0, 0, 0);
+      // keep this slice's MFMAs in front of the next slice's waits
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    stage = next;
+  }
+
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, int BKT>
+hipError_t launch_dl2(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
+                      hipStream_t s, GroupedArgs grp) {
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
+  const int tiles_n = epilogue == EPI_SWIGLU ? (2 * N) / BN : N / BN;
+  const dim3 grid(tiles_m * tiles_n), block(64 * WAVES_M * WAVES_N);
+  const size_t lds_bytes = (size_t)STAGES * (BM + BN) * BKT * 2;
+  const bf16_t* X = (const bf16_t*)x;
+  const bf16_t* Wp = (const bf16_t*)w;
+  bf16_t* Y = (bf16_t*)out;
+  const bf16_t* R = (const bf16_t*)residual;
+#define NF_DL2_LAUNCH(E)                                                                                           \
+  do {                                                                                                             \
+    auto kern = gemm_dl2_kernel<BM, BN, WAVES_M, WAVES_N, E, STAGES, GROUPED, BKT>;                                 \
+    static bool attr_set = false;                                                                                  \
+    if (lds_bytes > 64 * 1024 && !attr_set) {                                                                      \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,            \
+                                         (int)lds_bytes);                                                          \
+      if (e != hipSuccess) return e;                                                                               \
+      attr_set = true;                                                                                             \
+    }                                                                                                              \
+    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp);                              \
+  } while (0)
+  switch (epilogue) {
+    case EPI_NONE: NF_DL2_LAUNCH(EPI_NONE); break;
+    case EPI_RESIDUAL: NF_DL2_LAUNCH(EPI_RESIDUAL); break;
+    default: NF_DL2_LAUNCH(EPI_SWIGLU); break;
+  }
+#undef NF_DL2_LAUNCH
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, bool PIPE = false>
 hipError_t launch_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
                      hipStream_t s, GroupedArgs grp) {
@@ -237,8 +402,11 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
 // Variants: 7 = 128x128 tile, 4 wavefronts, 2 stages (two workgroups per CU);
 //           8 = 128x128, 4 wavefronts, 4 stages (one workgroup per CU);
 //           9 = 256x128, 8 wavefronts, 3 stages; 10 = 256x256, 8 wavefronts, 2 stages;
-//           11..14 = 7, 9, 10, 8 with the explicitly scheduled main loop.
-// Requires K % 64 == 0 and the (stacked) N % 128 == 0 (% 256 for variant 10).
+//           11..14 = 7, 9, 10, 8 with the explicitly scheduled main loop;
+//           15..19 = the second main loop: 256x256 with K-step 32 and 4 / 5 stages, 256x256 with
+//           K-step 64 and 2 stages, 256x128 with K-step 32 and 6 stages, 256x128 with K-step 64
+//           and 3 stages.
+// Requires K % 64 == 0 and the (stacked) N % 128 == 0 (% 256 for the 256-wide tiles).
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s) {
   const GroupedArgs none{nullptr, nullptr, 0, 0};
@@ -251,6 +419,11 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     case 12: return launch_dl<256, 128, 4, 2, 3, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 13: return launch_dl<256, 256, 2, 4, 2, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 14: return launch_dl<128, 128, 2, 2, 4, false, true>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 15: return launch_dl2<256, 256, 2, 4, 4, false, 32>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 16: return launch_dl2<256, 256, 2, 4, 5, false, 32>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 17: return launch_dl2<256, 256, 2, 4, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 18: return launch_dl2<256, 128, 4, 2, 6, false, 32>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 19: return launch_dl2<256, 128, 4, 2, 3, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
     default: return hipErrorInvalidValue;
   }
 }

@@ -18,7 +18,7 @@ void nf_profile_free(nf_ctx* ctx) {
 
 namespace {
 
-constexpr int kTiles[] = {1, 6, 7, 9, 10, 11, 12, 13};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
+constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
 constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 512, 768};
 
 struct Scratch {
@@ -263,7 +263,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
   if (!rc) {
     const int o = NF_DENSE_UG, M = (int)Mmax;
     const double g_best_ms = p->dense_us[o][steps - 1] / 1e3;
-    const int kPairTiles[] = {6, 7, 9, 10, 12, 13};
+    const int kPairTiles[] = {7, 12, 13, 19};
     p->rp.clear();
     for (int tile : kPairTiles) {
       if (rc) break;
