@@ -51,16 +51,22 @@ hipError_t nf_launch_rmsnorm(const void* x, const void* g, void* out, int n_toke
 
 // ------------------------------------------------- rotary embedding + append ---
 // One workgroup per token.  The pair (i, i + dh/2) of every Q and K head is
-// rotated by pos * theta^(-2i/dh); the angle is formed in double so that large
-// positions lose no accuracy.  Q is rotated in place in the qkv buffer; K and V go to
-// their page slot in the operand-ordered block layouts.
+// rotated by pos * theta^(-2i/dh).  The frequencies come from the host in double; the
+// angle is formed and reduced to [-pi, pi] in double (a product, a rounding and two fused
+// multiply-adds against a two-term 2 pi), so large positions lose no accuracy, and only the
+// reduced angle goes through the single-precision sine and cosine.  Q is rotated in place
+// in the qkv buffer; K and V go to their page slot in the operand-ordered block layouts.
+struct RopeFreq {
+  double f[64];  // theta^(-2i/dh), i < dh/2 <= 64
+};
+
 __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ qkv, bf16_t* __restrict__ pages,
                                                           const int32_t* __restrict__ tok_req,
                                                           const int32_t* __restrict__ q_indptr,
                                                           const int32_t* __restrict__ ctx_len,
                                                           const int32_t* __restrict__ page_indptr,
                                                           const int32_t* __restrict__ page_ids, int tok_begin,
-                                                          int Hq, int Hkv, int dh, float theta) {
+                                                          int Hq, int Hkv, int dh, RopeFreq freq) {
   const int t = tok_begin + blockIdx.x;
   const int r = tok_req[t];
   const int pos = ctx_len[r] + (t - q_indptr[r]);
@@ -69,41 +75,61 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
   const int half = dh >> 1;
   __shared__ float cs[64], sn[64];
   if ((int)threadIdx.x < half) {
-    const double freq = exp2(-2.0 * (double)threadIdx.x / (double)dh * log2((double)theta));
-    double sv, cv;
-    sincos((double)pos * freq, &sv, &cv);
-    cs[threadIdx.x] = (float)cv;
-    sn[threadIdx.x] = (float)sv;
+    const double angle = (double)pos * freq.f[threadIdx.x];
+    const double turns = rint(angle * 0.15915494309189535);  // 1 / (2 pi)
+    double red = fma(-turns, 6.283185307179586, angle);
+    red = fma(-turns, 2.4492935982947064e-16, red);  // 2 pi - (double)(2 pi)
+    float sv, cv;
+    sincosf((float)red, &sv, &cv);
+    cs[threadIdx.x] = cv;
+    sn[threadIdx.x] = sv;
   }
   __syncthreads();
   bf16_t* row = qkv + (size_t)t * ((Hq + 2 * Hkv) * dh);
   bf16_t* kpage = pages + ((size_t)page * 2 + 0) * Hkv * 16 * dh;
   bf16_t* vpage = pages + ((size_t)page * 2 + 1) * Hkv * 16 * dh;
-  const int n_pairs = (Hq + Hkv) * half;
-  for (int p = threadIdx.x; p < n_pairs; p += 256) {
-    const int h = p / half, i = p - h * half;
+  // one unit = 8 consecutive dimensions i of a head and their partners i + dh/2: 16-byte
+  // loads and stores (8 dimensions are also contiguous in the K block)
+  const int octets = half >> 3;
+  const int n_units = (Hq + Hkv) * octets;
+  for (int u = threadIdx.x; u < n_units; u += 256) {
+    const int h = u / octets, o = u - h * octets;
     bf16_t* hv = row + h * dh;
-    const float a = bf2f(hv[i]), b = bf2f(hv[i + half]);
-    const float c = cs[i], s = sn[i];
-    const bf16_t ra = f2bf(a * c - b * s), rb = f2bf(a * s + b * c);
+    const u32x4 av = *reinterpret_cast<const u32x4*>(hv + 8 * o);
+    const u32x4 bv = *reinterpret_cast<const u32x4*>(hv + half + 8 * o);
+    u32x4 ra, rb;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a0 = __uint_as_float(av[e] << 16), a1 = __uint_as_float(av[e] & 0xffff0000u);
+      const float b0 = __uint_as_float(bv[e] << 16), b1 = __uint_as_float(bv[e] & 0xffff0000u);
+      const float c0 = cs[8 * o + 2 * e], s0 = sn[8 * o + 2 * e];
+      const float c1 = cs[8 * o + 2 * e + 1], s1 = sn[8 * o + 2 * e + 1];
+      ra[e] = pack_bf2(a0 * c0 - b0 * s0, a1 * c1 - b1 * s1);
+      rb[e] = pack_bf2(a0 * s0 + b0 * c0, a1 * s1 + b1 * c1);
+    }
     if (h < Hq) {
-      hv[i] = ra;
-      hv[i + half] = rb;
+      *reinterpret_cast<u32x4*>(hv + 8 * o) = ra;
+      *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
     } else {
-      // K block [dh/8][16 keys][8]
+      // K block [dh/8][16 keys][8]: dimensions 8o .. 8o+7 are chunk o, their partners chunk o + dh/16
       bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh;
-      const int j = i + half;
-      kb[((i >> 3) * 16 + slot) * 8 + (i & 7)] = ra;
-      kb[((j >> 3) * 16 + slot) * 8 + (j & 7)] = rb;
+      *reinterpret_cast<u32x4*>(kb + (o * 16 + slot) * 8) = ra;
+      *reinterpret_cast<u32x4*>(kb + ((octets + o) * 16 + slot) * 8) = rb;
     }
   }
   const bf16_t* vrow = row + (Hq + Hkv) * dh;
-  for (int e = threadIdx.x; e < Hkv * dh; e += 256) {
-    const int h = e / dh, d = e - h * dh;
+  for (int e8 = threadIdx.x; e8 < Hkv * dh / 8; e8 += 256) {
+    const int e0 = e8 * 8;
+    const int h = e0 / dh, d0 = e0 - h * dh;
+    const u32x4 vv = *reinterpret_cast<const u32x4*>(vrow + e0);
     // V block [dh/32][16 c][4 g][2][4 keys]: dimension d = (2*quad + hb)*16 + c, key = 4*g + j
-    const int b = d >> 4, c = d & 15;
-    const int off = ((((b >> 1) * 16 + c) * 4 + (slot >> 2)) * 2 + (b & 1)) * 4 + (slot & 3);
-    vpage[(size_t)h * 16 * dh + off] = vrow[e];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int d = d0 + k;
+      const int b = d >> 4, c = d & 15;
+      const int off = ((((b >> 1) * 16 + c) * 4 + (slot >> 2)) * 2 + (b & 1)) * 4 + (slot & 3);
+      vpage[(size_t)h * 16 * dh + off] = (bf16_t)((k & 1) ? (vv[k >> 1] >> 16) : (vv[k >> 1] & 0xffffu));
+    }
   }
 }
 
@@ -112,9 +138,13 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
                                  int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
                                  float rope_theta, hipStream_t s) {
   if (tok_end <= tok_begin) return hipSuccess;
+  if (head_dim > 128 || head_dim % 16) return hipErrorInvalidValue;
+  RopeFreq freq;
+  for (int i = 0; i < 64; ++i)
+    freq.f[i] = i < head_dim / 2 ? pow((double)rope_theta, -2.0 * (double)i / (double)head_dim) : 0.0;
   rope_append_kernel<<<dim3(tok_end - tok_begin), dim3(256), 0, s>>>(
       (bf16_t*)qkv, (bf16_t*)pages, tok_req, q_indptr, ctx_len, page_indptr, page_ids, tok_begin, n_q_heads,
-      n_kv_heads, head_dim, rope_theta);
+      n_kv_heads, head_dim, freq);
   return hipGetLastError();
 }
 
