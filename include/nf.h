@@ -177,6 +177,23 @@ int nf_tune_set(const char *key, int value);
 /* ---- planning (Sec. 4.1: automated pipeline search) ---------------------------------------- */
 
 /*
+ * Measured ceilings of the device, for pricing kernels against what the chip delivers (the
+ * measurement section of the paper, Sec. 3.2 / Table 1, uses data-sheet numbers; on a
+ * power-limited part the delivered ceilings are lower).  Runs a register-only bf16 MFMA loop
+ * on every CU with all-zero operands and with varied operands, and a streaming read of a
+ * 4 GiB buffer.  Synchronous on the null stream; allocates and frees 4 GiB of device memory;
+ * takes about a second.  Returns NF_EHIP if the device refuses the allocation or a launch.
+ */
+typedef struct {
+  double mfma_bf16_tflops;               /* varied operands: what activation-like data can reach */
+  double mfma_bf16_tflops_zero_operands; /* all-zero operands: the clock is not pulled down */
+  double hbm_read_gbs;                   /* streaming read, best of three passes */
+  int32_t n_cus;
+  int32_t reserved;
+} nf_peaks;
+int nf_measure_peaks(nf_ctx *ctx, nf_peaks *out /* host */);
+
+/*
  * Kernel profiling for the auto-search (Sec. 4.1.1): times every dense
  * operation of `model` alone for batch sizes granule, 2*granule, ... max_tokens
  * with every GEMM tile shape (keeping the best: the kernel -> implementation map),
@@ -290,6 +307,25 @@ int nf_layer_forward(nf_ctx *ctx, const nf_model_desc *model, const nf_layer_wei
                      nf_kv_cache *kv, const nf_batch *batch, const nf_plan *plan,
                      const void *x_in, void *x_out, void *workspace, size_t workspace_bytes,
                      void *hip_stream);
+
+/*
+ * n_layers consecutive decoder layers on one dense batch (Sec. 2.1: a layer's output is the
+ * next layer's input), with one plan.  weights[l] and kv[l] (host arrays of n_layers
+ * structs) belong to layer l; the pools must be pairwise distinct (NF_EINVAL otherwise) and
+ * each must satisfy the batch's page table.  With an overlapped plan the nano-operations
+ * are pipelined across the layer boundary as in the paper's pipelines (Sec. 4.1.4): the KQV
+ * nano-operation of a token range in layer l + 1 is issued behind the Down nano-operation
+ * of that range in layer l, so its attention runs beside the remaining GEMMs of layer l.
+ * Results are bit-identical to n_layers calls of nf_layer_forward.  plan must not be NULL.
+ * workspace: at least nf_layers_workspace_bytes(plan, n_layers) bytes (the plan's workspace
+ * plus two intermediate activations).  Errors as nf_layer_forward.
+ */
+size_t nf_layers_workspace_bytes(const nf_plan *plan, int n_layers);
+int nf_layers_forward(nf_ctx *ctx, const nf_model_desc *model, int n_layers,
+                      const nf_layer_weights *weights /* host [n_layers] */,
+                      nf_kv_cache *kv /* host [n_layers] */, const nf_batch *batch, const nf_plan *plan,
+                      const void *x_in, void *x_out, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
 
 /* ---- single operations (kernel-level parity tests and profiling) ---------------------------- */
 

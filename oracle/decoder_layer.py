@@ -264,6 +264,23 @@ def layer_forward(model, weights, pages, batch, x, expert_choice=None, return_pa
     return z, k, v
 
 
+def layers_forward(model, weights_list, pages_list, batch, x):
+    """Consecutive decoder layers on one dense batch (Sec. 2.1: the output of the
+    down-projection "serves as the input to the next layer").  Layer l has its own weights
+    and its own KV pool; the batch (requests, positions, page table) is the same for all.
+
+    Returns the last layer's output and, per layer, the K and V rows it appended.
+    Nothing is rounded between layers.
+    """
+    ks, vs = [], []
+    z = np.asarray(x)
+    for w, pages in zip(weights_list, pages_list):
+        z, k, v = layer_forward(model, w, pages, batch, z)
+        ks.append(k)
+        vs.append(v)
+    return z, ks, vs
+
+
 def kv_slot(batch, model, t_req: int, pos: int):
     """(physical page id, slot) where the token at position pos of request
     t_req is stored (append rule: page = page list[pos // page_size])."""

@@ -25,7 +25,8 @@ EXPORTS = [
     "nf_ctx_set_trace", "nf_ctx_read_trace", "nf_ctx_lane_stream", "nf_ctx_mask_stream", "nf_tune_set",
     "nf_nano_ops_dependent", "nf_profile", "nf_search_pipeline", "nf_simulate_pipeline", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
     "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_workspace_region", "nf_layer_forward",
-    "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention",
+    "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
+    "nf_layers_workspace_bytes", "nf_layers_forward",
 ]
 
 
@@ -118,6 +119,10 @@ def lib() -> C.CDLL:
     L.nf_workspace_region.argtypes = [vp, C.c_char_p, P(sz), P(sz)]
     L.nf_layer_forward.argtypes = [vp, P(nf_model_desc), P(nf_layer_weights), P(nf_kv_cache), P(nf_batch), vp,
                                    vp, vp, vp, sz, vp]
+    L.nf_layers_workspace_bytes.argtypes = [vp, i32]
+    L.nf_layers_workspace_bytes.restype = sz
+    L.nf_layers_forward.argtypes = [vp, P(nf_model_desc), i32, P(nf_layer_weights), P(nf_kv_cache), P(nf_batch), vp,
+                                    vp, vp, vp, sz, vp]
     L.nf_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp]
     L.nf_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
     L.nf_op_rope_append.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, i32, i32, vp]
@@ -290,6 +295,20 @@ def nf_profile(ctx: Context, model, max_tokens: int, granule: int = 128, cache_p
                             cache_path.encode() if cache_path else None), "nf_profile", ctx)
 
 
+class nf_peaks(C.Structure):
+    _fields_ = [("mfma_bf16_tflops", C.c_double), ("mfma_bf16_tflops_zero_operands", C.c_double),
+                ("hbm_read_gbs", C.c_double), ("n_cus", C.c_int32), ("reserved", C.c_int32)]
+
+
+def nf_measure_peaks(ctx: Context) -> dict:
+    """Measured MFMA and HBM ceilings of the device (about a second of GPU time, 4 GiB of scratch)."""
+    pk = nf_peaks()
+    _check(lib().nf_measure_peaks(ctx.handle, C.byref(pk)), "nf_measure_peaks", ctx)
+    return {"mfma_bf16_tflops": pk.mfma_bf16_tflops,
+            "mfma_bf16_tflops_zero_operands": pk.mfma_bf16_tflops_zero_operands,
+            "hbm_read_gbs": pk.hbm_read_gbs, "n_cus": pk.n_cus}
+
+
 def nf_tune_set(key: str, value: int):
     _check(lib().nf_tune_set(key.encode(), int(value)), "nf_tune_set")
 
@@ -317,6 +336,25 @@ def nf_layer_forward(ctx: Context, model, weights: nf_layer_weights, pages_ptr: 
     _check(lib().nf_layer_forward(ctx.handle, C.byref(md), C.byref(weights), C.byref(kv), C.byref(batch.struct),
                                   plan.handle if plan is not None else None, x_in_ptr, x_out_ptr, workspace_ptr,
                                   int(workspace_bytes), stream), "nf_layer_forward", ctx)
+
+
+def nf_layers_workspace_bytes(plan: Plan, n_layers: int) -> int:
+    return int(lib().nf_layers_workspace_bytes(plan.handle, int(n_layers)))
+
+
+def nf_layers_forward(ctx: Context, model, weights: "list[nf_layer_weights]", pages_ptrs: "list[int]", num_pages: int,
+                      batch: BatchArgs, plan: Plan, x_in_ptr: int, x_out_ptr: int, workspace_ptr: int,
+                      workspace_bytes: int, stream: int = 0):
+    """n consecutive layers (layer l uses weights[l] and the pool at pages_ptrs[l]) with one plan."""
+    n = len(weights)
+    if len(pages_ptrs) != n:
+        raise ValueError("one KV pool per layer")
+    md = model_desc(model)
+    w_arr = (nf_layer_weights * n)(*weights)
+    kv_arr = (nf_kv_cache * n)(*[nf_kv_cache(p, int(num_pages)) for p in pages_ptrs])
+    _check(lib().nf_layers_forward(ctx.handle, C.byref(md), n, w_arr, kv_arr, C.byref(batch.struct), plan.handle,
+                                   x_in_ptr, x_out_ptr, workspace_ptr, int(workspace_bytes), stream),
+           "nf_layers_forward", ctx)
 
 
 def nf_op_rmsnorm(x_ptr, g_ptr, out_ptr, n_tokens, hidden, eps, stream=0):

@@ -380,26 +380,68 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
   }
 }
 
-int run_plan(nf_ctx* ctx, const nf_plan* p, const LayerArgs& a, hipStream_t user) {
+// Runs the plan on n_layers consecutive layers (a[l] holds layer l's weights, cache and
+// input / output buffers; the workspace is shared).  Overlapped plans are pipelined across
+// the layer boundary as the paper's pipelines are (Sec. 4.1, Fig. 6: the operations of the
+// next layer follow without a global join): the KQV nano-operation of a token range in layer
+// l + 1 is issued right behind the Down nano-operation of the same range in layer l, so the
+// attention of that range can run beside the remaining GEMMs of layer l.  This is safe with
+// one shared workspace because (i) every buffer is indexed by token row and the nano-batches
+// are disjoint row ranges, (ii) the operations of one range form a chain, and (iii) the
+// layers own distinct KV pools.  Events alternate between two sets from layer to layer: a
+// hoisted KQV re-records its event before the late operations of the previous layer have
+// enqueued their waits.
+int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, hipStream_t user) {
   if (!p->overlap) {
-    for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(ctx, p, op, a, user));
+    for (int l = 0; l < n_layers; ++l)
+      for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(ctx, p, op, a[l], user));
     return NF_OK;
   }
   // fork: the lane streams start after everything already enqueued on the caller's stream
   NF_HIP(ctx, hipEventRecord(p->ev_fork, user));
   for (int l = 0; l < NF_LANES; ++l) NF_HIP(ctx, hipStreamWaitEvent(p->lane_stream[l], p->ev_fork, 0));
-  for (size_t i = 0; i < p->ops.size(); ++i) {
+  auto emit = [&](int layer, size_t i, int after_prev_layer_op) -> int {
     const NfNanoOp& op = p->ops[i];
     hipStream_t s = p->lane_stream[op.lane];
-    for (int d : op.deps) NF_HIP(ctx, hipStreamWaitEvent(s, p->events[d], 0));
-    NF_HIP(ctx, launch_nano_op(ctx, p, op, a, s));
-    if (op.record) NF_HIP(ctx, hipEventRecord(p->events[i], s));
+    const std::vector<hipEvent_t>& ev = (layer & 1) ? p->events_alt : p->events;
+    for (int d : op.deps) NF_HIP(ctx, hipStreamWaitEvent(s, ev[d], 0));
+    if (after_prev_layer_op >= 0 && p->ops[after_prev_layer_op].lane != op.lane) {
+      const std::vector<hipEvent_t>& pev = ((layer - 1) & 1) ? p->events_alt : p->events;
+      NF_HIP(ctx, hipStreamWaitEvent(s, pev[after_prev_layer_op], 0));
+    }
+    NF_HIP(ctx, launch_nano_op(ctx, p, op, a[layer], s));
+    if (op.record) NF_HIP(ctx, hipEventRecord(ev[i], s));
+    return NF_OK;
+  };
+  for (int l = 0; l < n_layers; ++l) {
+    for (size_t i = 0; i < p->ops.size(); ++i) {
+      const NfNanoOp& op = p->ops[i];
+      if (l > 0 && op.kind == NF_OP_KQV) continue;  // issued behind the previous layer's Down
+      int rc = emit(l, i, -1);
+      if (rc) return rc;
+      if (op.kind == NF_OP_D && l + 1 < n_layers) {
+        for (size_t j = 0; j < p->ops.size(); ++j) {
+          const NfNanoOp& nx = p->ops[j];
+          if (nx.kind == NF_OP_KQV && nx.tok_begin == op.tok_begin && nx.tok_end == op.tok_end) {
+            rc = emit(l + 1, j, (int)i);
+            if (rc) return rc;
+          }
+        }
+      }
+    }
   }
   // join: the caller's stream continues after both lanes have drained
   for (int l = 0; l < NF_LANES; ++l) {
     NF_HIP(ctx, hipEventRecord(p->ev_join[l], p->lane_stream[l]));
     NF_HIP(ctx, hipStreamWaitEvent(user, p->ev_join[l], 0));
   }
+  return NF_OK;
+}
+
+int check_weights(const nf_model_desc* model, const nf_layer_weights* w) {
+  if (!w->g_attn_norm || !w->w_qkv || !w->w_o || !w->g_ffn_norm || !w->w_gate_up || !w->w_down ||
+      (model->n_experts > 1 && !w->w_router))
+    return NF_EINVAL;
   return NF_OK;
 }
 
@@ -416,9 +458,7 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
   if (rc) return rc;
   if (batch->n_tokens == 0) return NF_OK;
   if (!x_in || !x_out || x_in == x_out || !workspace) return NF_EINVAL;
-  if (!weights->g_attn_norm || !weights->w_qkv || !weights->w_o || !weights->g_ffn_norm || !weights->w_gate_up ||
-      !weights->w_down || (model->n_experts > 1 && !weights->w_router))
-    return NF_EINVAL;
+  if (check_weights(model, weights) != NF_OK) return NF_EINVAL;
   hipStream_t user = (hipStream_t)hip_stream;
 
   nf_plan* tmp = nullptr;
@@ -443,7 +483,7 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
     a.x_in = (const char*)x_in;
     a.x_out = (char*)x_out;
     a.ws = layout_workspace(model, batch->n_tokens, (size_t)std::max(1, plan->total_parts), (char*)workspace);
-    rc = run_plan(ctx, plan, a, user);
+    rc = run_layers(ctx, plan, &a, 1, user);
   }
   if (tmp) {
     // the temporary plan owns device work lists the kernels are reading: drain first
@@ -455,6 +495,52 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
     }
   }
   return rc;
+}
+
+extern "C" size_t nf_layers_workspace_bytes(const nf_plan* plan, int n_layers) {
+  if (!plan || n_layers < 1) return 0;
+  const size_t x_bytes = nf_align256((size_t)std::max(1, plan->n_tokens) * plan->model.hidden * 2);
+  return nf_align256(nf_plan_workspace_bytes(plan)) + (n_layers > 1 ? 2 * x_bytes : 0);
+}
+
+extern "C" int nf_layers_forward(nf_ctx* ctx, const nf_model_desc* model, int n_layers,
+                                 const nf_layer_weights* weights, nf_kv_cache* kv, const nf_batch* batch,
+                                 const nf_plan* plan, const void* x_in, void* x_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  if (!ctx || !weights || !kv || !batch || !plan || n_layers < 1) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!kv[l].pages || kv[l].num_pages < 0) return NF_EINVAL;
+    if (check_weights(model, &weights[l]) != NF_OK) return NF_EINVAL;
+    // the pipelining across the layer boundary relies on distinct pools (and so does the model)
+    for (int k = 0; k < l; ++k)
+      if (kv[k].pages == kv[l].pages) return NF_EINVAL;
+    rc = nf_validate_batch(model, batch, kv[l].num_pages);
+    if (rc) return rc;
+  }
+  if (batch->n_tokens == 0) return NF_OK;
+  if (!x_in || !x_out || x_in == x_out || !workspace) return NF_EINVAL;
+  if ((int)plan->bounds.size() - 1 > kMaxNanoOffsets) return NF_EPLAN;
+  if (plan->n_tokens != batch->n_tokens || plan->batch_sig != nf_batch_signature(batch) ||
+      memcmp(&plan->model, model, sizeof(nf_model_desc)) != 0)
+    return NF_EPLAN;
+  if (workspace_bytes < nf_layers_workspace_bytes(plan, n_layers)) return NF_EWORKSPACE;
+  const size_t x_bytes = nf_align256((size_t)batch->n_tokens * model->hidden * 2);
+  char* mid[2] = {(char*)workspace + nf_align256(nf_plan_workspace_bytes(plan)), nullptr};
+  mid[1] = mid[0] + x_bytes;
+  std::vector<LayerArgs> args((size_t)n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    LayerArgs& a = args[l];
+    a.m = model;
+    a.w = &weights[l];
+    a.kv = &kv[l];
+    a.b = batch;
+    a.x_in = l == 0 ? (const char*)x_in : mid[(l - 1) & 1];
+    a.x_out = l == n_layers - 1 ? (char*)x_out : mid[l & 1];
+    a.ws = layout_workspace(model, batch->n_tokens, (size_t)std::max(1, plan->total_parts), (char*)workspace);
+  }
+  return run_layers(ctx, plan, args.data(), n_layers, (hipStream_t)hip_stream);
 }
 
 // --------------------------------------------------------- single operations ---

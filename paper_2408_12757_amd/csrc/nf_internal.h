@@ -61,6 +61,7 @@ struct nf_plan {
   int attn_wgs = 0;                       // persistent attention workgroups (0 = one per CU, -1 = one per work unit)
   hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
   std::vector<hipEvent_t> events;  // one per nano-op that records
+  std::vector<hipEvent_t> events_alt;  // second set: consecutive layers of a multi-layer run alternate
   hipEvent_t ev_fork = nullptr, ev_join[NF_LANES] = {nullptr, nullptr};
   // device work lists
   void* dev_blob = nullptr;

@@ -240,8 +240,15 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
     }
     NF_HIP(ctx, hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
     p->events.assign(p->ops.size(), nullptr);
-    for (size_t a = 0; a < p->ops.size(); ++a)
-      if (p->ops[a].record) NF_HIP(ctx, hipEventCreateWithFlags(&p->events[a], hipEventDisableTiming));
+    p->events_alt.assign(p->ops.size(), nullptr);
+    for (size_t a = 0; a < p->ops.size(); ++a) {
+      // the last operation of a token range also records: in a multi-layer run the next
+      // layer's first operation on that range may sit on the other lane
+      if (p->ops[a].kind == NF_OP_D) p->ops[a].record = true;
+      if (!p->ops[a].record) continue;
+      NF_HIP(ctx, hipEventCreateWithFlags(&p->events[a], hipEventDisableTiming));
+      NF_HIP(ctx, hipEventCreateWithFlags(&p->events_alt[a], hipEventDisableTiming));
+    }
   }
   return NF_OK;
 }
@@ -292,6 +299,8 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
 extern "C" void nf_plan_destroy(nf_plan* p) {
   if (!p) return;
   for (hipEvent_t e : p->events)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->events_alt)
     if (e) (void)hipEventDestroy(e);
   if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
   for (int l = 0; l < NF_LANES; ++l)

@@ -82,3 +82,45 @@ def untouched_pages_equal(case: Case, pages_after: np.ndarray) -> bool:
             arr[page, 0][:, kidx[slot]] = 0
             arr[page, 1][:, vidx[slot]] = 0
     return bool(np.array_equal(before, after))
+
+
+class ChainCase:
+    """n_layers consecutive layers with their own weights and KV pools on one batch."""
+
+    def __init__(self, model, batch: wl.Batch, seed: int, n_layers: int, ctx=None):
+        self.model, self.batch, self.n_layers = model, batch, n_layers
+        self.weights = [wl.make_weights(model, seed + 17 * l) for l in range(n_layers)]
+        self.pools_bits = [wl.make_kv_pages_host(model, batch.num_pages, seed + 3 + 29 * l) for l in range(n_layers)]
+        self.x_bits = wl.make_x(batch.n_tokens, model.hidden, seed + 1)
+        self.ctx = ctx or nf.Context(0)
+        self.dev_w = [hz.DeviceWeights(w, DEV) for w in self.weights]
+        self.pools = [hz.bf16_tensor(p, DEV) for p in self.pools_bits]
+        self.args = hz.upload_batch(batch, DEV)
+        self.x = hz.bf16_tensor(self.x_bits, DEV)
+
+    def reset(self):
+        for t, bits in zip(self.pools, self.pools_bits):
+            t.copy_(hz.bf16_tensor(bits, DEV))
+
+    def run_chain(self, plan):
+        """One nf_layers_forward call.  Returns (z bits, [pool bits per layer])."""
+        self.reset()
+        out = torch.empty_like(self.x)
+        need = nf.nf_layers_workspace_bytes(plan, self.n_layers)
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        nf.nf_layers_forward(self.ctx, self.model, [w.struct for w in self.dev_w], [p.data_ptr() for p in self.pools],
+                             self.pools[0].shape[0], self.args, plan, self.x.data_ptr(), out.data_ptr(),
+                             ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return hz.bf16_bits(out), [hz.bf16_bits(p) for p in self.pools]
+
+    def run_layer_by_layer(self):
+        """n_layers separate nf_layer_forward calls (unsplit), the output of one fed to the next."""
+        self.reset()
+        cur = self.x
+        for l in range(self.n_layers):
+            runner = hz.LayerRunner(self.model, self.weights[l], self.pools[l], DEV, ctx=self.ctx)
+            runner.w = self.dev_w[l]
+            cur = runner.forward(self.args, cur, None)
+        torch.cuda.synchronize()
+        return hz.bf16_bits(cur), [hz.bf16_bits(p) for p in self.pools]

@@ -11,7 +11,7 @@ from paper_2408_12757_amd import binding as nf
 from paper_2408_12757_amd import harness as hz
 from paper_2408_12757_amd import workloads as wl
 
-from gpu_util import DEV, REL_TOL, Case, f64, rel_err, untouched_pages_equal
+from gpu_util import DEV, REL_TOL, Case, ChainCase, f64, rel_err, untouched_pages_equal
 
 pytestmark = pytest.mark.gpu
 
@@ -194,6 +194,67 @@ def test_nano_batched_and_overlapped_are_bit_exact_with_unsplit(ctx):
                 assert np.array_equal(z, z0), (bounds, overlap, acu)
                 assert np.array_equal(p, p0)
             plan.close()
+
+
+# ------------------------------------------------------- consecutive layers ---
+
+def test_layer_chain_matches_oracle_and_is_bit_exact_with_separate_calls(ctx):
+    """nf_layers_forward pipelines the nano-operations across the layer boundary; its result
+    must equal layer-by-layer calls bit for bit (output and every layer's pool) and the
+    oracle's chain within the tolerance."""
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2, spare_pages=5)
+    n_layers = 4
+    chain = ChainCase(cfg.model, b, cfg.seed, n_layers, ctx=ctx)
+    z_ref, pools_ref = chain.run_layer_by_layer()
+    for bounds, overlap in (([0, 64], False), ([0, 32, 64], False), ([0, 32, 64], True), ([0, 20, 41, 64], True),
+                            ([0, 16, 64], True)):
+        say("chain", n_layers, "layers", bounds, overlap)
+        plan = nf.nf_plan_manual(chain.ctx, cfg.model, chain.args, bounds, overlap, 0, 0)
+        for rep in range(2):
+            z, pools = chain.run_chain(plan)
+            assert np.array_equal(z, z_ref), (bounds, overlap, rep)
+            for l in range(n_layers):
+                assert np.array_equal(pools[l], pools_ref[l]), (bounds, overlap, l)
+        plan.close()
+    # against the oracle: the GPU rounds the activations to bf16 between layers, the oracle does not
+    zo, ks, vs = orc.layers_forward(cfg.model, chain.weights, chain.pools_bits, b, chain.x_bits)
+    e = rel_err(f64(z_ref), zo)
+    say("chain rel err", e)
+    assert e <= REL_TOL
+    tok = np.arange(b.n_tokens)
+    for l in range(n_layers):
+        kg, vg = hz.read_kv_rows(pools_ref[l], cfg.model, b, tok)
+        assert rel_err(f64(kg), ks[l]) <= REL_TOL and rel_err(f64(vg), vs[l]) <= REL_TOL, l
+
+
+def test_layer_chain_rejects_bad_arguments(ctx):
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    chain = ChainCase(cfg.model, b, cfg.seed, 2, ctx=ctx)
+    plan = nf.nf_plan_manual(chain.ctx, cfg.model, chain.args, [0, 32, 64], True, 0, 0)
+    out = torch.empty_like(chain.x)
+    need = nf.nf_layers_workspace_bytes(plan, 2)
+    assert need > plan.workspace_bytes
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    w = [d.struct for d in chain.dev_w]
+    n_pages = chain.pools[0].shape[0]
+    same_pool = [chain.pools[0].data_ptr(), chain.pools[0].data_ptr()]
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_layers_forward(chain.ctx, cfg.model, w, same_pool, n_pages, chain.args, plan, chain.x.data_ptr(),
+                             out.data_ptr(), ws.data_ptr(), ws.numel())
+    assert e.value.status == nf.NF_EINVAL
+    pools = [p.data_ptr() for p in chain.pools]
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_layers_forward(chain.ctx, cfg.model, w, pools, n_pages, chain.args, plan, chain.x.data_ptr(),
+                             out.data_ptr(), ws.data_ptr(), need - 256)
+    assert e.value.status == nf.NF_EWORKSPACE
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_layers_forward(chain.ctx, cfg.model, w, pools, n_pages, chain.args, plan, chain.x.data_ptr(),
+                             chain.x.data_ptr(), ws.data_ptr(), ws.numel())
+    assert e.value.status == nf.NF_EINVAL
+    plan.close()
+    torch.cuda.synchronize()
 
 
 def test_plan_mismatch_and_workspace_errors(ctx):

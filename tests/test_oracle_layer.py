@@ -95,6 +95,29 @@ def test_prefill_only_layer_matches_torch_library_routines():
     np.testing.assert_allclose(z, ref, rtol=1e-10, atol=1e-11)
 
 
+def test_layer_chain_matches_torch_library_routines_applied_in_sequence():
+    """Consecutive layers: each layer has its own weights and its own pool, the output of one
+    is the input of the next (Sec. 2.1).  A wrong hand-over (weights or pools swapped, an
+    input reused) changes the result."""
+    m = small_model()
+    ws = [float_weights(m, 61 + l) for l in range(3)]
+    q_lens = [6, 9]
+    b = mk_batch(q_lens, [0, 0], 2, m.page_size)
+    x = np.random.default_rng(62).standard_normal((b.n_tokens, m.hidden))
+    pools = [random_pages(m, b.num_pages, 63 + l) for l in range(3)]
+    z, ks, vs = orc.layers_forward(m, ws, pools, b, x)
+    ref = x
+    for w in ws:
+        ref = torch_prefill_layer(m, w, ref, q_lens)
+    np.testing.assert_allclose(z, ref, rtol=1e-9, atol=1e-10)
+    assert len(ks) == 3 and len(vs) == 3
+    # layer 0 of the chain is the single layer; the order of the layers matters
+    z0, k0, v0 = orc.layer_forward(m, ws[0], pools[0], b, x)
+    np.testing.assert_array_equal(ks[0], k0)
+    z_swapped, _, _ = orc.layers_forward(m, ws[::-1], pools, b, x)
+    assert np.max(np.abs(z_swapped - z)) > 1e-3
+
+
 def test_residuals_present():
     m = small_model()
     w = float_weights(m, 24)
