@@ -37,6 +37,10 @@ def parse_args():
     ap.add_argument("--profile-cache", default=None, help="file to keep the kernel profile in (default: re-measure)")
     ap.add_argument("--ablation-attn-wgs", type=int, default=256,
                     help="persistent attention workgroups of the overlapped ablation run")
+    ap.add_argument("--chained-layers", type=int, default=8,
+                    help="also time this many consecutive layers (distinct weights and KV pools) in one "
+                         "nf_layers_forward call and report the time per layer; 0 = skip")
+    ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA / HBM ceiling measurement")
     return ap.parse_args()
 
 
@@ -104,7 +108,7 @@ def main():
 
     nf.lib()  # fail loudly if the HIP library is missing
     cfg = wl.CONFIGS[args.config]
-    case = hz.DeviceCase(cfg, n_weight_copies=args.weight_copies)
+    case = hz.DeviceCase(cfg, n_weight_copies=max(args.weight_copies, args.chained_layers))
     b, m = case.batch, cfg.model
     B = b.n_tokens
     costs = cm.layer_costs(m, b)
@@ -116,6 +120,10 @@ def main():
         bcopy.copy_(a)
         torch.cuda.synchronize()
         del a, bcopy
+
+    # ---- the device's own ceilings (register-only MFMA loop, streaming read), next to the
+    # published ones the roofline is priced against ----
+    peaks = None if args.no_measured_peaks else nf.nf_measure_peaks(case.ctx)
 
     # ---- auto-search (Sec. 4.1): profile the kernels on this GPU, then search the pipeline ----
     t0 = time.perf_counter()
@@ -148,14 +156,22 @@ def main():
             best_c = {k: d[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
             best_c["origin"] += "; searched pipeline rejected by the trial run"
 
-    def timed(plan, steps, warmup, trace=0):
+    step_marks = []
+
+    def timed(plan, steps, warmup, trace=0, marks=None):
         for i in range(warmup):
             case.forward(plan, i)
         torch.cuda.synchronize()
         case.ctx.set_trace(trace)
+        if marks is not None:
+            marks.append(torch.cuda.Event(enable_timing=True))
+            marks[-1].record()
         t0 = time.perf_counter()
         for i in range(steps):
             case.forward(plan, warmup + i)
+            if marks is not None:
+                marks.append(torch.cuda.Event(enable_timing=True))
+                marks[-1].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         recs = case.ctx.read_trace(16 * steps + 16) if trace else []
@@ -164,7 +180,8 @@ def main():
 
     # ---- the timed run: exactly --steps layer iterations, attention kernel traced with
     # HIP events on the stream it is launched on ----
-    ms_step, recs = timed(best_plan, args.steps, args.warmup, trace=1)
+    ms_step, recs = timed(best_plan, args.steps, args.warmup, trace=1, marks=step_marks)
+    per_step = np.array([step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(len(step_marks) - 1)])
     attn_ms = [r["ms"] for r in recs if r["kernel"] == "attention"]
     launches_per_step = max(1, len(attn_ms) // args.steps)
     # algorithmic bytes of the attention kernel per step: K and V of every key read once per
@@ -177,6 +194,41 @@ def main():
     unsplit_ms, _ = timed(unsplit_plan, n_abl, 3)
     seq_ms, _ = timed(seq_plan, n_abl, 3)
     ovl_ms, _ = timed(ovl_plan, n_abl, 3)
+
+    # ---- consecutive layers in one call: layer l's tail may overlap layer l + 1's head ----
+    chained = None
+    if args.chained_layers > 1:
+        L = args.chained_layers
+        pools = case.layer_pools(L)
+        w_structs = [case.runners[l % len(case.runners)].w.struct for l in range(L)]
+        x_out = torch.empty_like(case.x)
+
+        def chain_ms(plan, reps=6):
+            need = nf.nf_layers_workspace_bytes(plan, L)
+            ws = torch.empty(need, dtype=torch.uint8, device=case.device)
+            stream = torch.cuda.current_stream().cuda_stream
+
+            def once():
+                nf.nf_layers_forward(case.ctx, m, w_structs, [p.data_ptr() for p in pools], pools[0].shape[0],
+                                     case.args, plan, case.x.data_ptr(), x_out.data_ptr(), ws.data_ptr(), ws.numel(),
+                                     stream)
+            once()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                once()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps / L
+
+        chained = {"layers": L, "unsplit_ms_per_layer": chain_ms(unsplit_plan),
+                   "nano_sequential_ms_per_layer": chain_ms(seq_plan),
+                   "nano_overlapped_ms_per_layer": chain_ms(ovl_plan), "structure": abl_bounds,
+                   "overlapped_attn_wgs": args.ablation_attn_wgs,
+                   "note": "one nf_layers_forward call over distinct weights and KV pools, time / layers; the "
+                           "overlapped run pipelines nano-operations across the layer boundary"}
+        del pools
 
     out = {
         "metric": METRIC,
@@ -195,6 +247,9 @@ def main():
                                f"{b.n_decode_reqs} decode requests, {int(b.ctx_len[b.n_prefill_reqs:].sum())} cached "
                                f"tokens in 16-token pages", "dense_batch": B,
                    "plan": best_c, "weight_copies": args.weight_copies},
+        "step_ms": {"median": float(np.median(per_step)), "p10": float(np.percentile(per_step, 10)),
+                    "p90": float(np.percentile(per_step, 90)), "min": float(per_step.min()),
+                    "max": float(per_step.max())},
         "iteration_roofline": {"t_ms": roof["t_roofline"] * 1e3, "bound": roof["bound"],
                                "flops": roof["flops"], "bytes": roof["bytes"], "T_R": roof["T_R"],
                                "frac": roof["t_roofline"] * 1e3 / ms_step,
@@ -212,6 +267,15 @@ def main():
                      "launches_per_step": launches_per_step, "avg_launch_ms": attn_ms_step / launches_per_step,
                      "algorithmic_bytes_per_step": attn_bytes_step},
     }
+    if chained is not None:
+        out["chained"] = chained
+    if peaks is not None:
+        # the same two fractions against what this device delivered in the register-only MFMA
+        # loop (varied operands) and the streaming read
+        t_meas = max(roof["flops"] / (peaks["mfma_bf16_tflops"] * 1e12), roof["bytes"] / (peaks["hbm_read_gbs"] * 1e9))
+        out["measured_peaks"] = dict(peaks, iteration_roofline_ms=t_meas * 1e3,
+                                     iteration_frac=t_meas * 1e3 / ms_step,
+                                     attention_frac=achieved / peaks["hbm_read_gbs"])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, case)
     print(json.dumps(out))

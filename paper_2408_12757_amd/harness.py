@@ -132,6 +132,20 @@ class DeviceCase:
         self._ws = r.workspace
         return out
 
+    def layer_pools(self, n_layers: int) -> "list[torch.Tensor]":
+        """KV pools for n_layers consecutive layers: the case's own pool first, then pools of
+        the same shape filled from the same seeded generator stream."""
+        pools = [self.pages]
+        gen = torch.Generator(device=self.device)
+        gen.manual_seed(self.cfg.seed + 7)
+        step = 1 << 14
+        for _ in range(1, n_layers):
+            p = torch.empty_like(self.pages)
+            for s in range(0, p.shape[0], step):
+                p[s:s + step].normal_(0.0, 1.0, generator=gen)
+            pools.append(p)
+        return pools
+
     def pages_of_requests(self, reqs) -> np.ndarray:
         """bf16 bits of the physical pages of the listed requests (device -> host)."""
         b = self.batch
