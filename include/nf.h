@@ -355,6 +355,79 @@ int nf_op_attention(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *
                     const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
                     void *workspace, size_t workspace_bytes, int nano_index, void *hip_stream);
 
+/* ---- continuous batching (Sec. 4.2.1 "Request scheduling"), host only ---------------------- */
+
+/*
+ * Forms the dense batch of every iteration the way the paper's runtime does: unfinished
+ * decode requests first (one token each), then prefill chunks cut at token granularity so
+ * that the batch holds exactly dense_batch tokens whenever enough prompt tokens are
+ * waiting; new requests are admitted only while the predicted peak of the page pool (every
+ * resident request running to the average output length) stays within the pool; if the
+ * pool still runs out, a decode request is swapped out (its pages are to be copied to the
+ * host by the caller) and brought back later without recomputation.  The scheduler owns
+ * the request states and the page allocator (page ids are shared by all layers' pools);
+ * it never touches the GPU.  End-of-sequence is the caller's news: nf_sched_complete(k)
+ * tells the scheduler that the outputs of iteration k are known, which lets the caller
+ * form iteration k + 1 before iteration k has finished (asynchronous scheduling: a
+ * request then decodes at most one token past its end).  The synthetic stand-in for
+ * "the model emitted EOS" is the request's output_len.
+ */
+typedef struct nf_sched nf_sched;
+typedef struct {
+  int32_t dense_batch;     /* tokens per iteration */
+  int32_t page_size;       /* tokens per page */
+  int64_t num_pages;       /* pages in (each layer's) pool */
+  int32_t max_requests;    /* most requests resident at once */
+  int32_t max_chunk;       /* longest prefill chunk of one request per iteration; 0 = no limit */
+  int32_t reserve_pages;   /* pages the memory prediction keeps free */
+  float avg_decode_len;    /* prior of the average output length (weight: 16 requests) */
+} nf_sched_config;
+
+/* One formed batch.  All arrays are host memory owned by the scheduler and stay valid
+ * until the next nf_sched_next_batch / nf_sched_destroy.  The first four arrays have the
+ * meaning and order of nf_batch (prefill entries first, then decode entries). */
+typedef struct {
+  int64_t iteration;
+  int32_t n_tokens, n_prefill_reqs, n_decode_reqs;
+  const int32_t *q_indptr, *ctx_len, *page_indptr, *page_ids;
+  const int64_t *request_ids;      /* [n_reqs] */
+  /* requests swapped out before this iteration runs: copy pages
+   * swap_out_pages[swap_out_indptr[i] .. swap_out_indptr[i+1]) of every layer to the host
+   * (they are reused from this iteration on) */
+  int32_t n_swap_out;
+  const int64_t *swap_out_req;
+  const int32_t *swap_out_indptr, *swap_out_pages;
+  /* requests brought back: copy their saved pages, in order, into these page ids */
+  int32_t n_swap_in;
+  const int64_t *swap_in_req;
+  const int32_t *swap_in_indptr, *swap_in_pages;
+  /* swapped-out requests that turned out to be finished: their host copies can be dropped */
+  int32_t n_released;
+  const int64_t *released_req;
+} nf_sched_batch;
+
+typedef struct {
+  int64_t iterations_formed, iterations_completed;
+  int64_t submitted, finished, waiting, resident, swapped;
+  int64_t prefill_tokens, decode_tokens, wasted_decode_tokens; /* scheduled so far; wasted = past EOS */
+  int64_t swap_outs, swap_ins;
+  int64_t free_pages;
+  double avg_decode_len;
+} nf_sched_stats;
+
+int nf_sched_create(const nf_sched_config *cfg, nf_sched **out);
+void nf_sched_destroy(nf_sched *s);
+/* Queues a request of prompt_len >= 1 prompt tokens that ends with its output_len-th
+ * (>= 1) generated token.  NF_EPAGES if it could never fit the pool. */
+int nf_sched_submit(nf_sched *s, int32_t prompt_len, int32_t output_len, int64_t *request_id);
+/* Forms the next iteration's batch (n_tokens may be below dense_batch, or 0, when work or
+ * memory is short). */
+int nf_sched_next_batch(nf_sched *s, nf_sched_batch *out);
+/* The outputs of iteration `iteration` are known; iterations complete in order
+ * (NF_EINVAL otherwise).  Retires the requests that emitted their last token. */
+int nf_sched_complete(nf_sched *s, int64_t iteration);
+int nf_sched_get_stats(const nf_sched *s, nf_sched_stats *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,8 @@ EXPORTS = [
     "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_workspace_region", "nf_layer_forward",
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
     "nf_layers_workspace_bytes", "nf_layers_forward",
+    "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
+    "nf_sched_get_stats",
 ]
 
 
@@ -381,3 +383,107 @@ def nf_op_attention(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Pl
     _check(lib().nf_op_attention(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle, qkv_ptr,
                                  attn_out_ptr, workspace_ptr, int(workspace_bytes), int(nano_index), stream),
            "nf_op_attention", ctx)
+
+
+# ------------------------------------------------------------ continuous batching ---
+
+class nf_sched_config(C.Structure):
+    _fields_ = [("dense_batch", C.c_int32), ("page_size", C.c_int32), ("num_pages", C.c_int64),
+                ("max_requests", C.c_int32), ("max_chunk", C.c_int32), ("reserve_pages", C.c_int32),
+                ("avg_decode_len", C.c_float)]
+
+
+class nf_sched_batch(C.Structure):
+    _I32P, _I64P = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    _fields_ = [("iteration", C.c_int64), ("n_tokens", C.c_int32), ("n_prefill_reqs", C.c_int32),
+                ("n_decode_reqs", C.c_int32), ("q_indptr", _I32P), ("ctx_len", _I32P), ("page_indptr", _I32P),
+                ("page_ids", _I32P), ("request_ids", _I64P),
+                ("n_swap_out", C.c_int32), ("swap_out_req", _I64P), ("swap_out_indptr", _I32P),
+                ("swap_out_pages", _I32P),
+                ("n_swap_in", C.c_int32), ("swap_in_req", _I64P), ("swap_in_indptr", _I32P), ("swap_in_pages", _I32P),
+                ("n_released", C.c_int32), ("released_req", _I64P)]
+
+
+class nf_sched_stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "iterations_formed", "iterations_completed", "submitted", "finished", "waiting", "resident", "swapped",
+        "prefill_tokens", "decode_tokens", "wasted_decode_tokens", "swap_outs", "swap_ins", "free_pages")] + [
+        ("avg_decode_len", C.c_double)]
+
+
+def _np_from(ptr, n, dtype):
+    if n <= 0:
+        return np.zeros(0, dtype)
+    return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dtype, copy=True)
+
+
+class FormedBatch:
+    """Host copy of one batch formed by the scheduler."""
+
+    def __init__(self, b: nf_sched_batch):
+        n = b.n_prefill_reqs + b.n_decode_reqs
+        self.iteration = int(b.iteration)
+        self.n_tokens, self.n_prefill_reqs, self.n_decode_reqs = int(b.n_tokens), int(b.n_prefill_reqs), int(b.n_decode_reqs)
+        self.q_indptr = _np_from(b.q_indptr, n + 1, np.int32)
+        self.ctx_len = _np_from(b.ctx_len, n, np.int32)
+        self.page_indptr = _np_from(b.page_indptr, n + 1, np.int32)
+        self.page_ids = _np_from(b.page_ids, int(self.page_indptr[-1]) if n else 0, np.int32)
+        self.request_ids = _np_from(b.request_ids, n, np.int64)
+
+        def groups(cnt, req, indptr, pages):
+            req = _np_from(req, cnt, np.int64)
+            ip = _np_from(indptr, cnt + 1, np.int32)
+            pg = _np_from(pages, int(ip[-1]) if cnt else 0, np.int32)
+            return [(int(req[i]), pg[ip[i]:ip[i + 1]].copy()) for i in range(cnt)]
+        self.swap_out = groups(b.n_swap_out, b.swap_out_req, b.swap_out_indptr, b.swap_out_pages)
+        self.swap_in = groups(b.n_swap_in, b.swap_in_req, b.swap_in_indptr, b.swap_in_pages)
+        self.released = [int(x) for x in _np_from(b.released_req, b.n_released, np.int64)]
+
+
+class Scheduler:
+    """Continuous-batching scheduler of the library (host only)."""
+
+    def __init__(self, dense_batch: int, page_size: int, num_pages: int, max_requests: int, max_chunk: int = 0,
+                 reserve_pages: int = 0, avg_decode_len: float = 256.0):
+        L = lib()
+        L.nf_sched_create.argtypes = [C.POINTER(nf_sched_config), C.POINTER(C.c_void_p)]
+        L.nf_sched_destroy.argtypes = [C.c_void_p]
+        L.nf_sched_destroy.restype = None
+        L.nf_sched_submit.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
+        L.nf_sched_next_batch.argtypes = [C.c_void_p, C.POINTER(nf_sched_batch)]
+        L.nf_sched_complete.argtypes = [C.c_void_p, C.c_int64]
+        L.nf_sched_get_stats.argtypes = [C.c_void_p, C.POINTER(nf_sched_stats)]
+        cfg = nf_sched_config(int(dense_batch), int(page_size), int(num_pages), int(max_requests), int(max_chunk),
+                              int(reserve_pages), float(avg_decode_len))
+        h = C.c_void_p()
+        _check(L.nf_sched_create(C.byref(cfg), C.byref(h)), "nf_sched_create")
+        self.handle = h
+
+    def submit(self, prompt_len: int, output_len: int) -> int:
+        rid = C.c_int64()
+        _check(lib().nf_sched_submit(self.handle, int(prompt_len), int(output_len), C.byref(rid)), "nf_sched_submit")
+        return int(rid.value)
+
+    def next_batch(self) -> FormedBatch:
+        b = nf_sched_batch()
+        _check(lib().nf_sched_next_batch(self.handle, C.byref(b)), "nf_sched_next_batch")
+        return FormedBatch(b)
+
+    def complete(self, iteration: int):
+        _check(lib().nf_sched_complete(self.handle, int(iteration)), "nf_sched_complete")
+
+    def stats(self) -> dict:
+        st = nf_sched_stats()
+        _check(lib().nf_sched_get_stats(self.handle, C.byref(st)), "nf_sched_get_stats")
+        return {n: getattr(st, n) for n, _ in nf_sched_stats._fields_}
+
+    def close(self):
+        if self.handle:
+            lib().nf_sched_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
