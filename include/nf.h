@@ -276,6 +276,8 @@ int nf_plan_manual(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batc
 /* Writes a JSON description of the plan into buf (host); returns the number of
  * bytes needed (excluding the terminator), or a negative status. */
 int nf_plan_describe(const nf_plan *plan, char *buf, size_t buf_len);
+/* Frees the plan.  The work enqueued with it must have completed: its device work lists go
+ * back to a small per-process pool (no device-wide wait) and may be rewritten by the next plan. */
 void nf_plan_destroy(nf_plan *plan);
 
 /* ---- the layer ------------------------------------------------------------------------------ */

@@ -65,6 +65,8 @@ struct nf_plan {
   hipEvent_t ev_fork = nullptr, ev_join[NF_LANES] = {nullptr, nullptr};
   // device work lists
   void* dev_blob = nullptr;
+  size_t dev_blob_bytes = 0;
+  int device = 0;
   int32_t* d_tok_req = nullptr;
   NfAttnItem* d_items = nullptr;
   NfAttnGroup* d_groups = nullptr;

@@ -5,9 +5,59 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "nf_internal.h"
+
+// Device buffers of destroyed plans are kept for the next plans instead of being returned to
+// the driver: hipFree waits for the whole device, which would stall a caller that forms the
+// next batch while the current iteration is still running (Sec. 4.2.1, asynchronous
+// scheduling).  A handful of buffers per process; the rest is freed.
+namespace {
+struct BlobPool {
+  struct Blob {
+    void* p;
+    size_t bytes;
+    int device;
+  };
+  std::mutex mu;
+  std::vector<Blob> free_list;
+  hipError_t acquire(int device, size_t bytes, void** out, size_t* got) {
+    {
+      std::lock_guard<std::mutex> g(mu);
+      int best = -1;
+      for (size_t i = 0; i < free_list.size(); ++i) {
+        const Blob& b = free_list[i];
+        if (b.device == device && b.bytes >= bytes && b.bytes <= 4 * bytes + (1u << 20) &&
+            (best < 0 || b.bytes < free_list[best].bytes))
+          best = (int)i;
+      }
+      if (best >= 0) {
+        *out = free_list[best].p;
+        *got = free_list[best].bytes;
+        free_list.erase(free_list.begin() + best);
+        return hipSuccess;
+      }
+    }
+    const size_t rounded = (bytes + bytes / 4 + 65535) & ~(size_t)65535;
+    *got = rounded;
+    return hipMalloc(out, rounded);
+  }
+  void release(int device, void* p, size_t bytes) {
+    {
+      std::lock_guard<std::mutex> g(mu);
+      if (free_list.size() < 16) {
+        free_list.push_back(Blob{p, bytes, device});
+        return;
+      }
+    }
+    (void)hipFree(p);
+  }
+};
+BlobPool g_blobs;
+}  // namespace
+
 
 size_t nf_align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -220,7 +270,8 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
   const size_t sz_items = nf_align256(std::max<size_t>(1, items.size()) * sizeof(NfAttnItem));
   const size_t sz_groups = nf_align256(std::max<size_t>(1, groups.size()) * sizeof(NfAttnGroup));
   NF_HIP(ctx, hipSetDevice(ctx->device));
-  NF_HIP(ctx, hipMalloc(&p->dev_blob, sz_tok + sz_items + sz_groups));
+  p->device = ctx->device;
+  NF_HIP(ctx, g_blobs.acquire(ctx->device, sz_tok + sz_items + sz_groups, &p->dev_blob, &p->dev_blob_bytes));
   char* base = (char*)p->dev_blob;
   p->d_tok_req = (int32_t*)base;
   p->d_items = (NfAttnItem*)(base + sz_tok);
@@ -305,7 +356,7 @@ extern "C" void nf_plan_destroy(nf_plan* p) {
   if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
   for (int l = 0; l < NF_LANES; ++l)
     if (p->ev_join[l]) (void)hipEventDestroy(p->ev_join[l]);
-  if (p->dev_blob) (void)hipFree(p->dev_blob);
+  if (p->dev_blob) g_blobs.release(p->device, p->dev_blob, p->dev_blob_bytes);
   delete p;
 }
 

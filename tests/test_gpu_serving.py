@@ -1,0 +1,140 @@
+"""The multi-layer iteration loop with continuous batching on the GPU against the oracle:
+the library's scheduler forms the batches, nf_layers_forward runs them on per-layer KV
+pools; the oracle side forms batches with its own scheduler model, keeps float pools and
+chains its plain layers.  Checked every iteration: the batch itself (bit-exact) and the
+layer output (tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_layer as orc
+from oracle.batch_formation import BatchFormation
+from paper_2408_12757_amd import binding as nf
+from paper_2408_12757_amd import harness as hz
+from paper_2408_12757_amd import serving
+from paper_2408_12757_amd import workloads as wl
+
+from gpu_util import DEV, REL_TOL, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+class OracleLoop:
+    """Float KV pools per layer + the oracle scheduler; swapping moves page contents."""
+
+    def __init__(self, model, weights, num_pages, **sched_kw):
+        self.m, self.w = model, weights
+        self.pools = [np.zeros((num_pages, model.page_elems)) for _ in weights]
+        self.sched = BatchFormation(page_size=model.page_size, num_pages=num_pages, **sched_kw)
+        self.store = {}
+        self.kidx, self.vidx = wl.page_block_index(model.head_dim, model.page_size)
+
+    def step(self, x_of):
+        b = self.sched.next_batch()
+        for rid in b["released"]:
+            self.store.pop(rid, None)
+        for rid, pages in b["swap_out"]:
+            self.store[rid] = [pool[pages].copy() for pool in self.pools]
+        for rid, pages in b["swap_in"]:
+            for pool, saved in zip(self.pools, self.store.pop(rid)):
+                pool[pages] = saved
+        if b["n_tokens"] == 0:
+            return b, None
+        ent = b["entries"]
+        q_lens = [e["q_len"] for e in ent]
+        batch = wl.Batch(n_tokens=b["n_tokens"], n_prefill_reqs=b["n_prefill"], n_decode_reqs=b["n_decode"],
+                         q_indptr=np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32),
+                         ctx_len=np.array([e["ctx_len"] for e in ent], np.int32),
+                         page_indptr=np.concatenate([[0], np.cumsum([len(e["pages"]) for e in ent])]).astype(np.int32),
+                         page_ids=np.concatenate([e["pages"] for e in ent]).astype(np.int32),
+                         num_pages=self.pools[0].shape[0])
+        x = x_of(b["iteration"], b["n_tokens"])
+        z, ks, vs = orc.layers_forward(self.m, self.w, self.pools, batch, f64(x))
+        # append: this iteration's K/V rows go to their page slots in every layer's pool
+        P, Hkv, dh = self.m.page_size, self.m.n_kv_heads, self.m.head_dim
+        t = 0
+        for e in ent:
+            for j in range(e["q_len"]):
+                pos = e["ctx_len"] + j
+                page, slot = e["pages"][pos // P], pos % P
+                for pool, k, v in zip(self.pools, ks, vs):
+                    pg = pool[page].reshape(2, Hkv, P * dh)
+                    for h in range(Hkv):
+                        pg[0, h][self.kidx[slot]] = k[t, h]
+                        pg[1, h][self.vidx[slot]] = v[t, h]
+                t += 1
+        return b, z
+
+
+def run_case(ctx, n_layers, dense_batch, num_pages, max_requests, avg, lag, reqs, seed, expect_swaps):
+    m = wl.CONFIGS["C1"].model
+    weights = [wl.make_weights(m, seed + 10 * l) for l in range(n_layers)]
+    kw = dict(dense_batch=dense_batch, max_requests=max_requests, avg_decode_len=avg)
+    oracle = OracleLoop(m, weights, num_pages, **kw)
+    eng = serving.ServingEngine(m, n_layers, num_pages, dense_batch, max_requests, host_weights=weights, device=DEV,
+                                async_lag=lag, avg_decode_len=avg, zero_pools=True, ctx=ctx)
+    for p, o in reqs:
+        oracle.sched.submit(p, o)
+        eng.submit(p, o)
+
+    def x_bits(it, n):
+        return wl.make_x(n, m.hidden, seed + 1000 + it)
+
+    worst, n_swaps, it = 0.0, 0, 0
+    outs = []
+    while True:
+        fb, z = eng.step(lambda fb: hz.bf16_tensor(x_bits(fb.iteration, fb.n_tokens), DEV))
+        ob, zo = oracle.step(x_bits)
+        if it - lag >= 0:
+            oracle.sched.complete(it - lag)
+        # the batch itself
+        assert fb.n_tokens == ob["n_tokens"] and fb.n_prefill_reqs == ob["n_prefill"], it
+        assert [int(x) for x in fb.request_ids] == [e["rid"] for e in ob["entries"]], it
+        assert [int(x) for x in fb.ctx_len] == [e["ctx_len"] for e in ob["entries"]], it
+        if ob["entries"]:
+            assert [int(x) for x in fb.page_ids] == [p for e in ob["entries"] for p in e["pages"]], it
+        n_swaps += len(fb.swap_out)
+        outs.append((z, zo))
+        it += 1
+        st = eng.stats()
+        if fb.n_tokens == 0 and st["waiting"] + st["resident"] + st["swapped"] == 0:
+            break
+        assert it < 2000
+    eng.drain()
+    for k in range(max(0, it - lag), it):
+        oracle.sched.complete(k)
+    for i, (z, zo) in enumerate(outs):
+        if z is None:
+            continue
+        got = f64(hz.bf16_bits(z))
+        assert np.all(np.isfinite(got)), i
+        worst = max(worst, rel_err(got, zo))
+    print("iterations", it, "swap-outs", n_swaps, "worst rel err", worst, flush=True)
+    assert worst <= REL_TOL
+    st = eng.stats()
+    assert st["finished"] == len(reqs) and st["free_pages"] == num_pages
+    assert (n_swaps > 0) == expect_swaps
+    eng.close()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = nf.Context(0)
+    yield c
+    c.close()
+
+
+def test_iteration_loop_matches_oracle_with_late_end_of_sequence(ctx):
+    rng = np.random.default_rng(3)
+    reqs = [(int(rng.integers(3, 70)), int(rng.integers(1, 14))) for _ in range(28)]
+    run_case(ctx, n_layers=3, dense_batch=64, num_pages=400, max_requests=40, avg=8.0, lag=1, reqs=reqs, seed=51,
+             expect_swaps=False)
+
+
+def test_iteration_loop_with_swap_out_and_reload_matches_oracle(ctx):
+    """A pool that the optimistic prediction overfills: requests are swapped to the host and
+    come back into other pages; outputs still follow the oracle, whose requests never move."""
+    rng = np.random.default_rng(4)
+    reqs = [(int(rng.integers(8, 30)), int(rng.integers(30, 70))) for _ in range(14)]
+    run_case(ctx, n_layers=2, dense_batch=32, num_pages=40, max_requests=32, avg=3.0, lag=1, reqs=reqs, seed=77,
+             expect_swaps=True)
