@@ -29,7 +29,14 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C2", help="workload: C1..C3 (C2 = the headline configuration)")
+    ap.add_argument("--config", default="C2",
+                    help="workload: C1..C4 = one layer iteration (C2 = the headline configuration); C5 = the "
+                         "multi-layer iteration loop with continuous batching (own options below)")
+    ap.add_argument("--loop-layers", type=int, default=32, help="C5: decoder layers")
+    ap.add_argument("--loop-requests", type=int, default=4000, help="C5: synthetic requests")
+    ap.add_argument("--loop-pool-gb", type=float, default=200.0, help="C5: HBM given to the KV pools of all layers")
+    ap.add_argument("--loop-lag", type=int, default=1, help="C5: iterations by which end-of-sequence news is late")
+    ap.add_argument("--loop-max-iterations", type=int, default=0, help="C5: stop after this many iterations (0 = run the stream out)")
     ap.add_argument("--weight-copies", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -92,12 +99,98 @@ def cpu_baseline(cfg, case, n_decode_sample: int = 448):
                       f"{b.n_decode_reqs} decode requests ({parts[1]:.1f} s, scaled x{scale:.1f}); numpy float64"}
 
 
+def run_loop(args):
+    """Configuration C5: LLaMA-3-8B layers in sequence, continuous batching at a dense batch of
+    2048 tokens over a synthetic request stream; steady-state tokens/s."""
+    import numpy as np
+    import torch
+
+    from paper_2408_12757_amd import binding as nf
+    from paper_2408_12757_amd import costmodel as cm
+    from paper_2408_12757_amd import serving
+    from paper_2408_12757_amd import workloads as wl
+
+    nf.lib()
+    m = wl.CONFIGS["C2"].model
+    L, B = args.loop_layers, 2048
+    page_bytes = m.page_elems * 2
+    num_pages = int(args.loop_pool_gb * 1e9 / L / page_bytes)
+    reqs = wl.make_request_stream(args.loop_requests, seed=5000)
+    eng = serving.ServingEngine(m, L, num_pages, B, max_requests=4096, weight_seed=5100, async_lag=args.loop_lag,
+                                avg_decode_len=float(np.mean([o for _, o in reqs])))
+    for p, o in reqs:
+        eng.submit(p, o)
+    x = torch.randn((B, m.hidden), device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(x)
+    marks, log = [], []
+    t0 = time.perf_counter()
+    while True:
+        fb, _ = eng.step(x, out)
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record(eng.stream)
+        st = eng.stats()
+        marks.append(ev)
+        log.append((fb.n_tokens, fb.n_decode_reqs, int(fb.ctx_len.sum()) if fb.n_tokens else 0, st["waiting"],
+                    len(fb.swap_out)))
+        if len(log) % 100 == 0:
+            print(f"iteration {len(log)}: decode {fb.n_decode_reqs} waiting {st['waiting']} free pages "
+                  f"{st['free_pages']} finished {st['finished']}", file=sys.stderr, flush=True)
+        done = st["waiting"] + st["resident"] + st["swapped"] == 0
+        if done or (args.loop_max_iterations and len(log) >= args.loop_max_iterations):
+            break
+    eng.drain()
+    wall = time.perf_counter() - t0
+    # steady state: full batches while requests are still waiting, minus the first tenth (ramp-up)
+    full = [i for i, r in enumerate(log) if r[0] == B and r[3] > 0]
+    lo = full[len(full) // 10] if full else 0
+    hi = full[-1] if full else len(log) - 1
+    ms = marks[lo].elapsed_time(marks[hi]) if hi > lo else float("nan")
+    tokens = sum(r[0] for r in log[lo + 1:hi + 1])
+    st = eng.stats()
+    it_ms = ms / max(1, hi - lo)
+    window = log[lo + 1:hi + 1]
+    out_json = {
+        "metric": "steady-state tokens/s of the multi-layer iteration loop with continuous batching (dense batch 2048)",
+        "value": tokens / (ms * 1e-3) if ms == ms else None, "unit": "tokens/s", "n_gpus": 1,
+        "steps": hi - lo, "warmup": lo, "ms_per_step": it_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"C5: {L} LLaMA-3-8B layers, {len(reqs)} requests (prompt lognormal median 512 max "
+                               f"4096, output lognormal median 256 max 2048), KV pools {num_pages} pages x {L} layers "
+                               f"= {num_pages * page_bytes * L / 1e9:.0f} GB, end-of-sequence seen {args.loop_lag} "
+                               "iteration(s) late; embedding, LM head and sampling not included",
+                   "dense_batch": B, "layers": L},
+        "loop": {"iterations": len(log), "wall_s": wall, "ms_per_layer_iteration": it_ms / L,
+                 "mean_decode_requests": float(np.mean([r[1] for r in window])) if window else None,
+                 "mean_cached_tokens": float(np.mean([r[2] for r in window])) if window else None,
+                 "generated_tokens_per_s": (sum(r[1] for r in window) / (ms * 1e-3)) if window and ms == ms else None,
+                 "swap_outs": st["swap_outs"], "wasted_decode_tokens": st["wasted_decode_tokens"],
+                 "finished": st["finished"], "prefill_tokens": st["prefill_tokens"],
+                 "decode_tokens": st["decode_tokens"]},
+    }
+    if window:
+        # roofline of the mean steady-state iteration: the layer costs at the mean cached-token count
+        mean_ctx = out_json["loop"]["mean_cached_tokens"]
+        kv_bytes = 2 * m.n_kv_heads * m.head_dim * 2 * mean_ctx
+        w_bytes = 2 * (m.n_qkv * m.hidden + m.q_dim * m.hidden + 3 * m.hidden * m.ffn_inner)
+        flops = 2 * B * (m.n_qkv * m.hidden + m.q_dim * m.hidden + 3 * m.hidden * m.ffn_inner) + \
+            4 * m.n_q_heads * m.head_dim * mean_ctx
+        t_roof = max(flops / cm.MI355X_PEAK_BF16_FLOPS, (kv_bytes + w_bytes) / cm.MI355X_PEAK_HBM_BPS)
+        out_json["iteration_roofline"] = {"t_ms_per_layer": t_roof * 1e3, "frac": t_roof * 1e3 / (it_ms / L),
+                                          "note": "weights + K/V of the mean cached-token count per layer; "
+                                                  "activations left out"}
+    print(json.dumps(out_json))
+    eng.close()
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build targets one GPU (no sharding, no collectives); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.config == "C5":
+        run_loop(args)
+        return
     import numpy as np
     import torch
 

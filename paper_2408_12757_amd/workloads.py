@@ -248,6 +248,18 @@ def batch_from_lengths(q_lens, ctx, n_prefill_reqs: int, rng: np.random.Generato
                  q_indptr, ctx, page_indptr, page_ids, num_pages)
 
 
+def make_request_stream(n_requests: int, seed: int, prompt_median: float = 512.0, prompt_max: int = 4096,
+                        output_median: float = 256.0, output_max: int = 2048) -> "list[tuple[int, int]]":
+    """Synthetic request stream of the 32-layer loop configuration: (prompt length, output
+    length) pairs, both lognormal with the given medians and the length spread used for the
+    contexts of the layer configurations, clipped to [1, max].  Stands in for the paper's
+    datasets (only their length statistics matter to the loop)."""
+    rng = np.random.default_rng(seed)
+    p = np.clip(np.rint(np.exp(rng.normal(np.log(prompt_median), LOGNORMAL_SIGMA, size=n_requests))), 1, prompt_max)
+    o = np.clip(np.rint(np.exp(rng.normal(np.log(output_median), LOGNORMAL_SIGMA, size=n_requests))), 1, output_max)
+    return [(int(a), int(b)) for a, b in zip(p, o)]
+
+
 def make_x(n_tokens: int, hidden: int, seed: int) -> np.ndarray:
     """Layer input activations, bf16 ~ N(0,1)."""
     return _normal_bf16(np.random.default_rng(seed), (n_tokens, hidden), 1.0)
