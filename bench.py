@@ -4,7 +4,12 @@ norms, KQV/O/gate-up/down GEMMs, rotary + KV append, paged decode + prefill atte
 nano-batched with overlap) over a synthetic dense batch of 2048 tokens at the
 LLaMA-3-8B layer shape, on one MI355X.
 
-Prints ONE JSON line (see the design doc for the meaning of every field).  Inputs are
+Prints ONE JSON line.  value = dense-batch tokens / step time; roofline = the attention
+kernel (the dominant one) against the published HBM bandwidth, measured with HIP events in
+the timed region; iteration_roofline = max(flops / peak MFMA, bytes / peak HBM) / step
+time; measured_peaks = the same fractions against ceilings measured on this device;
+ablation_ms / chained = unsplit, nano-batched and overlapped runs of one layer and of
+eight consecutive layers; cpu_baseline = the CPU oracle timed on a sample.  Inputs are
 resident in HBM before the timed region; weights rotate over several copies so that
 every step reads cold weights, and the KV pool (about 10 GB) is far larger than the
 caches.

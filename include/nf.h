@@ -17,7 +17,8 @@
  *   - The caller owns every device buffer it passes (weights, KV pages, batch
  *     arrays, activations, workspace).  The library owns only what its opaque
  *     handles hold (streams, events, the small device-side work lists of a
- *     plan) and frees it in the matching *_destroy call.
+ *     plan) and releases it in the matching *_destroy call (a plan's work
+ *     lists go back to a small per-process pool of device buffers).
  *   - Every function returns NF_OK (0) or a negative nf_status; nothing throws
  *     or aborts across the ABI.  Arguments are validated on the host (using the
  *     host mirrors in nf_batch) before anything is launched.

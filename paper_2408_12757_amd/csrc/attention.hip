@@ -33,10 +33,6 @@ struct PageRegs {
 };
 
 // Issues the loads of one page.  `page_base` is wave-uniform, so the loads take the
-// scalar-base + 32-bit lane offset form; a lane reads 16 bytes of one key per K step
-// (the 4 lanes of a key cover 64 contiguous bytes) and 8 bytes (4 keys of one
-// dimension) per V block (the wavefront covers 512 contiguous bytes).
-// Issues the loads of one page.  `page_base` is wave-uniform, so the loads take the
 // scalar-base + 32-bit lane offset form.  The page blocks are stored in MFMA operand order
 // (see the layout note in the C header), so every wavefront instruction reads 1 KiB of
 // contiguous memory: K step s is lanes x 16 bytes at s * 1024; V pair q (blocks 2q, 2q+1)

@@ -41,7 +41,7 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
                                  const int32_t* ctx_len, const int32_t* page_indptr, const int32_t* page_ids,
                                  int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
                                  float rope_theta, hipStream_t s);
-// tile: 0 = default, 1..4 = tile shape (see gemm.hip); all shapes give identical bits
+// tile: 0 = automatic, 1..19 = one implementation (see gemm.hip, gemm_dl.hip); all give identical bits
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                           int epilogue, int tile, hipStream_t s);
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
