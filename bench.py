@@ -293,6 +293,17 @@ def main():
     seq_ms, _ = timed(seq_plan, n_abl, 3)
     ovl_ms, _ = timed(ovl_plan, n_abl, 3)
 
+    # ---- simultaneous KV offload (Sec. 4.2.2): the fresh K/V rows leave for pinned host memory
+    # during the attention and FFN operations ----
+    row_bytes = 2 * m.n_kv_heads * m.head_dim * 2
+    host_rows = torch.empty(B * row_bytes, dtype=torch.uint8).pin_memory()
+    nf.nf_ctx_set_kv_offload(case.ctx, host_rows.data_ptr(), B * row_bytes)
+    try:
+        offload_ms, _ = timed(best_plan, n_abl, 3)
+    finally:
+        nf.nf_ctx_set_kv_offload(case.ctx, None)
+    plain_ms, _ = timed(best_plan, n_abl, 3)
+
     # ---- consecutive layers in one call: layer l's tail may overlap layer l + 1's head ----
     chained = None
     if args.chained_layers > 1:
@@ -357,6 +368,9 @@ def main():
                         "nano_overlapped": ovl_ms, "overlapped_attn_wgs": args.ablation_attn_wgs,
                         "speedup_overlapped_vs_sequential": seq_ms / ovl_ms,
                         "nano_batching_overhead": seq_ms / unsplit_ms - 1.0},
+        "kv_offload": {"ms_per_step": offload_ms, "ms_per_step_without": plain_ms,
+                       "slowdown": offload_ms / plain_ms - 1.0, "bytes_per_step": B * row_bytes,
+                       "note": "paper: 3.0 % slowdown on A100 (Sec. 6.4)"},
         "auto_search": {"profile_s": t_profile, "search_s": t_search, "searched": searched_c, "trial_run": verify},
         "roofline": {"bound": "hbm", "kernel": "attention_kernel<128>", "achieved": achieved,
                      "peak": cm.MI355X_PEAK_HBM_BPS / 1e9, "unit": "GB/s",

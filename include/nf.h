@@ -358,6 +358,21 @@ int nf_op_attention(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *
                     const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
                     void *workspace, size_t workspace_bytes, int nano_index, void *hip_stream);
 
+/*
+ * Simultaneous KV offload (Sec. 4.2.2 "Simultaneous offloading"): while it is switched on,
+ * every layer iteration copies the K row (after the rotary embedding) and the V row of every
+ * token of the batch, as they come out of KQV generation, to host memory, so that the host
+ * holds the same K/V as the cache.  The copy is issued by the GPU (a small kernel on a stream
+ * of the library) right after the KQV nano-operation and runs beside the attention and FFN
+ * operations; the call's work on hip_stream is complete only after the copies.
+ * host_rows: HOST memory the device can write (pinned, e.g. hipHostMalloc), 16-byte aligned;
+ *   layer l of a call writes row t (2 * n_kv_heads * head_dim bf16: K heads, then V heads) of
+ *   token t at host_rows + l * layer_stride_bytes + t * row bytes (l = 0 for nf_layer_forward).
+ *   A batch whose rows do not fit layer_stride_bytes is rejected with NF_EINVAL.
+ * host_rows = NULL switches the offload off.
+ */
+int nf_ctx_set_kv_offload(nf_ctx *ctx, void *host_rows /* host */, size_t layer_stride_bytes);
+
 /* ---- continuous batching (Sec. 4.2.1 "Request scheduling"), host only ---------------------- */
 
 /*

@@ -28,7 +28,7 @@ EXPORTS = [
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
-    "nf_sched_get_stats",
+    "nf_sched_get_stats", "nf_ctx_set_kv_offload",
 ]
 
 
@@ -309,6 +309,13 @@ def nf_measure_peaks(ctx: Context) -> dict:
     return {"mfma_bf16_tflops": pk.mfma_bf16_tflops,
             "mfma_bf16_tflops_zero_operands": pk.mfma_bf16_tflops_zero_operands,
             "hbm_read_gbs": pk.hbm_read_gbs, "n_cus": pk.n_cus}
+
+
+def nf_ctx_set_kv_offload(ctx: Context, host_ptr: Optional[int], layer_stride_bytes: int = 0):
+    """Switches the simultaneous KV offload on (host_ptr = address of pinned host memory) or off (None)."""
+    f = lib().nf_ctx_set_kv_offload
+    f.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+    _check(f(ctx.handle, host_ptr, int(layer_stride_bytes)), "nf_ctx_set_kv_offload", ctx)
 
 
 def nf_tune_set(key: str, value: int):

@@ -40,6 +40,8 @@ extern "C" void nf_ctx_destroy(nf_ctx* ctx) {
   }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
   for (auto& kv : ctx->streams) (void)hipStreamDestroy(kv.second);
+  for (hipEvent_t e : ctx->offload_events) (void)hipEventDestroy(e);
+  if (ctx->offload_stream) (void)hipStreamDestroy(ctx->offload_stream);
   nf_profile_free(ctx);
   delete ctx;
 }
@@ -122,6 +124,18 @@ extern "C" int nf_tune_set(const char* key, int value) {
     return NF_OK;
   }
   return NF_EINVAL;
+}
+
+extern "C" int nf_ctx_set_kv_offload(nf_ctx* ctx, void* host_rows, size_t layer_stride_bytes) {
+  if (!ctx) return NF_EINVAL;
+  if (host_rows && (layer_stride_bytes % 16 != 0 || ((uintptr_t)host_rows & 15) != 0)) return NF_EINVAL;
+  if (host_rows && !ctx->offload_stream) {
+    NF_HIP(ctx, hipSetDevice(ctx->device));
+    NF_HIP(ctx, hipStreamCreateWithFlags(&ctx->offload_stream, hipStreamNonBlocking));
+  }
+  ctx->offload_host = host_rows;
+  ctx->offload_layer_stride = host_rows ? layer_stride_bytes : 0;
+  return NF_OK;
 }
 
 // ---------------------------------------------------------------- workspace ---
@@ -312,7 +326,7 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       return traced(ctx, NF_K_ROPE_APPEND, op, s, [&] {
         return nf_launch_rope_append(a.ws.qkv, a.kv->pages, p->d_tok_req, a.b->q_indptr, a.b->ctx_len,
                                      a.b->page_indptr, a.b->page_ids, t0, op.tok_end, m->n_q_heads, m->n_kv_heads,
-                                     m->head_dim, m->rope_theta, s);
+                                     m->head_dim, m->rope_theta, ctx->offload_host != nullptr, s);
       });
     case NF_OP_ATTN: {
       const NfAttnShape shp{m->n_q_heads, m->n_kv_heads, m->head_dim, (int32_t)nqkv};
@@ -391,10 +405,53 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
 // layers own distinct KV pools.  Events alternate between two sets from layer to layer: a
 // hoisted KQV re-records its event before the late operations of the previous layer have
 // enqueued their waits.
+// Simultaneous KV offload (Sec. 4.2.2): right after the KQV nano-operation (rotary embedding
+// done, rows appended) the K and V parts of its qkv rows are copied to the host by a small
+// kernel on a stream of its own, so the copy runs during the attention and FFN operations
+// that follow.  `done` receives the event the copy records; whoever overwrites those qkv
+// rows next (the same range's KQV of the next layer) and the end of the call wait for it.
+struct Offload {
+  nf_ctx* ctx;
+  size_t cursor = 0;
+  bool on() const { return ctx->offload_host != nullptr; }
+  hipError_t event(hipEvent_t* e) {
+    if (cursor == ctx->offload_events.size()) {
+      hipEvent_t n = nullptr;
+      hipError_t r = hipEventCreateWithFlags(&n, hipEventDisableTiming);
+      if (r != hipSuccess) return r;
+      ctx->offload_events.push_back(n);
+    }
+    *e = ctx->offload_events[cursor++];
+    return hipSuccess;
+  }
+  hipError_t after_kqv(const NfNanoOp& op, const LayerArgs& a, int layer, hipStream_t s, hipEvent_t* done) {
+    hipEvent_t ready = nullptr;
+    hipError_t r = event(&ready);
+    if (r == hipSuccess) r = hipEventRecord(ready, s);
+    if (r == hipSuccess) r = hipStreamWaitEvent(ctx->offload_stream, ready, 0);
+    if (r == hipSuccess)
+      r = nf_launch_kv_offload(a.ws.qkv, (char*)ctx->offload_host + (size_t)layer * ctx->offload_layer_stride,
+                               op.tok_begin, op.tok_end, a.m->n_q_heads, a.m->n_kv_heads, a.m->head_dim,
+                               ctx->offload_stream);
+    if (r == hipSuccess) r = event(done);
+    if (r == hipSuccess) r = hipEventRecord(*done, ctx->offload_stream);
+    return r;
+  }
+};
+
 int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, hipStream_t user) {
+  Offload off{ctx};
+  std::vector<hipEvent_t> copied(p->ops.size(), nullptr);  // per KQV nano-op: its latest offload copy
   if (!p->overlap) {
     for (int l = 0; l < n_layers; ++l)
-      for (const NfNanoOp& op : p->ops) NF_HIP(ctx, launch_nano_op(ctx, p, op, a[l], user));
+      for (size_t i = 0; i < p->ops.size(); ++i) {
+        const NfNanoOp& op = p->ops[i];
+        if (op.kind == NF_OP_KQV && copied[i]) NF_HIP(ctx, hipStreamWaitEvent(user, copied[i], 0));
+        NF_HIP(ctx, launch_nano_op(ctx, p, op, a[l], user));
+        if (op.kind == NF_OP_KQV && off.on()) NF_HIP(ctx, off.after_kqv(op, a[l], l, user, &copied[i]));
+      }
+    for (hipEvent_t e : copied)
+      if (e) NF_HIP(ctx, hipStreamWaitEvent(user, e, 0));
     return NF_OK;
   }
   // fork: the lane streams start after everything already enqueued on the caller's stream
@@ -409,7 +466,9 @@ int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, 
       const std::vector<hipEvent_t>& pev = ((layer - 1) & 1) ? p->events_alt : p->events;
       NF_HIP(ctx, hipStreamWaitEvent(s, pev[after_prev_layer_op], 0));
     }
+    if (op.kind == NF_OP_KQV && copied[i]) NF_HIP(ctx, hipStreamWaitEvent(s, copied[i], 0));
     NF_HIP(ctx, launch_nano_op(ctx, p, op, a[layer], s));
+    if (op.kind == NF_OP_KQV && off.on()) NF_HIP(ctx, off.after_kqv(op, a[layer], layer, s, &copied[i]));
     if (op.record) NF_HIP(ctx, hipEventRecord(ev[i], s));
     return NF_OK;
   };
@@ -430,11 +489,13 @@ int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, 
       }
     }
   }
-  // join: the caller's stream continues after both lanes have drained
+  // join: the caller's stream continues after both lanes (and the offload copies) have drained
   for (int l = 0; l < NF_LANES; ++l) {
     NF_HIP(ctx, hipEventRecord(p->ev_join[l], p->lane_stream[l]));
     NF_HIP(ctx, hipStreamWaitEvent(user, p->ev_join[l], 0));
   }
+  for (hipEvent_t e : copied)
+    if (e) NF_HIP(ctx, hipStreamWaitEvent(user, e, 0));
   return NF_OK;
 }
 
@@ -474,6 +535,9 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
       memcmp(&plan->model, model, sizeof(nf_model_desc)) != 0)
     rc = NF_EPLAN;
   if (rc == NF_OK && workspace_bytes < nf_plan_workspace_bytes(plan)) rc = NF_EWORKSPACE;
+  if (rc == NF_OK && ctx->offload_host && ctx->offload_layer_stride != 0 &&
+      (size_t)batch->n_tokens * 2 * model->n_kv_heads * model->head_dim * 2 > ctx->offload_layer_stride)
+    rc = NF_EINVAL;
   if (rc == NF_OK) {
     LayerArgs a;
     a.m = model;
@@ -526,6 +590,8 @@ extern "C" int nf_layers_forward(nf_ctx* ctx, const nf_model_desc* model, int n_
       memcmp(&plan->model, model, sizeof(nf_model_desc)) != 0)
     return NF_EPLAN;
   if (workspace_bytes < nf_layers_workspace_bytes(plan, n_layers)) return NF_EWORKSPACE;
+  if (ctx->offload_host && (size_t)batch->n_tokens * 2 * model->n_kv_heads * model->head_dim * 2 > ctx->offload_layer_stride)
+    return NF_EINVAL;
   const size_t x_bytes = nf_align256((size_t)batch->n_tokens * model->hidden * 2);
   char* mid[2] = {(char*)workspace + nf_align256(nf_plan_workspace_bytes(plan)), nullptr};
   mid[1] = mid[0] + x_bytes;
@@ -573,7 +639,8 @@ extern "C" int nf_op_rope_append(nf_ctx* ctx, const nf_model_desc* model, nf_kv_
   if (tok_begin < 0 || tok_end > batch->n_tokens || tok_begin > tok_end) return NF_EINVAL;
   NF_HIP(ctx, nf_launch_rope_append(qkv, kv->pages, plan->d_tok_req, batch->q_indptr, batch->ctx_len,
                                     batch->page_indptr, batch->page_ids, tok_begin, tok_end, model->n_q_heads,
-                                    model->n_kv_heads, model->head_dim, model->rope_theta, (hipStream_t)hip_stream));
+                                    model->n_kv_heads, model->head_dim, model->rope_theta, 0,
+                                    (hipStream_t)hip_stream));
   return NF_OK;
 }
 

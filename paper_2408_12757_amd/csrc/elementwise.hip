@@ -1,6 +1,8 @@
 // Row-wise "other operations" of the decoder layer (paper Sec. 2.2): RMSNorm,
 // and rotary position embedding fused with the KV-cache append (Sec. 2.1: Key
 // and Value are concatenated into the existing KV cache).
+#include <algorithm>
+
 #include "nf_device.h"
 #include "nf_kernels.h"
 
@@ -66,7 +68,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
                                                           const int32_t* __restrict__ ctx_len,
                                                           const int32_t* __restrict__ page_indptr,
                                                           const int32_t* __restrict__ page_ids, int tok_begin,
-                                                          int Hq, int Hkv, int dh, RopeFreq freq) {
+                                                          int Hq, int Hkv, int dh, RopeFreq freq,
+                                                          int write_k_back) {
   const int t = tok_begin + blockIdx.x;
   const int r = tok_req[t];
   const int pos = ctx_len[r] + (t - q_indptr[r]);
@@ -115,6 +118,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
       bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh;
       *reinterpret_cast<u32x4*>(kb + (o * 16 + slot) * 8) = ra;
       *reinterpret_cast<u32x4*>(kb + ((octets + o) * 16 + slot) * 8) = rb;
+      if (write_k_back) {  // the offload copy takes the rotated K from the qkv row
+        *reinterpret_cast<u32x4*>(hv + 8 * o) = ra;
+        *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
+      }
     }
   }
   const bf16_t* vrow = row + (Hq + Hkv) * dh;
@@ -136,7 +143,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
 hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req, const int32_t* q_indptr,
                                  const int32_t* ctx_len, const int32_t* page_indptr, const int32_t* page_ids,
                                  int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
-                                 float rope_theta, hipStream_t s) {
+                                 float rope_theta, int write_k_back, hipStream_t s) {
   if (tok_end <= tok_begin) return hipSuccess;
   if (head_dim > 128 || head_dim % 16) return hipErrorInvalidValue;
   RopeFreq freq;
@@ -144,7 +151,7 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
     freq.f[i] = i < head_dim / 2 ? pow((double)rope_theta, -2.0 * (double)i / (double)head_dim) : 0.0;
   rope_append_kernel<<<dim3(tok_end - tok_begin), dim3(256), 0, s>>>(
       (bf16_t*)qkv, (bf16_t*)pages, tok_req, q_indptr, ctx_len, page_indptr, page_ids, tok_begin, n_q_heads,
-      n_kv_heads, head_dim, freq);
+      n_kv_heads, head_dim, freq, write_k_back);
   return hipGetLastError();
 }
 
@@ -176,5 +183,38 @@ hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float s
   const size_t want = (n_elems + 255) / 256;
   fill_random_kernel<<<dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, s>>>((bf16_t*)p, n_elems, seed,
                                                                                         stddev);
+  return hipGetLastError();
+}
+
+namespace {
+
+// Copies the K and V part of the qkv rows of tokens [tok_begin, tok_begin + n_tok) to rows
+// tok_begin.. of a host buffer the device can write (Sec. 4.2.2: the fresh K/V vectors are
+// contiguous right after KQV generation and leave the GPU through a copy the GPU itself
+// issues).  One 16-byte store per thread.
+__global__ __launch_bounds__(256) void kv_offload_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ host,
+                                                         int tok_begin, int n_tok, int n_qkv, int kv_first,
+                                                         int row_elems) {
+  const int chunks = row_elems / 8;
+  const long total = (long)n_tok * chunks;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    const int t = tok_begin + (int)(i / chunks), c = (int)(i % chunks);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(qkv + (size_t)t * n_qkv + kv_first + c * 8);
+    *reinterpret_cast<u32x4*>(host + (size_t)t * row_elems + c * 8) = v;
+  }
+}
+
+}  // namespace
+
+hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin, int tok_end, int n_q_heads,
+                                int n_kv_heads, int head_dim, hipStream_t s) {
+  if (tok_end <= tok_begin) return hipSuccess;
+  const int row_elems = 2 * n_kv_heads * head_dim;
+  const int n_qkv = (n_q_heads + 2 * n_kv_heads) * head_dim;
+  const long total = (long)(tok_end - tok_begin) * (row_elems / 8);
+  // a small grid on purpose: the copy is bound by the host link, not by the GPU
+  const int blocks = (int)std::min<long>(64, (total + 255) / 256);
+  kv_offload_kernel<<<dim3(blocks), dim3(256), 0, s>>>((const bf16_t*)qkv, (bf16_t*)host_rows, tok_begin,
+                                                       tok_end - tok_begin, n_qkv, n_q_heads * head_dim, row_elems);
   return hipGetLastError();
 }

@@ -47,6 +47,11 @@ struct nf_ctx {
   // lane streams keyed by (lane, first CU bit, CU count); count 0 = unmasked stream
   std::map<long, hipStream_t> streams;
   NfProfile* profile = nullptr;
+  // simultaneous KV offload (Sec. 4.2.2): device-writable host rows, stride between layers
+  void* offload_host = nullptr;
+  size_t offload_layer_stride = 0;
+  hipStream_t offload_stream = nullptr;
+  std::vector<hipEvent_t> offload_events;  // reused from call to call
 };
 
 struct nf_plan {

@@ -40,7 +40,11 @@ hipError_t nf_launch_rmsnorm(const void* x, const void* g, void* out, int n_toke
 hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req, const int32_t* q_indptr,
                                  const int32_t* ctx_len, const int32_t* page_indptr, const int32_t* page_ids,
                                  int tok_begin, int tok_end, int n_q_heads, int n_kv_heads, int head_dim,
-                                 float rope_theta, hipStream_t s);
+                                 float rope_theta, int write_k_back, hipStream_t s);
+// Copies the (rotated) K and V parts of qkv rows [tok_begin, tok_end) to the same rows of a
+// device-writable host buffer of 2 * n_kv_heads * head_dim elements per row.
+hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin, int tok_end, int n_q_heads,
+                                int n_kv_heads, int head_dim, hipStream_t s);
 // tile: 0 = automatic, 1..19 = one implementation (see gemm.hip, gemm_dl.hip); all give identical bits
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                           int epilogue, int tile, hipStream_t s);

@@ -235,7 +235,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     if (!rc)
       rc = time_ms(ctx, sg, 5, [&] {
         return nf_launch_rope_append(qkv, pool, plans[1]->d_tok_req, sb[1].d_q, sb[1].d_c, sb[1].d_pi, sb[1].d_pid, 0,
-                                     n_req, m->n_q_heads, m->n_kv_heads, m->head_dim, m->rope_theta, sg) == hipSuccess
+                                     n_req, m->n_q_heads, m->n_kv_heads, m->head_dim, m->rope_theta, 0, sg) == hipSuccess
                    ? NF_OK
                    : NF_EHIP;
       }, &t_rope);

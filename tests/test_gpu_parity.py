@@ -257,6 +257,42 @@ def test_layer_chain_rejects_bad_arguments(ctx):
     torch.cuda.synchronize()
 
 
+def test_kv_offload_delivers_the_appended_rows_and_changes_nothing_else(ctx):
+    """Simultaneous KV offload: the host receives, per layer and token, exactly the K row
+    (after the rotary embedding) and V row that the layer appended to its pool; outputs and
+    pools are the same bits as without the offload."""
+    cfg = wl.CONFIGS["C1"]
+    m = cfg.model
+    b = wl.make_batch(cfg.batch, cfg.seed + 2, spare_pages=5)
+    n_layers = 3
+    chain = ChainCase(m, b, cfg.seed, n_layers, ctx=ctx)
+    row = 2 * m.n_kv_heads * m.head_dim
+    stride = b.n_tokens * row * 2
+    tok = np.arange(b.n_tokens)
+    for bounds, overlap in (([0, 64], False), ([0, 20, 41, 64], True)):
+        plan = nf.nf_plan_manual(chain.ctx, m, chain.args, bounds, overlap, 0, 0)
+        z_ref, pools_ref = chain.run_chain(plan)
+        host = torch.full((n_layers, b.n_tokens, row), 7.0, dtype=torch.bfloat16).pin_memory()
+        nf.nf_ctx_set_kv_offload(chain.ctx, host.data_ptr(), stride)
+        try:
+            z, pools = chain.run_chain(plan)
+            # a stride too small for the batch is refused before anything runs
+            nf.nf_ctx_set_kv_offload(chain.ctx, host.data_ptr(), stride - 16)
+            with pytest.raises(nf.NfError) as e:
+                chain.run_chain(plan)
+            assert e.value.status == nf.NF_EINVAL
+        finally:
+            nf.nf_ctx_set_kv_offload(chain.ctx, None)
+        assert np.array_equal(z, z_ref)
+        got = hz.bf16_bits(host)
+        for l in range(n_layers):
+            assert np.array_equal(pools[l], pools_ref[l]), (bounds, l)
+            kg, vg = hz.read_kv_rows(pools[l], m, b, tok)
+            want = np.concatenate([kg.reshape(b.n_tokens, -1), vg.reshape(b.n_tokens, -1)], axis=1)
+            assert np.array_equal(got[l], want), (bounds, overlap, l)
+        plan.close()
+
+
 def test_plan_mismatch_and_workspace_errors(ctx):
     cfg = wl.CONFIGS["C1"]
     b = wl.make_batch(cfg.batch, cfg.seed + 2)
