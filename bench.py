@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--loop-requests", type=int, default=4000, help="C5: synthetic requests")
     ap.add_argument("--loop-pool-gb", type=float, default=200.0, help="C5: HBM given to the KV pools of all layers")
     ap.add_argument("--loop-lag", type=int, default=1, help="C5: iterations by which end-of-sequence news is late")
+    ap.add_argument("--loop-vocab", type=int, default=128256,
+                    help="C5: vocabulary of the embedding / LM head / greedy sampling around the layers "
+                         "(0 = feed synthetic activations and skip them)")
     ap.add_argument("--loop-max-iterations", type=int, default=0, help="C5: stop after this many iterations (0 = run the stream out)")
     ap.add_argument("--weight-copies", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -121,8 +124,9 @@ def run_loop(args):
     page_bytes = m.page_elems * 2
     num_pages = int(args.loop_pool_gb * 1e9 / L / page_bytes)
     reqs = wl.make_request_stream(args.loop_requests, seed=5000)
+    tp = serving.TokenPath(m, args.loop_vocab, B, 4096, "cuda:0", seed=5200) if args.loop_vocab > 0 else None
     eng = serving.ServingEngine(m, L, num_pages, B, max_requests=4096, weight_seed=5100, async_lag=args.loop_lag,
-                                avg_decode_len=float(np.mean([o for _, o in reqs])))
+                                avg_decode_len=float(np.mean([o for _, o in reqs])), token_path=tp)
     for p, o in reqs:
         eng.submit(p, o)
     x = torch.randn((B, m.hidden), device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
@@ -130,7 +134,7 @@ def run_loop(args):
     marks, log = [], []
     t0 = time.perf_counter()
     while True:
-        fb, _ = eng.step(x, out)
+        fb, _ = eng.step(None if tp is not None else x, out)
         ev = torch.cuda.Event(enable_timing=True)
         ev.record(eng.stream)
         st = eng.stats()
@@ -162,7 +166,9 @@ def run_loop(args):
         "config": {"workload": f"C5: {L} LLaMA-3-8B layers, {len(reqs)} requests (prompt lognormal median 512 max "
                                f"4096, output lognormal median 256 max 2048), KV pools {num_pages} pages x {L} layers "
                                f"= {num_pages * page_bytes * L / 1e9:.0f} GB, end-of-sequence seen {args.loop_lag} "
-                               "iteration(s) late; embedding, LM head and sampling not included",
+                               "iteration(s) late; " + (f"embedding, final norm, LM head and greedy sampling over a vocabulary of "
+                                                    f"{args.loop_vocab}" if tp is not None else
+                                                    "synthetic layer inputs, no embedding / LM head / sampling"),
                    "dense_batch": B, "layers": L},
         "loop": {"iterations": len(log), "wall_s": wall, "ms_per_layer_iteration": it_ms / L,
                  "mean_decode_requests": float(np.mean([r[1] for r in window])) if window else None,

@@ -358,6 +358,24 @@ int nf_op_attention(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *
                     const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
                     void *workspace, size_t workspace_bytes, int nano_index, void *hip_stream);
 
+/* ---- the ends of the iteration (Sec. 2.1: tokens enter through the embedding and leave through
+ * the LM head and sampling; Sec. 2.2 counts them among the "other operations") ------------- */
+
+/* out[t, :] = table[id(t), :] for t < n_rows, rows of `width` bf16 (width % 8 == 0), where
+ * id(t) = slot_tokens[from_slot[t]] if from_slot is given and from_slot[t] >= 0, else
+ * token_ids[t].  The indirection lets a decode token be the token the previous iteration
+ * sampled for its request without a trip to the host.  Ids outside [0, table_rows) are
+ * clamped.  With table = an activation matrix and token_ids = row numbers this is a row
+ * gather (the rows that need logits).  All pointers are device pointers. */
+int nf_op_embedding(const int32_t *token_ids, const int32_t *from_slot, const int32_t *slot_tokens,
+                    const void *table, int table_rows, void *out, int n_rows, int width, void *hip_stream);
+
+/* Greedy sampling: out[out_index ? out_index[r] : r] = index of the largest of the `vocab`
+ * bf16 logits of row r (vocab % 8 == 0), the lowest index among equal values.  The LM head
+ * itself is nf_op_rmsnorm followed by nf_op_gemm on the gathered rows. */
+int nf_op_argmax(const void *logits, int n_rows, int vocab, const int32_t *out_index, int32_t *out,
+                 void *hip_stream);
+
 /*
  * Simultaneous KV offload (Sec. 4.2.2 "Simultaneous offloading"): while it is switched on,
  * every layer iteration copies the K row (after the rotary embedding) and the V row of every
@@ -422,6 +440,9 @@ typedef struct {
   /* swapped-out requests that turned out to be finished: their host copies can be dropped */
   int32_t n_released;
   const int64_t *released_req;
+  /* requests retired (their last token seen) since the previous batch was formed */
+  int32_t n_finished;
+  const int64_t *finished_req;
 } nf_sched_batch;
 
 typedef struct {

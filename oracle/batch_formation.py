@@ -58,6 +58,7 @@ class BatchFormation:
         self.n_formed = self.n_completed = 0
         self.finished_outputs = []
         self.released_pending = []
+        self.finished_pending = []
         self.wasted = 0
 
     # ---- helpers -------------------------------------------------------------------
@@ -89,6 +90,7 @@ class BatchFormation:
     def next_batch(self):
         swap_out, swap_in = [], []
         released, self.released_pending = self.released_pending, []
+        finished, self.finished_pending = self.finished_pending, []
 
         # reload, oldest first
         while self.swapped and len(self.resident) < self.max_requests:
@@ -177,7 +179,7 @@ class BatchFormation:
         self.issued[self.n_formed] = issued
         batch = {"iteration": self.n_formed, "entries": entries, "n_prefill": len(prefill), "n_decode": len(decode),
                  "n_tokens": sum(e["q_len"] for e in entries), "swap_out": swap_out, "swap_in": swap_in,
-                 "released": released}
+                 "released": released, "finished": finished}
         self.n_formed += 1
         return batch
 
@@ -201,6 +203,7 @@ class BatchFormation:
                     self.swapped.remove(rid)
                     self.released_pending.append(rid)
                 r.where = "done"
+                self.finished_pending.append(rid)
                 self.finished_outputs.append(r.output)
                 del self.requests[rid]
         self.n_completed += 1

@@ -28,7 +28,7 @@ EXPORTS = [
     "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
-    "nf_sched_get_stats", "nf_ctx_set_kv_offload",
+    "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax",
 ]
 
 
@@ -311,6 +311,20 @@ def nf_measure_peaks(ctx: Context) -> dict:
             "hbm_read_gbs": pk.hbm_read_gbs, "n_cus": pk.n_cus}
 
 
+def nf_op_embedding(token_ids_ptr, from_slot_ptr, slot_tokens_ptr, table_ptr, table_rows, out_ptr, n_rows, width,
+                    stream=0):
+    f = lib().nf_op_embedding
+    f.argtypes = [C.c_void_p] * 4 + [C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    _check(f(token_ids_ptr, from_slot_ptr, slot_tokens_ptr, table_ptr, int(table_rows), out_ptr, int(n_rows),
+             int(width), stream), "nf_op_embedding")
+
+
+def nf_op_argmax(logits_ptr, n_rows, vocab, out_index_ptr, out_ptr, stream=0):
+    f = lib().nf_op_argmax
+    f.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(f(logits_ptr, int(n_rows), int(vocab), out_index_ptr, out_ptr, stream), "nf_op_argmax")
+
+
 def nf_ctx_set_kv_offload(ctx: Context, host_ptr: Optional[int], layer_stride_bytes: int = 0):
     """Switches the simultaneous KV offload on (host_ptr = address of pinned host memory) or off (None)."""
     f = lib().nf_ctx_set_kv_offload
@@ -408,7 +422,8 @@ class nf_sched_batch(C.Structure):
                 ("n_swap_out", C.c_int32), ("swap_out_req", _I64P), ("swap_out_indptr", _I32P),
                 ("swap_out_pages", _I32P),
                 ("n_swap_in", C.c_int32), ("swap_in_req", _I64P), ("swap_in_indptr", _I32P), ("swap_in_pages", _I32P),
-                ("n_released", C.c_int32), ("released_req", _I64P)]
+                ("n_released", C.c_int32), ("released_req", _I64P),
+                ("n_finished", C.c_int32), ("finished_req", _I64P)]
 
 
 class nf_sched_stats(C.Structure):
@@ -445,6 +460,7 @@ class FormedBatch:
         self.swap_out = groups(b.n_swap_out, b.swap_out_req, b.swap_out_indptr, b.swap_out_pages)
         self.swap_in = groups(b.n_swap_in, b.swap_in_req, b.swap_in_indptr, b.swap_in_pages)
         self.released = [int(x) for x in _np_from(b.released_req, b.n_released, np.int64)]
+        self.finished = [int(x) for x in _np_from(b.finished_req, b.n_finished, np.int64)]
 
 
 class Scheduler:

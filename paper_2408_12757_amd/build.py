@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(os.path.dirname(HERE), "_build")
 LIB = os.path.join(HERE, "libnanoflow.so")
 
-SOURCES = ["elementwise.hip", "gemm.hip", "gemm_dl.hip", "attention.hip", "moe.hip", "peaks.hip", "plan.cpp", "planner.cpp", "profile.cpp", "sched.cpp", "api.cpp"]
+SOURCES = ["elementwise.hip", "gemm.hip", "gemm_dl.hip", "attention.hip", "moe.hip", "token_path.hip", "peaks.hip", "plan.cpp", "planner.cpp", "profile.cpp", "sched.cpp", "api.cpp"]
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -667,3 +667,23 @@ extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf
                                         plan->group_cnt[nano_index], shp, attn_out, s));
   return NF_OK;
 }
+
+extern "C" int nf_op_embedding(const int32_t* token_ids, const int32_t* from_slot, const int32_t* slot_tokens,
+                               const void* table, int table_rows, void* out, int n_rows, int width,
+                               void* hip_stream) {
+  if (!token_ids || !table || !out || n_rows < 0 || table_rows < 1 || width < 8) return NF_EINVAL;
+  if ((from_slot != nullptr) != (slot_tokens != nullptr)) return NF_EINVAL;
+  if (width % 8) return NF_ESHAPE;
+  return nf_launch_gather_rows(token_ids, from_slot, slot_tokens, table, table_rows, out, n_rows, width,
+                               (hipStream_t)hip_stream) == hipSuccess
+             ? NF_OK
+             : NF_EHIP;
+}
+
+extern "C" int nf_op_argmax(const void* logits, int n_rows, int vocab, const int32_t* out_index, int32_t* out,
+                            void* hip_stream) {
+  if (!logits || !out || n_rows < 0 || vocab < 8) return NF_EINVAL;
+  if (vocab % 8) return NF_ESHAPE;
+  return nf_launch_argmax(logits, n_rows, vocab, out_index, out, (hipStream_t)hip_stream) == hipSuccess ? NF_OK
+                                                                                                        : NF_EHIP;
+}

@@ -64,6 +64,12 @@ hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int r
 hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                      const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                      long long w_stride, int variant, hipStream_t s);
+// Embedding / row gather and greedy sampling (token_path.hip)
+hipError_t nf_launch_gather_rows(const int32_t* token_ids, const int32_t* from_slot, const int32_t* slot_tokens,
+                                 const void* table, int n_rows_table, void* out, int n_rows, int width,
+                                 hipStream_t s);
+hipError_t nf_launch_argmax(const void* logits, int n_rows, int vocab, const int32_t* out_index, int32_t* out,
+                            hipStream_t s);
 // Mixture-of-experts helpers (moe.hip)
 hipError_t nf_launch_moe_router(const void* h, const void* w_router, int32_t* expert_ids, float* expert_w,
                                 int tok_begin, int tok_end, int hidden, int n_experts, int top_k, hipStream_t s);

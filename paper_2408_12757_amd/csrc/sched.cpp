@@ -57,7 +57,7 @@ struct nf_sched {
   // output arrays of the last batch
   std::vector<int32_t> q_indptr, ctx_len, page_indptr, page_ids;
   std::vector<int64_t> request_ids;
-  std::vector<int64_t> so_req, si_req, released, released_pending;
+  std::vector<int64_t> so_req, si_req, released, released_pending, finished, finished_pending;
   std::vector<int32_t> so_indptr, so_pages, si_indptr, si_pages;
 
   int32_t pages_for(int64_t tokens) const {
@@ -148,6 +148,8 @@ extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) {
   s->si_pages.clear();
   s->released.swap(s->released_pending);
   s->released_pending.clear();
+  s->finished.swap(s->finished_pending);
+  s->finished_pending.clear();
 
   // 1. bring swapped-out requests back, oldest first, while pages and the prediction allow
   while (!s->swapped.empty() && (int)s->resident.size() < c.max_requests) {
@@ -274,6 +276,8 @@ extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) {
   out->swap_in_pages = s->si_pages.data();
   out->n_released = (int32_t)s->released.size();
   out->released_req = s->released.data();
+  out->n_finished = (int32_t)s->finished.size();
+  out->finished_req = s->finished.data();
   return NF_OK;
 }
 
@@ -300,6 +304,7 @@ extern "C" int nf_sched_complete(nf_sched* s, int64_t iteration) {
         s->swapped.erase(std::find(s->swapped.begin(), s->swapped.end(), r.id));
         s->released_pending.push_back(r.id);
       }
+      s->finished_pending.push_back(r.id);
       s->n_finished++;
       s->sum_finished_output += r.output;
       s->st.finished++;

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import decoder_layer as orc
+from oracle import token_path as otp
 from oracle.batch_formation import BatchFormation
 from paper_2408_12757_amd import binding as nf
 from paper_2408_12757_amd import harness as hz
@@ -48,8 +49,8 @@ class OracleLoop:
                          page_indptr=np.concatenate([[0], np.cumsum([len(e["pages"]) for e in ent])]).astype(np.int32),
                          page_ids=np.concatenate([e["pages"] for e in ent]).astype(np.int32),
                          num_pages=self.pools[0].shape[0])
-        x = x_of(b["iteration"], b["n_tokens"])
-        z, ks, vs = orc.layers_forward(self.m, self.w, self.pools, batch, f64(x))
+        x = x_of(b)
+        z, ks, vs = orc.layers_forward(self.m, self.w, self.pools, batch, f64(x) if x.dtype == np.uint16 else x)
         # append: this iteration's K/V rows go to their page slots in every layer's pool
         P, Hkv, dh = self.m.page_size, self.m.n_kv_heads, self.m.head_dim
         t = 0
@@ -84,7 +85,7 @@ def run_case(ctx, n_layers, dense_batch, num_pages, max_requests, avg, lag, reqs
     outs = []
     while True:
         fb, z = eng.step(lambda fb: hz.bf16_tensor(x_bits(fb.iteration, fb.n_tokens), DEV))
-        ob, zo = oracle.step(x_bits)
+        ob, zo = oracle.step(lambda b: x_bits(b["iteration"], b["n_tokens"]))
         if it - lag >= 0:
             oracle.sched.complete(it - lag)
         # the batch itself
@@ -138,3 +139,77 @@ def test_iteration_loop_with_swap_out_and_reload_matches_oracle(ctx):
     reqs = [(int(rng.integers(8, 30)), int(rng.integers(30, 70))) for _ in range(14)]
     run_case(ctx, n_layers=2, dense_batch=32, num_pages=40, max_requests=32, avg=3.0, lag=1, reqs=reqs, seed=77,
              expect_swaps=True)
+
+
+def test_tokens_flow_through_embedding_layers_lm_head_and_sampling(ctx):
+    """Token path: embedding -> layers -> final norm -> LM head -> greedy sampling, the sampled
+    token feeding the request's next iteration on the device.  The sampling decision is taken
+    in the kernel's precision: the oracle is handed the GPU's tokens as the next inputs, and
+    every choice must be the float64 argmax or within the tolerance of it (a near-tie)."""
+    m = wl.CONFIGS["C1"].model
+    n_layers, B, num_pages, vocab, lag, seed = 2, 64, 300, 512, 1, 91
+    weights = [wl.make_weights(m, seed + 10 * l) for l in range(n_layers)]
+    tw = serving.make_token_weights(m, vocab, seed + 5)
+    rng = np.random.default_rng(8)
+    reqs = [(int(rng.integers(3, 50)), int(rng.integers(1, 10))) for _ in range(20)]
+    oracle = OracleLoop(m, weights, num_pages, dense_batch=B, max_requests=32, avg_decode_len=6.0)
+    tp = serving.TokenPath(m, vocab, B, 32, DEV, host=tw)
+    eng = serving.ServingEngine(m, n_layers, num_pages, B, 32, host_weights=weights, device=DEV, async_lag=lag,
+                                avg_decode_len=6.0, zero_pools=True, ctx=ctx, token_path=tp)
+    for p, o in reqs:
+        oracle.sched.submit(p, o)
+        eng.submit(p, o)
+    prompt = {i: p for i, (p, _) in enumerate(reqs)}
+    last_token = {}     # request -> token the GPU sampled for it last
+    exact = total = 0
+    worst_z = worst_gap = 0.0
+    it = 0
+    while True:
+        fb, z = eng.step()
+        eng.stream.synchronize()
+        slot_tokens = tp.slot_tokens.cpu().numpy()
+
+        def x_of(b):
+            ids = []
+            for e in b["entries"]:
+                if e["decode"]:
+                    ids.append(last_token[e["rid"]])
+                else:
+                    ids += [serving.prompt_token(e["rid"], e["ctx_len"] + j, vocab) for j in range(e["q_len"])]
+            return otp.embedding(tw["embedding"], ids)
+        ob, zo = oracle.step(x_of)
+        if it - lag >= 0:
+            oracle.sched.complete(it - lag)
+        assert [int(x) for x in fb.request_ids] == [e["rid"] for e in ob["entries"]], it
+        if z is not None:
+            worst_z = max(worst_z, rel_err(f64(hz.bf16_bits(z)), zo))
+            # rows that produce a token, in batch order
+            t, rows, owners = 0, [], []
+            for e in ob["entries"]:
+                if e["decode"] or e["ctx_len"] + e["q_len"] == prompt[e["rid"]]:
+                    rows.append(t + e["q_len"] - 1)
+                    owners.append(e["rid"])
+                t += e["q_len"]
+            if rows:
+                logits = otp.lm_head_logits(zo[rows], tw["g_final"], tw["w_lm"], m.rms_eps)
+                best = otp.greedy(logits)
+                scale = np.max(np.abs(logits))
+                for r, rid in enumerate(owners):
+                    tok = int(slot_tokens[tp.slot_of[rid]]) if rid in tp.slot_of else None
+                    assert tok is not None and 0 <= tok < vocab
+                    gap = float(logits[r, best[r]] - logits[r, tok]) / scale
+                    worst_gap = max(worst_gap, gap)
+                    exact += int(tok == best[r])
+                    total += 1
+                    last_token[rid] = tok
+        it += 1
+        st = eng.stats()
+        if fb.n_tokens == 0 and st["waiting"] + st["resident"] + st["swapped"] == 0:
+            break
+        assert it < 1000
+    eng.drain()
+    print("iterations", it, "sampled", total, "equal to the float64 argmax", exact, "worst gap", worst_gap,
+          "worst z err", worst_z, flush=True)
+    assert worst_z <= REL_TOL and worst_gap <= REL_TOL
+    assert total == sum(o for _, o in reqs) + st["wasted_decode_tokens"] and exact >= 0.9 * total
+    eng.close()

@@ -163,7 +163,8 @@ def lib_batch_as_dict(fb):
                         "decode": i >= fb.n_prefill_reqs})
     return {"iteration": fb.iteration, "entries": entries, "n_prefill": fb.n_prefill_reqs, "n_decode": fb.n_decode_reqs,
             "n_tokens": fb.n_tokens, "swap_out": [(r, [int(x) for x in p]) for r, p in fb.swap_out],
-            "swap_in": [(r, [int(x) for x in p]) for r, p in fb.swap_in], "released": list(fb.released)}
+            "swap_in": [(r, [int(x) for x in p]) for r, p in fb.swap_in], "released": list(fb.released),
+            "finished": list(fb.finished)}
 
 
 CASES = [
