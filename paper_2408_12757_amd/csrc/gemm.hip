@@ -175,6 +175,8 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 // same order with the same MFMA, so the choice never changes an output bit.
 static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
+static int g_grouped_tile = 0;  // implementation of the grouped (mixture-of-experts) GEMM; 0 = automatic
+void nf_set_grouped_gemm_tile(int v) { g_grouped_tile = v; }
 
 // Timing-only ablations of the 128x128 kernel (results are wrong): 1 = no global loads in
 // the main loop, 2 = also no LDS writes, 3 = also no barriers.
@@ -243,9 +245,10 @@ hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int r
   const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
-  // the process-wide tuning override also selects the grouped implementation (1 = staged through registers)
-  const int tile = g_gemm_tile ? g_gemm_tile : 12;
-  if (tile == 7 || tile == 9 || tile == 11 || tile == 12)
+  // 256x256 tiles halve the re-reads of the gathered rows; 256x128 where the width does not allow them
+  int tile = g_grouped_tile ? g_grouped_tile : (n_eff % 256 == 0 ? 13 : 19);
+  if (tile == 13 && n_eff % 256 != 0) tile = 19;
+  if (tile == 7 || tile == 9 || tile == 11 || tile == 12 || tile == 13 || tile == 19)
     return nf_launch_gemm_dl_grouped(x, w, out, rows, N, K, epilogue, expert_offset, row_index, n_experts, w_stride,
                                      tile, s);
   return launch<128, 128, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);

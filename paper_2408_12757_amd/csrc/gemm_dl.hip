@@ -428,7 +428,7 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
   }
 }
 
-// Grouped mode (see GroupedArgs): 7 / 11 = 128x128 tiles, 9 / 12 = 256x128 tiles.
+// Grouped mode (see GroupedArgs): 7 / 11 = 128x128 tiles, 9 / 12 / 19 = 256x128 tiles, 13 = 256x256 tiles.
 hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                      const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                      long long w_stride, int variant, hipStream_t s) {
@@ -438,6 +438,8 @@ hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, in
     case 9: return launch_dl<256, 128, 4, 2, 3, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     case 11: return launch_dl<128, 128, 2, 2, 2, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     case 12: return launch_dl<256, 128, 4, 2, 3, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 13: return launch_dl<256, 256, 2, 4, 2, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 19: return launch_dl2<256, 128, 4, 2, 3, true, 64>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     default: return hipErrorInvalidValue;
   }
 }

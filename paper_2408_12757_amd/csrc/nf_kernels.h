@@ -58,6 +58,7 @@ hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* grou
 hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float stddev, hipStream_t s);
 void nf_set_attention_variant(int v);
 void nf_set_gemm_tile(int v);
+void nf_set_grouped_gemm_tile(int v);
 hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                   const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                   long long w_stride, hipStream_t s);
