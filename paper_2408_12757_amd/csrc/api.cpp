@@ -12,7 +12,7 @@
 
 // ------------------------------------------------------------------ context ---
 
-extern "C" int nf_ctx_create(int device, nf_ctx** out) {
+extern "C" int nf_ctx_create(int device, nf_ctx** out) try {
   if (!out) return NF_EINVAL;
   *out = nullptr;
   int count = 0;
@@ -30,6 +30,10 @@ extern "C" int nf_ctx_create(int device, nf_ctx** out) {
   c->num_cus = prop.multiProcessorCount;
   *out = c;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" void nf_ctx_destroy(nf_ctx* ctx) {
@@ -248,7 +252,7 @@ extern "C" int nf_ctx_set_trace(nf_ctx* ctx, int level) {
   return NF_OK;
 }
 
-extern "C" int nf_ctx_read_trace(nf_ctx* ctx, nf_trace_rec* recs, int max_recs) {
+extern "C" int nf_ctx_read_trace(nf_ctx* ctx, nf_trace_rec* recs, int max_recs) try {
   if (!ctx || max_recs < 0 || (max_recs > 0 && !recs)) return NF_EINVAL;
   const int n = (int)ctx->trace.size();
   for (int i = 0; i < n; ++i) {
@@ -265,6 +269,10 @@ extern "C" int nf_ctx_read_trace(nf_ctx* ctx, nf_trace_rec* recs, int max_recs) 
   }
   ctx->trace.clear();
   return n;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 // ----------------------------------------------------------------- executor ---
@@ -516,7 +524,7 @@ int check_weights(const nf_model_desc* model, const nf_layer_weights* w) {
 
 extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const nf_layer_weights* weights,
                                 nf_kv_cache* kv, const nf_batch* batch, const nf_plan* plan, const void* x_in,
-                                void* x_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                void* x_out, void* workspace, size_t workspace_bytes, void* hip_stream) try {
   if (!ctx || !weights || !kv || !batch) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
@@ -565,6 +573,10 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
     }
   }
   return rc;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" size_t nf_layers_workspace_bytes(const nf_plan* plan, int n_layers) {
@@ -576,7 +588,7 @@ extern "C" size_t nf_layers_workspace_bytes(const nf_plan* plan, int n_layers) {
 extern "C" int nf_layers_forward(nf_ctx* ctx, const nf_model_desc* model, int n_layers,
                                  const nf_layer_weights* weights, nf_kv_cache* kv, const nf_batch* batch,
                                  const nf_plan* plan, const void* x_in, void* x_out, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
+                                 size_t workspace_bytes, void* hip_stream) try {
   if (!ctx || !weights || !kv || !batch || !plan || n_layers < 1) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
@@ -613,6 +625,10 @@ extern "C" int nf_layers_forward(nf_ctx* ctx, const nf_model_desc* model, int n_
     a.ws = layout_workspace(model, batch->n_tokens, (size_t)std::max(1, plan->total_parts), (char*)workspace);
   }
   return run_layers(ctx, plan, args.data(), n_layers, (hipStream_t)hip_stream);
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 // --------------------------------------------------------- single operations ---

@@ -3,6 +3,7 @@
 // loop (all-zero and varied operands: the second is the power-limited rate activation-like
 // data allows) and a streaming read of a buffer far larger than the caches.
 #include <algorithm>
+#include <new>
 
 #include "nf_device.h"
 #include "nf_internal.h"
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const char* __restrict
 
 }  // namespace
 
-extern "C" int nf_measure_peaks(nf_ctx* ctx, nf_peaks* out) {
+extern "C" int nf_measure_peaks(nf_ctx* ctx, nf_peaks* out) try {
   if (!ctx || !out) return NF_EINVAL;
   NF_HIP(ctx, hipSetDevice(ctx->device));
   hipDeviceProp_t prop;
@@ -126,4 +127,8 @@ extern "C" int nf_measure_peaks(nf_ctx* ctx, nf_peaks* out) {
   if (buf) (void)hipFree(buf);
   if (sink) (void)hipFree(sink);
   return rc;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }

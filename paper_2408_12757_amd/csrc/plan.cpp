@@ -314,7 +314,7 @@ static int check_bounds(const nf_batch* batch, int n_nano, const int32_t* bounds
 
 extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int n_nano,
                               const int32_t* bounds, int overlap, int attn_cus, int gemm_cus, int attn_wgs,
-                              nf_plan** out) {
+                              nf_plan** out) try {
   if (!ctx || !out) return NF_EINVAL;
   *out = nullptr;
   int rc = nf_validate_model(model);
@@ -327,6 +327,11 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
     return NF_EINVAL;
   nf_plan* p = new (std::nothrow) nf_plan();
   if (!p) return NF_ENOMEM;
+  // released on every early exit, also when a container throws
+  struct Guard {
+    nf_plan* p;
+    ~Guard() { nf_plan_destroy(p); }
+  } guard{p};
   p->model = *model;
   p->bounds.assign(bounds, bounds + n_nano + 1);
   p->origin = "manual";
@@ -339,12 +344,14 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
   p->lane_cus[NF_LANE_GEMM] = gemm_cus;
   p->lane_cu_first[NF_LANE_GEMM] = (gemm_cus && attn_cus + gemm_cus <= ctx->num_cus) ? attn_cus : 0;
   rc = nf_plan_finalize(ctx, p, batch);
-  if (rc) {
-    nf_plan_destroy(p);
-    return rc;
-  }
+  if (rc) return rc;
+  guard.p = nullptr;
   *out = p;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" void nf_plan_destroy(nf_plan* p) {
@@ -365,7 +372,7 @@ static const char* kind_name(int k) {
   return (k >= 0 && k < NF_OP_KINDS) ? n[k] : "?";
 }
 
-extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) {
+extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) try {
   if (!p) return NF_EINVAL;
   std::string s = "{\"origin\": \"" + p->origin + "\", \"n_tokens\": " + std::to_string(p->n_tokens) +
                   ", \"overlap\": " + std::to_string(p->overlap) + ", \"bounds\": [";
@@ -389,4 +396,8 @@ extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) {
     buf[n] = 0;
   }
   return (int)s.size();
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }

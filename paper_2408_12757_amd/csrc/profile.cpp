@@ -384,7 +384,7 @@ const NfProfile* pick_profile(const nf_ctx* ctx, const nf_model_desc* m, int n_t
 }  // namespace
 
 extern "C" int nf_profile(nf_ctx* ctx, const nf_model_desc* model, int max_tokens, int granule,
-                          const char* cache_path) {
+                          const char* cache_path) try {
   if (!ctx || max_tokens < 1 || granule < 1) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
@@ -405,10 +405,14 @@ extern "C" int nf_profile(nf_ctx* ctx, const nf_model_desc* model, int max_token
   ctx->profile = p;
   if (cache_path) return nf_profile_save(*p, cache_path);
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
-                                  int max_nano, int granule, nf_pipeline_desc* out) {
+                                  int max_nano, int granule, nf_pipeline_desc* out) try {
   if (!out || granule < 1 || max_nano < 0) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
@@ -436,10 +440,14 @@ extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* ba
   out->est_us_stage1 = pl.est_us_stage1;
   out->est_us_unsplit = pl.est_us_unsplit;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" int nf_simulate_pipeline(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
-                                    int n_nano, const int32_t* bounds, int overlap, int rp_row, double* est_us) {
+                                    int n_nano, const int32_t* bounds, int overlap, int rp_row, double* est_us) try {
   if (!est_us || !bounds || n_nano < 1) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
@@ -461,10 +469,14 @@ extern "C" int nf_simulate_pipeline(const nf_model_desc* model, const nf_batch* 
   *est_us = nf_simulate(prof, in, std::vector<int>(bounds, bounds + n_nano + 1), overlap,
                         rp_row < 0 ? nullptr : &prof.rp[rp_row]);
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
-                                   int granule, nf_plan** out) {
+                                   int granule, nf_plan** out) try {
   if (!ctx || !out || granule < 1 || max_nano < 0) return NF_EINVAL;
   *out = nullptr;
   int rc = nf_validate_model(model);
@@ -496,4 +508,8 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
     op.gemm_tile = (pl.overlap && pl.gemm_tile) ? pl.gemm_tile : prof->dense_tile[dense][idx];
   }
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }

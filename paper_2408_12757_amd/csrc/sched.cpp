@@ -103,7 +103,7 @@ struct nf_sched {
   }
 };
 
-extern "C" int nf_sched_create(const nf_sched_config* cfg, nf_sched** out) {
+extern "C" int nf_sched_create(const nf_sched_config* cfg, nf_sched** out) try {
   if (!cfg || !out) return NF_EINVAL;
   *out = nullptr;
   if (cfg->dense_batch < 1 || cfg->page_size < 1 || cfg->num_pages < 1 || cfg->num_pages > INT32_MAX ||
@@ -117,11 +117,15 @@ extern "C" int nf_sched_create(const nf_sched_config* cfg, nf_sched** out) {
   for (int64_t i = 0; i < cfg->num_pages; ++i) s->free_pages[(size_t)i] = (int32_t)(cfg->num_pages - 1 - i);
   *out = s;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
 extern "C" void nf_sched_destroy(nf_sched* s) { delete s; }
 
-extern "C" int nf_sched_submit(nf_sched* s, int32_t prompt_len, int32_t output_len, int64_t* request_id) {
+extern "C" int nf_sched_submit(nf_sched* s, int32_t prompt_len, int32_t output_len, int64_t* request_id) try {
   if (!s || prompt_len < 1 || output_len < 1) return NF_EINVAL;
   // a request alone in the pool must fit with every token it can ever cache
   if (s->pages_for((int64_t)prompt_len + output_len) > s->cfg.num_pages - s->cfg.reserve_pages) return NF_EPAGES;
@@ -134,9 +138,13 @@ extern "C" int nf_sched_submit(nf_sched* s, int32_t prompt_len, int32_t output_l
   s->st.submitted++;
   if (request_id) *request_id = r.id;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
-extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) {
+extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) try {
   if (!s || !out) return NF_EINVAL;
   const nf_sched_config& c = s->cfg;
   const int32_t P = c.page_size;
@@ -279,9 +287,13 @@ extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) {
   out->n_finished = (int32_t)s->finished.size();
   out->finished_req = s->finished.data();
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
-extern "C" int nf_sched_complete(nf_sched* s, int64_t iteration) {
+extern "C" int nf_sched_complete(nf_sched* s, int64_t iteration) try {
   if (!s || iteration != s->n_completed || iteration >= s->n_formed) return NF_EINVAL;
   auto it = s->inflight.find(iteration);
   if (it == s->inflight.end()) return NF_EINVAL;
@@ -314,9 +326,13 @@ extern "C" int nf_sched_complete(nf_sched* s, int64_t iteration) {
   s->inflight.erase(it);
   s->n_completed++;
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
 
-extern "C" int nf_sched_get_stats(const nf_sched* s, nf_sched_stats* out) {
+extern "C" int nf_sched_get_stats(const nf_sched* s, nf_sched_stats* out) try {
   if (!s || !out) return NF_EINVAL;
   *out = s->st;
   out->iterations_formed = s->n_formed;
@@ -327,4 +343,8 @@ extern "C" int nf_sched_get_stats(const nf_sched* s, nf_sched_stats* out) {
   out->free_pages = (int64_t)s->free_pages.size();
   out->avg_decode_len = s->avg_decode_len();
   return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
 }
