@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--profile-cache", default=None, help="file to keep the kernel profile in (default: re-measure)")
     ap.add_argument("--ablation-attn-wgs", type=int, default=256,
                     help="persistent attention workgroups of the overlapped ablation run")
+    ap.add_argument("--rp-sensitivity", action="store_true",
+                    help="instead of the benchmark: measure the GEMM || attention resource mapping for every dense "
+                         "operation and several batch sizes and print its spread (Sec. 4.1.1, sensitivity analysis)")
     ap.add_argument("--chained-layers", type=int, default=8,
                     help="also time this many consecutive layers (distinct weights and KV pools) in one "
                          "nf_layers_forward call and report the time per layer; 0 = skip")
@@ -105,6 +108,86 @@ def cpu_baseline(cfg, case, n_decode_sample: int = 448):
     return {"value": b.n_tokens / t_full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{cfg.name}: all {b.n_prefill_reqs} prefill request(s) ({parts[0]:.1f} s) + {len(dec)} of "
                       f"{b.n_decode_reqs} decode requests ({parts[1]:.1f} s, scaled x{scale:.1f}); numpy float64"}
+
+
+def run_rp_sensitivity(args):
+    """Sec. 4.1.1 states that the R -> P mapping is consistent over GEMM shapes and batch sizes
+    (standard deviation within 5 % of the mean), which is what allows one table for every
+    operation.  This measures it here: each dense operation of the model at four batch sizes
+    runs back to back on one stream while the decode attention of the C2 batch runs on
+    another; P = stand-alone time / co-running time of each."""
+    import numpy as np
+    import torch
+
+    from paper_2408_12757_amd import binding as nf
+    from paper_2408_12757_amd import harness as hz
+    from paper_2408_12757_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.config if args.config in ("C2", "C3") else "C2"]
+    case = hz.DeviceCase(cfg, n_weight_copies=2, keep_host_weights=False)
+    m, B, dev = cfg.model, case.batch.n_tokens, case.device
+    D, I = m.hidden, m.ffn_inner
+    wt = [r.w.t for r in case.runners]
+    shapes = [("KQV", "w_qkv", m.n_qkv, D, nf.NF_EPI_NONE), ("O", "w_o", D, m.q_dim, nf.NF_EPI_RESIDUAL),
+              ("UpGate", "w_gate_up", I, D, nf.NF_EPI_SWIGLU), ("Down", "w_down", D, I, nf.NF_EPI_RESIDUAL)]
+    x = torch.randn((B, max(D, I)), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    res = torch.randn((B, max(D, m.n_qkv)), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((B, max(I, m.n_qkv)), device=dev, dtype=torch.bfloat16)
+    qkv = torch.randn((B, m.n_qkv), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    attn_out = torch.empty((B, m.q_dim), device=dev, dtype=torch.bfloat16)
+    s_g, s_a = torch.cuda.Stream(), torch.cuda.Stream()
+    rows = []
+    for wgs in (128, 256):
+        plan = nf.nf_plan_manual(case.ctx, m, case.args, [0, B], False, 0, 0, wgs)
+        ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+
+        def attn(stream):
+            nf.nf_op_attention(case.ctx, m, case.pages.data_ptr(), case.pages.shape[0], case.args, plan, qkv.data_ptr(),
+                               attn_out.data_ptr(), ws.data_ptr(), ws.numel(), 0, stream)
+
+        def timed(n_gemm, gemm, n_attn):
+            torch.cuda.synchronize()
+            e0, eg, ea = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            s_g.wait_event(e0)
+            s_a.wait_event(e0)
+            for i in range(max(n_gemm, n_attn)):
+                if i < n_gemm:
+                    gemm(i, s_g.cuda_stream)
+                if i < n_attn:
+                    attn(s_a.cuda_stream)
+            eg.record(s_g)
+            ea.record(s_a)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(eg) / max(1, n_gemm), e0.elapsed_time(ea) / max(1, n_attn)
+        timed(0, None, 2)  # warm-up
+        _, t_attn = timed(0, None, 6)
+        for name, key, N, K, epi in shapes:
+            for M in (B // 4, B // 2, 3 * B // 4, B):
+                def gemm(i, stream):
+                    w = wt[i % 2][key]
+                    nf.nf_op_gemm(x.data_ptr(), w.data_ptr(), out.data_ptr(), res.data_ptr(), M, N, K, epi, stream)
+                timed(2, gemm, 0)  # warm-up
+                t_g, _ = timed(8, gemm, 0)
+                # the kernel whose P is measured must run inside the other one's activity from
+                # start to end: GEMMs worth two attention launches beside eight attention launches,
+                # then three attention launches beside GEMMs worth eight
+                per_attn = max(1.0, t_attn / t_g)
+                tg_co, _ = timed(int(2 * per_attn) + 1, gemm, 8)
+                _, ta_co = timed(int(8 * per_attn) + 1, gemm, 3)
+                rows.append({"attn_wgs": wgs, "op": name, "M": M, "gemm_alone_ms": t_g, "attn_alone_ms": t_attn,
+                             "p_gemm": t_g / tg_co, "p_attn": t_attn / ta_co})
+        plan.close()
+    summary = {}
+    for wgs in (128, 256):
+        pg = np.array([r["p_gemm"] for r in rows if r["attn_wgs"] == wgs])
+        pa = np.array([r["p_attn"] for r in rows if r["attn_wgs"] == wgs])
+        summary[str(wgs)] = {"p_gemm_mean": float(pg.mean()), "p_gemm_std_over_mean": float(pg.std() / pg.mean()),
+                             "p_attn_mean": float(pa.mean()), "p_attn_std_over_mean": float(pa.std() / pa.mean()),
+                             "p_sum_mean": float((pg + pa).mean())}
+    print(json.dumps({"rp_sensitivity": summary, "pairs": rows,
+                      "note": "paper: standard deviation within 5 % of the mean over all GEMM shapes and 64 batch "
+                              "size combinations (A100)"}))
 
 
 def run_loop(args):
@@ -199,6 +282,9 @@ def main():
         print("bench.py: this build targets one GPU (no sharding, no collectives); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.rp_sensitivity:
+        run_rp_sensitivity(args)
+        return
     if args.config == "C5":
         run_loop(args)
         return
