@@ -383,7 +383,27 @@ def main():
     n_abl = max(10, args.steps // 4)
     unsplit_ms, _ = timed(unsplit_plan, n_abl, 3)
     seq_ms, _ = timed(seq_plan, n_abl, 3)
-    ovl_ms, _ = timed(ovl_plan, n_abl, 3)
+    # the overlapped structure under a few (attention share, GEMM implementation) pairs: the pair
+    # decides how the two kernels share the CUs (Sec. 4.1.1); the best one is reported
+    ovl_trials = []
+    for wgs, tile in ((args.ablation_attn_wgs, 0), (args.ablation_attn_wgs, 19), (192, 19), (128, 19), (192, 7)):
+        pl = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, True, 0, 0, wgs)
+        nf.nf_tune_set("gemm.tile", tile)
+        try:
+            t_ms, _ = timed(pl, max(8, n_abl // 2), 3)
+        finally:
+            nf.nf_tune_set("gemm.tile", 0)
+        ovl_trials.append({"attn_wgs": wgs, "gemm_tile": tile, "ms": t_ms})
+        pl.close()
+    best_trial = min(ovl_trials, key=lambda r: r["ms"])
+    ovl_plan.close()
+    ovl_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, True, 0, 0, best_trial["attn_wgs"])
+    ovl_tile = best_trial["gemm_tile"]
+    nf.nf_tune_set("gemm.tile", ovl_tile)
+    try:
+        ovl_ms, _ = timed(ovl_plan, n_abl, 3)
+    finally:
+        nf.nf_tune_set("gemm.tile", 0)
 
     # ---- simultaneous KV offload (Sec. 4.2.2): the fresh K/V rows leave for pinned host memory
     # during the attention and FFN operations ----
@@ -423,10 +443,16 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / reps / L
 
-        chained = {"layers": L, "unsplit_ms_per_layer": chain_ms(unsplit_plan),
-                   "nano_sequential_ms_per_layer": chain_ms(seq_plan),
-                   "nano_overlapped_ms_per_layer": chain_ms(ovl_plan), "structure": abl_bounds,
-                   "overlapped_attn_wgs": args.ablation_attn_wgs,
+        t_unsplit, t_seq = chain_ms(unsplit_plan), chain_ms(seq_plan)
+        nf.nf_tune_set("gemm.tile", ovl_tile)
+        try:
+            t_ovl = chain_ms(ovl_plan)
+        finally:
+            nf.nf_tune_set("gemm.tile", 0)
+        chained = {"layers": L, "unsplit_ms_per_layer": t_unsplit,
+                   "nano_sequential_ms_per_layer": t_seq,
+                   "nano_overlapped_ms_per_layer": t_ovl, "structure": abl_bounds,
+                   "overlapped_attn_wgs": best_trial["attn_wgs"], "overlapped_gemm_tile": ovl_tile,
                    "note": "one nf_layers_forward call over distinct weights and KV pools, time / layers; the "
                            "overlapped run pipelines nano-operations across the layer boundary"}
         del pools
@@ -457,7 +483,8 @@ def main():
                                "peaks": {"bf16_mfma_flops": cm.MI355X_PEAK_BF16_FLOPS,
                                          "hbm_bytes_per_s": cm.MI355X_PEAK_HBM_BPS}},
         "ablation_ms": {"structure": abl_bounds, "unsplit": unsplit_ms, "nano_sequential": seq_ms,
-                        "nano_overlapped": ovl_ms, "overlapped_attn_wgs": args.ablation_attn_wgs,
+                        "nano_overlapped": ovl_ms, "overlapped_attn_wgs": best_trial["attn_wgs"],
+                        "overlapped_gemm_tile": ovl_tile, "overlapped_trials": ovl_trials,
                         "speedup_overlapped_vs_sequential": seq_ms / ovl_ms,
                         "nano_batching_overhead": seq_ms / unsplit_ms - 1.0},
         "kv_offload": {"ms_per_step": offload_ms, "ms_per_step_without": plain_ms,
