@@ -378,6 +378,24 @@ def test_moe_layer_matches_oracle_and_is_split_invariant(ctx):
     plan1.close()
 
 
+def test_moe_layer_chain_is_bit_exact_with_separate_calls(ctx):
+    """Consecutive mixture-of-experts layers in one call (routing arrays and grouped-GEMM
+    offsets live in the shared workspace per nano-batch): same bits as layer-by-layer calls."""
+    m = moe_model()
+    b = wl.batch_from_lengths([40, 9] + [1] * 79, [0, 30] + list(np.random.default_rng(3).integers(5, 400, 79)), 2,
+                              np.random.default_rng(4), spare_pages=2)
+    chain = ChainCase(m, b, 4200, 3, ctx=ctx)
+    z_ref, pools_ref = chain.run_layer_by_layer()
+    for bounds, overlap in (([0, b.n_tokens], False), ([0, 64, 128], True), ([0, 16, 50, 128], True)):
+        plan = nf.nf_plan_manual(chain.ctx, m, chain.args, bounds, overlap)
+        for rep in range(2):
+            z, pools = chain.run_chain(plan)
+            assert np.array_equal(z, z_ref), (bounds, overlap, rep)
+            for l in range(3):
+                assert np.array_equal(pools[l], pools_ref[l]), (bounds, l)
+        plan.close()
+
+
 def test_moe_skewed_routing_and_empty_experts(ctx):
     # a router that sends every token to experts 5 and 1: six experts get no rows
     m = moe_model(n_experts=8, top_k=2)
