@@ -169,7 +169,10 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * per kernel are profiled).  key "attention.variant": 0..7 = pages in flight / occupancy /
  * load-hint trade-off of the attention kernel.  key "gemm.tile": 0 = automatic, 1..19 = force
  * one GEMM implementation (tile shape, LDS feeding scheme, main loop) for every dense
- * operation.  key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 = force
+ * operation.  key "search.layers": 1 (default) = the auto-search and nf_simulate_pipeline price
+ * one layer on its own; n in 2..16 = they price the time per layer of n consecutive layers
+ * pipelined across the layer boundaries, as nf_layers_forward runs them.
+ * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
  * (wrong results).  Apart from "gemm.debug", variants never change a result bit.
  * Returns NF_EINVAL for an unknown key or a value out of range.

@@ -35,14 +35,18 @@ def interp_dense(table: Sequence[float], granule: int, m: int) -> float:
 
 
 def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, overlap,
-             row: Optional[dict], dt: float = 0.02, misc=None) -> float:
+             row: Optional[dict], dt: float = 0.02, misc=None, layers: int = 1) -> float:
     """dense: dict op -> table of the best implementation; row: dict(p_gemm, p_attn,
     p_attn_solo[, p_gemm_solo][, dense]) or None.  A row that carries its own "dense" tables
     (the times of the GEMM implementation it was measured with) makes every GEMM of an
     overlapped pipeline run in that implementation: its table gives D, and the overlapped
     speed p_gemm (normalised to the best implementation) is re-expressed relative to it.
     misc: ((a, b), (a, b), (a, b)) fixed + per-token cost of the small kernels added to the KQV
-    stage, the O/Up/Gate/Down stage and the attention stage."""
+    stage, the O/Up/Gate/Down stage and the attention stage.
+    layers > 1: that many consecutive layers (the output of a layer is the next layer's input,
+    Sec. 2.1), pipelined across the layer boundary: on the compute resource the KQV
+    nano-operation of a range in layer l + 1 is launched right behind the O/Up/Gate/Down
+    nano-operation of that range in layer l; the total time is returned."""
     if overlap and row is not None and row.get("dense") is not None:
         dense = row["dense"]
         solo = row.get("p_gemm_solo", 1.0)
@@ -59,23 +63,33 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
             rest[-1] += misc[1][0] + misc[1][1] * m
             att[-1] += misc[2][0] + misc[2][1] * m
     if not overlap:
-        return sum(kqv) + sum(att) + sum(rest)
-    # launch order on the compute resource: all KQV nano-ops, then O+UG+D per nano-batch
-    compute = [("kqv", i) for i in range(n)] + [("rest", i) for i in range(n)]
-    memory = [("att", i) for i in range(n)]
-    work = {("kqv", i): kqv[i] for i in range(n)}
-    work.update({("att", i): att[i] for i in range(n)})
-    work.update({("rest", i): rest[i] for i in range(n)})
+        return (sum(kqv) + sum(att) + sum(rest)) * layers
+    # launch order on the compute resource: all KQV nano-ops of the first layer, then per layer
+    # O+UG+D of every nano-batch, each followed by the next layer's KQV of the same range
+    compute = [("kqv", i, 0) for i in range(n)]
+    memory = []
+    for l in range(layers):
+        for i in range(n):
+            compute.append(("rest", i, l))
+            if l + 1 < layers:
+                compute.append(("kqv", i, l + 1))
+        memory += [("att", i, l) for i in range(n)]
+    work = {}
+    for l in range(layers):
+        for i in range(n):
+            work[("kqv", i, l)] = kqv[i]
+            work[("att", i, l)] = att[i]
+            work[("rest", i, l)] = rest[i]
     done = set()
 
     def ready(op):
-        kind, i = op
+        kind, i, l = op
         if kind == "kqv":
-            return True
+            return True                     # the launch order already puts it behind its predecessor
         if kind == "rest":
-            return ("att", i) in done
+            return ("att", i, l) in done
         lo = req_start[bounds[i]]           # attention also reads K/V appended by earlier ranges
-        return all(("kqv", j) in done for j in range(i + 1) if bounds[j + 1] > lo)
+        return all(("kqv", j, l) in done for j in range(i + 1) if bounds[j + 1] > lo)
 
     t = 0.0
     ci = mi = 0

@@ -122,6 +122,11 @@ extern "C" int nf_tune_set(const char* key, int value) {
     nf_set_gemm_debug(value);
     return NF_OK;
   }
+  if (!strcmp(key, "search.layers")) {
+    if (value < 1 || value > 16) return NF_EINVAL;
+    nf_set_search_layers(value);
+    return NF_OK;
+  }
   if (!strcmp(key, "gemm.grouped_tile")) {
     if (value != 0 && value != 1 && value != 7 && value != 9 && value != 11 && value != 12 && value != 13 && value != 19)
       return NF_EINVAL;

@@ -173,8 +173,9 @@ struct SimOp {
 }  // namespace
 
 double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
-                   const NfRpRow* row) {
+                   const NfRpRow* row, int n_layers) {
   const int n = (int)bounds.size() - 1;
+  const int L = std::max(1, n_layers);
   std::vector<double> kqv(n), att(n), rest(n);
   // With a table row, every GEMM runs in the row's implementation: its own interference-free
   // time is the work, and its overlapped speed is relative to that implementation alone.
@@ -194,25 +195,34 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
   if (!overlap) {
     double t = 0;
     for (int i = 0; i < n; ++i) t += kqv[i] + att[i] + rest[i];
-    return t;
+    return t * L;
   }
-  // ops: KQV_i = i, ATTN_i = n + i, REST_i (O, Up/Gate, Down) = 2n + i
-  std::vector<SimOp> ops(3 * n);
-  for (int i = 0; i < n; ++i) {
-    ops[i] = SimOp{0, kqv[i], {}};
-    ops[n + i] = SimOp{1, att[i], {}};
-    ops[2 * n + i] = SimOp{0, rest[i], {n + i}};
-    // attention needs the K/V of its own tokens and of the earlier tokens of a prefill
-    // request it starts inside of
-    const int lo = in.req_start_of_tok.empty() ? bounds[i] : in.req_start_of_tok[bounds[i]];
-    for (int j = 0; j <= i; ++j)
-      if (bounds[j + 1] > lo) ops[n + i].deps.push_back(j);
-  }
+  // ops of layer l: KQV_i = 3nl + i, ATTN_i = 3nl + n + i, REST_i (O, Up/Gate, Down) = 3nl + 2n + i.
+  // Consecutive layers are pipelined as the executor does it: the KQV nano-operation of a range
+  // in layer l + 1 is launched right behind the O/Up/Gate/Down of that range in layer l.
+  std::vector<SimOp> ops((size_t)3 * n * L);
   std::vector<int> q[2];
-  for (int i = 0; i < n; ++i) q[0].push_back(i);
-  for (int i = 0; i < n; ++i) q[0].push_back(2 * n + i);
-  for (int i = 0; i < n; ++i) q[1].push_back(n + i);
-  std::vector<char> done(3 * n, 0);
+  for (int l = 0; l < L; ++l) {
+    const int base = 3 * n * l;
+    for (int i = 0; i < n; ++i) {
+      ops[base + i] = SimOp{0, kqv[i], {}};
+      ops[base + n + i] = SimOp{1, att[i], {}};
+      ops[base + 2 * n + i] = SimOp{0, rest[i], {base + n + i}};
+      // attention needs the K/V of its own tokens and of the earlier tokens of a prefill
+      // request it starts inside of
+      const int lo = in.req_start_of_tok.empty() ? bounds[i] : in.req_start_of_tok[bounds[i]];
+      for (int j = 0; j <= i; ++j)
+        if (bounds[j + 1] > lo) ops[base + n + i].deps.push_back(base + j);
+    }
+    if (l == 0)
+      for (int i = 0; i < n; ++i) q[0].push_back(i);
+    for (int i = 0; i < n; ++i) {
+      q[0].push_back(base + 2 * n + i);
+      if (l + 1 < L) q[0].push_back(base + 3 * n + i);
+    }
+    for (int i = 0; i < n; ++i) q[1].push_back(base + n + i);
+  }
+  std::vector<char> done(ops.size(), 0);
   size_t head[2] = {0, 0};
   double rem[2] = {0, 0};
   bool running[2] = {false, false};
@@ -259,6 +269,16 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
   return t;
 }
 
+// Time per layer of a long run of consecutive layers: the increment between one layer and
+// in.layers layers (the ramp-up of the first layer and the drain of the last drop out).
+double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
+                             int overlap, const NfRpRow* row) {
+  if (in.layers <= 1) return nf_simulate(prof, in, bounds, overlap, row, 1);
+  const double t1 = nf_simulate(prof, in, bounds, overlap, row, 1);
+  const double tl = nf_simulate(prof, in, bounds, overlap, row, in.layers);
+  return (tl - t1) / (in.layers - 1);
+}
+
 // ---------------------------------------------------------------------- search ---
 
 namespace {
@@ -286,7 +306,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   out->bounds = whole;
   out->overlap = 0;
   out->attn_wgs = 0;
-  out->est_us_unsplit = in.n_tokens ? nf_simulate(prof, in, whole, 0, nullptr) : 0.0;
+  out->est_us_unsplit = in.n_tokens ? nf_simulate_per_layer(prof, in, whole, 0, nullptr) : 0.0;
   out->est_us = out->est_us_stage1 = out->est_us_unsplit;
   const int max_n = in.max_nano > 0 ? std::min(in.max_nano, NF_MAX_NANO) : NF_MAX_NANO;
   if (max_n < 2 || in.n_tokens < 2 * in.granule) return NF_OK;
@@ -301,7 +321,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     std::vector<std::vector<int>> all;
     std::vector<int> cur = {0};
     enumerate(n, 0, in.n_tokens, in.granule, cur, all);
-    for (auto& b : all) cands.push_back(Cand{b, nf_simulate(prof, in, b, 1, nullptr)});
+    for (auto& b : all) cands.push_back(Cand{b, nf_simulate_per_layer(prof, in, b, 1, nullptr)});
   }
   if (cands.empty()) return NF_OK;
   // fewer nano-operations win ties: splitting costs batching efficiency (Sec. 4.1.2)
@@ -318,7 +338,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     const size_t n_rows = prof.rp.empty() ? 1 : prof.rp.size();
     for (size_t r = 0; r < n_rows; ++r) {
       const NfRpRow& row = prof.rp.empty() ? ideal : prof.rp[r];
-      const double t2 = nf_simulate(prof, in, cands[c].bounds, 1, &row);
+      const double t2 = nf_simulate_per_layer(prof, in, cands[c].bounds, 1, &row);
       if (t2 < best - 1e-9) {
         best = t2;
         out->bounds = cands[c].bounds;

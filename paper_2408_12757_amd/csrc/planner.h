@@ -60,6 +60,7 @@ struct NfSearchInput {
   int n_tokens = 0;
   int granule = 128;
   int max_nano = 0;                  // 0 = search up to NF_MAX_NANO
+  int layers = 1;                    // > 1: minimise the time per layer of that many consecutive layers
   std::vector<double> attn_mb_prefix;  // [n_tokens + 1] prefix sums of attention megabytes per token
   std::vector<int> req_start_of_tok;   // [n_tokens] first token of the request that owns token t
 };
@@ -80,6 +81,10 @@ constexpr int NF_MAX_NANO = 4;
 // interference (Stage I); otherwise overlapped GEMM and attention progress at p_gemm and
 // p_attn of their stand-alone speeds and attention alone at p_attn_solo (Stage II).
 double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
-                   const NfRpRow* row);
+                   const NfRpRow* row, int n_layers = 1);
+// The objective of the search: the makespan of one layer, or (in.layers > 1) the time per layer
+// of a run of consecutive layers pipelined across the layer boundaries.
+double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
+                             int overlap, const NfRpRow* row);
 // Two-stage search.  Returns NF_OK and fills `out`.
 int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out);

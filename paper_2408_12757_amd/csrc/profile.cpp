@@ -11,6 +11,12 @@
 #include "nf_internal.h"
 #include "planner.h"
 
+// Objective of the search: 1 = one layer on its own; n > 1 = time per layer of n consecutive
+// layers (process-wide tuning knob "search.layers").
+static int g_search_layers = 1;
+void nf_set_search_layers(int n) { g_search_layers = n; }
+int nf_search_layers() { return g_search_layers; }
+
 void nf_profile_free(nf_ctx* ctx) {
   delete ctx->profile;
   ctx->profile = nullptr;
@@ -357,6 +363,7 @@ void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano,
   in->n_tokens = b->n_tokens;
   in->granule = granule;
   in->max_nano = max_nano;
+  in->layers = nf_search_layers();
   in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
   in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
   const double tok_mb = 2.0 * m->n_kv_heads * m->head_dim * 2 / 1e6;
@@ -466,8 +473,8 @@ extern "C" int nf_simulate_pipeline(const nf_model_desc* model, const nf_batch* 
   if (rp_row >= (int)prof.rp.size()) return NF_EINVAL;
   NfSearchInput in;
   build_search_input(model, batch, 0, prof.granule, &in);
-  *est_us = nf_simulate(prof, in, std::vector<int>(bounds, bounds + n_nano + 1), overlap,
-                        rp_row < 0 ? nullptr : &prof.rp[rp_row]);
+  *est_us = nf_simulate_per_layer(prof, in, std::vector<int>(bounds, bounds + n_nano + 1), overlap,
+                                  rp_row < 0 ? nullptr : &prof.rp[rp_row]);
   return NF_OK;
 } catch (const std::bad_alloc&) {
   return NF_ENOMEM;

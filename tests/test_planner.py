@@ -181,6 +181,79 @@ def test_rows_carry_their_gemm_implementation_and_small_kernels_are_counted(tmp_
         assert got["gemm_tile"] == best_row["gemm_tile"]
 
 
+# ------------------------------------------------- consecutive layers ---
+
+def steady(dense, g, fixed, per_mb, pre, start, bounds, overlap, row, layers, dt=0.01, misc=None):
+    """Time per layer of a long run, from the oracle's total times of 1 and `layers` layers."""
+    t1 = pm.makespan(dense, g, fixed, per_mb, pre, start, bounds, overlap, row, dt=dt, misc=misc, layers=1)
+    tl = pm.makespan(dense, g, fixed, per_mb, pre, start, bounds, overlap, row, dt=dt, misc=misc, layers=layers)
+    return (tl - t1) / (layers - 1)
+
+
+@pytest.mark.parametrize("k,r,a", [(1.0, 3.0, 4.0), (1.0, 2.0, 6.0), (2.0, 6.0, 3.0), (1.0, 1.0, 1.0)])
+def test_oracle_layer_chain_reaches_the_closed_form_period(k, r, a):
+    """Two equal nano-batches, no interference.  Per layer the compute resource has 2 (k + r)
+    of work, the memory resource 2 a, and each range's own operations form a chain of
+    k + a + r that the next layer's KQV of that range has to wait for; a long run of layers
+    settles at the largest of the three per layer."""
+    g = 16
+    b = wl.batch_from_lengths([1] * 32, np.full(32, 1000), 0, np.random.default_rng(0))
+    pre, start = attn_prefix(MODEL, b)
+    dense = {"KQV": [10 * k, 20 * k], "O": [0.0, 0.0], "UG": [10 * r, 20 * r], "D": [0.0, 0.0]}
+    per_mb = 10 * a / (pre[16] - pre[0])
+    want = 10 * max(2 * (k + r), 2 * a, k + a + r)
+    got = steady(dense, g, 0.0, per_mb, pre, start, [0, 16, 32], True, None, layers=6)
+    assert got == pytest.approx(want, abs=0.2)
+    # one layer on its own is longer: nothing hides its first KQV and its last O/Up/Gate/Down
+    one = pm.makespan(dense, g, 0.0, per_mb, pre, start, [0, 16, 32], True, None, dt=0.01)
+    assert one >= want - 0.2
+    # sequential execution has no pipelining to gain from
+    assert steady(dense, g, 0.0, per_mb, pre, start, [0, 16, 32], False, None, layers=4) == pytest.approx(
+        10 * 2 * (k + r + a), abs=1e-6)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_layer_chain_objective_matches_the_oracle(tmp_path, seed):
+    """With search.layers = n the library prices the time per layer of n consecutive layers; the
+    simulator must agree with the oracle's model and the search with its brute force."""
+    r = np.random.default_rng(100 + seed)
+    g, n_gran, layers = 8, 4, 3
+    n_tok = g * n_gran
+    q_lens = [int(r.integers(3, 12))] + [1] * (n_tok - 0)
+    q_lens = q_lens[:1] + [1] * (n_tok - q_lens[0])
+    ctxs = [0] + list(r.integers(50, 3000, size=len(q_lens) - 1))
+    b = wl.batch_from_lengths(q_lens, ctxs, 1, r)
+    dense = {o: list(np.cumsum(r.uniform(4, 12, size=n_gran)) * s + r.uniform(2, 6))
+             for o, s in zip(OPS, (1.0, 0.7, 3.0, 1.5))}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = r.uniform(0.8, 2.5) * sum(sum(v) for v in dense.values()) / n_gran / pre[-1]
+    rows = table3_rows()
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows)
+    nf.nf_tune_set("search.layers", layers)
+    try:
+        for bounds in ([0, 16, 32], [0, 8, 32], [0, 8, 24, 32]):
+            for row_idx in (-1, 1, len(rows) - 1):
+                row = None if row_idx < 0 else rows[row_idx]
+                want = steady(dense, g, 2.0, per_mb, pre, start, bounds, True, row, layers)
+                got = nf.nf_simulate_pipeline(MODEL, host_batch(b), bounds, True, row_idx, path)
+                assert got == pytest.approx(want, rel=2e-3, abs=0.2), (bounds, row_idx)
+        got = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=3, granule=g)
+    finally:
+        nf.nf_tune_set("search.layers", 1)
+    best = steady(dense, g, 2.0, per_mb, pre, start, [0, n_tok], False, None, layers)
+    assert got["est_us_unsplit"] == pytest.approx(best, rel=1e-6)
+    for n in (2, 3):
+        for bd in pm.all_bounds(n_tok, g, n):
+            for row in rows:
+                best = min(best, steady(dense, g, 2.0, per_mb, pre, start, bd, True, row, layers))
+    assert got["est_us"] == pytest.approx(best, rel=3e-3, abs=0.3)
+    # back at the default the same call prices a single layer again
+    one = nf.nf_simulate_pipeline(MODEL, host_batch(b), [0, 16, 32], True, -1, path)
+    assert one == pytest.approx(pm.makespan(dense, g, 2.0, per_mb, pre, start, [0, 16, 32], True, None, dt=0.01),
+                                rel=2e-3, abs=0.2)
+
+
 def test_search_never_returns_a_pipeline_slower_than_unsplit(tmp_path):
     # heavy interference: overlapping is useless, the search must fall back to the unsplit layer
     g = 16
