@@ -449,7 +449,35 @@ def main():
             t_ovl = chain_ms(ovl_plan)
         finally:
             nf.nf_tune_set("gemm.tile", 0)
-        chained = {"layers": L, "unsplit_ms_per_layer": t_unsplit,
+        # the auto-search with the time per layer of L consecutive layers as its objective; the
+        # model's ranking of the R -> P rows is then refined by trial runs of its best candidates
+        trials, best_chain = [], None
+        for rank in range(6):
+            nf.nf_tune_set("search.layers", L)
+            nf.nf_tune_set("search.rank", rank)
+            try:
+                pl = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
+            finally:
+                nf.nf_tune_set("search.layers", 1)
+                nf.nf_tune_set("search.rank", 0)
+            d = pl.describe()
+            rec = {k: d[k] for k in ("bounds", "overlap", "attn_wgs", "est_time_us")}
+            if any(t["bounds"] == rec["bounds"] and t["attn_wgs"] == rec["attn_wgs"] and
+                   abs(t["est_time_us"] - rec["est_time_us"]) < 1e-6 for t in trials):
+                pl.close()
+                continue
+            rec["ms_per_layer"] = chain_ms(pl, reps=3)
+            trials.append(rec)
+            if best_chain is None or rec["ms_per_layer"] < best_chain[0]["ms_per_layer"]:
+                if best_chain is not None:
+                    best_chain[1].close()
+                best_chain = (rec, pl)
+            else:
+                pl.close()
+        chain_searched = dict(best_chain[0], trials=trials)
+        chain_searched["ms_per_layer"] = chain_ms(best_chain[1])
+        best_chain[1].close()
+        chained = {"layers": L, "unsplit_ms_per_layer": t_unsplit, "searched": chain_searched,
                    "nano_sequential_ms_per_layer": t_seq,
                    "nano_overlapped_ms_per_layer": t_ovl, "structure": abl_bounds,
                    "overlapped_attn_wgs": best_trial["attn_wgs"], "overlapped_gemm_tile": ovl_tile,

@@ -172,6 +172,9 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * operation.  key "search.layers": 1 (default) = the auto-search and nf_simulate_pipeline price
  * one layer on its own; n in 2..16 = they price the time per layer of n consecutive layers
  * pipelined across the layer boundaries, as nf_layers_forward runs them.
+ * key "search.rank": 0 (default) = the search returns its best pipeline; r in 1..64 = the best
+ * pipeline of the r-th best row of the R -> P table, whatever its estimate (unsplit when there
+ * are fewer rows), so that a caller can refine the model's choice with trial runs.
  * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
  * (wrong results).  Apart from "gemm.debug", variants never change a result bit.

@@ -331,24 +331,38 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   });
   const size_t keep = std::min<size_t>(cands.size(), 64);
 
-  // Stage II: resource share per structure, with interference
-  double best = out->est_us_unsplit;
+  // Stage II: resource share per structure, with interference.  The best structure is kept
+  // per table row; the rows are then ranked by their estimates.  in.rank = 0 asks for the best
+  // pipeline (unsplit if nothing beats it); in.rank = r > 0 for the r-th best row's pipeline
+  // whatever its estimate, so that a caller can refine the choice with trial runs.
   const NfRpRow ideal{0, 1.0, 1.0, 1.0, 0, 1.0};
-  for (size_t c = 0; c < keep; ++c) {
-    const size_t n_rows = prof.rp.empty() ? 1 : prof.rp.size();
-    for (size_t r = 0; r < n_rows; ++r) {
-      const NfRpRow& row = prof.rp.empty() ? ideal : prof.rp[r];
-      const double t2 = nf_simulate_per_layer(prof, in, cands[c].bounds, 1, &row);
-      if (t2 < best - 1e-9) {
-        best = t2;
-        out->bounds = cands[c].bounds;
-        out->overlap = 1;
-        out->attn_wgs = row.attn_wgs;
-        out->gemm_tile = row.gemm_tile;
-        out->est_us = t2;
-        out->est_us_stage1 = cands[c].t1;
+  struct RowBest {
+    double t2 = 1e300;
+    size_t cand = 0;
+    NfRpRow row;
+  };
+  const size_t n_rows = prof.rp.empty() ? 1 : prof.rp.size();
+  std::vector<RowBest> per_row(n_rows);
+  for (size_t r = 0; r < n_rows; ++r) {
+    per_row[r].row = prof.rp.empty() ? ideal : prof.rp[r];
+    for (size_t c = 0; c < keep; ++c) {
+      const double t2 = nf_simulate_per_layer(prof, in, cands[c].bounds, 1, &per_row[r].row);
+      if (t2 < per_row[r].t2 - 1e-9) {
+        per_row[r].t2 = t2;
+        per_row[r].cand = c;
       }
     }
+  }
+  std::stable_sort(per_row.begin(), per_row.end(), [](const RowBest& a, const RowBest& b) { return a.t2 < b.t2; });
+  const size_t rank = (size_t)std::max(0, in.rank);
+  if (rank < per_row.size() && (rank > 0 || per_row[0].t2 < out->est_us_unsplit - 1e-9)) {
+    const RowBest& b = per_row[rank];
+    out->bounds = cands[b.cand].bounds;
+    out->overlap = 1;
+    out->attn_wgs = b.row.attn_wgs;
+    out->gemm_tile = b.row.gemm_tile;
+    out->est_us = b.t2;
+    out->est_us_stage1 = cands[b.cand].t1;
   }
   return NF_OK;
 }

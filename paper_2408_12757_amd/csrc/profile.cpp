@@ -16,6 +16,9 @@
 static int g_search_layers = 1;
 void nf_set_search_layers(int n) { g_search_layers = n; }
 int nf_search_layers() { return g_search_layers; }
+// Which of the ranked candidates the search returns (tuning knob "search.rank").
+static int g_search_rank = 0;
+void nf_set_search_rank(int r) { g_search_rank = r; }
 
 void nf_profile_free(nf_ctx* ctx) {
   delete ctx->profile;
@@ -25,7 +28,7 @@ void nf_profile_free(nf_ctx* ctx) {
 namespace {
 
 constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
-constexpr int kAttnWgSettings[] = {64, 128, 192, 256, 512, 768};
+constexpr int kAttnWgSettings[] = {64, 96, 128, 160, 192, 256, 512};
 
 struct Scratch {
   std::vector<void*> ptrs;
@@ -263,25 +266,36 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     }
   }
 
-  // ---- pairwise interference: Up/Gate GEMM at the full batch (every tile shape) || attention
-  // with k persistent workgroups.  Performance is normalised to the best stand-alone
-  // implementation of each kernel. ----
+  // ---- pairwise interference: the GEMM work of a two-nano-batch pipeline (O, Up/Gate, Down and
+  // the next KQV on half of the batch, in every tile shape) || attention with k persistent
+  // workgroups.  Performance is normalised to the best stand-alone implementation of each
+  // kernel.  One "GEMM" below is that group of four. ----
   if (!rc) {
-    const int o = NF_DENSE_UG, M = (int)Mmax;
-    const double g_best_ms = p->dense_us[o][steps - 1] / 1e3;
+    const int half_steps = std::max(1, steps / 2);
+    const int M = half_steps * granule;
+    double g_best_ms = 0;
+    for (int o = 0; o < NF_DENSE_OPS; ++o) g_best_ms += p->dense_us[o][half_steps - 1] / 1e3;
     const int kPairTiles[] = {7, 12, 13, 19};
     p->rp.clear();
     for (int tile : kPairTiles) {
       if (rc) break;
       int flip = 0;
-      double g_solo_ms = 0;
-      rc = time_ms(ctx, sg, 3, [&] {
+      auto launch_group = [&]() -> hipError_t {
+        static const int order[NF_DENSE_OPS] = {NF_DENSE_O, NF_DENSE_UG, NF_DENSE_D, NF_DENSE_KQV};
         flip ^= 1;
-        return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg) == hipSuccess ? NF_OK
-                                                                                                             : NF_EHIP;
-      }, &g_solo_ms);
+        for (int o : order) {
+          hipError_t e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
+          if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+      };
+      double g_solo_ms = 0;
+      rc = time_ms(ctx, sg, 3, [&] { return launch_group() == hipSuccess ? NF_OK : NF_EHIP; }, &g_solo_ms);
       if (rc) break;
-      const int n_gemm = std::min(64, (int)ceil(3.0 * best_long / g_solo_ms) + 2);
+      // kAttnReps attention launches back to back: the pair is measured in a sustained state
+      // (a single launch sees clocks that a longer co-run does not keep)
+      constexpr int kAttnReps = 5;
+      const int n_gemm = std::min(160, (int)ceil(3.0 * kAttnReps * best_long / g_solo_ms) + 2);
       std::vector<hipEvent_t> ev((size_t)n_gemm + 3);
       for (auto& e : ev)
         if (hipEventCreate(&e) != hipSuccess) rc = NF_EHIP;
@@ -292,12 +306,12 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
         if (e == hipSuccess) e = hipStreamWaitEvent(sa, fork, 0);
         // GEMMs first in issue order; attention joins right behind
         for (int i = 0; i < n_gemm && e == hipSuccess; ++i) {
-          flip ^= 1;
-          e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
+          e = launch_group();
           if (e == hipSuccess) e = hipEventRecord(ev[i], sg);
           if (i == 0 && e == hipSuccess) {
             e = hipEventRecord(a0, sa);
-            if (e == hipSuccess && attn_call(1, kAttnWgSettings[k], sa) != NF_OK) e = hipErrorUnknown;
+            for (int rep = 0; rep < kAttnReps && e == hipSuccess; ++rep)
+              if (attn_call(1, kAttnWgSettings[k], sa) != NF_OK) e = hipErrorUnknown;
             if (e == hipSuccess) e = hipEventRecord(a1, sa);
           }
         }
@@ -328,7 +342,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
         row.gemm_tile = tile;
         // one GEMM of this tile is worth g_best_ms of the best implementation's time
         row.p_gemm = std::min(1.0, done * g_best_ms / window);
-        row.p_attn = std::min(1.0, best_long / window);
+        row.p_attn = std::min(1.0, kAttnReps * best_long / window);
         row.p_attn_solo = std::min(1.0, best_long / t_long_ms[k]);
         row.p_gemm_solo = std::min(1.0, g_best_ms / g_solo_ms);
         p->rp.push_back(row);
@@ -364,6 +378,7 @@ void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano,
   in->granule = granule;
   in->max_nano = max_nano;
   in->layers = nf_search_layers();
+  in->rank = g_search_rank;
   in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
   in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
   const double tok_mb = 2.0 * m->n_kv_heads * m->head_dim * 2 / 1e6;

@@ -102,7 +102,7 @@ class ServingEngine:
                  device="cuda:0", async_lag: int = 1, avg_decode_len: float = 256.0, max_chunk: int = 0,
                  reserve_pages: int = 0, zero_pools: bool = False, ctx: Optional[nf.Context] = None,
                  bounds_fn: Optional[Callable[[int], List[int]]] = None, overlap: bool = False, attn_wgs: int = 0,
-                 token_path: Optional[TokenPath] = None):
+                 token_path: Optional[TokenPath] = None, auto_search: bool = False, granule: int = 128):
         self.model, self.n_layers, self.device = model, n_layers, torch.device(device)
         self.dense_batch, self.async_lag = dense_batch, async_lag
         self.ctx = ctx or nf.Context(self.device.index or 0)
@@ -126,6 +126,11 @@ class ServingEngine:
         self.tokens_launched = 0
         self.tok = token_path
         self.prompt_len: Dict[int, int] = {}
+        # auto-search (Sec. 4.1): profile the kernels once, then search the pipeline of every batch
+        # with the time per layer of a run of consecutive layers as the objective
+        self.auto_search, self.granule = auto_search, granule
+        if auto_search:
+            nf.nf_profile(self.ctx, model, dense_batch, granule, None)
 
     # ---- requests ---------------------------------------------------------------------
     def submit(self, prompt_len: int, output_len: int) -> int:
@@ -234,9 +239,16 @@ class ServingEngine:
             elif callable(x):
                 x = x(fb)
             args = self._upload(fb)
-            bounds = self.bounds_fn(fb.n_tokens) if self.bounds_fn else [0, fb.n_tokens]
-            plan = nf.nf_plan_manual(self.ctx, self.model, args, bounds, self.overlap and len(bounds) > 2, 0, 0,
-                                     self.attn_wgs)
+            if self.auto_search and fb.n_tokens >= 2 * self.granule:
+                nf.nf_tune_set("search.layers", max(1, min(16, self.n_layers)))
+                try:
+                    plan = nf.nf_plan_nanobatches(self.ctx, self.model, args, 0, self.granule)
+                finally:
+                    nf.nf_tune_set("search.layers", 1)
+            else:
+                bounds = self.bounds_fn(fb.n_tokens) if self.bounds_fn else [0, fb.n_tokens]
+                plan = nf.nf_plan_manual(self.ctx, self.model, args, bounds, self.overlap and len(bounds) > 2, 0, 0,
+                                         self.attn_wgs)
             need = nf.nf_layers_workspace_bytes(plan, self.n_layers)
             if self.workspace is None or self.workspace.numel() < need:
                 # grows rarely; the old buffer stays alive until the iterations using it are done
