@@ -75,7 +75,7 @@ def measured_traffic(kernel_tag: str):
     return None
 
 
-def cpu_baseline(cfg, case, n_decode_sample: int = 448):
+def cpu_baseline(cfg, case, n_decode_sample: int = 1792):
     """Times the CPU oracle (as it stands, numpy float64) on a bounded sample of the
     workload: the prefill request plus n_decode_sample decode requests; the decode
     part is scaled to the full request count."""
