@@ -477,6 +477,11 @@ def main():
         chain_searched = dict(best_chain[0], trials=trials)
         chain_searched["ms_per_layer"] = chain_ms(best_chain[1])
         best_chain[1].close()
+        # the pipeline a run of layers would use: the searched one if the trial confirms it, else unsplit
+        chain_searched["kept"] = bool(chain_searched["ms_per_layer"] < t_unsplit)
+        chain_searched["best_ms_per_layer"] = min(chain_searched["ms_per_layer"], t_unsplit)
+        chain_searched["best_tokens_per_s"] = B / (chain_searched["best_ms_per_layer"] * 1e-3)
+        chain_searched["best_iteration_roofline_frac"] = roof["t_roofline"] * 1e3 / chain_searched["best_ms_per_layer"]
         chained = {"layers": L, "unsplit_ms_per_layer": t_unsplit, "searched": chain_searched,
                    "nano_sequential_ms_per_layer": t_seq,
                    "nano_overlapped_ms_per_layer": t_ovl, "structure": abl_bounds,

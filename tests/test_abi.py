@@ -63,3 +63,31 @@ def test_host_validation_status_codes():
     assert nf.nf_check_batch(dataclasses.replace(m, n_q_heads=7), host_args(b), b.num_pages) == nf.NF_ESHAPE
     assert nf.nf_workspace_bytes(dataclasses.replace(m, head_dim=96), 64, 128) == 0
     assert nf.nf_workspace_bytes(m, 64, 128) > 64 * m.hidden * 2 * 3
+
+
+def test_argument_errors_are_reported_before_anything_touches_the_gpu():
+    """Calls with null pointers, bad shapes or unknown keys return a status on a machine
+    without a GPU (nothing is launched)."""
+    for args, status in (((None, None, None, None, 10, None, 4, 64), nf.NF_EINVAL),):
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_op_embedding(*args)
+        assert e.value.status == status
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_embedding(1, None, None, 1, 10, 1, 4, 60)      # row width not a multiple of 8
+    assert e.value.status == nf.NF_ESHAPE
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_embedding(1, 1, None, 1, 10, 1, 4, 64)         # slot indirection needs both arrays
+    assert e.value.status == nf.NF_EINVAL
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_argmax(None, 4, 64, None, None)
+    assert e.value.status == nf.NF_EINVAL
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_argmax(1, 4, 60, None, 1)
+    assert e.value.status == nf.NF_ESHAPE
+    for key, value in (("no.such.key", 1), ("gemm.tile", 99), ("search.layers", 0), ("search.rank", -1),
+                       ("gemm.grouped_tile", 3), ("attention.variant", 8)):
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_tune_set(key, value)
+        assert e.value.status == nf.NF_EINVAL, key
+    for key, value in (("gemm.tile", 0), ("search.layers", 1), ("search.rank", 0), ("gemm.grouped_tile", 0)):
+        nf.nf_tune_set(key, value)
