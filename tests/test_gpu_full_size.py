@@ -107,6 +107,73 @@ def test_c2_attention_rows_are_convex_combinations(c2):
     pages[:, 1] = saved
 
 
+@pytest.mark.timeout(600)
+def test_c2_two_chained_layers_overlapped_pipeline_matches_layer_by_layer(c2):
+    """Two consecutive C2 layers in one nf_layers_forward call with an overlapped plan of the
+    shape the search picks (two nano-batches, attention on 128 workgroups beside the GEMMs,
+    the second layer's KQV hoisted behind the first layer's tail): the output and both KV
+    pools carry the same bits as two separate unsplit nf_layer_forward calls, and sampled
+    rows agree with the oracle's two-layer chain."""
+    cfg, case = c2
+    b, m = case.batch, cfg.model
+    L = 2
+    pools = case.layer_pools(L)
+    n_pages = pools[0].shape[0]
+    before = [p.clone() for p in pools]
+    w = [case.runners[0].w.struct] * L
+    stream = torch.cuda.current_stream().cuda_stream
+
+    rng = np.random.default_rng(12)
+    dec = np.sort(rng.choice(np.arange(b.n_prefill_reqs, b.n_reqs), size=8, replace=False))
+    reqs = np.unique(np.concatenate([[0], dec]))
+    sub, tok, phys = wl.subset_batch(b, reqs)
+    idx = torch.from_numpy(phys).to(case.device)
+    pages_before = [hz.bf16_bits(p.index_select(0, idx)) for p in pools]
+
+    say("reference: two unsplit nf_layer_forward calls")
+    plan1 = nf.nf_plan_manual(case.ctx, m, case.args, [0, b.n_tokens])
+    ws1 = torch.empty(plan1.workspace_bytes, dtype=torch.uint8, device=case.device)
+    mid, ref = torch.empty_like(case.x), torch.empty_like(case.x)
+    nf.nf_layer_forward(case.ctx, m, w[0], pools[0].data_ptr(), n_pages, case.args, plan1, case.x.data_ptr(),
+                        mid.data_ptr(), ws1.data_ptr(), ws1.numel(), stream)
+    nf.nf_layer_forward(case.ctx, m, w[1], pools[1].data_ptr(), n_pages, case.args, plan1, mid.data_ptr(),
+                        ref.data_ptr(), ws1.data_ptr(), ws1.numel(), stream)
+    torch.cuda.synchronize()
+    ref_pools = [p.clone() for p in pools]
+    assert not torch.equal(ref_pools[1], before[1])          # the append did write
+
+    say("oracle chain on the sample")
+    z, ks, vs = orc.layers_forward(m, [case.host_weights[0]] * L, pages_before, sub, case.x_bits[tok])
+    e_z = rel_err(f64(hz.bf16_bits(ref)[tok]), z)
+    errs = [e_z]
+    for l in range(L):
+        kg, vg = hz.read_kv_rows(hz.bf16_bits(pools[l].index_select(0, idx)), m, sub, np.arange(sub.n_tokens))
+        errs += [rel_err(f64(kg), ks[l]), rel_err(f64(vg), vs[l])]
+    say("chain rel err z, k0, v0, k1, v1", errs)
+    assert max(errs) <= REL_TOL, errs
+
+    for bounds, overlap, wgs, tile in ([[0, 1152, 2048], True, 128, 13], [[0, 1024, 2048], True, 128, 0],
+                                       [[0, 768, 1408, 2048], True, 96, 0], [[0, 1024, 2048], False, 0, 0]):
+        say("chain plan", bounds, "overlap", overlap, "attn_wgs", wgs, "gemm.tile", tile)
+        for p, p0 in zip(pools, before):
+            p.copy_(p0)
+        plan = nf.nf_plan_manual(case.ctx, m, case.args, bounds, overlap, 0, 0, wgs)
+        ws = torch.empty(nf.nf_layers_workspace_bytes(plan, L), dtype=torch.uint8, device=case.device)
+        out = torch.empty_like(case.x)
+        nf.nf_tune_set("gemm.tile", tile)
+        try:
+            nf.nf_layers_forward(case.ctx, m, w, [p.data_ptr() for p in pools], n_pages, case.args, plan,
+                                 case.x.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            torch.cuda.synchronize()
+        finally:
+            nf.nf_tune_set("gemm.tile", 0)
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), bounds
+        for l in range(L):
+            assert torch.equal(pools[l].view(torch.int16), ref_pools[l].view(torch.int16)), (bounds, l)
+    # leave the shared pool as the other tests found it
+    pools[0].copy_(before[0])
+
+
 def routing_from_workspace(case, plan, B, k):
     off, nb = plan.workspace_region("moe.expert_ids")
     return case._ws[off:off + nb].view(torch.int32).cpu().numpy().reshape(B, k)
