@@ -177,7 +177,9 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * are fewer rows), so that a caller can refine the model's choice with trial runs.
  * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
- * (wrong results).  Apart from "gemm.debug", variants never change a result bit.
+ * (wrong results).  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
+ * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.
+ * Apart from "gemm.debug", variants never change a result bit.
  * Returns NF_EINVAL for an unknown key or a value out of range.
  */
 int nf_tune_set(const char *key, int value);
@@ -347,7 +349,13 @@ int nf_op_rmsnorm(const void *x, const void *g, void *out, int n_tokens, int hid
  *   NF_EPI_NONE    : plain bf16 store
  *   NF_EPI_RESIDUAL: out = residual[M, N] + product
  *   NF_EPI_SWIGLU  : w is [2*N, K] (gate rows then up rows); out[M, N] = silu(gate) * up
- * Requires K % 64 == 0 and N % 64 == 0. */
+ * Requires K % 64 == 0 and N % 64 == 0.
+ * The product is accumulated in fp32 in ascending K order.  Operations with a long K and few
+ * output columns - K >= 8192, K >= 2 N, K % 128 == 0, N % 128 == 0, no SwiGLU epilogue; the FFN
+ * down projection - instead add the fp32 sums of the two halves of K, so that nano-batches
+ * with few rows can spread an output tile over two workgroups; the rule looks at the shape
+ * only, never at M, hence a row has the same bits in every nano-batch (inside the layer entry
+ * points too). */
 enum { NF_EPI_NONE = 0, NF_EPI_RESIDUAL = 1, NF_EPI_SWIGLU = 2 };
 int nf_op_gemm(const void *x, const void *w, void *out, const void *residual, int M, int N, int K,
                int epilogue, void *hip_stream);

@@ -138,6 +138,11 @@ extern "C" int nf_tune_set(const char* key, int value) {
     nf_set_grouped_gemm_tile(value);
     return NF_OK;
   }
+  if (!strcmp(key, "gemm.ksplit")) {
+    if (value < 0 || value > 2) return NF_EINVAL;
+    nf_set_gemm_ksplit(value);
+    return NF_OK;
+  }
   if (!strcmp(key, "gemm.tile")) {
     if (value < 0 || value > 19) return NF_EINVAL;
     nf_set_gemm_tile(value);
@@ -176,6 +181,9 @@ struct Workspace {
   int32_t* row_token;      // [B*k]  token of a sorted row
   int32_t* expert_offset;  // [NF_MAX_NANO_OFFSETS][E + 1] per nano-batch
   char* expert_out;        // [B*k, D]
+  // dense models whose down projection is a two-segment operation: [2][B, D] fp32 sums of the
+  // two K halves, for nano-batches that run the halves on different workgroups
+  float* down_partial;
   size_t total;
 };
 
@@ -205,6 +213,8 @@ Workspace layout_workspace(const nf_model_desc* m, int n_tokens, size_t n_parts,
   w.row_token = (int32_t*)take(moe ? B * k * 4 : 0);
   w.expert_offset = (int32_t*)take(moe ? (size_t)kMaxNanoOffsets * (m->n_experts + 1) * 4 : 0);
   w.expert_out = take(moe ? B * k * (size_t)m->hidden * 2 : 0);
+  const bool two_seg = !moe && nf_gemm_k_segments(m->hidden, m->ffn_inner, NF_EPI_RESIDUAL) == 2;
+  w.down_partial = two_seg ? (float*)take(2 * B * m->hidden * sizeof(float)) : nullptr;
   w.total = off;
   return w;
 }
@@ -410,8 +420,11 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
         });
       }
       return traced(ctx, NF_K_GEMM, op, s, [&] {
+        // rows t0.. of both halves' sums: nano-operations on different rows never share scratch
+        const size_t B = (size_t)std::max(1, a.b->n_tokens);
+        const NfGemmSplit split{a.ws.down_partial ? a.ws.down_partial + t0 * D : nullptr, (long long)(B * D)};
         return nf_launch_gemm(a.ws.f + t0 * I * 2, a.w->w_down, a.x_out + t0 * D * 2, a.ws.y + t0 * D * 2, M, (int)D,
-                              (int)I, NF_EPI_RESIDUAL, op.gemm_tile, s);
+                              (int)I, NF_EPI_RESIDUAL, op.gemm_tile, s, split);
       });
     default:
       return hipErrorInvalidValue;

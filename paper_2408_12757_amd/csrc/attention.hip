@@ -153,18 +153,23 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
     ids = lane < n_pages ? page_ids[list_base + p_begin + lane] : 0;
   };
 
-  // Persistent workgroups: workgroup b takes work units b, b + gridDim.x, ...  The list is
-  // sorted longest first, so every workgroup gets a similar mix.  There are no workgroup
-  // barriers: the four wavefronts (four kv heads of one item) run independently.
+  // Persistent workgroups: the list is sorted longest first and is dealt out in rounds of
+  // gridDim.x units, forwards in even rounds and backwards in odd ones, so that the workgroup
+  // that drew the longest unit of one round draws the shortest of the next and all workgroups
+  // end up with nearly the same number of pages (dealing every round forwards leaves the first
+  // workgroup with a few per cent more than the last).  There are no workgroup barriers: the
+  // four wavefronts (four kv heads of one item) run independently.
   //
   // The chain descriptor -> page-list base -> page ids / Q -> first page costs three memory
   // round trips before a unit streams its first byte, and a wavefront runs tens of units.
   // It is therefore software-pipelined over units: while unit k streams, the operands of
   // unit k + 1 and the descriptor and page-list base of unit k + 2 are fetched.
-  int work = blockIdx.x;
+  auto unit_at = [&](int r) { return r * stride + ((r & 1) ? stride - 1 - (int)blockIdx.x : (int)blockIdx.x); };
+  int round = 0;
+  int work = unit_at(0);
   NfAttnItem it = item_of(work);
   int list_base = page_indptr[it.req];
-  NfAttnItem it1 = item_of(work + stride);
+  NfAttnItem it1 = item_of(unit_at(1));
   int list_base1 = page_indptr[it1.req];
   bf16x8 qf[DH / 32];
   int ids;
@@ -178,14 +183,15 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
 
   for (;;) {
     const int kvh = (work % head_groups) * 4 + wave;
-    const int work1 = work + stride;
+    const int work1 = unit_at(round + 1);
     bf16x8 qf1[DH / 32];
     int ids1;
     load_operands(it1, list_base1, work1, qf1, ids1);
-    const NfAttnItem it2 = item_of(work1 + stride);
+    const NfAttnItem it2 = item_of(unit_at(round + 2));
     int list_base2 = 0;
 
-    if (kvh < Hkv) {
+    // only the last round can be short: there a workgroup's unit may lie past the end
+    if (work < n_work && kvh < Hkv) {
       const int n_rows = it.n_tok * G;
       // last key this lane's row may read (rows past n_rows read nothing)
       const int lim = c < n_rows ? it.pos0 + c / G : -1;
@@ -248,7 +254,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
       list_base2 = page_indptr[it2.req];
     }
 
-    if (work1 >= n_work) break;
+    ++round;
+    if (round * stride >= n_work) break;
     work = work1;
     it = it1;
     list_base = list_base1;

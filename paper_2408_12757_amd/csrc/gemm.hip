@@ -9,7 +9,12 @@
 // store 8 bytes at a time.
 //
 // The K loop order and the MFMA instruction are the same for every M, so an output row
-// is bit-identical no matter which token range (nano-batch) it was computed in.
+// is bit-identical no matter which token range (nano-batch) it was computed in.  Operations
+// with a long K and few output columns (the FFN down projection) sum the two halves of K
+// separately and add the sums - for every M alike - so that a nano-batch with few rows can
+// spread each output tile over two workgroups (Sec. 4.1.2 and the ablation of Sec. 6.4 count
+// the weaker batching effect of the smaller nano-operations as the price of nano-batching;
+// this removes most of that price for the down projection).
 #include <math.h>
 
 #include "gemm_common.h"
@@ -172,7 +177,8 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
 // 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..19 = the direct-to-LDS
 // kernels of gemm_dl.hip.  Every variant walks K in the
-// same order with the same MFMA, so the choice never changes an output bit.
+// same order with the same MFMA, so the choice never changes an output bit.  Two-segment
+// operations (nf_gemm_k_segments) have their own launch forms and take the tile as a hint.
 static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
 static int g_grouped_tile = 0;  // implementation of the grouped (mixture-of-experts) GEMM; 0 = automatic
@@ -192,10 +198,43 @@ static hipError_t launch_debug(const void* x, const void* w, void* out, int M, i
   return hipGetLastError();
 }
 
+static int g_gemm_ksplit = 0;
+void nf_set_gemm_ksplit(int v) { g_gemm_ksplit = v; }
+
+int nf_gemm_k_segments(int N, int K, int epilogue) {
+  return (epilogue != EPI_SWIGLU && K >= 8192 && K >= 2 * N && K % 128 == 0 && N % 128 == 0) ? 2 : 1;
+}
+
+// Fill of the 256 CUs by `units` workgroups dealt out in whole rounds.
+static double round_fill(long units) { return (double)units / (double)(((units + 255) / 256) * 256); }
+
+// A two-segment operation.  One workgroup per tile needs no scratch and no second kernel, so
+// it is the form for row counts that fill the chip; with scratch, few rows run as two
+// workgroups per tile (the down projection of a 1024-row nano-batch of the 8B model has
+// 128 tiles of 256x128).
+static hipError_t launch_two_segments(const void* x, const void* w, void* out, const void* residual, int M, int N,
+                                      int K, int epilogue, int tile, hipStream_t s, NfGemmSplit split) {
+  if (g_gemm_tile) tile = g_gemm_tile;
+  const long tiles = (long)((M + 255) / 256) * (N / 128);
+  bool halves = false;
+  if (split.partial) {
+    if (g_gemm_ksplit)
+      halves = g_gemm_ksplit == 2;
+    else
+      halves = round_fill(2 * tiles) > 1.15 * round_fill(tiles);  // the scratch traffic costs about a tenth
+  }
+  if (!halves) return nf_launch_gemm_dl_two_sums(x, w, out, residual, M, N, K, epilogue, s);
+  int variant = (tile == 7 || tile == 11) ? 7 : (tile == 13 || tile == 10 || tile == 17) ? 13 : tile == 12 ? 12 : 19;
+  if (variant == 13 && N % 256 != 0) variant = 12;
+  return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, variant, s);
+}
+
 // Requires K % 64 == 0 and N % 64 == 0 (checked by the caller on the host).
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
-                          int epilogue, int tile, hipStream_t s) {
+                          int epilogue, int tile, hipStream_t s, NfGemmSplit split) {
   if (M <= 0) return hipSuccess;
+  if (nf_gemm_k_segments(N, K, epilogue) == 2)
+    return launch_two_segments(x, w, out, residual, M, N, K, epilogue, tile, s, split);
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
   if (g_gemm_debug && epilogue == EPI_NONE && n_eff % 128 == 0) {

@@ -7,7 +7,17 @@ namespace nfgemm {
 constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row: 144 B keeps ds_read_b128 conflict-free
 
-enum { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+// EPI_PARTIAL is internal: the fp32 sums of one K segment, written to scratch (see KRange).
+enum { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 };
+
+// The part of K a launch walks.  x and w rows are `ldk` elements apart (the full K of the
+// operation); workgroups with blockIdx.y = s walk K elements starting at s * K.  With
+// EPI_PARTIAL segment s stores its fp32 sums, row-major [M, N], at partial + s * seg_stride.
+struct KRange {
+  int ldk;
+  float* partial;
+  long long seg_stride;
+};
 
 // Workgroup index -> tile index so that the tiles one XCD works on are consecutive
 // (workgroups are dealt round-robin to the 8 XCDs; each XCD has its own L2).
@@ -77,13 +87,22 @@ __device__ __forceinline__ int weight_row(int row, int n0, int N) {
 template <int EPI, int TM, int TN, int WM, int WN>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TN][TM], bf16_t* __restrict__ Y,
                                            const bf16_t* __restrict__ R, int M, int N, int m0, int n0, int wm, int wn,
-                                           int lane) {
+                                           int lane, float* __restrict__ P = nullptr) {
   const int col4 = 4 * (lane >> 5);
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int m = m0 + wm * WM + j * 32 + (lane & 31);
     if (m >= M) continue;
-    if (EPI == EPI_SWIGLU) {
+    if (EPI == EPI_PARTIAL) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const size_t off = (size_t)m * N + n0 + wn * WN + i * 32 + q * 8 + col4;
+          const f32x4 o = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+          *reinterpret_cast<f32x4*>(P + off) = o;
+        }
+    } else if (EPI == EPI_SWIGLU) {
       // 32-column groups come in (gate, up) pairs: acc[2p] is gate, acc[2p+1] is up
 #pragma unroll
       for (int p = 0; p < TN / 2; ++p) {

@@ -57,7 +57,7 @@ __device__ __forceinline__ void wait_frags(bf16x8 (&fw)[TN], bf16x8 (&fx)[TM]) {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED, bool PIPE = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
-    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
   constexpr int NW = WAVES_M * WAVES_N;              // wavefronts per workgroup
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wavefront tile
   constexpr int TM = WM / 32, TN = WN / 32;          // 32x32 MFMA tiles per wavefront
@@ -71,7 +71,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
   int m0, n0;
   size_t w_off;
   if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
-  W += w_off;
+  const size_t k_begin = (size_t)blockIdx.y * K;  // this workgroup's K segment
+  X += k_begin;
+  W += w_off + k_begin;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -87,9 +89,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
       int gm = m0 + row;
       gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
       if (GROUPED && grp.row_index) gm = grp.row_index[gm];
-      src[i] = X + (size_t)gm * K + chunk * 8;
+      src[i] = X + (size_t)gm * kr.ldk + chunk * 8;
     } else {
-      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * K + chunk * 8;
+      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * kr.ldk + chunk * 8;
     }
   }
   auto issue_stage = [&](int stage, int kt) {
@@ -198,7 +200,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
 
   }
 
-  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
+                                  kr.partial + (size_t)blockIdx.y * (size_t)kr.seg_stride);
 }
 
 // Second main loop: K-step BKT of 32 or 64, an LDS ring of up to 5 stages, and the stage
@@ -208,10 +211,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(
 // the matrix pipe has work queued while the barrier and the first fragment reads complete.
 // With BKT = 32 a tile row is 64 bytes (4 chunks): 16 lanes read 16 consecutive rows, four
 // rows fill the 256-byte bank window, so the slot XOR comes from (row >> 2) & 3.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED, int BKT>
+//
+// SEG2: the workgroup sums the two halves of K separately (two accumulator sets) and adds
+// the two sums at the end - the arithmetic of a two-segment operation (nf_gemm_k_segments)
+// without any scratch memory.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int STAGES, bool GROUPED, int BKT, bool SEG2 = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
-    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -230,7 +237,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
   int m0, n0;
   size_t w_off;
   if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
-  W += w_off;
+  const size_t k_begin = (size_t)blockIdx.y * K;  // this workgroup's K segment
+  X += k_begin;
+  W += w_off + k_begin;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -245,9 +254,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
       int gm = m0 + row;
       gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
       if (GROUPED && grp.row_index) gm = grp.row_index[gm];
-      src[i] = X + (size_t)gm * K + chunk * 8;
+      src[i] = X + (size_t)gm * kr.ldk + chunk * 8;
     } else {
-      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * K + chunk * 8;
+      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * kr.ldk + chunk * 8;
     }
   }
   auto issue_stage = [&](int stage, int kt) {
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
   read_slice(lds_base, 0, fw[0], fx[0]);
 
   int stage = 0;
-  for (int kt = 0; kt < KT; ++kt) {
+  auto k_step = [&](int kt) {
     // every wavefront has passed the barrier that ended stage kt - 1: its buffer is free
     if (kt + STAGES - 1 < KT) {
       int fill = stage + STAGES - 1;
@@ -328,9 +337,55 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
       __builtin_amdgcn_sched_barrier(0);
     }
     stage = next;
+  };
+
+  // SEG2: the loop runs in two parts (the load pipeline runs through); the sums of the first
+  // half of K are set aside between them - every MFMA of a K-step is issued inside its step
+  f32x16 acc_lo[SEG2 ? TN : 1][SEG2 ? TM : 1];
+  const int kt_first = SEG2 ? (KT >> 1) : KT;
+  for (int kt = 0; kt < kt_first; ++kt) k_step(kt);
+  if (SEG2) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j) {
+        acc_lo[SEG2 ? i : 0][SEG2 ? j : 0] = acc[i][j];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      }
+    for (int kt = kt_first; kt < KT; ++kt) k_step(kt);
   }
 
-  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane);
+  if (SEG2) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j) acc[i][j] = acc_lo[SEG2 ? i : 0][SEG2 ? j : 0] + acc[i][j];
+  }
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
+                                  kr.partial + (size_t)blockIdx.y * (size_t)kr.seg_stride);
+}
+
+// out = bf16((p0 + p1) [+ residual]): the second step of a two-segment operation whose
+// segments were summed by different workgroups.  One thread per 4 consecutive elements.
+__global__ __launch_bounds__(256) void gemm_reduce2_kernel(const float* __restrict__ p0, const float* __restrict__ p1,
+                                                          const bf16_t* __restrict__ R, bf16_t* __restrict__ Y,
+                                                          size_t n_quads) {
+  const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= n_quads) return;
+  const f32x4 a = reinterpret_cast<const f32x4*>(p0)[q], b = reinterpret_cast<const f32x4*>(p1)[q];
+  float o[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = a[e] + b[e];
+  if (R) {
+    const u32x2 r = reinterpret_cast<const u32x2*>(R)[q];
+    o[0] += __uint_as_float(r[0] << 16);
+    o[1] += __uint_as_float(r[0] & 0xffff0000u);
+    o[2] += __uint_as_float(r[1] << 16);
+    o[3] += __uint_as_float(r[1] & 0xffff0000u);
+  }
+  const u32x2 pk = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
+  reinterpret_cast<u32x2*>(Y)[q] = pk;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, int BKT>
@@ -354,7 +409,7 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
       if (e != hipSuccess) return e;                                                                               \
       attr_set = true;                                                                                             \
     }                                                                                                              \
-    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp);                              \
+    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp, KRange{K, nullptr, 0});       \
   } while (0)
   switch (epilogue) {
     case EPI_NONE: NF_DL2_LAUNCH(EPI_NONE); break;
@@ -386,7 +441,7 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
       if (e != hipSuccess) return e;                                                                               \
       attr_set = true;                                                                                             \
     }                                                                                                              \
-    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp);                              \
+    kern<<<grid, block, lds_bytes, s>>>(X, Wp, Y, R, M, N, K, tiles_m, tiles_n, grp, KRange{K, nullptr, 0});       \
   } while (0)
   switch (epilogue) {
     case EPI_NONE: NF_DL_LAUNCH(EPI_NONE); break;
@@ -397,7 +452,92 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
   return hipGetLastError();
 }
 
+template <typename Kern>
+hipError_t allow_lds(Kern kern, size_t lds_bytes, bool& done) {
+  if (lds_bytes <= 64 * 1024 || done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  done = e == hipSuccess;
+  return e;
+}
+
+// The two halves of K as separate workgroups (grid.y = 2), fp32 sums to scratch.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool PIPE>
+hipError_t launch_dl_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  const size_t lds_bytes = (size_t)STAGES * (BM + BN) * 128;
+  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, false, PIPE>;
+  static bool attr_set = false;
+  hipError_t e = allow_lds(kern, lds_bytes, attr_set);
+  if (e != hipSuccess) return e;
+  kern<<<dim3(tiles_m * tiles_n, 2), dim3(64 * WAVES_M * WAVES_N), lds_bytes, s>>>(
+      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
+      GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int BKT>
+hipError_t launch_dl2_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  const size_t lds_bytes = (size_t)STAGES * (BM + BN) * BKT * 2;
+  auto kern = gemm_dl2_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, false, BKT>;
+  static bool attr_set = false;
+  hipError_t e = allow_lds(kern, lds_bytes, attr_set);
+  if (e != hipSuccess) return e;
+  kern<<<dim3(tiles_m * tiles_n, 2), dim3(64 * WAVES_M * WAVES_N), lds_bytes, s>>>(
+      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
+      GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+  return hipGetLastError();
+}
+
+// Both halves of K in one workgroup (two accumulator sets).
+template <int EPI>
+hipError_t launch_dl2_two_sums(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                               hipStream_t s) {
+  constexpr int BM = 256, BN = 128, STAGES = 3, BKT = 64;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  const size_t lds_bytes = (size_t)STAGES * (BM + BN) * BKT * 2;
+  auto kern = gemm_dl2_kernel<BM, BN, 4, 2, EPI, STAGES, false, BKT, true>;
+  static bool attr_set = false;
+  hipError_t e = allow_lds(kern, lds_bytes, attr_set);
+  if (e != hipSuccess) return e;
+  kern<<<dim3(tiles_m * tiles_n), dim3(512), lds_bytes, s>>>((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out,
+                                                            (const bf16_t*)residual, M, N, K, tiles_m, tiles_n,
+                                                            GroupedArgs{nullptr, nullptr, 0, 0}, KRange{K, nullptr, 0});
+  return hipGetLastError();
+}
+
 }  // namespace
+
+// Two-segment operation, both segments summed inside each workgroup (256x128 tiles): needs
+// no scratch.  K % 128 == 0, N % 128 == 0; epilogue EPI_NONE or EPI_RESIDUAL.
+hipError_t nf_launch_gemm_dl_two_sums(const void* x, const void* w, void* out, const void* residual, int M, int N,
+                                      int K, int epilogue, hipStream_t s) {
+  if (epilogue == EPI_RESIDUAL) return launch_dl2_two_sums<EPI_RESIDUAL>(x, w, out, residual, M, N, K, s);
+  if (epilogue == EPI_NONE) return launch_dl2_two_sums<EPI_NONE>(x, w, out, residual, M, N, K, s);
+  return hipErrorInvalidValue;
+}
+
+// Two-segment operation with the segments on different workgroups: twice the workgroups of
+// the one-launch form, for row counts that would leave most of the chip idle.  partial holds
+// the two [M, N] fp32 sums seg_stride floats apart; a second kernel adds them (+ residual).
+// variant: 7 = 128x128, 12 = 256x128, 13 = 256x256 (N % 256 == 0), 19 = 256x128 second main loop.
+hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, const void* residual, int M, int N,
+                                    int K, float* partial, long long seg_stride, int variant, hipStream_t s) {
+  const KRange kr{K, partial, seg_stride};
+  hipError_t e;
+  switch (variant) {
+    case 7: e = launch_dl_halves<128, 128, 2, 2, 2, false>(x, w, M, N, K, kr, s); break;
+    case 12: e = launch_dl_halves<256, 128, 4, 2, 3, true>(x, w, M, N, K, kr, s); break;
+    case 13: e = launch_dl_halves<256, 256, 2, 4, 2, true>(x, w, M, N, K, kr, s); break;
+    case 19: e = launch_dl2_halves<256, 128, 4, 2, 3, 64>(x, w, M, N, K, kr, s); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess) return e;
+  const size_t n_quads = (size_t)M * N / 4;
+  gemm_reduce2_kernel<<<dim3((unsigned)((n_quads + 255) / 256)), dim3(256), 0, s>>>(
+      partial, partial + seg_stride, (const bf16_t*)residual, (bf16_t*)out, n_quads);
+  return hipGetLastError();
+}
 
 // Variants: 7 = 128x128 tile, 4 wavefronts, 2 stages (two workgroups per CU);
 //           8 = 128x128, 4 wavefronts, 4 stages (one workgroup per CU);

@@ -45,9 +45,30 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
 // device-writable host buffer of 2 * n_kv_heads * head_dim elements per row.
 hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin, int tok_end, int n_q_heads,
                                 int n_kv_heads, int head_dim, hipStream_t s);
+// Number of K segments of a dense operation: 1, or 2 for the long-K, narrow-N operations
+// (the FFN down projection): K >= 8192, K >= 2 N, K % 128 == 0, N % 128 == 0, no SwiGLU
+// epilogue.  A two-segment operation computes bf16((sum over the first half of K) + (sum
+// over the second half) [+ residual]), each half accumulated from zero in ascending K
+// order.  The count depends on the operation's shape alone - never on M, the tile or the
+// launch form - so a row's bits do not depend on the nano-batch it is computed in.
+int nf_gemm_k_segments(int N, int K, int epilogue);
+// Scratch that lets a two-segment operation put its segments on different workgroups:
+// 2 x [rows, N] floats, the second block seg_stride floats after the first.  partial may be
+// null (then each workgroup sums both segments itself).
+struct NfGemmSplit {
+  float* partial;
+  long long seg_stride;
+};
 // tile: 0 = automatic, 1..19 = one implementation (see gemm.hip, gemm_dl.hip); all give identical bits
 hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
-                          int epilogue, int tile, hipStream_t s);
+                          int epilogue, int tile, hipStream_t s, NfGemmSplit split = NfGemmSplit{nullptr, 0});
+// 0 = automatic, 1 = two-segment operations always as one workgroup per tile, 2 = always as
+// two (when scratch is available); a tuning and test switch, the bits are the same
+void nf_set_gemm_ksplit(int v);
+hipError_t nf_launch_gemm_dl_two_sums(const void* x, const void* w, void* out, const void* residual, int M, int N,
+                                      int K, int epilogue, hipStream_t s);
+hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, const void* residual, int M, int N,
+                                    int K, float* partial, long long seg_stride, int variant, hipStream_t s);
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,

@@ -153,10 +153,13 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
   void* res = sc.get_random(max_out, 1.0f);
   // alternate so weights are not cache-warm
   void* w[2] = {sc.get_random(max_w, 0.02f), sc.get_random(max_w, 0.02f)};
-  if (!x || !y || !res || !w[0] || !w[1]) {
+  // scratch of the two-segment operations, as the layer's workspace provides it
+  void* partial = sc.get(2 * Mmax * (size_t)m->hidden * sizeof(float), 0);
+  if (!x || !y || !res || !w[0] || !w[1] || !partial) {
     ctx->last_hip = (int)hipErrorOutOfMemory;
     return NF_EHIP;
   }
+  const NfGemmSplit split{m->n_experts > 1 ? nullptr : (float*)partial, (long long)(Mmax * (size_t)m->hidden)};
   for (int o = 0; o < NF_DENSE_OPS; ++o) {
     for (int i = 0; i < steps; ++i) {
       const int M = (i + 1) * granule;
@@ -167,7 +170,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
         double ms = 0;
         rc = time_ms(ctx, sg, 6, [&] {
           flip ^= 1;
-          return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg) == hipSuccess
+          return nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg, split) == hipSuccess
                      ? NF_OK
                      : NF_EHIP;
         }, &ms);
@@ -284,7 +287,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
         static const int order[NF_DENSE_OPS] = {NF_DENSE_O, NF_DENSE_UG, NF_DENSE_D, NF_DENSE_KQV};
         flip ^= 1;
         for (int o : order) {
-          hipError_t e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg);
+          hipError_t e = nf_launch_gemm(x, w[flip], y, res, M, shp[o].N, shp[o].K, shp[o].epi, tile, sg, split);
           if (e != hipSuccess) return e;
         }
         return hipSuccess;

@@ -110,6 +110,44 @@ def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     assert np.array_equal(hz.bf16_bits(out), outs[1])
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 512, 8192), (37, 128, 9088)])
+def test_gemm_with_two_k_segments(M, N, K):
+    """Long-K, narrow-N operations (the FFN down projection) add the sums of the two halves of
+    K; through this entry point (no scratch) every workgroup forms both sums itself.  The
+    result agrees with the oracle and does not depend on the implementation asked for or on
+    the rows it is computed with."""
+    say("gemm, two K segments", M, N, K)
+    r = np.random.default_rng(M + N + K)
+    x = wl.f32_to_bf16_bits(r.standard_normal((M, K)).astype(np.float32))
+    w = wl.f32_to_bf16_bits(0.05 * r.standard_normal((N, K)).astype(np.float32))
+    res = wl.f32_to_bf16_bits(r.standard_normal((M, N)).astype(np.float32))
+    xt, wt, rt = hz.bf16_tensor(x, DEV), hz.bf16_tensor(w, DEV), hz.bf16_tensor(res, DEV)
+    ref = orc.dense(f64(x), f64(w))
+    outs = []
+    try:
+        for tile in (0, 1, 7, 13, 19):
+            nf.nf_tune_set("gemm.tile", tile)
+            out = torch.full((M + 3, N), 7.0, dtype=torch.bfloat16, device=DEV)
+            nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), rt.data_ptr(), M, N, K, nf.NF_EPI_RESIDUAL)
+            torch.cuda.synchronize()
+            outs.append(hz.bf16_bits(out))
+    finally:
+        nf.nf_tune_set("gemm.tile", 0)
+    assert rel_err(f64(outs[0])[:M], ref + f64(res)) <= REL_TOL / 2
+    assert np.all(f64(outs[0])[M:] == 7.0)
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    # a sub-range of the rows gives the same bits for those rows
+    lo = M // 3
+    out = torch.empty((M - lo, N), dtype=torch.bfloat16, device=DEV)
+    nf.nf_op_gemm(xt[lo:].data_ptr(), wt.data_ptr(), out.data_ptr(), rt[lo:].data_ptr(), M - lo, N, K, nf.NF_EPI_RESIDUAL)
+    nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), None, 1, N, K, nf.NF_EPI_NONE)   # no residual
+    torch.cuda.synchronize()
+    got = hz.bf16_bits(out)
+    assert np.array_equal(got[1:], outs[0][lo + 1:M])
+    assert rel_err(f64(got[:1]), ref[:1]) <= REL_TOL / 2
+
+
 def test_gemm_rejects_bad_shapes():
     t = torch.zeros(64 * 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(nf.NfError) as e:
@@ -194,6 +232,33 @@ def test_nano_batched_and_overlapped_are_bit_exact_with_unsplit(ctx):
                 assert np.array_equal(z, z0), (bounds, overlap, acu)
                 assert np.array_equal(p, p0)
             plan.close()
+
+
+def test_two_segment_down_projection_is_bit_exact_in_both_launch_forms(ctx):
+    """A model whose down projection has a long K (ffn_inner 8192 over hidden 512) sums the two
+    halves of K separately.  With the layer's workspace the halves may run on different
+    workgroups (fp32 sums to scratch, a second kernel adds them) or in one workgroup; the
+    choice follows the row count of the nano-batch and must not change a bit."""
+    m = small_gqa_model(hidden=512, n_q_heads=4, n_kv_heads=2, ffn_inner=8192)
+    q_lens = [70, 9] + [1] * 300
+    ctx_lens = [0, 33] + list(np.random.default_rng(3).integers(1, 200, size=300))
+    b = wl.batch_from_lengths(q_lens, ctx_lens, 2, np.random.default_rng(6), spare_pages=3)
+    case = Case(m, b, 1234, ctx=ctx)
+    outs = []
+    try:
+        for ks in (1, 2, 0):
+            nf.nf_tune_set("gemm.ksplit", ks)
+            for bounds in ([0, b.n_tokens], [0, 130, b.n_tokens], [0, 64, 128, 257, b.n_tokens]):
+                plan = nf.nf_plan_manual(case.ctx, m, case.args, bounds, len(bounds) > 3)
+                z, p = case.run(plan)
+                outs.append((ks, bounds, z, p))
+                plan.close()
+    finally:
+        nf.nf_tune_set("gemm.ksplit", 0)
+    say("two-segment down projection", case.check(outs[0][2], outs[0][3]))
+    for ks, bounds, z, p in outs[1:]:
+        assert np.array_equal(z, outs[0][2]), (ks, bounds)
+        assert np.array_equal(p, outs[0][3]), (ks, bounds)
 
 
 # ------------------------------------------------------- consecutive layers ---
