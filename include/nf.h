@@ -351,7 +351,7 @@ int nf_op_rmsnorm(const void *x, const void *g, void *out, int n_tokens, int hid
  *   NF_EPI_SWIGLU  : w is [2*N, K] (gate rows then up rows); out[M, N] = silu(gate) * up
  * Requires K % 64 == 0 and N % 64 == 0.
  * The product is accumulated in fp32 in ascending K order.  Operations with a long K and few
- * output columns - K >= 8192, K >= 2 N, K % 128 == 0, N % 128 == 0, no SwiGLU epilogue; the FFN
+ * output columns - K >= 8192, K >= 2 N, N < 8192, K % 128 == 0, N % 128 == 0, no SwiGLU epilogue; the FFN
  * down projection - instead add the fp32 sums of the two halves of K, so that nano-batches
  * with few rows can spread an output tile over two workgroups; the rule looks at the shape
  * only, never at M, hence a row has the same bits in every nano-batch (inside the layer entry

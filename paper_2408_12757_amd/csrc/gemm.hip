@@ -202,7 +202,7 @@ static int g_gemm_ksplit = 0;
 void nf_set_gemm_ksplit(int v) { g_gemm_ksplit = v; }
 
 int nf_gemm_k_segments(int N, int K, int epilogue) {
-  return (epilogue != EPI_SWIGLU && K >= 8192 && K >= 2 * N && K % 128 == 0 && N % 128 == 0) ? 2 : 1;
+  return (epilogue != EPI_SWIGLU && K >= 8192 && K >= 2 * N && N < 8192 && K % 128 == 0 && N % 128 == 0) ? 2 : 1;
 }
 
 // Fill of the 256 CUs by `units` workgroups dealt out in whole rounds.

@@ -46,8 +46,8 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
 hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin, int tok_end, int n_q_heads,
                                 int n_kv_heads, int head_dim, hipStream_t s);
 // Number of K segments of a dense operation: 1, or 2 for the long-K, narrow-N operations
-// (the FFN down projection): K >= 8192, K >= 2 N, K % 128 == 0, N % 128 == 0, no SwiGLU
-// epilogue.  A two-segment operation computes bf16((sum over the first half of K) + (sum
+// (the FFN down projection): K >= 8192, K >= 2 N, N < 8192 (wider outputs give a 1024-row
+// nano-batch a tile for every CU anyway), K % 128 == 0, N % 128 == 0, no SwiGLU epilogue.  A two-segment operation computes bf16((sum over the first half of K) + (sum
 // over the second half) [+ residual]), each half accumulated from zero in ascending K
 // order.  The count depends on the operation's shape alone - never on M, the tile or the
 // launch form - so a row's bits do not depend on the nano-batch it is computed in.
