@@ -121,6 +121,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
                                                         int head_groups, int Hq, int Hkv, int n_qkv,
                                                         float scale_log2, float* __restrict__ parts,
                                                         bf16_t* __restrict__ out) {
+  constexpr int NIDS = NF_ATTN_CHUNK / 1024;  // page-id registers: 64 pages of 16 keys each
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = Hq / Hkv;
@@ -131,10 +132,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   auto item_of = [&](int w) { return items[(w < n_work ? w : n_work - 1) / head_groups]; };
   // Operands that do not depend on the page data: the Q^T fragments (lane (row c, k-group g)
   // holds Q[row c][(4s+g)*8 .. +8] for step s; rows past the item's are zero) and the physical
-  // ids of the item's pages.  The chunk spans at most 64 pages: lane i keeps the id of page
-  // p_begin + i, so the id of any page is one cross-lane read away and no page load waits on
-  // the page table.
-  auto load_operands = [&](const NfAttnItem& it, int list_base, int w, bf16x8 (&qf)[DH / 32], int& ids) {
+  // ids of the item's pages.  The chunk spans at most 64 * NIDS pages: lane i keeps the ids of
+  // pages p_begin + i, p_begin + 64 + i, ..., so the id of any page is one cross-lane read away
+  // and no page load waits on the page table.
+  auto load_operands = [&](const NfAttnItem& it, int list_base, int w, bf16x8 (&qf)[DH / 32], int (&ids)[NIDS]) {
     int kvh = (w % head_groups) * 4 + wave;
     kvh = kvh < Hkv ? kvh : Hkv - 1;
     const int n_rows = it.n_tok * G;
@@ -150,7 +151,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
     }
     const int p_begin = it.key_begin >> 4;
     const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
-    ids = lane < n_pages ? page_ids[list_base + p_begin + lane] : 0;
+#pragma unroll
+    for (int k = 0; k < NIDS; ++k)
+      ids[k] = lane + 64 * k < n_pages ? page_ids[list_base + p_begin + 64 * k + lane] : 0;
   };
 
   // Persistent workgroups: the list is sorted longest first and is dealt out in rounds of
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   NfAttnItem it1 = item_of(unit_at(1));
   int list_base1 = page_indptr[it1.req];
   bf16x8 qf[DH / 32];
-  int ids;
+  int ids[NIDS];
   load_operands(it, list_base, work, qf, ids);
 
   const size_t blk_bytes = (size_t)16 * DH * 2;
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
     const int kvh = (work % head_groups) * 4 + wave;
     const int work1 = unit_at(round + 1);
     bf16x8 qf1[DH / 32];
-    int ids1;
+    int ids1[NIDS];
     load_operands(it1, list_base1, work1, qf1, ids1);
     const NfAttnItem it2 = item_of(unit_at(round + 2));
     int list_base2 = 0;
@@ -203,7 +206,14 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
       const int p_begin = it.key_begin >> 4;
       const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
       const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
-#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)__builtin_amdgcn_readlane(ids, (i)) * page_bytes)
+      auto page_id = [&](int i) {
+        int v = __builtin_amdgcn_readlane(ids[0], i & 63);
+#pragma unroll
+        for (int k = 1; k < NIDS; ++k)
+          if ((i >> 6) == k) v = __builtin_amdgcn_readlane(ids[k], i & 63);
+        return v;
+      };
+#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)page_id(i) * page_bytes)
       // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
       // page has been consumed
       PageRegs<DH> buf[NBUF];
@@ -261,7 +271,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
     list_base = list_base1;
 #pragma unroll
     for (int s = 0; s < DH / 32; ++s) qf[s] = qf1[s];
-    ids = ids1;
+#pragma unroll
+    for (int k = 0; k < NIDS; ++k) ids[k] = ids1[k];
     it1 = it2;
     list_base1 = list_base2;
   }

@@ -11,10 +11,6 @@
 #include "../../include/nf.h"
 #include "nf_kernels.h"
 
-// Keys per attention work item.  Part of the numerics contract: a request's keys are
-// always cut at multiples of this length, whatever the batch split or CU share.
-constexpr int NF_ATTN_CHUNK = 1024;
-
 enum NfOpKind { NF_OP_KQV = 0, NF_OP_ATTN = 1, NF_OP_O = 2, NF_OP_UG = 3, NF_OP_D = 4, NF_OP_KINDS = 5 };
 enum NfLane { NF_LANE_GEMM = 0, NF_LANE_ATTN = 1, NF_LANES = 2 };
 

@@ -4,6 +4,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Keys per attention work item (a multiple of 1024: the kernel keeps the ids of 64 pages per
+// register).  Part of the numerics contract: a request's keys are always cut at multiples of
+// this length, whatever the batch split or CU share.
+constexpr int NF_ATTN_CHUNK = 4096;
+
 // One attention work item: the rows of up to 16/G consecutive tokens of one
 // request (G = q heads per kv head) against keys [key_begin, key_end) of that
 // request.  Token tok0 + j sits at position pos0 + j and may read keys

@@ -213,7 +213,9 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     rc = nf_plan_manual(ctx, m, &sb[v].b, 1, bounds, 0, 0, 0, 0, &plans[v]);
     if (rc) break;
     if (v == 1) {
-      parts = (float*)sc.get((size_t)plans[1]->total_parts * m->n_kv_heads * nf_attn_part_floats(m->head_dim) * 4, 0);
+      // (no partial results at all when every context fits one chunk)
+      parts = (float*)sc.get(std::max<size_t>(256, (size_t)plans[1]->total_parts * m->n_kv_heads *
+                                                       nf_attn_part_floats(m->head_dim) * 4), 0);
       if (!parts) rc = NF_EHIP;
     }
   }
