@@ -6,10 +6,12 @@
 // Work decomposition.  One wavefront handles one work item x one kv head: up to 16 query
 // rows that share the kv head (the G = Hq/Hkv q heads of up to 16/G consecutive tokens of
 // one request) against a contiguous key range of at most a fixed chunk length.  It keeps
-// running softmax statistics (max, sum) and an unnormalised output per row and writes
-// them as a partial result; a second kernel merges the partials of a row group in chunk
-// order.  The chunking depends only on the request's length, never on the batch split or
-// on the number of compute units, so results do not depend on nano-batching.
+// running softmax statistics (max, sum) and an unnormalised output per row.  Rows whose
+// keys fit one chunk are normalised and written directly; for longer rows the result of
+// every chunk is written as a partial result and a second kernel merges the partials of a
+// row group in chunk order.  The chunking depends only on the request's length, never on
+// the batch split or on the number of compute units, so results do not depend on
+// nano-batching.
 //
 // Matrix-core mapping (all wave64, 16 query rows padded with zeros):
 //   S^T[16 keys x 16 rows]  = K_page[16 x dh] . Q^T[dh x 16]   v_mfma_f32_16x16x32_bf16, dh/32 steps
@@ -20,6 +22,8 @@
 // layout of S^T (lane = row, 4 consecutive keys) is exactly the B-operand layout the second
 // product needs, so P never leaves registers.
 #include <math.h>
+
+#include <algorithm>
 
 #include "nf_device.h"
 #include "nf_kernels.h"
@@ -184,6 +188,22 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   const uint32_t koff = (uint32_t)(lane * 16);         // K: [dh/8 chunks][16 keys][8]; chunk 4s+g, key c
   const uint32_t voff = (uint32_t)((c * 4 + g) * 16);  // V: [dh/32][16 c][4 g][2][4 keys]
 
+  // The ring of page registers lives across units: while the last pages of a unit are
+  // multiplied, its free slots already receive the first pages of the next unit (`pre` of
+  // them), so the memory pipeline does not drain and refill at every unit boundary (that cost
+  // 6 - 8 us per unit).  A unit occupies a whole number of turns of the ring - an odd page
+  // count leaves a slot position unused - which keeps the slot of every page a compile-time
+  // index.
+  PageRegs<DH> buf[NBUF];
+  int pre = 0;
+  auto page_id = [&](const int (&id)[NIDS], int i) {
+    int v = __builtin_amdgcn_readlane(id[0], i & 63);
+#pragma unroll
+    for (int k = 1; k < NIDS; ++k)
+      if ((i >> 6) == k) v = __builtin_amdgcn_readlane(id[k], i & 63);
+    return v;
+  };
+
   for (;;) {
     const int kvh = (work % head_groups) * 4 + wave;
     const int work1 = unit_at(round + 1);
@@ -206,31 +226,55 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
       const int p_begin = it.key_begin >> 4;
       const int n_pages = ((it.key_end + 15) >> 4) - p_begin;
       const char* head_base = reinterpret_cast<const char*>(pages) + (size_t)kvh * blk_bytes;
-      auto page_id = [&](int i) {
-        int v = __builtin_amdgcn_readlane(ids[0], i & 63);
+      // the next unit of this wavefront, if it has one: its page ids are in ids1 by now
+      const int kvh1 = (work1 % head_groups) * 4 + wave;
+      const int np1 = (work1 < n_work && kvh1 < Hkv) ? ((it1.key_end + 15) >> 4) - (it1.key_begin >> 4) : 0;
+      const char* head_base1 = reinterpret_cast<const char*>(pages) + (size_t)(kvh1 < Hkv ? kvh1 : 0) * blk_bytes;
+      // The ids of the next unit's first pages come through the scalar cache: a cross-lane read
+      // of ids1 here would have to wait for that vector load, and with it (loads return in
+      // order, the number issued since is not known at compile time) for every page in flight.
+      int nid[NBUF];
 #pragma unroll
-        for (int k = 1; k < NIDS; ++k)
-          if ((i >> 6) == k) v = __builtin_amdgcn_readlane(ids[k], i & 63);
-        return v;
-      };
-#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)page_id(i) * page_bytes)
+      for (int j = 0; j < NBUF; ++j) nid[j] = j < np1 ? page_ids[list_base1 + (it1.key_begin >> 4) + j] : 0;
+#define NF_PAGE_BASE(i) (head_base + (size_t)(uint32_t)page_id(ids, (i)) * page_bytes)
+#define NF_NEXT_PAGE_BASE(j) (head_base1 + (size_t)(uint32_t)nid[j] * page_bytes)
       // NBUF pages in flight per wavefront: a ring of register buffers, refilled as soon as a
-      // page has been consumed
-      PageRegs<DH> buf[NBUF];
+      // page has been consumed; the first `pre` pages were loaded during the previous unit.
+      // (Loads return in order, and because a page's loads are conditional the generated code
+      // waits for everything in flight once per turn of the ring.  A variant with a fixed
+      // number of loads per step - a dummy page for a slot with nothing to fetch - gets exact
+      // waits from the compiler, but measured slower for every ring depth and grid size but
+      // one; more slots serve a small grid better.)
 #pragma unroll
       for (int j = 0; j < NBUF; ++j)
-        if (j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+        if (j >= pre && j < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(j), v_block_off, koff, voff);
+      const int padded = (n_pages + NBUF - 1) / NBUF * NBUF;
+      int pre_next = 0;
       for (int i = 0; i < n_pages; i += NBUF) {
 #pragma unroll
         for (int j = 0; j < NBUF; ++j) {
-          if (i + j < n_pages) {
-            attend_page<DH>(st, buf[j], qf, p_begin + i + j, g, lim, it.key_end, scale_log2);
-            if (i + j + NBUF < n_pages) load_page<DH, NT>(buf[j], NF_PAGE_BASE(i + j + NBUF), v_block_off, koff, voff);
+          const int q = i + j, t = q + NBUF;  // this slot's page, and the stream position it is refilled for
+          // where the slot's next page comes from is decided first, so that there is one load
+          // site per slot (two sites in two branches cost 10 % at small grids: the generated
+          // waits get more conservative with every site)
+          const char* base = reinterpret_cast<const char*>(pages);
+          bool has_page = true;
+          if (t < n_pages) {
+            base = NF_PAGE_BASE(t);
+          } else if (t >= padded && t - padded < np1) {
+            base = NF_NEXT_PAGE_BASE(j);  // t - padded == j
+            ++pre_next;
+          } else {
+            has_page = false;
           }
+          if (q < n_pages) attend_page<DH>(st, buf[j], qf, p_begin + q, g, lim, it.key_end, scale_log2);
+          if (has_page) load_page<DH, NT>(buf[j], base, v_block_off, koff, voff);
         }
         if (i == 0) list_base2 = page_indptr[it2.req];  // its descriptor has arrived by now
       }
+      pre = pre_next;
 #undef NF_PAGE_BASE
+#undef NF_NEXT_PAGE_BASE
 
       float l_run = st.l_run;
       l_run += __shfl_xor(l_run, 16, 64);
@@ -262,6 +306,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
       }
     } else {
       list_base2 = page_indptr[it2.req];
+      pre = 0;
     }
 
     ++round;
@@ -310,9 +355,11 @@ __global__ __launch_bounds__(DH) void attention_merge_kernel(const float* __rest
 }  // namespace
 
 // Kernel variant: pages in flight per wavefront (more pages = more bytes in flight per
-// wavefront but fewer resident wavefronts).
+// wavefront but fewer resident wavefronts).  With the default (5: two pages) the launcher
+// switches to four pages for small grids, where each wavefront has to stream more.
 static int g_attn_variant = 5;
 void nf_set_attention_variant(int v) { g_attn_variant = v; }
+
 
 template <int DH>
 static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* pages,
@@ -346,9 +393,11 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
   const int n_work = n_items * head_groups;
-  // Default: one persistent workgroup per compute unit.  Measured on MI355X: 4 wavefronts per
-  // CU already saturate HBM, a grid that is a multiple of the CU count keeps every CU equally
-  // loaded (320 workgroups on 256 CUs lose 25 %), and short grids end with a shorter tail.
+  // Default: persistent workgroups on 11/16 of the compute units (176 of 256), one per CU.
+  // Measured on MI355X at the 8B layer's dense batch of 2048: 1.50 ms against 1.54 with one
+  // workgroup on every CU and 1.55 with 160 - enough bytes in flight to saturate HBM, fewer
+  // requesters queueing in front of it; more workgroups than CUs lose much more (320 on 256
+  // CUs: 25 %).
   static int n_cus = 0;
   if (n_cus == 0) {
     int dev = 0;
@@ -357,14 +406,18 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
       n_cus = prop.multiProcessorCount;
     if (n_cus <= 0) n_cus = 256;
   }
-  int wgs = max_workgroups > 0 ? max_workgroups : (max_workgroups < 0 ? n_work : n_cus);
+  int wgs = max_workgroups > 0 ? max_workgroups : (max_workgroups < 0 ? n_work : std::max(8, n_cus * 11 / 16 / 8 * 8));
   if (wgs > n_work) wgs = n_work;
   const dim3 grid((unsigned)wgs);
+  // measured: at 5/8 of the CUs and below, four pages in flight per wavefront beat two (128
+  // workgroups: 1.72 against 1.83 ms)
+  const int variant = (g_attn_variant == 5 && max_workgroups >= 0 && 8 * wgs <= 5 * n_cus) ? 6 : g_attn_variant;
+
   if (shp.head_dim == 128)
-    return launch_attention_dh<128>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
+    return launch_attention_dh<128>(variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
                                     page_ids, items, n_work, head_groups, shp, scale_log2, parts, (bf16_t*)attn_out);
   if (shp.head_dim == 64)
-    return launch_attention_dh<64>(g_attn_variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
+    return launch_attention_dh<64>(variant, grid, s, (const bf16_t*)qkv, (const bf16_t*)pages, page_indptr,
                                    page_ids, items, n_work, head_groups, shp, scale_log2, parts, (bf16_t*)attn_out);
   return hipErrorInvalidValue;
 }
