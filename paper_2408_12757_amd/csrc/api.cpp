@@ -367,7 +367,7 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       e = traced(ctx, NF_K_ATTENTION, op, s, [&] {
         return nf_launch_attention(a.ws.qkv, a.kv->pages, a.b->page_indptr, a.b->page_ids,
                                    p->d_items + p->item_off[op.nano], p->item_cnt[op.nano], shp, a.ws.parts,
-                                   a.ws.attn, p->attn_wgs, s);
+                                   a.ws.attn, p->attn_wgs, s, p->item_pages[op.nano]);
       });
       if (e != hipSuccess) return e;
       return traced(ctx, NF_K_ATTN_MERGE, op, s, [&] {
@@ -707,7 +707,7 @@ extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf
   hipStream_t s = (hipStream_t)hip_stream;
   NF_HIP(ctx, nf_launch_attention(qkv, kv->pages, batch->page_indptr, batch->page_ids,
                                   plan->d_items + plan->item_off[nano_index], plan->item_cnt[nano_index], shp,
-                                  (float*)workspace, attn_out, plan->attn_wgs, s));
+                                  (float*)workspace, attn_out, plan->attn_wgs, s, plan->item_pages[nano_index]));
   NF_HIP(ctx, nf_launch_attention_merge((const float*)workspace, plan->d_groups + plan->group_off[nano_index],
                                         plan->group_cnt[nano_index], shp, attn_out, s));
   return NF_OK;

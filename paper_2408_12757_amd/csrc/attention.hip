@@ -388,16 +388,18 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
-                               hipStream_t s) {
+                               hipStream_t s, long long item_pages) {
   if (n_items <= 0) return hipSuccess;
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
   const int n_work = n_items * head_groups;
-  // Default: persistent workgroups on 11/16 of the compute units (176 of 256), one per CU.
-  // Measured on MI355X at the 8B layer's dense batch of 2048: 1.50 ms against 1.54 with one
-  // workgroup on every CU and 1.55 with 160 - enough bytes in flight to saturate HBM, fewer
-  // requesters queueing in front of it; more workgroups than CUs lose much more (320 on 256
-  // CUs: 25 %).
+  // Default: one persistent workgroup per compute unit; for a launch long enough to be bound
+  // by HBM (more than 1024 pages per workgroup) only 11/16 of that (176 of 256).  Measured on
+  // MI355X at the 8B layer's dense batch of 2048 with 2.5 M cached tokens: 1.50 ms against
+  // 1.54 with a workgroup on every CU and 1.55 with 160 - enough bytes in flight to saturate
+  // HBM, fewer requesters queueing in front of it - while the short launches of the iteration
+  // loop (0.6 M cached tokens, many prefill rows) lose 2 % of the layer with 176.  More
+  // workgroups than CUs lose much more (320 on 256 CUs: 25 %).
   static int n_cus = 0;
   if (n_cus == 0) {
     int dev = 0;
@@ -406,7 +408,9 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
       n_cus = prop.multiProcessorCount;
     if (n_cus <= 0) n_cus = 256;
   }
-  int wgs = max_workgroups > 0 ? max_workgroups : (max_workgroups < 0 ? n_work : std::max(8, n_cus * 11 / 16 / 8 * 8));
+  const bool hbm_bound = item_pages * head_groups >= 1024LL * n_cus;
+  const int automatic = hbm_bound ? std::max(8, n_cus * 11 / 16 / 8 * 8) : n_cus;
+  int wgs = max_workgroups > 0 ? max_workgroups : (max_workgroups < 0 ? n_work : automatic);
   if (wgs > n_work) wgs = n_work;
   const dim3 grid((unsigned)wgs);
   // measured: at 5/8 of the CUs and below, four pages in flight per wavefront beat two (128

@@ -72,6 +72,7 @@ struct nf_plan {
   NfAttnItem* d_items = nullptr;
   NfAttnGroup* d_groups = nullptr;
   std::vector<int> item_off, item_cnt, group_off, group_cnt;  // per nano-batch
+  std::vector<long long> item_pages;                          // per nano-batch: KV pages its items read (per kv head)
   int total_parts = 0;
   double est_time_us = 0.0;  // planner's estimate of the pipeline length
   std::string origin;        // "manual" | "search"

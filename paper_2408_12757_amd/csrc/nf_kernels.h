@@ -7,7 +7,7 @@
 // Keys per attention work item (a multiple of 1024: the kernel keeps the ids of 64 pages per
 // register).  Part of the numerics contract: a request's keys are always cut at multiples of
 // this length, whatever the batch split or CU share.
-constexpr int NF_ATTN_CHUNK = 4096;
+constexpr int NF_ATTN_CHUNK = 2048;
 
 // One attention work item: the rows of up to 16/G consecutive tokens of one
 // request (G = q heads per kv head) against keys [key_begin, key_end) of that
@@ -74,10 +74,13 @@ hipError_t nf_launch_gemm_dl_two_sums(const void* x, const void* w, void* out, c
                                       int K, int epilogue, hipStream_t s);
 hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, const void* residual, int M, int N,
                                     int K, float* partial, long long seg_stride, int variant, hipStream_t s);
+// max_workgroups: > 0 = that many persistent workgroups, 0 = automatic, < 0 = one workgroup
+// per work unit.  item_pages: KV pages the items read per kv head (the automatic grid depends
+// on it: a long, HBM-bound launch does better with fewer workgroups than CUs); 0 = unknown.
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
-                               hipStream_t s);
+                               hipStream_t s, long long item_pages = 0);
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
 // Fills a bf16 buffer with pseudo-random, roughly normal values (timing buffers only).

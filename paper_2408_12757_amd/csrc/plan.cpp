@@ -224,6 +224,7 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
   std::vector<NfAttnGroup> groups;
   p->item_off.assign(n_nano, 0);
   p->item_cnt.assign(n_nano, 0);
+  p->item_pages.assign(n_nano, 0);
   p->group_off.assign(n_nano, 0);
   p->group_cnt.assign(n_nano, 0);
   int part = 0;
@@ -257,6 +258,8 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
       t += n_tok;
     }
     p->item_cnt[i] = (int)items.size() - p->item_off[i];
+    for (size_t k = (size_t)p->item_off[i]; k < items.size(); ++k)
+      p->item_pages[i] += ((items[k].key_end + 15) >> 4) - (items[k].key_begin >> 4);
     p->group_cnt[i] = (int)groups.size() - p->group_off[i];
     // longest work first: the hardware dispatches workgroups in index order
     std::stable_sort(items.begin() + p->item_off[i], items.end(), [](const NfAttnItem& x, const NfAttnItem& y) {

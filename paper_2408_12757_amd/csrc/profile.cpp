@@ -221,7 +221,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
   }
   auto attn_call = [&](int v, int wgs, hipStream_t s) {
     hipError_t e = nf_launch_attention(qkv, pool, sb[v].d_pi, sb[v].d_pid, plans[v]->d_items, plans[v]->item_cnt[0],
-                                       ash, parts, aout, wgs, s);
+                                       ash, parts, aout, wgs, s, plans[v]->item_pages[0]);
     if (e == hipSuccess)
       e = nf_launch_attention_merge(parts, plans[v]->d_groups, plans[v]->group_cnt[0], ash, aout, s);
     return e == hipSuccess ? NF_OK : NF_EHIP;

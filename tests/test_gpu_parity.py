@@ -181,10 +181,10 @@ def small_gqa_model(**kw):
     # contexts around page boundaries, single-token batch pieces
     ("page_edges", small_gqa_model(), [1] * 8, [0, 1, 14, 15, 16, 17, 31, 32], 0),
     # contexts around the 64-page groups of the kernel's page-id registers (1024 keys each) and
-    # several attention chunks per request (chunk = 4096 keys) incl. exact multiples
-    ("long_ctx", small_gqa_model(), [1] * 10, [1023, 1024, 1025, 2047, 3000, 4094, 4095, 4096, 8191, 9000], 0),
-    # chunked prefill with cached prefix, chunk crossing pages, a page-id group and the 4096-key chunk edge
-    ("prefill_prior", small_gqa_model(), [37, 5, 40, 1, 1], [1000, 0, 4080, 77, 200], 3),
+    # several attention chunks per request (chunk = 2048 keys) incl. exact multiples
+    ("long_ctx", small_gqa_model(), [1] * 12, [1023, 1024, 1025, 2046, 2047, 2048, 3000, 4094, 4095, 4096, 8191, 9000], 0),
+    # chunked prefill with cached prefix, chunk crossing pages, a page-id group and the 2048-key chunk edge
+    ("prefill_prior", small_gqa_model(), [37, 5, 40, 40, 1, 1], [1000, 0, 2030, 4080, 77, 200], 4),
     # G = 8 (two tokens per row group), dh = 128
     ("gqa8", small_gqa_model(n_q_heads=16, n_kv_heads=2), [19, 1, 1, 1], [3, 40, 129, 16], 1),
     # G = 1, dh = 64 (sixteen tokens per row group)
