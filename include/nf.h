@@ -79,11 +79,12 @@ typedef struct nf_layer_weights {
  * memory).  One page holds page_size = 16 tokens and is bf16 [2][Hkv][16*dh]:
  * pages[p][0][h] is the K block and pages[p][1][h] the V block of kv head h.
  * Inside a block the 16 x dh elements are stored in the order the matrix cores
- * consume them, so that the attention kernel reads every block with fully
- * coalesced 1 KiB wavefront loads and no transpose:
- *   K block: [dh/8][16 tokens][8]            element (t, d) at ((d/8)*16 + t)*8 + d%8
- *   V block: [dh/32][16][4][2][4]            element (t, d) at
- *            ((((d/32)*16 + d%16)*4 + t/4)*2 + (d/16)%2)*4 + t%4
+ * consume them, so that the attention kernel reads every block with wavefront
+ * loads of long contiguous runs and no transpose, and a token's own elements
+ * stay within few cache lines:
+ *   K block: [dh/32][16 tokens][32]          element (t, d) at ((d/32)*16 + t)*32 + d%32
+ *   V block: [4][dh/32][16][2][4]            element (t, d) at
+ *            ((((t/4)*(dh/32) + d/32)*16 + d%16)*2 + (d/16)%2)*4 + t%4
  * nf_layer_forward WRITES the K/V of the batch's tokens into their slots.
  */
 typedef struct nf_kv_cache {

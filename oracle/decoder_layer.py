@@ -34,9 +34,9 @@ notes of the repository):
     logits, weighted sum of the selected experts' SwiGLU outputs;
   * KV pages hold page_size = 16 tokens; pages[p, 0, h] is the K block and
     pages[p, 1, h] the V block of kv head h.  The paper gives no layout; the one
-    read here is the library's interface: K block [dh/8][16 tokens][8], V block
-    [dh/32][16][4][2][4] with element (t, d) at index
-    ((((d//32)*16 + d%16)*4 + t//4)*2 + (d//16)%2)*4 + t%4  (see unpack_page_blocks).
+    read here is the library's interface: K block [dh/32][16 tokens][32], V block
+    [4][dh/32][16][2][4] with element (t, d) at index
+    ((((t//4)*(dh//32) + d//32)*16 + d%16)*2 + (d//16)%2)*4 + t%4  (see unpack_page_blocks).
 
 Inputs are bf16 bit patterns (uint16) or float arrays; every bf16 value is
 widened exactly and all arithmetic is float64.  Values produced in this
@@ -162,12 +162,12 @@ def moe_ffn(h, w_router, w_gate_up, w_down, top_k, expert_choice=None):
 def unpack_page_blocks(kblk, vblk, head_dim: int, page_size: int):
     """K and V of one page and kv head as [page_size, head_dim] arrays.
 
-    kblk: [head_dim/8, 16, 8]          kblk[c, t, e]       = K[t, 8c + e]
-    vblk: [head_dim/32, 16, 4, 2, 4]   vblk[q, c, g, h, j] = V[4g + j, 32q + 16h + c]
+    kblk: [head_dim/32, 16, 32]        kblk[s, t, e]       = K[t, 32s + e]
+    vblk: [4, head_dim/32, 16, 2, 4]   vblk[g, q, c, h, j] = V[4g + j, 32q + 16h + c]
     """
     assert page_size == 16
-    K = kblk.reshape(head_dim // 8, 16, 8).transpose(1, 0, 2).reshape(16, head_dim)
-    V = vblk.reshape(head_dim // 32, 16, 4, 2, 4).transpose(2, 4, 0, 3, 1).reshape(16, head_dim)
+    K = kblk.reshape(head_dim // 32, 16, 32).transpose(1, 0, 2).reshape(16, head_dim)
+    V = vblk.reshape(4, head_dim // 32, 16, 2, 4).transpose(0, 4, 1, 3, 2).reshape(16, head_dim)
     return K, V
 
 

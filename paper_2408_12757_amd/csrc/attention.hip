@@ -16,9 +16,16 @@
 // Matrix-core mapping (all wave64, 16 query rows padded with zeros):
 //   S^T[16 keys x 16 rows]  = K_page[16 x dh] . Q^T[dh x 16]   v_mfma_f32_16x16x32_bf16, dh/32 steps
 //   O^T[dh x 16 rows]      += V_page^T[dh x 16 keys] . P^T      v_mfma_f32_16x16x16_bf16, dh/16 blocks
-// The K and V blocks of a page are stored in MFMA operand order, so every wavefront load is
-// 1 KiB of contiguous memory that lands straight in operand registers: K as [dh/8 chunks]
-// [16 keys][8], V as [dh/32][16 dims][4 key groups][2 blocks][4 keys].  The accumulator
+// The K and V blocks of a page are stored in MFMA operand order, so every wavefront load
+// lands straight in operand registers: K as [dh/32][16 keys][32] (a wavefront load is 1 KiB
+// of contiguous memory: 16 keys x 64 bytes), V as [4 key groups][dh/32][16 dims][2 blocks]
+// [4 keys] (a wavefront load is four runs of 256 bytes).  Measured: the four-run V load
+// streams as fast as a contiguous one, while a row-major K block (sixteen 64-byte runs per
+// load) is 22 % slower.  Both orders keep the pieces a single token writes close together
+// (4 and 8 cache lines per head instead of 16 and 32 with the key index innermost in K and
+// the key group innermost in V): the append of the batch's tokens is a scatter of partial
+// cache lines, and it costs in its own kernel and again when this kernel reads the pages
+// while the partial lines are written back.  The accumulator
 // layout of S^T (lane = row, 4 consecutive keys) is exactly the B-operand layout the second
 // product needs, so P never leaves registers.
 #include <math.h>
@@ -37,10 +44,9 @@ struct PageRegs {
 };
 
 // Issues the loads of one page.  `page_base` is wave-uniform, so the loads take the
-// scalar-base + 32-bit lane offset form.  The page blocks are stored in MFMA operand order
-// (see the layout note in the C header), so every wavefront instruction reads 1 KiB of
-// contiguous memory: K step s is lanes x 16 bytes at s * 1024; V pair q (blocks 2q, 2q+1)
-// is lanes x 16 bytes at q * 1024.
+// scalar-base + 32-bit lane offset form.  K step s (dimensions 32s .. 32s+31 of all 16 keys)
+// is lanes x 16 bytes at s * 1024; V pair q (blocks 2q, 2q+1) is lanes x 16 bytes at
+// q * 256 inside each key group's run.
 template <int DH, bool NT = false>
 __device__ __forceinline__ void load_page(PageRegs<DH>& r, const char* __restrict__ page_base, uint32_t v_block_off,
                                           uint32_t koff, uint32_t voff) {
@@ -52,7 +58,7 @@ __device__ __forceinline__ void load_page(PageRegs<DH>& r, const char* __restric
   }
 #pragma unroll
   for (int q = 0; q < DH / 32; ++q) {
-    const bf16x8* p = reinterpret_cast<const bf16x8*>(vb + voff + q * 1024);
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(vb + voff + q * 256);
     const bf16x8 t = NT ? __builtin_nontemporal_load(p) : *p;
     r.v[2 * q] = __builtin_bit_cast(s16x4, (bf16x4){t[0], t[1], t[2], t[3]});
     r.v[2 * q + 1] = __builtin_bit_cast(s16x4, (bf16x4){t[4], t[5], t[6], t[7]});
@@ -185,8 +191,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
   const size_t blk_bytes = (size_t)16 * DH * 2;
   const size_t page_bytes = 2 * (size_t)Hkv * blk_bytes;
   const uint32_t v_block_off = (uint32_t)((size_t)Hkv * blk_bytes);
-  const uint32_t koff = (uint32_t)(lane * 16);         // K: [dh/8 chunks][16 keys][8]; chunk 4s+g, key c
-  const uint32_t voff = (uint32_t)((c * 4 + g) * 16);  // V: [dh/32][16 c][4 g][2][4 keys]
+  const uint32_t koff = (uint32_t)((c * 4 + g) * 16);      // K: [dh/32][16 keys][32]; step s at s * 1024, key c, dims 8g..
+  const uint32_t voff = (uint32_t)(g * DH * 8 + c * 16);  // V: [4 g][dh/32][16 c][2][4 keys]
 
   // The ring of page registers lives across units: while the last pages of a unit are
   // multiplied, its free slots already receive the first pages of the next unit (`pre` of

@@ -114,10 +114,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
       *reinterpret_cast<u32x4*>(hv + 8 * o) = ra;
       *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
     } else {
-      // K block [dh/8][16 keys][8]: dimensions 8o .. 8o+7 are chunk o, their partners chunk o + dh/16
+      // K block [dh/32][16 keys][32]: dimensions 8o .. 8o+7 are octet o, their partners octet o + dh/16
       bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh;
-      *reinterpret_cast<u32x4*>(kb + (o * 16 + slot) * 8) = ra;
-      *reinterpret_cast<u32x4*>(kb + ((octets + o) * 16 + slot) * 8) = rb;
+      const int o2 = octets + o;
+      *reinterpret_cast<u32x4*>(kb + ((o >> 2) * 16 + slot) * 32 + (o & 3) * 8) = ra;
+      *reinterpret_cast<u32x4*>(kb + ((o2 >> 2) * 16 + slot) * 32 + (o2 & 3) * 8) = rb;
       if (write_k_back) {  // the offload copy takes the rotated K from the qkv row
         *reinterpret_cast<u32x4*>(hv + 8 * o) = ra;
         *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
@@ -129,12 +130,12 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
     const int e0 = e8 * 8;
     const int h = e0 / dh, d0 = e0 - h * dh;
     const u32x4 vv = *reinterpret_cast<const u32x4*>(vrow + e0);
-    // V block [dh/32][16 c][4 g][2][4 keys]: dimension d = (2*quad + hb)*16 + c, key = 4*g + j
+    // V block [4 g][dh/32][16 c][2][4 keys]: dimension d = (2*quad + hb)*16 + c, key = 4*g + j
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int d = d0 + k;
       const int b = d >> 4, c = d & 15;
-      const int off = ((((b >> 1) * 16 + c) * 4 + (slot >> 2)) * 2 + (b & 1)) * 4 + (slot & 3);
+      const int off = ((((slot >> 2) * (dh >> 5) + (b >> 1)) * 16 + c) * 2 + (b & 1)) * 4 + (slot & 3);
       vpage[(size_t)h * 16 * dh + off] = (bf16_t)((k & 1) ? (vv[k >> 1] >> 16) : (vv[k >> 1] & 0xffffu));
     }
   }

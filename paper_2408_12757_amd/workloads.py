@@ -275,12 +275,12 @@ def make_kv_pages_host(m: ModelDesc, num_pages: int, seed: int) -> np.ndarray:
 def page_block_index(head_dim: int, page_size: int = PAGE_SIZE):
     """Index maps of the page block layouts of the library's interface: kidx[t, d] and
     vidx[t, d] give the position of element (token slot t, dimension d) inside the K block
-    ([dh/8][16][8]) and the V block ([dh/32][16][4][2][4]).  Data formatting only."""
+    ([dh/32][16][32]) and the V block ([4][dh/32][16][2][4]).  Data formatting only."""
     assert page_size == 16
     t = np.arange(page_size)[:, None]
     d = np.arange(head_dim)[None, :]
-    kidx = ((d // 8) * 16 + t) * 8 + d % 8
-    vidx = ((((d // 32) * 16 + d % 16) * 4 + t // 4) * 2 + (d // 16) % 2) * 4 + t % 4
+    kidx = ((d // 32) * 16 + t) * 32 + d % 32
+    vidx = ((((t // 4) * (head_dim // 32) + d // 32) * 16 + d % 16) * 2 + (d // 16) % 2) * 4 + t % 4
     return kidx, vidx
 
 

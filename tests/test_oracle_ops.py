@@ -245,8 +245,8 @@ def test_moe_selects_the_routed_expert_only():
 
 def test_gather_kv_layout():
     # The page block layouts, pinned element by element with the index formulas of the
-    # interface: K (t, d) at ((d//8)*16 + t)*8 + d%8;
-    # V (t, d) at ((((d//32)*16 + d%16)*4 + t//4)*2 + (d//16)%2)*4 + t%4.
+    # interface: K (t, d) at ((d//32)*16 + t)*32 + d%32;
+    # V (t, d) at ((((t//4)*(dh//32) + d//32)*16 + d%16)*2 + (d//16)%2)*4 + t%4.
     Hkv, dh, P = 2, 64, 16
     n_pages = 3
     pages = np.zeros((n_pages, 2, Hkv, P * dh))
@@ -255,8 +255,8 @@ def test_gather_kv_layout():
         for h in range(Hkv):
             for t in range(P):
                 for d in range(dh):
-                    pages[p, 0, h, ((d // 8) * 16 + t) * 8 + d % 8] = val(p, h, t, d)
-                    pages[p, 1, h, ((((d // 32) * 16 + d % 16) * 4 + t // 4) * 2 + (d // 16) % 2) * 4 + t % 4] = \
+                    pages[p, 0, h, ((d // 32) * 16 + t) * 32 + d % 32] = val(p, h, t, d)
+                    pages[p, 1, h, ((((t // 4) * (dh // 32) + d // 32) * 16 + d % 16) * 2 + (d // 16) % 2) * 4 + t % 4] = \
                         -val(p, h, t, d)
     # every position of a block is used exactly once
     assert len(np.unique(pages[0, 0, 0])) == P * dh and len(np.unique(pages[0, 1, 0])) == P * dh
