@@ -175,7 +175,7 @@ hipError_t launch(const void* x, const void* w, void* out, const void* residual,
 }  // namespace
 
 // Tile choice.  0 = heuristic; 1 = 128x128; 2 = 256x128 (BM x BN); 3 = 128x256; 4 = 256x256;
-// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..19 = the direct-to-LDS
+// 5 = 256x256 and 6 = 256x128 with 8 wavefronts (512 threads); 7..20 = the direct-to-LDS
 // kernels of gemm_dl.hip.  Every variant walks K in the
 // same order with the same MFMA, so the choice never changes an output bit.  Two-segment
 // operations (nf_gemm_k_segments) have their own launch forms and take the tile as a hint.
@@ -255,9 +255,12 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
       return speed * sqrt((double)tiles / (double)(rounds * 256));
     };
     const double s13 = score(256, 256, 1.0), s12 = score(256, 128, 0.92), s7 = score(128, 128, 0.84);
+    const double s20 = (epilogue != EPI_SWIGLU && n_eff % 192 == 0) ? score(256, 192, 0.97) : 0.0;
     tile = (s13 >= s12 && s13 >= s7) ? 13 : (s12 >= s7 ? 19 : 7);
+    if (s20 > s13 && s20 > s12 && s20 > s7) tile = 20;
   }
-  if (tile >= 7 && tile <= 19) {
+  if (tile >= 7 && tile <= 20) {
+    if (tile == 20 && (n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 19;
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
     if (tile == 13 && n_eff % 256 != 0) tile = 12;
     if ((tile == 15 || tile == 16) && n_eff % 256 != 0) tile = 18;

@@ -545,7 +545,7 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
 //           11..14 = 7, 9, 10, 8 with the explicitly scheduled main loop;
 //           15..19 = the second main loop: 256x256 with K-step 32 and 4 / 5 stages, 256x256 with
 //           K-step 64 and 2 stages, 256x128 with K-step 32 and 6 stages, 256x128 with K-step 64
-//           and 3 stages.
+//           and 3 stages; 20 = 256x192 with K-step 64 and 2 stages (N % 192 == 0, no SwiGLU).
 // Requires K % 64 == 0 and the (stacked) N % 128 == 0 (% 256 for the 256-wide tiles).
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s) {
@@ -564,6 +564,11 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     case 17: return launch_dl2<256, 256, 2, 4, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 18: return launch_dl2<256, 128, 4, 2, 6, false, 32>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 19: return launch_dl2<256, 128, 4, 2, 3, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 20:
+      // 256x192: N = 6144 (the 8B layer's KQV) gives 8 x 32 = 256 tiles, one per CU; the SwiGLU
+      // epilogue needs an even number of 32-column groups per wavefront and has no such form
+      if (epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
+      return launch_dl2<256, 192, 4, 2, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
     default: return hipErrorInvalidValue;
   }
 }
