@@ -360,6 +360,9 @@ int nf_op_rmsnorm(const void *x, const void *g, void *out, int n_tokens, int hid
 enum { NF_EPI_NONE = 0, NF_EPI_RESIDUAL = 1, NF_EPI_SWIGLU = 2 };
 int nf_op_gemm(const void *x, const void *w, void *out, const void *residual, int M, int N, int K,
                int epilogue, void *hip_stream);
+/* Number of K segments (1 or 2) the library sums a dense operation of this shape in - the rule
+ * stated above, part of the numerics contract.  Host only; 0 for arguments nf_op_gemm rejects. */
+int nf_gemm_segments(int N, int K, int epilogue);
 
 /* Rotary embedding of the Q and K heads of qkv[n_tokens, (Hq+2Hkv)*dh] (Q rotated
  * in place) and append of K, V into the pages, for tokens [tok_begin, tok_end). */

@@ -25,7 +25,7 @@ EXPORTS = [
     "nf_ctx_set_trace", "nf_ctx_read_trace", "nf_ctx_lane_stream", "nf_ctx_mask_stream", "nf_tune_set",
     "nf_nano_ops_dependent", "nf_profile", "nf_search_pipeline", "nf_simulate_pipeline", "nf_plan_nanobatches", "nf_plan_manual", "nf_plan_describe", "nf_plan_destroy",
     "nf_workspace_bytes", "nf_plan_workspace_bytes", "nf_workspace_region", "nf_layer_forward",
-    "nf_op_rmsnorm", "nf_op_gemm", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
+    "nf_op_rmsnorm", "nf_op_gemm", "nf_gemm_segments", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax",
@@ -127,6 +127,8 @@ def lib() -> C.CDLL:
                                     vp, vp, vp, sz, vp]
     L.nf_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp]
     L.nf_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.nf_gemm_segments.argtypes = [i32, i32, i32]
+    L.nf_gemm_segments.restype = i32
     L.nf_op_rope_append.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, i32, i32, vp]
     L.nf_op_attention.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, vp, vp, sz, i32, vp]
     _lib = L
@@ -382,6 +384,10 @@ def nf_layers_forward(ctx: Context, model, weights: "list[nf_layer_weights]", pa
 
 def nf_op_rmsnorm(x_ptr, g_ptr, out_ptr, n_tokens, hidden, eps, stream=0):
     _check(lib().nf_op_rmsnorm(x_ptr, g_ptr, out_ptr, int(n_tokens), int(hidden), float(eps), stream), "nf_op_rmsnorm")
+
+
+def nf_gemm_segments(N: int, K: int, epilogue: int = NF_EPI_NONE) -> int:
+    return int(lib().nf_gemm_segments(int(N), int(K), int(epilogue)))
 
 
 def nf_op_gemm(x_ptr, w_ptr, out_ptr, residual_ptr, M, N, K, epilogue=NF_EPI_NONE, stream=0):

@@ -663,6 +663,11 @@ extern "C" int nf_op_rmsnorm(const void* x, const void* g, void* out, int n_toke
   return nf_launch_rmsnorm(x, g, out, n_tokens, hidden, eps, (hipStream_t)hip_stream) == hipSuccess ? NF_OK : NF_EHIP;
 }
 
+extern "C" int nf_gemm_segments(int N, int K, int epilogue) {
+  if (N <= 0 || K <= 0 || epilogue < NF_EPI_NONE || epilogue > NF_EPI_SWIGLU || K % 64 || N % 64) return 0;
+  return nf_gemm_k_segments(N, K, epilogue);
+}
+
 extern "C" int nf_op_gemm(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                           int epilogue, void* hip_stream) {
   if (!x || !w || !out || M < 0 || N <= 0 || K <= 0) return NF_EINVAL;

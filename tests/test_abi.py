@@ -91,3 +91,24 @@ def test_argument_errors_are_reported_before_anything_touches_the_gpu():
         assert e.value.status == nf.NF_EINVAL, key
     for key, value in (("gemm.tile", 0), ("search.layers", 1), ("search.rank", 0), ("gemm.grouped_tile", 0)):
         nf.nf_tune_set(key, value)
+
+
+def test_k_segment_rule_looks_at_the_shape_only():
+    """Which dense operations add the sums of the two halves of K is part of the numerics
+    contract (a row's bits must not depend on the nano-batch it is computed in, so the rule may
+    not involve M): the down projections of the 8B layer and of long-K toy models do, the
+    other operations of the configurations here do not."""
+    E = (nf.NF_EPI_NONE, nf.NF_EPI_RESIDUAL, nf.NF_EPI_SWIGLU)
+    assert nf.nf_gemm_segments(4096, 14336, nf.NF_EPI_RESIDUAL) == 2        # 8B Down
+    assert nf.nf_gemm_segments(512, 8192, nf.NF_EPI_NONE) == 2
+    assert nf.nf_gemm_segments(8192, 28672, nf.NF_EPI_RESIDUAL) == 1        # 70B Down: N = 8192 fills the chip anyway
+    assert nf.nf_gemm_segments(6144, 4096, nf.NF_EPI_NONE) == 1             # KQV
+    assert nf.nf_gemm_segments(4096, 4096, nf.NF_EPI_RESIDUAL) == 1         # O
+    assert nf.nf_gemm_segments(14336, 4096, nf.NF_EPI_SWIGLU) == 1          # Up/Gate
+    assert nf.nf_gemm_segments(128, 8192, nf.NF_EPI_SWIGLU) == 1            # never with the SwiGLU epilogue
+    assert nf.nf_gemm_segments(4096, 8128, nf.NF_EPI_NONE) == 1             # K below 8192
+    assert nf.nf_gemm_segments(4160, 8320, nf.NF_EPI_NONE) == 1             # N, K not multiples of 128
+    assert nf.nf_gemm_segments(4096, 8192, nf.NF_EPI_NONE) == 2 and nf.nf_gemm_segments(4224, 8192, nf.NF_EPI_NONE) == 1  # K >= 2 N
+    for bad in ((0, 64, 0), (64, 0, 0), (64, 64, 7), (60, 64, 0), (64, 100, 0)):
+        assert nf.nf_gemm_segments(*bad) == 0
+    assert all(nf.nf_gemm_segments(256, 16384, e) in (1, 2) for e in E)
