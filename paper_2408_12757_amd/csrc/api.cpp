@@ -181,6 +181,7 @@ struct Workspace {
   int32_t* row_token;      // [B*k]  token of a sorted row
   int32_t* expert_offset;  // [NF_MAX_NANO_OFFSETS][E + 1] per nano-batch
   char* expert_out;        // [B*k, D]
+  float* expert_partial;   // [2][B*k, D] fp32 sums of the K halves when the experts' down projection has two segments
   // dense models whose down projection is a two-segment operation: [2][B, D] fp32 sums of the
   // two K halves, for nano-batches that run the halves on different workgroups
   float* down_partial;
@@ -212,7 +213,9 @@ Workspace layout_workspace(const nf_model_desc* m, int n_tokens, size_t n_parts,
   w.slot_of = (int32_t*)take(moe ? B * k * 4 : 0);
   w.row_token = (int32_t*)take(moe ? B * k * 4 : 0);
   w.expert_offset = (int32_t*)take(moe ? (size_t)kMaxNanoOffsets * (m->n_experts + 1) * 4 : 0);
-  w.expert_out = take(moe ? B * k * (size_t)m->hidden * 2 : 0);
+  const bool moe_two_seg = moe && nf_gemm_k_segments(m->hidden, m->ffn_inner, NF_EPI_NONE) == 2;
+  w.expert_out = take(moe && !moe_two_seg ? B * k * (size_t)m->hidden * 2 : 0);
+  w.expert_partial = moe_two_seg ? (float*)take(2 * B * k * (size_t)m->hidden * sizeof(float)) : nullptr;
   const bool two_seg = !moe && nf_gemm_k_segments(m->hidden, m->ffn_inner, NF_EPI_RESIDUAL) == 2;
   w.down_partial = two_seg ? (float*)take(2 * B * m->hidden * sizeof(float)) : nullptr;
   w.total = off;
@@ -409,14 +412,16 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       if (m->n_experts > 1) {
         const int E = m->n_experts, k = m->top_k;
         const int32_t* eoff = a.ws.expert_offset + (size_t)op.nano * (E + 1);
+        const size_t Bk = (size_t)std::max(1, a.b->n_tokens) * k;
+        const NfGemmSplit moe_split{a.ws.expert_partial, (long long)(Bk * D)};
         e = traced(ctx, NF_K_GEMM, op, s, [&] {
           return nf_launch_grouped_gemm(a.ws.f, a.w->w_down, a.ws.expert_out, M * k, (int)D, (int)I, NF_EPI_NONE, eoff,
-                                        nullptr, E, (long long)(D * I), s);
+                                        nullptr, E, (long long)(D * I), s, moe_split);
         });
         if (e != hipSuccess) return e;
         return traced(ctx, NF_K_MOE_COMBINE, op, s, [&] {
           return nf_launch_moe_combine(a.ws.y, a.ws.expert_out, a.ws.slot_of, a.ws.expert_w, a.x_out, t0, op.tok_end,
-                                       (int)D, k, s);
+                                       (int)D, k, s, moe_split.partial, moe_split.seg_stride);
         });
       }
       return traced(ctx, NF_K_GEMM, op, s, [&] {

@@ -282,10 +282,20 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
 // (N % 128 == 0 for SwiGLU counts the stacked 2N rows), K % 64 == 0.
 hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                   const int32_t* expert_offset, const int32_t* row_index, int n_experts,
-                                  long long w_stride, hipStream_t s) {
+                                  long long w_stride, hipStream_t s, NfGemmSplit split) {
   if (rows <= 0) return hipSuccess;
   const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+  if (split.partial && epilogue == EPI_NONE && nf_gemm_k_segments(N, K, epilogue) == 2) {
+    // The experts' down projection: few output columns and a long K.  Every (expert, tile)
+    // splits into its two K halves, which doubles the workgroups (the 8-expert layer at 2048
+    // tokens has about 320 tiles of 256x256 for 256 CUs) and halves the work a partly
+    // filled tile wastes.
+    int variant = g_grouped_tile == 12 ? 12 : (g_grouped_tile == 19 ? 19 : 13);  // measured: 256x256 halves best
+    if (variant == 13 && N % 256 != 0) variant = 19;
+    return nf_launch_gemm_dl_grouped_halves(x, w, rows, N, K, split.partial, split.seg_stride, expert_offset,
+                                            row_index, n_experts, w_stride, variant, s);
+  }
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
   // 256x256 tiles halve the re-reads of the gathered rows; 256x128 where the width does not allow them
   int tile = g_grouped_tile ? g_grouped_tile : (n_eff % 256 == 0 ? 13 : 19);

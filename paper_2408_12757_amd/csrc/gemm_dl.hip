@@ -460,32 +460,33 @@ hipError_t allow_lds(Kern kern, size_t lds_bytes, bool& done) {
   return e;
 }
 
-// The two halves of K as separate workgroups (grid.y = 2), fp32 sums to scratch.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool PIPE>
-hipError_t launch_dl_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s) {
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+// The two halves of K as separate workgroups (grid.y = 2), fp32 sums to scratch.  GROUPED:
+// M is the total row count, every expert may add one partial tile (see GroupedArgs).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool PIPE, bool GROUPED = false>
+hipError_t launch_dl_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s,
+                            GroupedArgs grp = GroupedArgs{nullptr, nullptr, 0, 0}) {
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM, tiles_n = N / BN;
   const size_t lds_bytes = (size_t)STAGES * (BM + BN) * 128;
-  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, false, PIPE>;
+  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, GROUPED, PIPE>;
   static bool attr_set = false;
   hipError_t e = allow_lds(kern, lds_bytes, attr_set);
   if (e != hipSuccess) return e;
   kern<<<dim3(tiles_m * tiles_n, 2), dim3(64 * WAVES_M * WAVES_N), lds_bytes, s>>>(
-      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
-      GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n, grp, kr);
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int BKT>
-hipError_t launch_dl2_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s) {
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int BKT, bool GROUPED = false>
+hipError_t launch_dl2_halves(const void* x, const void* w, int M, int N, int K, KRange kr, hipStream_t s,
+                             GroupedArgs grp = GroupedArgs{nullptr, nullptr, 0, 0}) {
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM, tiles_n = N / BN;
   const size_t lds_bytes = (size_t)STAGES * (BM + BN) * BKT * 2;
-  auto kern = gemm_dl2_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, false, BKT>;
+  auto kern = gemm_dl2_kernel<BM, BN, WAVES_M, WAVES_N, EPI_PARTIAL, STAGES, GROUPED, BKT>;
   static bool attr_set = false;
   hipError_t e = allow_lds(kern, lds_bytes, attr_set);
   if (e != hipSuccess) return e;
   kern<<<dim3(tiles_m * tiles_n, 2), dim3(64 * WAVES_M * WAVES_N), lds_bytes, s>>>(
-      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
-      GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+      (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n, grp, kr);
   return hipGetLastError();
 }
 
@@ -537,6 +538,23 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
   gemm_reduce2_kernel<<<dim3((unsigned)((n_quads + 255) / 256)), dim3(256), 0, s>>>(
       partial, partial + seg_stride, (const bf16_t*)residual, (bf16_t*)out, n_quads);
   return hipGetLastError();
+}
+
+// Grouped mode of the two-segment operation (the experts' down projection): the fp32 sums of
+// the two halves of K go to partial and partial + seg_stride, rows at their sorted positions;
+// the consumer (the combine kernel) adds them.  variant: 12 / 19 = 256x128 tiles, 13 = 256x256.
+hipError_t nf_launch_gemm_dl_grouped_halves(const void* x, const void* w, int rows, int N, int K, float* partial,
+                                            long long seg_stride, const int32_t* expert_offset,
+                                            const int32_t* row_index, int n_experts, long long w_stride, int variant,
+                                            hipStream_t s) {
+  const GroupedArgs grp{expert_offset, row_index, n_experts, w_stride};
+  const KRange kr{K, partial, seg_stride};
+  switch (variant) {
+    case 12: return launch_dl_halves<256, 128, 4, 2, 3, true, true>(x, w, rows, N, K, kr, s, grp);
+    case 13: return launch_dl_halves<256, 256, 2, 4, 2, true, true>(x, w, rows, N, K, kr, s, grp);
+    case 19: return launch_dl2_halves<256, 128, 4, 2, 3, 64, true>(x, w, rows, N, K, kr, s, grp);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 // Variants: 7 = 128x128 tile, 4 wavefronts, 2 stages (two workgroups per CU);

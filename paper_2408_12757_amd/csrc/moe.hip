@@ -124,7 +124,11 @@ __global__ __launch_bounds__(1024) void moe_scatter_kernel(const int32_t* __rest
 }
 
 // z[t] = y[t] + sum_k w[t,k] * expert_out[slot_of[t,k]], summed in k order (fp32).
+// PARTIAL: an expert's output row is given as the fp32 sums of the two halves of its down
+// projection's K (p0, p1) and is bf16(p0 + p1) - the value a two-segment dense operation stores.
+template <bool PARTIAL>
 __global__ __launch_bounds__(256) void moe_combine_kernel(const bf16_t* __restrict__ y, const bf16_t* __restrict__ eo,
+                                                          const float* __restrict__ p0, const float* __restrict__ p1,
                                                           const int32_t* __restrict__ slot_of,
                                                           const float* __restrict__ wts, bf16_t* __restrict__ z,
                                                           int tok_begin, int D, int K) {
@@ -139,11 +143,22 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const bf16_t* __restri
     }
     for (int k = 0; k < K; ++k) {
       const float w = wts[(size_t)t * K + k];
-      const u32x4 ee = *reinterpret_cast<const u32x4*>(eo + (size_t)slot_of[(size_t)t * K + k] * D + v * 8);
+      const size_t row = (size_t)slot_of[(size_t)t * K + k] * D + v * 8;
+      if (PARTIAL) {
+        const f32x4 a0 = *reinterpret_cast<const f32x4*>(p0 + row), a1 = *reinterpret_cast<const f32x4*>(p0 + row + 4);
+        const f32x4 b0 = *reinterpret_cast<const f32x4*>(p1 + row), b1 = *reinterpret_cast<const f32x4*>(p1 + row + 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc[2 * i] += w * __uint_as_float(ee[i] << 16);
-        acc[2 * i + 1] += w * __uint_as_float(ee[i] & 0xffff0000u);
+        for (int i = 0; i < 4; ++i) {
+          acc[i] += w * bf2f(f2bf(a0[i] + b0[i]));
+          acc[4 + i] += w * bf2f(f2bf(a1[i] + b1[i]));
+        }
+      } else {
+        const u32x4 ee = *reinterpret_cast<const u32x4*>(eo + row);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] += w * __uint_as_float(ee[i] << 16);
+          acc[2 * i + 1] += w * __uint_as_float(ee[i] & 0xffff0000u);
+        }
       }
     }
     u32x4 o;
@@ -174,10 +189,16 @@ hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int t
 }
 
 hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
-                                 void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s) {
+                                 void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s,
+                                 const float* expert_partial, long long seg_stride) {
   if (tok_end <= tok_begin) return hipSuccess;
-  moe_combine_kernel<<<dim3(tok_end - tok_begin), dim3(256), 0, s>>>((const bf16_t*)y, (const bf16_t*)expert_out,
-                                                                    slot_of, expert_w, (bf16_t*)z, tok_begin, hidden,
-                                                                    top_k);
+  if (expert_partial)
+    moe_combine_kernel<true><<<dim3(tok_end - tok_begin), dim3(256), 0, s>>>(
+        (const bf16_t*)y, nullptr, expert_partial, expert_partial + seg_stride, slot_of, expert_w, (bf16_t*)z,
+        tok_begin, hidden, top_k);
+  else
+    moe_combine_kernel<false><<<dim3(tok_end - tok_begin), dim3(256), 0, s>>>(
+        (const bf16_t*)y, (const bf16_t*)expert_out, nullptr, nullptr, slot_of, expert_w, (bf16_t*)z, tok_begin,
+        hidden, top_k);
   return hipGetLastError();
 }

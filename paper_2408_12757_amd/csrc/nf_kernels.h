@@ -88,9 +88,16 @@ hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float s
 void nf_set_attention_variant(int v);
 void nf_set_gemm_tile(int v);
 void nf_set_grouped_gemm_tile(int v);
+// split: scratch for a two-segment operation (nf_gemm_k_segments); with it such an operation
+// leaves the fp32 sums of its two K halves in the scratch and does NOT write `out`: the
+// consumer adds the halves (nf_launch_moe_combine with the same scratch).
 hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                   const int32_t* expert_offset, const int32_t* row_index, int n_experts,
-                                  long long w_stride, hipStream_t s);
+                                  long long w_stride, hipStream_t s, NfGemmSplit split = NfGemmSplit{nullptr, 0});
+hipError_t nf_launch_gemm_dl_grouped_halves(const void* x, const void* w, int rows, int N, int K, float* partial,
+                                            long long seg_stride, const int32_t* expert_offset,
+                                            const int32_t* row_index, int n_experts, long long w_stride, int variant,
+                                            hipStream_t s);
 hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                      const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                      long long w_stride, int variant, hipStream_t s);
@@ -105,8 +112,12 @@ hipError_t nf_launch_moe_router(const void* h, const void* w_router, int32_t* ex
                                 int tok_begin, int tok_end, int hidden, int n_experts, int top_k, hipStream_t s);
 hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int tok_end, int n_experts, int top_k,
                                  int32_t* expert_offset, int32_t* row_token, int32_t* slot_of, hipStream_t s);
+// expert_partial (optional): the experts' outputs as the fp32 sums of two K halves, seg_stride
+// floats apart (see nf_launch_grouped_gemm); then expert_out is not read and a row's output is
+// bf16(half 0 + half 1).
 hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
-                                 void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s);
+                                 void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s,
+                                 const float* expert_partial = nullptr, long long seg_stride = 0);
 void nf_set_gemm_debug(int v);
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s);

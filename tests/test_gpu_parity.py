@@ -492,6 +492,26 @@ def test_moe_top1_and_four_experts(ctx):
     plan.close()
 
 
+def test_moe_down_projection_with_two_k_segments(ctx):
+    """Experts with a long inner dimension (8192 over hidden 512): the grouped down projection
+    leaves the fp32 sums of its two K halves in the workspace and the combine kernel adds them.
+    Checked against the oracle and for split invariance (rows land in different tiles, and
+    beside different rows, in every structure)."""
+    m = moe_model(hidden=512, n_q_heads=4, n_kv_heads=2, ffn_inner=8192, n_experts=4, top_k=2)
+    b = wl.batch_from_lengths([40] + [1] * 150, [7] + list(np.random.default_rng(4).integers(1, 120, size=150)), 1,
+                              np.random.default_rng(10))
+    case = Case(m, b, 4300, ctx=ctx)
+    ref = None
+    for bounds, overlap in (([0, b.n_tokens], False), ([0, 64, b.n_tokens], True), ([0, 30, 100, b.n_tokens], False)):
+        plan = nf.nf_plan_manual(case.ctx, m, case.args, bounds, overlap)
+        z, pages, e = check_moe_case(case, plan)
+        say("two-segment expert down projection", bounds, "rel err", e)
+        if ref is None:
+            ref = (z, pages)
+        assert np.array_equal(z, ref[0]) and np.array_equal(pages, ref[1]), bounds
+        plan.close()
+
+
 # ------------------------------------------------------------- HIP graph capture ---
 
 @pytest.mark.skip(reason="capturing nf_layer_forward with torch.cuda.graph ended in a host-side segmentation fault "
