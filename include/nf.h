@@ -180,6 +180,8 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
  * (wrong results).  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
  * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.
+ * key "offload.dma": 1 (default) = the simultaneous KV offload copies the rows with a strided
+ * device-to-host copy on the copy engines, 0 = with a small kernel that stores to the host buffer.
  * Apart from "gemm.debug", variants never change a result bit.
  * Returns NF_EINVAL for an unknown key or a value out of range.
  */

@@ -119,5 +119,6 @@ hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const in
                                  void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s,
                                  const float* expert_partial = nullptr, long long seg_stride = 0);
 void nf_set_gemm_debug(int v);
+void nf_set_offload_dma(int v);
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s);
