@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
   const int t = tok_begin + blockIdx.x;
   const int r = tok_req[t];
   const int pos = ctx_len[r] + (t - q_indptr[r]);
+  const bool lone = q_indptr[r + 1] - q_indptr[r] == 1;
   const int page = page_ids[page_indptr[r] + (pos >> 4)];
   const int slot = pos & 15;
   const int half = dh >> 1;
@@ -115,13 +116,21 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
       *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
     } else {
       // K block [dh/32][16 keys][32]: dimensions 8o .. 8o+7 are octet o, their partners octet o + dh/16.
-      // The page stores are non-temporal: they are partial cache lines, and written back lazily
-      // they cost the attention kernel that follows more than they cost here (measured at the 8B
-      // layer: 25 us of the layer).
+      // The page stores of a request's only token (a decode request) are non-temporal: they are
+      // partial cache lines that nothing completes, and written back lazily they cost the
+      // attention kernel that follows more than they cost here (measured at the 8B layer: 25 us
+      // of the layer).  The tokens of a prefill chunk fill lines together and keep plain stores.
       bf16_t* kb = kpage + (size_t)(h - Hq) * 16 * dh;
       const int o2 = octets + o;
-      __builtin_nontemporal_store(ra, reinterpret_cast<u32x4*>(kb + ((o >> 2) * 16 + slot) * 32 + (o & 3) * 8));
-      __builtin_nontemporal_store(rb, reinterpret_cast<u32x4*>(kb + ((o2 >> 2) * 16 + slot) * 32 + (o2 & 3) * 8));
+      u32x4* ka = reinterpret_cast<u32x4*>(kb + ((o >> 2) * 16 + slot) * 32 + (o & 3) * 8);
+      u32x4* kc = reinterpret_cast<u32x4*>(kb + ((o2 >> 2) * 16 + slot) * 32 + (o2 & 3) * 8);
+      if (lone) {
+        __builtin_nontemporal_store(ra, ka);
+        __builtin_nontemporal_store(rb, kc);
+      } else {
+        *ka = ra;
+        *kc = rb;
+      }
       if (write_k_back) {  // the offload copy takes the rotated K from the qkv row
         *reinterpret_cast<u32x4*>(hv + 8 * o) = ra;
         *reinterpret_cast<u32x4*>(hv + half + 8 * o) = rb;
@@ -139,8 +148,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
       const int d = d0 + k;
       const int b = d >> 4, c = d & 15;
       const int off = ((((slot >> 2) * (dh >> 5) + (b >> 1)) * 16 + c) * 2 + (b & 1)) * 4 + (slot & 3);
-      __builtin_nontemporal_store((bf16_t)((k & 1) ? (vv[k >> 1] >> 16) : (vv[k >> 1] & 0xffffu)),
-                                  &vpage[(size_t)h * 16 * dh + off]);
+      const bf16_t val = (bf16_t)((k & 1) ? (vv[k >> 1] >> 16) : (vv[k >> 1] & 0xffffu));
+      if (lone)
+        __builtin_nontemporal_store(val, &vpage[(size_t)h * 16 * dh + off]);
+      else
+        vpage[(size_t)h * 16 * dh + off] = val;
     }
   }
 }
