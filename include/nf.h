@@ -401,9 +401,10 @@ int nf_op_argmax(const void *logits, int n_rows, int vocab, const int32_t *out_i
  * Simultaneous KV offload (Sec. 4.2.2 "Simultaneous offloading"): while it is switched on,
  * every layer iteration copies the K row (after the rotary embedding) and the V row of every
  * token of the batch, as they come out of KQV generation, to host memory, so that the host
- * holds the same K/V as the cache.  The copy is issued by the GPU (a small kernel on a stream
- * of the library) right after the KQV nano-operation and runs beside the attention and FFN
- * operations; the call's work on hip_stream is complete only after the copies.
+ * holds the same K/V as the cache.  The copy is enqueued on a stream of the library behind the
+ * nano-batch's attention launch (a strided device-to-host copy on the copy engines, or a small
+ * kernel: key "offload.dma" of nf_tune_set) and runs beside the attention and FFN operations;
+ * the call's work on hip_stream is complete only after the copies.
  * host_rows: HOST memory the device can write (pinned, e.g. hipHostMalloc), 16-byte aligned;
  *   layer l of a call writes row t (2 * n_kv_heads * head_dim bf16: K heads, then V heads) of
  *   token t at host_rows + l * layer_stride_bytes + t * row bytes (l = 0 for nf_layer_forward).
