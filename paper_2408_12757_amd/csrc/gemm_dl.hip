@@ -16,6 +16,8 @@
 // the two halves of that window, so the slot must vary with r >> 1.  Measured: 179 B/clk/CU
 // against 119 with the XOR taken from r & 7 (two-way conflicts) and 172 with rows padded to
 // 144 bytes.
+#include <utility>
+
 #include "gemm_common.h"
 #include "nf_kernels.h"
 
@@ -41,6 +43,24 @@ __device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr) {
   u32x4 v;
   asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
   return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read_frag_at(uint32_t addr) {
+  static_assert(OFFSET >= 0 && OFFSET < 65536, "immediate offset of a DS instruction");
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+// dst[i] = the fragment at addr + BASE + i * STRIDE (immediate offsets: no address arithmetic)
+template <int BASE, int STRIDE, int N, int... I>
+__device__ __forceinline__ void lds_read_frags(bf16x8 (&dst)[N], uint32_t addr, std::integer_sequence<int, I...>) {
+  ((dst[I] = lds_read_frag_at<BASE + I * STRIDE>(addr)), ...);
+}
+template <int OFFSET>
+__device__ __forceinline__ void lds_write_at(uint32_t addr, const u32x4& v) {
+  static_assert(OFFSET >= 0 && OFFSET < 65536, "immediate offset of a DS instruction");
+  asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFFSET) : "memory");
 }
 
 // Waits until at most N LDS operations of this wavefront are outstanding; the fragments are
@@ -366,6 +386,167 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
                                   kr.partial + (size_t)blockIdx.y * (size_t)kr.seg_stride);
 }
 
+// Fourth main loop: four wavefronts (one per SIMD), each with a 128x128 share of a 256x256
+// tile (256 accumulator registers, the whole register file of its SIMD).  A 128x128
+// wavefront tile reads a third less from LDS per flop than the 128x64 tiles of the
+// eight-wavefront loops above, whose LDS instructions fill the LDS queues (measured:
+// SQ_WAIT_INST_LDS 17 % of the wavefront cycles, the LDS data FIFO full when the tiles are
+// written from registers).  The tiles come by direct global -> LDS loads of whole 128-byte
+// lines (K-step 64; with 64-byte rows the texture path is busy 1.7x as long for the same
+// bytes), two LDS stages of 64 KiB, rows and slot XOR as in the loops at the top of this file.
+// One workgroup barrier per K-step, between its second and third K-slice: by then a wavefront
+// has all four slices' fragments of K-step k in registers (four fragment buffers) and its
+// part of K-step k + 1 has landed; behind the barrier it requests the first two slices of
+// K-step k + 1 and issues the loads of K-step k + 2 - into the stage K-step k has just left -
+// one by one between the MFMAs of slices 2 and 3.  Same MFMA and K order as the other loops,
+// hence the same output bits.  Requires K % 128 == 0.
+template <int EPI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
+    int M, int N, int K, int tiles_m, int tiles_n, KRange kr) {
+  constexpr int BM = 256, BN = 256, NW = 4, WM = 128, WN = 128, TM = 4, TN = 4;
+  constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
+  constexpr int ROWS = BM + BN;
+  constexpr int LOADS = ROWS / RPI / NW;  // 16 per K-step: 8 of x, 8 of w
+  constexpr int STAGE_BYTES = ROWS * RB;  // 64 KiB
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  int m0, n0;
+  size_t w_off;
+  locate_tile<BM, BN, false>(tiles_m, tiles_n, GroupedArgs{nullptr, nullptr, 0, 0}, m0, n0, M, w_off);
+  const size_t k_begin = (size_t)blockIdx.y * K;  // this workgroup's K segment
+  X += k_begin;
+  W += k_begin;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // Loader: instruction i of this wavefront fills LDS rows (i*4 + wave)*8 .. +8 of a stage
+  // (i < 8: rows of x, else rows of w); this lane supplies row +lane/8, slot lane%8, i.e. global
+  // chunk (lane%8) ^ ((row >> 1) & 7).
+  const bf16_t* src[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int row = (i * NW + wave) * RPI + lane / CPR;
+    const int chunk = (lane % CPR) ^ ((row >> 1) & 7);
+    if (row < BM) {
+      int gm = m0 + row;
+      gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+      src[i] = X + (size_t)gm * kr.ldk + chunk * 8;
+    } else {
+      src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * kr.ldk + chunk * 8;
+    }
+  }
+  // load I of the K-step the pointers stand at, into LDS stage `stage`
+  auto load_one = [&](const int I, const int stage) __attribute__((always_inline)) {
+    __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16, 0,
+                                     0);
+    src[I] += BKT;
+  };
+  auto load_step = [&](const int stage) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) load_one(i, stage);
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int KT = K / BKT;  // even
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+  const int frag_row = lane & 31, g = lane >> 5;
+  const uint32_t swz = (uint32_t)((frag_row >> 1) & 7);
+  uint32_t x_addr[4], w_addr[4];  // fragment addresses of the four K-slices in stage 0
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const uint32_t slot = (((uint32_t)(2 * kk + g)) ^ swz) * 16;
+    x_addr[kk] = lds_base + (uint32_t)((wm * WM + frag_row) * RB) + slot;
+    w_addr[kk] = lds_base + (uint32_t)((BM + wn * WN + frag_row) * RB) + slot;
+  }
+  bf16x8 fw[4][TN], fx[4][TM];  // one fragment buffer per K-slice
+  using seq4 = std::make_integer_sequence<int, 4>;
+#define NF_W4_READ(KK, BASE)                                                                                    \
+  lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (BASE), seq4{});                                               \
+  lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (BASE), seq4{})
+
+  // prologue: K-steps 0 and 1 on their way, K-step 0 landed, its first two slices requested
+  load_step(0);
+  load_step(1);
+  wait_vmcnt<LOADS>();
+  __builtin_amdgcn_s_barrier();
+  NF_W4_READ(0, 0);
+  NF_W4_READ(1, 0);
+
+#define NF_W4_MFMA(B, I, J)                                                                                     \
+  acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][I], fx[B][J], acc[I][J], 0, 0, 0);                   \
+  __builtin_amdgcn_sched_barrier(0)
+#define NF_W4_LOAD(I)                                                                                           \
+  if (RELOAD) load_one(I, STAGE);                                                                               \
+  __builtin_amdgcn_sched_barrier(0)
+#define NF_W4_SLICE(B)                                                                                          \
+  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3);                           \
+  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3);                           \
+  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3);                           \
+  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3)
+#define NF_W4_SLICE_LOADS(B, L0)                                                                                \
+  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_LOAD(L0 + 0);                                                 \
+  NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3); NF_W4_LOAD(L0 + 1);                                                 \
+  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_LOAD(L0 + 2);                                                 \
+  NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3); NF_W4_LOAD(L0 + 3);                                                 \
+  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_LOAD(L0 + 4);                                                 \
+  NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3); NF_W4_LOAD(L0 + 5);                                                 \
+  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_LOAD(L0 + 6);                                                 \
+  NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3); NF_W4_LOAD(L0 + 7)
+  // K-step k in LDS stage STAGE = k & 1.  MORE: there is a K-step k + 1; RELOAD: there is a
+  // K-step k + 2 (compile-time, so that the steady state has no branches)
+  auto k_step = [&](auto stage_c, auto more_c, auto reload_c) {
+    constexpr int STAGE = decltype(stage_c)::value;
+    constexpr bool MORE = decltype(more_c)::value, RELOAD = decltype(reload_c)::value;
+    constexpr int CUR = STAGE * STAGE_BYTES, NEXT = (1 - STAGE) * STAGE_BYTES;
+    // slices 0 and 1 were requested behind the previous barrier
+    wait_frags<TN + TM, TN, TM>(fw[0], fx[0]);
+    NF_W4_READ(2, CUR);
+    NF_W4_SLICE(0);
+    wait_frags<TN + TM, TN, TM>(fw[1], fx[1]);
+    NF_W4_READ(3, CUR);
+    NF_W4_SLICE(1);
+    // this wavefront has read all it needs of K-step k, and its part of K-step k + 1 is in LDS
+    wait_frags<0, TN, TM>(fw[2], fx[2]);
+    wait_frags<0, TN, TM>(fw[3], fx[3]);
+    if (MORE) wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (MORE) { NF_W4_READ(0, NEXT); }
+    __builtin_amdgcn_sched_barrier(0);
+    NF_W4_SLICE_LOADS(2, 0);
+    if (MORE) { NF_W4_READ(1, NEXT); }
+    __builtin_amdgcn_sched_barrier(0);
+    NF_W4_SLICE_LOADS(3, 8);
+  };
+  using T = std::true_type;
+  using F = std::false_type;
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  int k = 0;
+  for (; k + 2 < KT; k += 2) {
+    k_step(C0{}, T{}, T{});
+    k_step(C1{}, T{}, T{});
+  }
+  k_step(C0{}, T{}, F{});
+  k_step(C1{}, F{}, F{});
+#undef NF_W4_MFMA
+#undef NF_W4_LOAD
+#undef NF_W4_SLICE
+#undef NF_W4_SLICE_LOADS
+#undef NF_W4_READ
+
+  store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
+                                  kr.partial + (size_t)blockIdx.y * (size_t)kr.seg_stride);
+}
+
 // out = bf16((p0 + p1) [+ residual]): the second step of a two-segment operation whose
 // segments were summed by different workgroups.  One thread per 4 consecutive elements.
 __global__ __launch_bounds__(256) void gemm_reduce2_kernel(const float* __restrict__ p0, const float* __restrict__ p1,
@@ -417,6 +598,33 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
     default: NF_DL2_LAUNCH(EPI_SWIGLU); break;
   }
 #undef NF_DL2_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_w4(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
+                     hipStream_t s) {
+  const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+  if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
+  const int tiles_m = (M + 255) / 256, tiles_n = n_eff / 256;
+  const dim3 grid(tiles_m * tiles_n), block(256);
+  const size_t lds_bytes = (size_t)4 * 512 * 64;
+#define NF_W4_LAUNCH(E)                                                                                            \
+  static bool attr_##E = false;                                                                                    \
+  if (!attr_##E) {                                                                                                 \
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_w4_kernel<E>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                       (int)lds_bytes);                                                            \
+    if (e != hipSuccess) return e;                                                                                 \
+    attr_##E = true;                                                                                               \
+  }                                                                                                                \
+  gemm_w4_kernel<E><<<grid, block, lds_bytes, s>>>((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out,               \
+                                                   (const bf16_t*)residual, M, N, K, tiles_m, tiles_n,             \
+                                                   KRange{K, nullptr, 0})
+  switch (epilogue) {
+    case EPI_NONE: { NF_W4_LAUNCH(EPI_NONE); break; }
+    case EPI_RESIDUAL: { NF_W4_LAUNCH(EPI_RESIDUAL); break; }
+    default: { NF_W4_LAUNCH(EPI_SWIGLU); break; }
+  }
+#undef NF_W4_LAUNCH
   return hipGetLastError();
 }
 
@@ -587,6 +795,7 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
       // epilogue needs an even number of 32-column groups per wavefront and has no such form
       if (epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
       return launch_dl2<256, 192, 4, 2, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 21: return launch_w4(x, w, out, residual, M, N, K, epilogue, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -80,7 +80,7 @@ def test_gemm_kernel_swiglu(M, I, K):
 
 
 @pytest.mark.parametrize("M,N,K,epi", [(300, 512, 256, "none"), (1100, 1024, 1408, "residual"), (257, 768, 512, "swiglu"),
-                                       (700, 1536, 320, "residual")])
+                                       (700, 1536, 320, "residual"), (513, 512, 1024, "none"), (64, 256, 128, "none")])
 def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     """All tile shapes and both LDS feeding schemes walk K in the same order with the same
     MFMA instruction, so the implementation choice (which the profile makes per operation
@@ -95,7 +95,7 @@ def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     res_ptr = rt.data_ptr() if epi == "residual" else None
     outs = {}
     try:
-        for tile in range(1, 21):
+        for tile in range(1, 22):
             nf.nf_tune_set("gemm.tile", tile)
             out = torch.full((M + 1, N), 7.0, dtype=torch.bfloat16, device=DEV)
             nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), res_ptr, M, N, K, code)
