@@ -739,6 +739,19 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
     case 12: e = launch_dl_halves<256, 128, 4, 2, 3, true>(x, w, M, N, K, kr, s); break;
     case 13: e = launch_dl_halves<256, 256, 2, 4, 2, true>(x, w, M, N, K, kr, s); break;
     case 19: e = launch_dl2_halves<256, 128, 4, 2, 3, 64>(x, w, M, N, K, kr, s); break;
+    case 21: {
+      // the four-wavefront loop: each half of K must be a multiple of its 128-element period
+      if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
+      const int tiles_m = (M + 255) / 256, tiles_n = N / 256;
+      const size_t lds_bytes = (size_t)2 * 512 * 128;
+      static bool attr_set = false;
+      e = allow_lds(gemm_w4_kernel<EPI_PARTIAL>, lds_bytes, attr_set);
+      if (e != hipSuccess) return e;
+      gemm_w4_kernel<EPI_PARTIAL><<<dim3(tiles_m * tiles_n, 2), dim3(256), lds_bytes, s>>>(
+          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n, kr);
+      e = hipGetLastError();
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;

@@ -248,15 +248,17 @@ def test_two_segment_down_projection_is_bit_exact_in_both_launch_forms(ctx):
     case = Case(m, b, 1234, ctx=ctx)
     outs = []
     try:
-        for ks in (1, 2, 0):
+        for ks, tile in ((1, 0), (2, 0), (0, 0), (0, 21)):  # 21: the four-wavefront loop on each half of K
             nf.nf_tune_set("gemm.ksplit", ks)
+            nf.nf_tune_set("gemm.tile", tile)
             for bounds in ([0, b.n_tokens], [0, 130, b.n_tokens], [0, 64, 128, 257, b.n_tokens]):
                 plan = nf.nf_plan_manual(case.ctx, m, case.args, bounds, len(bounds) > 3)
                 z, p = case.run(plan)
-                outs.append((ks, bounds, z, p))
+                outs.append(((ks, tile), bounds, z, p))
                 plan.close()
     finally:
         nf.nf_tune_set("gemm.ksplit", 0)
+        nf.nf_tune_set("gemm.tile", 0)
     say("two-segment down projection", case.check(outs[0][2], outs[0][3]))
     for ks, bounds, z, p in outs[1:]:
         assert np.array_equal(z, outs[0][2]), (ks, bounds)
