@@ -138,7 +138,8 @@ extern "C" int nf_tune_set(const char* key, int value) {
     return NF_OK;
   }
   if (!strcmp(key, "gemm.grouped_tile")) {
-    if (value != 0 && value != 1 && value != 7 && value != 9 && value != 11 && value != 12 && value != 13 && value != 19)
+    if (value != 0 && value != 1 && value != 7 && value != 9 && value != 11 && value != 12 && value != 13 && value != 19 &&
+        value != 21)
       return NF_EINVAL;
     nf_set_grouped_gemm_tile(value);
     return NF_OK;

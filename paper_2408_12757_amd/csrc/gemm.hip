@@ -304,16 +304,18 @@ hipError_t nf_launch_grouped_gemm(const void* x, const void* w, void* out, int r
     // splits into its two K halves, which doubles the workgroups (the 8-expert layer at 2048
     // tokens has about 320 tiles of 256x256 for 256 CUs) and halves the work a partly
     // filled tile wastes.
-    int variant = g_grouped_tile == 12 ? 12 : (g_grouped_tile == 19 ? 19 : 13);  // measured: 256x256 halves best
+    int variant = g_grouped_tile == 12 ? 12 : (g_grouped_tile == 19 ? 19 : (g_grouped_tile == 13 ? 13 : 21));
+    if (variant == 21 && (K % 256 != 0 || N % 256 != 0)) variant = 13;
     if (variant == 13 && N % 256 != 0) variant = 19;
     return nf_launch_gemm_dl_grouped_halves(x, w, rows, N, K, split.partial, split.seg_stride, expert_offset,
                                             row_index, n_experts, w_stride, variant, s);
   }
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
   // 256x256 tiles halve the re-reads of the gathered rows; 256x128 where the width does not allow them
-  int tile = g_grouped_tile ? g_grouped_tile : (n_eff % 256 == 0 ? 13 : 19);
+  int tile = g_grouped_tile ? g_grouped_tile : (n_eff % 256 == 0 ? 21 : 19);
+  if (tile == 21 && (n_eff % 256 != 0 || K % 128 != 0)) tile = 13;
   if (tile == 13 && n_eff % 256 != 0) tile = 19;
-  if (tile == 7 || tile == 9 || tile == 11 || tile == 12 || tile == 13 || tile == 19)
+  if (tile == 7 || tile == 9 || tile == 11 || tile == 12 || tile == 13 || tile == 19 || tile == 21)
     return nf_launch_gemm_dl_grouped(x, w, out, rows, N, K, epilogue, expert_offset, row_index, n_experts, w_stride,
                                      tile, s);
   return launch<128, 128, 2, 2, 1, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);

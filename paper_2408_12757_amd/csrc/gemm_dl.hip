@@ -400,10 +400,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
 // K-step k + 1 and issues the loads of K-step k + 2 - into the stage K-step k has just left -
 // one by one between the MFMAs of slices 2 and 3.  Same MFMA and K order as the other loops,
 // hence the same output bits.  Requires K % 128 == 0.
-template <int EPI>
+template <int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
-    int M, int N, int K, int tiles_m, int tiles_n, KRange kr) {
+    int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
   constexpr int BM = 256, BN = 256, NW = 4, WM = 128, WN = 128, TM = 4, TN = 4;
   constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
   constexpr int ROWS = BM + BN;
@@ -413,10 +413,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   int m0, n0;
   size_t w_off;
-  locate_tile<BM, BN, false>(tiles_m, tiles_n, GroupedArgs{nullptr, nullptr, 0, 0}, m0, n0, M, w_off);
+  if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
   const size_t k_begin = (size_t)blockIdx.y * K;  // this workgroup's K segment
   X += k_begin;
-  W += k_begin;
+  W += w_off + k_begin;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;
@@ -432,6 +432,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (row < BM) {
       int gm = m0 + row;
       gm = gm < M ? gm : M - 1;  // rows past M are computed on a copy of the last row and never stored
+      if (GROUPED && grp.row_index) gm = grp.row_index[gm];
       src[i] = X + (size_t)gm * kr.ldk + chunk * 8;
     } else {
       src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * kr.ldk + chunk * 8;
@@ -569,6 +570,14 @@ __global__ __launch_bounds__(256) void gemm_reduce2_kernel(const float* __restri
   reinterpret_cast<u32x2*>(Y)[q] = pk;
 }
 
+template <typename Kern>
+hipError_t allow_lds(Kern kern, size_t lds_bytes, bool& done) {
+  if (lds_bytes <= 64 * 1024 || done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  done = e == hipSuccess;
+  return e;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, int BKT>
 hipError_t launch_dl2(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
                       hipStream_t s, GroupedArgs grp) {
@@ -601,28 +610,27 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
   return hipGetLastError();
 }
 
+template <bool GROUPED>
 hipError_t launch_w4(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
-                     hipStream_t s) {
+                     hipStream_t s, GroupedArgs grp) {
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
-  const int tiles_m = (M + 255) / 256, tiles_n = n_eff / 256;
+  const int tiles_m = GROUPED ? (M + 255) / 256 + grp.n_experts : (M + 255) / 256, tiles_n = n_eff / 256;
   const dim3 grid(tiles_m * tiles_n), block(256);
-  const size_t lds_bytes = (size_t)4 * 512 * 64;
+  const size_t lds_bytes = (size_t)2 * 512 * 128;
 #define NF_W4_LAUNCH(E)                                                                                            \
-  static bool attr_##E = false;                                                                                    \
-  if (!attr_##E) {                                                                                                 \
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_w4_kernel<E>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                       (int)lds_bytes);                                                            \
+  do {                                                                                                             \
+    auto kern = gemm_w4_kernel<E, GROUPED>;                                                                         \
+    static bool attr_set = false;                                                                                  \
+    hipError_t e = allow_lds(kern, lds_bytes, attr_set);                                                           \
     if (e != hipSuccess) return e;                                                                                 \
-    attr_##E = true;                                                                                               \
-  }                                                                                                                \
-  gemm_w4_kernel<E><<<grid, block, lds_bytes, s>>>((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out,               \
-                                                   (const bf16_t*)residual, M, N, K, tiles_m, tiles_n,             \
-                                                   KRange{K, nullptr, 0})
+    kern<<<grid, block, lds_bytes, s>>>((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out, (const bf16_t*)residual, \
+                                        M, N, K, tiles_m, tiles_n, grp, KRange{K, nullptr, 0});                   \
+  } while (0)
   switch (epilogue) {
-    case EPI_NONE: { NF_W4_LAUNCH(EPI_NONE); break; }
-    case EPI_RESIDUAL: { NF_W4_LAUNCH(EPI_RESIDUAL); break; }
-    default: { NF_W4_LAUNCH(EPI_SWIGLU); break; }
+    case EPI_NONE: NF_W4_LAUNCH(EPI_NONE); break;
+    case EPI_RESIDUAL: NF_W4_LAUNCH(EPI_RESIDUAL); break;
+    default: NF_W4_LAUNCH(EPI_SWIGLU); break;
   }
 #undef NF_W4_LAUNCH
   return hipGetLastError();
@@ -660,13 +668,6 @@ hipError_t launch_dl(const void* x, const void* w, void* out, const void* residu
   return hipGetLastError();
 }
 
-template <typename Kern>
-hipError_t allow_lds(Kern kern, size_t lds_bytes, bool& done) {
-  if (lds_bytes <= 64 * 1024 || done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-  done = e == hipSuccess;
-  return e;
-}
 
 // The two halves of K as separate workgroups (grid.y = 2), fp32 sums to scratch.  GROUPED:
 // M is the total row count, every expert may add one partial tile (see GroupedArgs).
@@ -748,7 +749,8 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
       e = allow_lds(gemm_w4_kernel<EPI_PARTIAL>, lds_bytes, attr_set);
       if (e != hipSuccess) return e;
       gemm_w4_kernel<EPI_PARTIAL><<<dim3(tiles_m * tiles_n, 2), dim3(256), lds_bytes, s>>>(
-          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n, kr);
+          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
+          GroupedArgs{nullptr, nullptr, 0, 0}, kr);
       e = hipGetLastError();
       break;
     }
@@ -774,6 +776,17 @@ hipError_t nf_launch_gemm_dl_grouped_halves(const void* x, const void* w, int ro
     case 12: return launch_dl_halves<256, 128, 4, 2, 3, true, true>(x, w, rows, N, K, kr, s, grp);
     case 13: return launch_dl_halves<256, 256, 2, 4, 2, true, true>(x, w, rows, N, K, kr, s, grp);
     case 19: return launch_dl2_halves<256, 128, 4, 2, 3, 64, true>(x, w, rows, N, K, kr, s, grp);
+    case 21: {
+      if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
+      const int tiles_m = (rows + 255) / 256 + n_experts, tiles_n = N / 256;
+      const size_t lds_bytes = (size_t)2 * 512 * 128;
+      static bool attr_set = false;
+      hipError_t e = allow_lds(gemm_w4_kernel<EPI_PARTIAL, true>, lds_bytes, attr_set);
+      if (e != hipSuccess) return e;
+      gemm_w4_kernel<EPI_PARTIAL, true><<<dim3(tiles_m * tiles_n, 2), dim3(256), lds_bytes, s>>>(
+          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, rows, N, K / 2, tiles_m, tiles_n, grp, kr);
+      return hipGetLastError();
+    }
     default: return hipErrorInvalidValue;
   }
 }
@@ -808,7 +821,7 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
       // epilogue needs an even number of 32-column groups per wavefront and has no such form
       if (epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
       return launch_dl2<256, 192, 4, 2, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
-    case 21: return launch_w4(x, w, out, residual, M, N, K, epilogue, s);
+    case 21: return launch_w4<false>(x, w, out, residual, M, N, K, epilogue, s, none);
     default: return hipErrorInvalidValue;
   }
 }
@@ -825,6 +838,7 @@ hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, in
     case 12: return launch_dl<256, 128, 4, 2, 3, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     case 13: return launch_dl<256, 256, 2, 4, 2, true, true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     case 19: return launch_dl2<256, 128, 4, 2, 3, true, 64>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
+    case 21: return launch_w4<true>(x, w, out, nullptr, rows, N, K, epilogue, s, grp);
     default: return hipErrorInvalidValue;
   }
 }
