@@ -488,44 +488,54 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #define NF_W4_LOAD(I)                                                                                           \
   if (RELOAD) load_one(I, STAGE);                                                                               \
   __builtin_amdgcn_sched_barrier(0)
-#define NF_W4_SLICE(B)                                                                                          \
-  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3);                           \
-  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3);                           \
-  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3);                           \
-  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3)
-#define NF_W4_SLICE_LOADS(B, L0)                                                                                \
-  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_LOAD(L0 + 0);                                                 \
-  NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3); NF_W4_LOAD(L0 + 1);                                                 \
-  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_LOAD(L0 + 2);                                                 \
-  NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3); NF_W4_LOAD(L0 + 3);                                                 \
-  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_LOAD(L0 + 4);                                                 \
-  NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3); NF_W4_LOAD(L0 + 5);                                                 \
-  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_LOAD(L0 + 6);                                                 \
-  NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3); NF_W4_LOAD(L0 + 7)
+  // fragment I (0..3: w, 4..7: x) of K-slice KK from the stage at BASE, if ON
+#define NF_W4_RD1(ON, KK, BASE, I)                                                                              \
+  if (ON) {                                                                                                     \
+    if ((I) < 4)                                                                                                \
+      fw[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (BASE));                              \
+    else                                                                                                        \
+      fx[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (BASE));                              \
+  }                                                                                                             \
+  __builtin_amdgcn_sched_barrier(0)
+  // 16 MFMAs of slice B; behind every second one a fragment read of slice KK (stage BASE)
+#define NF_W4_SLICE_READS(B, ON, KK, BASE)                                                                      \
+  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, BASE, 0);                                         \
+  NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, BASE, 1);                                         \
+  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, BASE, 2);                                         \
+  NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, BASE, 3);                                         \
+  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, BASE, 4);                                         \
+  NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, BASE, 5);                                         \
+  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, BASE, 6);                                         \
+  NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, BASE, 7)
+  // the same with a global load behind the other MFMAs
+#define NF_W4_SLICE_READS_LOADS(B, ON, KK, BASE, L0)                                                            \
+  NF_W4_MFMA(B, 0, 0); NF_W4_LOAD(L0 + 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, BASE, 0);                     \
+  NF_W4_MFMA(B, 0, 2); NF_W4_LOAD(L0 + 1); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, BASE, 1);                     \
+  NF_W4_MFMA(B, 1, 0); NF_W4_LOAD(L0 + 2); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, BASE, 2);                     \
+  NF_W4_MFMA(B, 1, 2); NF_W4_LOAD(L0 + 3); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, BASE, 3);                     \
+  NF_W4_MFMA(B, 2, 0); NF_W4_LOAD(L0 + 4); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, BASE, 4);                     \
+  NF_W4_MFMA(B, 2, 2); NF_W4_LOAD(L0 + 5); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, BASE, 5);                     \
+  NF_W4_MFMA(B, 3, 0); NF_W4_LOAD(L0 + 6); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, BASE, 6);                     \
+  NF_W4_MFMA(B, 3, 2); NF_W4_LOAD(L0 + 7); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, BASE, 7)
   // K-step k in LDS stage STAGE = k & 1.  MORE: there is a K-step k + 1; RELOAD: there is a
-  // K-step k + 2 (compile-time, so that the steady state has no branches)
+  // K-step k + 2 (compile-time, so that the steady state has no branches).  The fragments of a
+  // slice are requested two slices ahead, one read behind every second MFMA: at the top of a
+  // slice at most the eight reads of the next slice are outstanding behind its own.
   auto k_step = [&](auto stage_c, auto more_c, auto reload_c) {
     constexpr int STAGE = decltype(stage_c)::value;
     constexpr bool MORE = decltype(more_c)::value, RELOAD = decltype(reload_c)::value;
     constexpr int CUR = STAGE * STAGE_BYTES, NEXT = (1 - STAGE) * STAGE_BYTES;
-    // slices 0 and 1 were requested behind the previous barrier
     wait_frags<TN + TM, TN, TM>(fw[0], fx[0]);
-    NF_W4_READ(2, CUR);
-    NF_W4_SLICE(0);
+    NF_W4_SLICE_READS(0, true, 2, CUR);
     wait_frags<TN + TM, TN, TM>(fw[1], fx[1]);
-    NF_W4_READ(3, CUR);
-    NF_W4_SLICE(1);
+    NF_W4_SLICE_READS(1, true, 3, CUR);
     // this wavefront has read all it needs of K-step k, and its part of K-step k + 1 is in LDS
     wait_frags<0, TN, TM>(fw[2], fx[2]);
     wait_frags<0, TN, TM>(fw[3], fx[3]);
     if (MORE) wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (MORE) { NF_W4_READ(0, NEXT); }
-    __builtin_amdgcn_sched_barrier(0);
-    NF_W4_SLICE_LOADS(2, 0);
-    if (MORE) { NF_W4_READ(1, NEXT); }
-    __builtin_amdgcn_sched_barrier(0);
-    NF_W4_SLICE_LOADS(3, 8);
+    NF_W4_SLICE_READS_LOADS(2, MORE, 0, NEXT, 0);
+    NF_W4_SLICE_READS_LOADS(3, MORE, 1, NEXT, 8);
   };
   using T = std::true_type;
   using F = std::false_type;
@@ -540,8 +550,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   k_step(C1{}, F{}, F{});
 #undef NF_W4_MFMA
 #undef NF_W4_LOAD
-#undef NF_W4_SLICE
-#undef NF_W4_SLICE_LOADS
+#undef NF_W4_SLICE_READS
+#undef NF_W4_SLICE_READS_LOADS
+#undef NF_W4_RD1
 #undef NF_W4_READ
 
   store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
