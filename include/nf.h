@@ -168,7 +168,7 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
 /*
  * Process-wide kernel-variant knobs for tuning runs (Sec. 4.1.1: several implementations
  * per kernel are profiled).  key "attention.variant": 0..7 = pages in flight / occupancy /
- * load-hint trade-off of the attention kernel.  key "gemm.tile": 0 = automatic, 1..20 = force
+ * load-hint trade-off of the attention kernel.  key "gemm.tile": 0 = automatic, 1..21 = force
  * one GEMM implementation (tile shape, LDS feeding scheme, main loop) for every dense
  * operation.  key "search.layers": 1 (default) = the auto-search and nf_simulate_pipeline price
  * one layer on its own; n in 2..16 = they price the time per layer of n consecutive layers
@@ -176,7 +176,7 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * key "search.rank": 0 (default) = the search returns its best pipeline; r in 1..64 = the best
  * pipeline of the r-th best row of the R -> P table, whatever its estimate (unsplit when there
  * are fewer rows), so that a caller can refine the model's choice with trial runs.
- * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 = force
+ * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 / 21 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
  * (wrong results).  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
  * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.
