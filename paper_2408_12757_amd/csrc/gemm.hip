@@ -271,8 +271,8 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     if (s20 > s13 && s20 > s12 && s20 > s7) tile = 20;
     if (s21 > s20 && s21 > s12 && s21 > s7) tile = 21;
   }
-  if (tile >= 7 && tile <= 21) {
-    if (tile == 21 && (K % 128 != 0 || n_eff % 256 != 0)) tile = 13;
+  if (tile >= 7 && tile <= 22) {
+    if ((tile == 21 || tile == 22) && (K % 128 != 0 || n_eff % 256 != 0)) tile = 13;
     if (tile == 20 && (n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 19;
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
     if (tile == 13 && n_eff % 256 != 0) tile = 12;

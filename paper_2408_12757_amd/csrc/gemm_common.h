@@ -13,10 +13,12 @@ enum { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 };
 // The part of K a launch walks.  x and w rows are `ldk` elements apart (the full K of the
 // operation); workgroups with blockIdx.y = s walk K elements starting at s * K.  With
 // EPI_PARTIAL segment s stores its fp32 sums, row-major [M, N], at partial + s * seg_stride.
+// n_first is honoured by the four-wavefront loop only.
 struct KRange {
   int ldk;
   float* partial;
   long long seg_stride;
+  int n_first = 0;  // output columns start at this tile column (a launch that covers a column range)
 };
 
 // Workgroup index -> tile index so that the tiles one XCD works on are consecutive

@@ -400,20 +400,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl2_kernel(
 // K-step k + 1 and issues the loads of K-step k + 2 - into the stage K-step k has just left -
 // one by one between the MFMAs of slices 2 and 3.  Same MFMA and K order as the other loops,
 // hence the same output bits.  Requires K % 128 == 0.
-template <int EPI, bool GROUPED = false>
+template <int EPI, bool GROUPED = false, int TM = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
-  constexpr int BM = 256, BN = 256, NW = 4, WM = 128, WN = 128, TM = 4, TN = 4;
+  constexpr int WM = 32 * TM, BM = 2 * WM, BN = 256, NW = 4, WN = 128, TN = 4;
+  static_assert(TM == 4 || TM == 2, "256x256 tiles, or 128x256 tiles with 64x128 wavefront shares");
   constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
   constexpr int ROWS = BM + BN;
-  constexpr int LOADS = ROWS / RPI / NW;  // 16 per K-step: 8 of x, 8 of w
+  constexpr int LOADS = ROWS / RPI / NW;  // per K-step: BM / 32 of x, then 8 of w
   constexpr int STAGE_BYTES = ROWS * RB;  // 64 KiB
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   int m0, n0;
   size_t w_off;
   if (!locate_tile<BM, BN, GROUPED>(tiles_m, tiles_n, grp, m0, n0, M, w_off)) return;  // before any barrier
+  n0 += kr.n_first * BN;
   const size_t k_begin = (size_t)blockIdx.y * K;  // this workgroup's K segment
   X += k_begin;
   W += w_off + k_begin;
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int wm = wave & 1, wn = wave >> 1;
 
   // Loader: instruction i of this wavefront fills LDS rows (i*4 + wave)*8 .. +8 of a stage
-  // (i < 8: rows of x, else rows of w); this lane supplies row +lane/8, slot lane%8, i.e. global
+  // (i < BM / 32: rows of x, else rows of w); this lane supplies row +lane/8, slot lane%8, i.e. global
   // chunk (lane%8) ^ ((row >> 1) & 7).
   const bf16_t* src[LOADS];
 #pragma unroll
@@ -472,7 +474,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   using seq4 = std::make_integer_sequence<int, 4>;
 #define NF_W4_READ(KK, BASE)                                                                                    \
   lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (BASE), seq4{});                                               \
-  lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (BASE), seq4{})
+  lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (BASE), std::make_integer_sequence<int, TM>{})
 
   // prologue: K-steps 0 and 1 on their way, K-step 0 landed, its first two slices requested
   load_step(0);
@@ -483,18 +485,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   NF_W4_READ(1, 0);
 
 #define NF_W4_MFMA(B, I, J)                                                                                     \
-  acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][I], fx[B][J], acc[I][J], 0, 0, 0);                   \
+  if constexpr ((J) < TM)                                                                                       \
+    acc[I][(J) < TM ? (J) : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][I], fx[B][(J) < TM ? (J) : 0],    \
+                                                                        acc[I][(J) < TM ? (J) : 0], 0, 0, 0);   \
   __builtin_amdgcn_sched_barrier(0)
 #define NF_W4_LOAD(I)                                                                                           \
-  if (RELOAD) load_one(I, STAGE);                                                                               \
+  if constexpr (RELOAD && (I) < LOADS) load_one(I, STAGE);                                                       \
   __builtin_amdgcn_sched_barrier(0)
   // fragment I (0..3: w, 4..7: x) of K-slice KK from the stage at BASE, if ON
 #define NF_W4_RD1(ON, KK, BASE, I)                                                                              \
-  if (ON) {                                                                                                     \
-    if ((I) < 4)                                                                                                \
+  if constexpr (ON) {                                                                                           \
+    if constexpr ((I) < 4)                                                                                      \
       fw[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (BASE));                              \
-    else                                                                                                        \
-      fx[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (BASE));                              \
+    else if constexpr (((I) & 3) < TM)                                                                          \
+      fx[KK][((I) & 3) < TM ? ((I) & 3) : 0] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (BASE));       \
   }                                                                                                             \
   __builtin_amdgcn_sched_barrier(0)
   // 16 MFMAs of slice B; behind every second one a fragment read of slice KK (stage BASE)
@@ -621,22 +625,25 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
   return hipGetLastError();
 }
 
-template <bool GROUPED>
-hipError_t launch_w4(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
-                     hipStream_t s, GroupedArgs grp) {
-  const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
-  if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
-  const int tiles_m = GROUPED ? (M + 255) / 256 + grp.n_experts : (M + 255) / 256, tiles_n = n_eff / 256;
-  const dim3 grid(tiles_m * tiles_n), block(256);
-  const size_t lds_bytes = (size_t)2 * 512 * 128;
+// One launch of the four-wavefront loop with tiles of 64 * TM rows over the tile columns
+// [n_first, n_first + n_tiles).
+template <bool GROUPED, int TM>
+hipError_t launch_w4_columns(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
+                             int epilogue, hipStream_t s, GroupedArgs grp, int n_first, int n_tiles) {
+  constexpr int BM = 64 * TM;
+  const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
+  const dim3 grid(tiles_m * n_tiles), block(256);
+  const size_t lds_bytes = (size_t)2 * (BM + 256) * 128;
+  KRange kr{K, nullptr, 0};
+  kr.n_first = n_first;
 #define NF_W4_LAUNCH(E)                                                                                            \
   do {                                                                                                             \
-    auto kern = gemm_w4_kernel<E, GROUPED>;                                                                         \
+    auto kern = gemm_w4_kernel<E, GROUPED, TM>;                                                                     \
     static bool attr_set = false;                                                                                  \
     hipError_t e = allow_lds(kern, lds_bytes, attr_set);                                                           \
     if (e != hipSuccess) return e;                                                                                 \
     kern<<<grid, block, lds_bytes, s>>>((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out, (const bf16_t*)residual, \
-                                        M, N, K, tiles_m, tiles_n, grp, KRange{K, nullptr, 0});                   \
+                                        M, N, K, tiles_m, n_tiles, grp, kr);                                       \
   } while (0)
   switch (epilogue) {
     case EPI_NONE: NF_W4_LAUNCH(EPI_NONE); break;
@@ -645,6 +652,30 @@ hipError_t launch_w4(const void* x, const void* w, void* out, const void* residu
   }
 #undef NF_W4_LAUNCH
   return hipGetLastError();
+}
+
+// 256x256 tiles.  When the tiles beyond the last whole round of 256 fill at most half a round
+// (the 8B layer's Up/Gate at 2048 rows: 896 tiles = 3.5 rounds), the tile columns of that
+// remainder run as a second launch of 128x256 tiles - twice the workgroups of half the work,
+// so the last round takes about two thirds as long.  Every output element is still one
+// accumulation in ascending K order: the bits do not change.
+template <bool GROUPED>
+hipError_t launch_w4(const void* x, const void* w, void* out, const void* residual, int M, int N, int K, int epilogue,
+                     hipStream_t s, GroupedArgs grp) {
+  const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+  if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
+  const int tiles_n = n_eff / 256;
+  if (!GROUPED) {
+    const int tiles_m = (M + 255) / 256;
+    const long tiles = (long)tiles_m * tiles_n, whole = tiles / 256 * 256, rest = tiles - whole;
+    if (whole > 0 && rest > 0 && rest <= 128 && whole % tiles_m == 0) {
+      const int n_whole = (int)(whole / tiles_m);
+      hipError_t e = launch_w4_columns<false, 4>(x, w, out, residual, M, N, K, epilogue, s, grp, 0, n_whole);
+      if (e != hipSuccess) return e;
+      return launch_w4_columns<false, 2>(x, w, out, residual, M, N, K, epilogue, s, grp, n_whole, tiles_n - n_whole);
+    }
+  }
+  return launch_w4_columns<GROUPED, 4>(x, w, out, residual, M, N, K, epilogue, s, grp, 0, tiles_n);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GROUPED, bool PIPE = false>
@@ -833,6 +864,11 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
       if (epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
       return launch_dl2<256, 192, 4, 2, 2, false, 64>(x, w, out, residual, M, N, K, epilogue, s, none);
     case 21: return launch_w4<false>(x, w, out, residual, M, N, K, epilogue, s, none);
+    case 22: {  // the four-wavefront loop with 128x256 tiles
+      const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+      if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
+      return launch_w4_columns<false, 2>(x, w, out, residual, M, N, K, epilogue, s, none, 0, n_eff / 256);
+    }
     default: return hipErrorInvalidValue;
   }
 }
