@@ -510,8 +510,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   // load I of the K-step the pointers stand at, into LDS stage `stage`
   auto load_one = [&](const int I, const int stage) __attribute__((always_inline)) {
-    __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16, 0,
-                                     0);
+    // weight rows are used by the few tiles of one tile column and then never again: loaded
+    // non-temporal they do not push the x rows, which every tile column re-reads, out of the
+    // L2 (measured: 2-3 % on Up/Gate; non-temporal x rows or both: no gain; with 128x256 tiles,
+    // where twice as many tiles share a weight row, it costs 15 %, so those load normally)
+    if (I * RPI * NW < BM || TM != 4)
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16,
+                                       0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16,
+                                       0, 2);
     src[I] += BKT;
   };
   auto load_step = [&](const int stage) __attribute__((always_inline)) {
