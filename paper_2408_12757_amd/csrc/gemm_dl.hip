@@ -466,8 +466,10 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
 // has all four slices' fragments of K-step k in registers (four fragment buffers) and its
 // part of K-step k + 1 has landed; behind the barrier it requests the first two slices of
 // K-step k + 1 and issues the loads of K-step k + 2 - into the stage K-step k has just left -
-// one by one between the MFMAs of slices 2 and 3.  Same MFMA and K order as the other loops,
-// hence the same output bits.  Requires K % 128 == 0.
+// one by one between the MFMAs of slices 2 and 3.  TM = 4: 256x256 tiles; TM = 2: 128x256
+// tiles with 64x128 shares (for shapes whose 256x256 tiles leave CUs idle, and for the
+// remainder of a launch beyond its last whole round of tiles).  Same MFMA and K order as the
+// other loops, hence the same output bits.  Requires K % 128 == 0 and 256 | N.
 template <int EPI, bool GROUPED = false, int TM = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
