@@ -224,12 +224,15 @@ static hipError_t launch_two_segments(const void* x, const void* w, void* out, c
       halves = round_fill(2 * tiles) > 1.15 * round_fill(tiles);  // the scratch traffic costs about a tenth
   }
   // Rows that fill the chip with 256x256 tiles of half K each take the four-wavefront loop
-  // (measured on the 8B layer's down projection at 2048 rows: 240 -> 22x us including the
+  // (measured on the 8B layer's down projection at 2048 rows: 240 -> 217 us including the
   // second kernel); its accumulators leave no room for two sums in one workgroup.
   const long units21 = 2L * ((M + 255) / 256) * (N / 256);
   const bool w4 = split.partial && K % 256 == 0 && N % 256 == 0 && g_gemm_ksplit != 1 &&
                   (tile == 21 || (tile == 0 && round_fill(units21) >= 0.9));
   if (w4) return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, 21, s);
+  // the same loop with 128x256 tiles, when the profile asks for it (few rows)
+  if (tile == 22 && split.partial && K % 256 == 0 && N % 256 == 0 && g_gemm_ksplit != 1)
+    return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, 22, s);
   if (!halves) return nf_launch_gemm_dl_two_sums(x, w, out, residual, M, N, K, epilogue, s);
   int variant = (tile == 7 || tile == 11) ? 7 : (tile == 13 || tile == 10 || tile == 17) ? 13 : tile == 12 ? 12 : 19;
   if (variant == 13 && N % 256 != 0) variant = 12;

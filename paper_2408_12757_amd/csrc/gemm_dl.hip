@@ -881,6 +881,19 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
       e = hipGetLastError();
       break;
     }
+    case 22: {  // the same with 128x256 tiles: twice the workgroups for few rows
+      if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
+      const int tiles_m = (M + 127) / 128, tiles_n = N / 256;
+      const size_t lds_bytes = (size_t)2 * 384 * 128;
+      static bool attr_set = false;
+      e = allow_lds(gemm_w4_kernel<EPI_PARTIAL, false, 2>, lds_bytes, attr_set);
+      if (e != hipSuccess) return e;
+      gemm_w4_kernel<EPI_PARTIAL, false, 2><<<dim3(tiles_m * tiles_n, 2), dim3(256), lds_bytes, s>>>(
+          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
+          GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+      e = hipGetLastError();
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;

@@ -250,7 +250,7 @@ def test_two_segment_down_projection_is_bit_exact_in_both_launch_forms(ctx):
     case = Case(m, b, 1234, ctx=ctx)
     outs = []
     try:
-        for ks, tile in ((1, 0), (2, 0), (0, 0), (0, 21)):  # 21: the four-wavefront loop on each half of K
+        for ks, tile in ((1, 0), (2, 0), (0, 0), (0, 21), (0, 22)):  # 21 / 22: the four-wavefront loops on each half of K
             nf.nf_tune_set("gemm.ksplit", ks)
             nf.nf_tune_set("gemm.tile", tile)
             for bounds in ([0, b.n_tokens], [0, 130, b.n_tokens], [0, 64, 128, 257, b.n_tokens]):
