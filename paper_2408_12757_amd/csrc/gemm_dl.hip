@@ -461,12 +461,15 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
 // SQ_WAIT_INST_LDS 17 % of the wavefront cycles, the LDS data FIFO full when the tiles are
 // written from registers).  The tiles come by direct global -> LDS loads of whole 128-byte
 // lines (K-step 64; with 64-byte rows the texture path is busy 1.7x as long for the same
-// bytes), two LDS stages of 64 KiB, rows and slot XOR as in the loops at the top of this file.
+// bytes), two LDS stages of x rows and three of w rows (160 KiB with 256x256 tiles, all the
+// LDS of a CU), rows and slot XOR as in the loops at the top of this file.
 // One workgroup barrier per K-step, between its second and third K-slice: by then a wavefront
 // has all four slices' fragments of K-step k in registers (four fragment buffers) and its
 // part of K-step k + 1 has landed; behind the barrier it requests the first two slices of
-// K-step k + 1 and issues the loads of K-step k + 2 - into the stage K-step k has just left -
-// one by one between the MFMAs of slices 2 and 3.  TM = 4: 256x256 tiles; TM = 2: 128x256
+// K-step k + 1 and issues the loads of the x rows of K-step k + 2 and of the w rows of K-step
+// k + 3 - into the stages K-step k has just left - one by one between the MFMAs of slices 2
+// and 3.  The w rows so have two K-steps to arrive (measured against two stages of both on one
+// device: 2-2.5 % on Up/Gate and KQV, 5 % on O, 6 % on the 70B KQV).  TM = 4: 256x256 tiles; TM = 2: 128x256
 // tiles with 64x128 shares (for shapes whose 256x256 tiles leave CUs idle, and for the
 // remainder of a launch beyond its last whole round of tiles).  Same MFMA and K order as the
 // other loops, hence the same output bits.  Requires K % 128 == 0 and 256 | N.
@@ -479,7 +482,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
   constexpr int ROWS = BM + BN;
   constexpr int LOADS = ROWS / RPI / NW;  // per K-step: BM / 32 of x, then 8 of w
-  constexpr int STAGE_BYTES = ROWS * RB;  // 64 KiB
+  constexpr int XLOADS = BM / RPI / NW, WLOADS = BN / RPI / NW;
+  // LDS: two stages of x rows, then three stages of w rows (a third stage of both would not fit)
+  constexpr int XSTAGE = BM * RB, WSTAGE = BN * RB, WBASE = 2 * XSTAGE;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   int m0, n0;
@@ -510,23 +515,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       src[i] = W + (size_t)weight_row<EPI>(row - BM, n0, N) * kr.ldk + chunk * 8;
     }
   }
-  // load I of the K-step the pointers stand at, into LDS stage `stage`
-  auto load_one = [&](const int I, const int stage) __attribute__((always_inline)) {
+  // load I of the K-step its pointer stands at: an x load into x stage xs, a w load to byte
+  // offset wf of the w region
+  auto load_one = [&](const int I, const int xs, const int wf) __attribute__((always_inline)) {
     // weight rows are used by the few tiles of one tile column and then never again: loaded
     // non-temporal they do not push the x rows, which every tile column re-reads, out of the
     // L2 (measured: 2-3 % on Up/Gate; non-temporal x rows or both: no gain; with 128x256 tiles,
     // where twice as many tiles share a weight row, it costs 15 %, so those load normally)
-    if (I * RPI * NW < BM || TM != 4)
-      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16,
-                                       0, 0);
+    if (I < XLOADS)
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + xs * XSTAGE + (I * NW + wave) * 1024), 16, 0, 0);
+    else if (TM != 4)
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I],
+                                       (lptr_t)(lds + WBASE + wf + ((I - XLOADS) * NW + wave) * 1024), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + stage * STAGE_BYTES + (I * NW + wave) * 1024), 16,
-                                       0, 2);
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I],
+                                       (lptr_t)(lds + WBASE + wf + ((I - XLOADS) * NW + wave) * 1024), 16, 0, 2);
     src[I] += BKT;
-  };
-  auto load_step = [&](const int stage) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) load_one(i, stage);
   };
 
   f32x16 acc[TN][TM];
@@ -541,26 +545,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
   const int frag_row = lane & 31, g = lane >> 5;
   const uint32_t swz = (uint32_t)((frag_row >> 1) & 7);
-  uint32_t x_addr[4], w_addr[4];  // fragment addresses of the four K-slices in stage 0
+  uint32_t x_addr[4], w_addr[4];  // fragment addresses of the four K-slices in stage 0 of their regions
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     const uint32_t slot = (((uint32_t)(2 * kk + g)) ^ swz) * 16;
     x_addr[kk] = lds_base + (uint32_t)((wm * WM + frag_row) * RB) + slot;
-    w_addr[kk] = lds_base + (uint32_t)((BM + wn * WN + frag_row) * RB) + slot;
+    w_addr[kk] = lds_base + (uint32_t)(WBASE + (wn * WN + frag_row) * RB) + slot;
   }
   bf16x8 fw[4][TN], fx[4][TM];  // one fragment buffer per K-slice
   using seq4 = std::make_integer_sequence<int, 4>;
-#define NF_W4_READ(KK, BASE)                                                                                    \
-  lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (BASE), seq4{});                                               \
-  lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (BASE), std::make_integer_sequence<int, TM>{})
+#define NF_W4_READ(KK, XB, WB)                                                                                  \
+  lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (WB), seq4{});                                                 \
+  lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (XB), std::make_integer_sequence<int, TM>{})
 
-  // prologue: K-steps 0 and 1 on their way, K-step 0 landed, its first two slices requested
-  load_step(0);
-  load_step(1);
-  wait_vmcnt<LOADS>();
+  // prologue: x rows of K-steps 0 and 1 and w rows of K-steps 0, 1 and 2 on their way (the w
+  // rows of K-step 2 last, so that a wait can leave exactly them in flight), K-step 0 landed,
+  // its first two slices requested
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) load_one(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) load_one(i, 1, WSTAGE);
+  if (2 < KT) {
+#pragma unroll
+    for (int i = XLOADS; i < LOADS; ++i) load_one(i, 0, 2 * WSTAGE);
+  }
+  if (2 < KT)
+    wait_vmcnt<LOADS + WLOADS>();
+  else
+    wait_vmcnt<LOADS>();
   __builtin_amdgcn_s_barrier();
-  NF_W4_READ(0, 0);
-  NF_W4_READ(1, 0);
+  NF_W4_READ(0, 0, 0);
+  NF_W4_READ(1, 0, 0);
 
 #define NF_W4_MFMA(B, I, J)                                                                                     \
   if constexpr ((J) < TM)                                                                                       \
@@ -568,68 +583,94 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                                                         acc[I][(J) < TM ? (J) : 0], 0, 0, 0);   \
   __builtin_amdgcn_sched_barrier(0)
 #define NF_W4_LOAD(I)                                                                                           \
-  if constexpr (RELOAD && (I) < LOADS) load_one(I, STAGE);                                                       \
+  if constexpr ((I) < XLOADS ? XRELOAD : (WRELOAD && (I) < LOADS)) load_one(I, STAGE, w_cur);                    \
   __builtin_amdgcn_sched_barrier(0)
   // fragment I (0..3: w, 4..7: x) of K-slice KK from the stage at BASE, if ON
-#define NF_W4_RD1(ON, KK, BASE, I)                                                                              \
+#define NF_W4_RD1(ON, KK, XB, WB, I)                                                                            \
   if constexpr (ON) {                                                                                           \
     if constexpr ((I) < 4)                                                                                      \
-      fw[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (BASE));                              \
+      fw[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (WB));                                \
     else if constexpr (((I) & 3) < TM)                                                                          \
-      fx[KK][((I) & 3) < TM ? ((I) & 3) : 0] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (BASE));       \
+      fx[KK][((I) & 3) < TM ? ((I) & 3) : 0] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (XB));         \
   }                                                                                                             \
   __builtin_amdgcn_sched_barrier(0)
   // 16 MFMAs of slice B; behind every second one a fragment read of slice KK (stage BASE)
-#define NF_W4_SLICE_READS(B, ON, KK, BASE)                                                                      \
-  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, BASE, 0);                                         \
-  NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, BASE, 1);                                         \
-  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, BASE, 2);                                         \
-  NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, BASE, 3);                                         \
-  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, BASE, 4);                                         \
-  NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, BASE, 5);                                         \
-  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, BASE, 6);                                         \
-  NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, BASE, 7)
+#define NF_W4_SLICE_READS(B, ON, KK, XB, WB)                                                                      \
+  NF_W4_MFMA(B, 0, 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, XB, WB, 0);                                         \
+  NF_W4_MFMA(B, 0, 2); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, XB, WB, 1);                                         \
+  NF_W4_MFMA(B, 1, 0); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, XB, WB, 2);                                         \
+  NF_W4_MFMA(B, 1, 2); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, XB, WB, 3);                                         \
+  NF_W4_MFMA(B, 2, 0); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, XB, WB, 4);                                         \
+  NF_W4_MFMA(B, 2, 2); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, XB, WB, 5);                                         \
+  NF_W4_MFMA(B, 3, 0); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, XB, WB, 6);                                         \
+  NF_W4_MFMA(B, 3, 2); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, XB, WB, 7)
   // the same with a global load behind the other MFMAs
-#define NF_W4_SLICE_READS_LOADS(B, ON, KK, BASE, L0)                                                            \
-  NF_W4_MFMA(B, 0, 0); NF_W4_LOAD(L0 + 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, BASE, 0);                     \
-  NF_W4_MFMA(B, 0, 2); NF_W4_LOAD(L0 + 1); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, BASE, 1);                     \
-  NF_W4_MFMA(B, 1, 0); NF_W4_LOAD(L0 + 2); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, BASE, 2);                     \
-  NF_W4_MFMA(B, 1, 2); NF_W4_LOAD(L0 + 3); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, BASE, 3);                     \
-  NF_W4_MFMA(B, 2, 0); NF_W4_LOAD(L0 + 4); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, BASE, 4);                     \
-  NF_W4_MFMA(B, 2, 2); NF_W4_LOAD(L0 + 5); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, BASE, 5);                     \
-  NF_W4_MFMA(B, 3, 0); NF_W4_LOAD(L0 + 6); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, BASE, 6);                     \
-  NF_W4_MFMA(B, 3, 2); NF_W4_LOAD(L0 + 7); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, BASE, 7)
-  // K-step k in LDS stage STAGE = k & 1.  MORE: there is a K-step k + 1; RELOAD: there is a
-  // K-step k + 2 (compile-time, so that the steady state has no branches).  The fragments of a
+#define NF_W4_SLICE_READS_LOADS(B, ON, KK, XB, WB, L0)                                                            \
+  NF_W4_MFMA(B, 0, 0); NF_W4_LOAD(L0 + 0); NF_W4_MFMA(B, 0, 1); NF_W4_RD1(ON, KK, XB, WB, 0);                     \
+  NF_W4_MFMA(B, 0, 2); NF_W4_LOAD(L0 + 1); NF_W4_MFMA(B, 0, 3); NF_W4_RD1(ON, KK, XB, WB, 1);                     \
+  NF_W4_MFMA(B, 1, 0); NF_W4_LOAD(L0 + 2); NF_W4_MFMA(B, 1, 1); NF_W4_RD1(ON, KK, XB, WB, 2);                     \
+  NF_W4_MFMA(B, 1, 2); NF_W4_LOAD(L0 + 3); NF_W4_MFMA(B, 1, 3); NF_W4_RD1(ON, KK, XB, WB, 3);                     \
+  NF_W4_MFMA(B, 2, 0); NF_W4_LOAD(L0 + 4); NF_W4_MFMA(B, 2, 1); NF_W4_RD1(ON, KK, XB, WB, 4);                     \
+  NF_W4_MFMA(B, 2, 2); NF_W4_LOAD(L0 + 5); NF_W4_MFMA(B, 2, 3); NF_W4_RD1(ON, KK, XB, WB, 5);                     \
+  NF_W4_MFMA(B, 3, 0); NF_W4_LOAD(L0 + 6); NF_W4_MFMA(B, 3, 1); NF_W4_RD1(ON, KK, XB, WB, 6);                     \
+  NF_W4_MFMA(B, 3, 2); NF_W4_LOAD(L0 + 7); NF_W4_MFMA(B, 3, 3); NF_W4_RD1(ON, KK, XB, WB, 7)
+  // K-step k with its x rows in stage STAGE = k & 1.  MORE: there is a K-step k + 1 (the tail
+  // flags are compile-time, so that the steady state has no branches).  The fragments of a
   // slice are requested two slices ahead, one read behind every second MFMA: at the top of a
   // slice at most the eight reads of the next slice are outstanding behind its own.
-  auto k_step = [&](auto stage_c, auto more_c, auto reload_c) {
+  // w_cur / w_next: byte offsets of the w stages of K-steps k and k + 1 (k % 3 and (k + 1) % 3
+  // stages in); the w rows of K-step k + 3 go where those of K-step k were.  XRELOAD: there is
+  // a K-step k + 2; WRELOAD: a K-step k + 3.  The loads of a K-step are issued x rows first:
+  // waiting until only WLOADS loads are outstanding leaves the w rows of K-step k + 2 in flight
+  // and has everything of K-step k + 1 in LDS.
+  auto k_step = [&](auto stage_c, auto more_c, auto xreload_c, auto wreload_c, const uint32_t w_cur,
+                    const uint32_t w_next) {
     constexpr int STAGE = decltype(stage_c)::value;
-    constexpr bool MORE = decltype(more_c)::value, RELOAD = decltype(reload_c)::value;
-    constexpr int CUR = STAGE * STAGE_BYTES, NEXT = (1 - STAGE) * STAGE_BYTES;
+    constexpr bool MORE = decltype(more_c)::value, XRELOAD = decltype(xreload_c)::value,
+                   WRELOAD = decltype(wreload_c)::value;
+    constexpr int CUR = STAGE * XSTAGE, NEXT = (1 - STAGE) * XSTAGE;
     wait_frags<TN + TM, TN, TM>(fw[0], fx[0]);
-    NF_W4_SLICE_READS(0, true, 2, CUR);
+    NF_W4_SLICE_READS(0, true, 2, CUR, w_cur);
     wait_frags<TN + TM, TN, TM>(fw[1], fx[1]);
-    NF_W4_SLICE_READS(1, true, 3, CUR);
+    NF_W4_SLICE_READS(1, true, 3, CUR, w_cur);
     // this wavefront has read all it needs of K-step k, and its part of K-step k + 1 is in LDS
     wait_frags<0, TN, TM>(fw[2], fx[2]);
     wait_frags<0, TN, TM>(fw[3], fx[3]);
-    if (MORE) wait_vmcnt<0>();
+    if (MORE) {
+      if (XRELOAD)
+        wait_vmcnt<WLOADS>();  // the w rows of K-step k + 2 stay in flight
+      else
+        wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
-    NF_W4_SLICE_READS_LOADS(2, MORE, 0, NEXT, 0);
-    NF_W4_SLICE_READS_LOADS(3, MORE, 1, NEXT, 8);
+    NF_W4_SLICE_READS_LOADS(2, MORE, 0, NEXT, w_next, 0);
+    NF_W4_SLICE_READS_LOADS(3, MORE, 1, NEXT, w_next, 8);
   };
   using T = std::true_type;
   using F = std::false_type;
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
+  uint32_t w_cur = 0, w_next = WSTAGE;
+  auto advance = [&]() {
+    w_cur = w_next;
+    w_next = w_next == 2 * WSTAGE ? 0 : w_next + WSTAGE;
+  };
   int k = 0;
-  for (; k + 2 < KT; k += 2) {
-    k_step(C0{}, T{}, T{});
-    k_step(C1{}, T{}, T{});
+  for (; k + 4 < KT; k += 2) {
+    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next);
+    advance();
+    k_step(C1{}, T{}, T{}, T{}, w_cur, w_next);
+    advance();
   }
-  k_step(C0{}, T{}, F{});
-  k_step(C1{}, F{}, F{});
+  if (k + 2 < KT) {  // K-steps KT - 4 and KT - 3
+    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next);
+    advance();
+    k_step(C1{}, T{}, T{}, F{}, w_cur, w_next);
+    advance();
+  }
+  k_step(C0{}, T{}, F{}, F{}, w_cur, w_next);
+  advance();
+  k_step(C1{}, F{}, F{}, F{}, w_cur, w_next);
 #undef NF_W4_MFMA
 #undef NF_W4_LOAD
 #undef NF_W4_SLICE_READS
@@ -717,8 +758,8 @@ hipError_t launch_w4_columns(const void* x, const void* w, void* out, const void
   constexpr int BM = 64 * TM;
   const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
   const dim3 grid(tiles_m * n_tiles), block(256);
-  // two tile stages; the epilogue reuses them as 4 regions of (BM / 2) rows x 272 bytes
-  const size_t lds_bytes = std::max((size_t)2 * (BM + 256) * 128, (size_t)4 * (BM / 2) * 272);
+  // two x stages and three w stages; the epilogue reuses them as 4 regions of (BM / 2) rows x 272 bytes
+  const size_t lds_bytes = std::max((size_t)(2 * BM + 3 * 256) * 128, (size_t)4 * (BM / 2) * 272);
   KRange kr{K, nullptr, 0};
   kr.n_first = n_first;
 #define NF_W4_LAUNCH(E)                                                                                            \
@@ -871,7 +912,7 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
       // the four-wavefront loop: each half of K must be a multiple of its 128-element period
       if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
       const int tiles_m = (M + 255) / 256, tiles_n = N / 256;
-      const size_t lds_bytes = (size_t)2 * 512 * 128;
+      const size_t lds_bytes = (size_t)(2 * 256 + 3 * 256) * 128;
       static bool attr_set = false;
       e = allow_lds(gemm_w4_kernel<EPI_PARTIAL>, lds_bytes, attr_set);
       if (e != hipSuccess) return e;
@@ -884,7 +925,7 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
     case 22: {  // the same with 128x256 tiles: twice the workgroups for few rows
       if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
       const int tiles_m = (M + 127) / 128, tiles_n = N / 256;
-      const size_t lds_bytes = (size_t)2 * 384 * 128;
+      const size_t lds_bytes = (size_t)(2 * 128 + 3 * 256) * 128;
       static bool attr_set = false;
       e = allow_lds(gemm_w4_kernel<EPI_PARTIAL, false, 2>, lds_bytes, attr_set);
       if (e != hipSuccess) return e;
@@ -919,7 +960,7 @@ hipError_t nf_launch_gemm_dl_grouped_halves(const void* x, const void* w, int ro
     case 21: {
       if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
       const int tiles_m = (rows + 255) / 256 + n_experts, tiles_n = N / 256;
-      const size_t lds_bytes = (size_t)2 * 512 * 128;
+      const size_t lds_bytes = (size_t)(2 * 256 + 3 * 256) * 128;
       static bool attr_set = false;
       hipError_t e = allow_lds(gemm_w4_kernel<EPI_PARTIAL, true>, lds_bytes, attr_set);
       if (e != hipSuccess) return e;
