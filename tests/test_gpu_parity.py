@@ -82,7 +82,10 @@ def test_gemm_kernel_swiglu(M, I, K):
 @pytest.mark.parametrize("M,N,K,epi", [(300, 512, 256, "none"), (1100, 1024, 1408, "residual"), (257, 768, 512, "swiglu"),
                                        (700, 1536, 320, "residual"), (513, 512, 1024, "none"), (64, 256, 128, "none"),
                                        # 8 x 48 tiles of 256x256 = 1.5 rounds of 256: the remainder runs as 128x256 tiles
-                                       (2048, 12288, 128, "residual"), (2000, 6144, 256, "swiglu")])
+                                       (2048, 12288, 128, "residual"), (2000, 6144, 256, "swiglu"),
+                                       # 6 and 10 K-steps of 64: with 2, 4 and 16 above, every start-up and tail
+                                       # form of the loop that keeps three stages of weight rows in LDS
+                                       (520, 768, 384, "swiglu"), (300, 512, 640, "residual")])
 def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     """All tile shapes and both LDS feeding schemes walk K in the same order with the same
     MFMA instruction, so the implementation choice (which the profile makes per operation
