@@ -277,8 +277,12 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     // on the 8B layer's O projection: 63 us against 74 with 256x128 and 83 with 256x256)
     const double s22 = four_waves ? score(128, 256, 0.95) : 0.0;
     if (s22 > s21 && s22 > s20 && s22 > s12 && s22 > s7 && s22 > s13) tile = 22;
+    // and with 256x192 tiles (the 8B layer's KQV at 2048 rows: one tile per CU instead of 192 tiles)
+    const double s23 = (four_waves && epilogue != EPI_SWIGLU && n_eff % 192 == 0) ? score(256, 192, 1.15) : 0.0;
+    if (s23 > s22 && s23 > s21 && s23 > s20 && s23 > s12 && s23 > s7 && s23 > s13) tile = 23;
   }
-  if (tile >= 7 && tile <= 22) {
+  if (tile >= 7 && tile <= 23) {
+    if (tile == 23 && (K % 128 != 0 || n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 21;
     if ((tile == 21 || tile == 22) && (K % 128 != 0 || n_eff % 256 != 0)) tile = 13;
     if (tile == 20 && (n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 19;
     if (tile == 10 && n_eff % 256 != 0) tile = 9;

@@ -402,16 +402,20 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
   constexpr int WO = EPI == EPI_SWIGLU ? WN / 2 : WN;  // output columns of this wavefront
   constexpr int ROWB = WO * 2 + 16;                     // bytes per LDS row
   constexpr int CPR = WO / 8, RPI = 64 / CPR;           // 16-byte chunks per row, rows per wavefront instruction
+  constexpr int PASSES = (WM + RPI - 1) / RPI;          // (96-column shares: 12 chunks, 5 rows, 4 lanes idle)
   const int col0 = EPI == EPI_SWIGLU ? (n0 >> 1) + wn * WO : n0 + wn * WO;
   const int row_lo = m0 + wm * WM;
   const int rr = lane / CPR, kc = lane % CPR;
+  const bool lane_on = rr < RPI;
   if (EPI == EPI_RESIDUAL) {
 #pragma unroll
-    for (int t = 0; t < WM / RPI; ++t) {
+    for (int t = 0; t < PASSES; ++t) {
       const int row = t * RPI + rr;
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (row_lo + row < M) v = *reinterpret_cast<const u32x4*>(R + (size_t)(row_lo + row) * N + col0 + kc * 8);
-      asm volatile("ds_write_b128 %0, %1" ::"v"(region + (uint32_t)(row * ROWB + kc * 16)), "v"(v) : "memory");
+      if (lane_on && row < WM) {
+        if (row_lo + row < M) v = *reinterpret_cast<const u32x4*>(R + (size_t)(row_lo + row) * N + col0 + kc * 8);
+        asm volatile("ds_write_b128 %0, %1" ::"v"(region + (uint32_t)(row * ROWB + kc * 16)), "v"(v) : "memory");
+      }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
@@ -446,11 +450,13 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-  for (int t = 0; t < WM / RPI; ++t) {
+  for (int t = 0; t < PASSES; ++t) {
     const int row = t * RPI + rr;
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(region + (uint32_t)(row * ROWB + kc * 16)) : "memory");
-    if (row_lo + row < M) *reinterpret_cast<u32x4*>(Y + (size_t)(row_lo + row) * N + col0 + kc * 8) = v;
+    if (lane_on && row < WM) {
+      u32x4 v;
+      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(region + (uint32_t)(row * ROWB + kc * 16)) : "memory");
+      if (row_lo + row < M) *reinterpret_cast<u32x4*>(Y + (size_t)(row_lo + row) * N + col0 + kc * 8) = v;
+    }
   }
 }
 
@@ -471,14 +477,17 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
 // and 3.  The w rows so have two K-steps to arrive (measured against two stages of both on one
 // device: 2-2.5 % on Up/Gate and KQV, 5 % on O, 6 % on the 70B KQV).  TM = 4: 256x256 tiles; TM = 2: 128x256
 // tiles with 64x128 shares (for shapes whose 256x256 tiles leave CUs idle, and for the
-// remainder of a launch beyond its last whole round of tiles).  Same MFMA and K order as the
-// other loops, hence the same output bits.  Requires K % 128 == 0 and 256 | N.
-template <int EPI, bool GROUPED = false, int TM = 4>
+// remainder of a launch beyond its last whole round of tiles).  TN = 3: 256x192 tiles with
+// 128x96 shares (N = 6144, the 8B layer's KQV: 8 x 32 = 256 tiles, one per CU, where 256x256
+// gives 192; not for SwiGLU, whose epilogue pairs 32-column groups).  Same MFMA and K order as
+// the other loops, hence the same output bits.  Requires K % 128 == 0 and 64 * TN | N.
+template <int EPI, bool GROUPED = false, int TM = 4, int TN = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
-  constexpr int WM = 32 * TM, BM = 2 * WM, BN = 256, NW = 4, WN = 128, TN = 4;
+  constexpr int WM = 32 * TM, BM = 2 * WM, BN = 64 * TN, NW = 4, WN = 32 * TN;
   static_assert(TM == 4 || TM == 2, "256x256 tiles, or 128x256 tiles with 64x128 wavefront shares");
+  static_assert(TN == 4 || (TN == 3 && TM == 4 && EPI != EPI_SWIGLU), "or 256x192 tiles with 128x96 shares");
   constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
   constexpr int ROWS = BM + BN;
   constexpr int LOADS = ROWS / RPI / NW;  // per K-step: BM / 32 of x, then 8 of w
@@ -553,9 +562,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     w_addr[kk] = lds_base + (uint32_t)(WBASE + (wn * WN + frag_row) * RB) + slot;
   }
   bf16x8 fw[4][TN], fx[4][TM];  // one fragment buffer per K-slice
-  using seq4 = std::make_integer_sequence<int, 4>;
+  using seq_w = std::make_integer_sequence<int, TN>;
 #define NF_W4_READ(KK, XB, WB)                                                                                  \
-  lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (WB), seq4{});                                                 \
+  lds_read_frags<0, 32 * RB>(fw[KK], w_addr[KK] + (WB), seq_w{});                                                \
   lds_read_frags<0, 32 * RB>(fx[KK], x_addr[KK] + (XB), std::make_integer_sequence<int, TM>{})
 
   // prologue: x rows of K-steps 0 and 1 and w rows of K-steps 0, 1 and 2 on their way (the w
@@ -578,9 +587,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   NF_W4_READ(1, 0, 0);
 
 #define NF_W4_MFMA(B, I, J)                                                                                     \
-  if constexpr ((J) < TM)                                                                                       \
-    acc[I][(J) < TM ? (J) : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][I], fx[B][(J) < TM ? (J) : 0],    \
-                                                                        acc[I][(J) < TM ? (J) : 0], 0, 0, 0);   \
+  if constexpr ((J) < TM && (I) < TN)                                                                           \
+    acc[(I) < TN ? (I) : 0][(J) < TM ? (J) : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                       \
+        fw[B][(I) < TN ? (I) : 0], fx[B][(J) < TM ? (J) : 0], acc[(I) < TN ? (I) : 0][(J) < TM ? (J) : 0], 0, 0, \
+        0);                                                                                                     \
   __builtin_amdgcn_sched_barrier(0)
 #define NF_W4_LOAD(I)                                                                                           \
   if constexpr ((I) < XLOADS ? XRELOAD : (WRELOAD && (I) < LOADS)) load_one(I, STAGE, w_cur);                    \
@@ -588,9 +598,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // fragment I (0..3: w, 4..7: x) of K-slice KK from the stage at BASE, if ON
 #define NF_W4_RD1(ON, KK, XB, WB, I)                                                                            \
   if constexpr (ON) {                                                                                           \
-    if constexpr ((I) < 4)                                                                                      \
-      fw[KK][(I) & 3] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (WB));                                \
-    else if constexpr (((I) & 3) < TM)                                                                          \
+    if constexpr ((I) < 4) {                                                                                    \
+      if constexpr (((I) & 3) < TN)                                                                             \
+        fw[KK][((I) & 3) < TN ? ((I) & 3) : 0] = lds_read_frag_at<((I) & 3) * 32 * RB>(w_addr[KK] + (WB));       \
+    } else if constexpr (((I) & 3) < TM)                                                                        \
       fx[KK][((I) & 3) < TM ? ((I) & 3) : 0] = lds_read_frag_at<((I) & 3) * 32 * RB>(x_addr[KK] + (XB));         \
   }                                                                                                             \
   __builtin_amdgcn_sched_barrier(0)
@@ -682,7 +693,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     store_tile<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
                                     kr.partial + (size_t)blockIdx.y * (size_t)kr.seg_stride);
   } else {
-    // 128 x 272 bytes per wavefront at most: the launcher sizes the LDS for it
+    // WM x (2 * WN + 16) bytes per wavefront: the launcher sizes the LDS for it
     store_tile_rows<EPI, TM, TN, WM, WN>(acc, Y, R, M, N, m0, n0, wm, wn, lane,
                                          lds_base + (uint32_t)(wave * (WM * (WN * 2 + 16))));
   }
@@ -752,19 +763,19 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
 
 // One launch of the four-wavefront loop with tiles of 64 * TM rows over the tile columns
 // [n_first, n_first + n_tiles).
-template <bool GROUPED, int TM>
+template <bool GROUPED, int TM, int TN = 4>
 hipError_t launch_w4_columns(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, hipStream_t s, GroupedArgs grp, int n_first, int n_tiles) {
-  constexpr int BM = 64 * TM;
+  constexpr int BM = 64 * TM, BN = 64 * TN;
   const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
   const dim3 grid(tiles_m * n_tiles), block(256);
   // two x stages and three w stages; the epilogue reuses them as 4 regions of (BM / 2) rows x 272 bytes
-  const size_t lds_bytes = std::max((size_t)(2 * BM + 3 * 256) * 128, (size_t)4 * (BM / 2) * 272);
+  const size_t lds_bytes = std::max((size_t)(2 * BM + 3 * BN) * 128, (size_t)4 * (BM / 2) * (BN + 16));
   KRange kr{K, nullptr, 0};
   kr.n_first = n_first;
 #define NF_W4_LAUNCH(E)                                                                                            \
   do {                                                                                                             \
-    auto kern = gemm_w4_kernel<E, GROUPED, TM>;                                                                     \
+    auto kern = gemm_w4_kernel<E, GROUPED, TM, TN>;                                                                 \
     static bool attr_set = false;                                                                                  \
     hipError_t e = allow_lds(kern, lds_bytes, attr_set);                                                           \
     if (e != hipSuccess) return e;                                                                                 \
@@ -774,7 +785,13 @@ hipError_t launch_w4_columns(const void* x, const void* w, void* out, const void
   switch (epilogue) {
     case EPI_NONE: NF_W4_LAUNCH(EPI_NONE); break;
     case EPI_RESIDUAL: NF_W4_LAUNCH(EPI_RESIDUAL); break;
-    default: NF_W4_LAUNCH(EPI_SWIGLU); break;
+    default:
+      if constexpr (TN == 4) {
+        NF_W4_LAUNCH(EPI_SWIGLU);
+      } else {
+        return hipErrorInvalidValue;
+      }
+      break;
   }
 #undef NF_W4_LAUNCH
   return hipGetLastError();
@@ -1008,6 +1025,9 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
       if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
       return launch_w4_columns<false, 2>(x, w, out, residual, M, N, K, epilogue, s, none, 0, n_eff / 256);
     }
+    case 23:  // the four-wavefront loop with 256x192 tiles
+      if (K % 128 != 0 || N % 192 != 0 || epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
+      return launch_w4_columns<false, 4, 3>(x, w, out, residual, M, N, K, epilogue, s, none, 0, N / 192);
     default: return hipErrorInvalidValue;
   }
 }
