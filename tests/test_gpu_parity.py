@@ -85,7 +85,9 @@ def test_gemm_kernel_swiglu(M, I, K):
                                        (2048, 12288, 128, "residual"), (2000, 6144, 256, "swiglu"),
                                        # 6 and 10 K-steps of 64: with 2, 4 and 16 above, every start-up and tail
                                        # form of the loop that keeps three stages of weight rows in LDS
-                                       (520, 768, 384, "swiglu"), (300, 512, 640, "residual")])
+                                       (520, 768, 384, "swiglu"), (300, 512, 640, "residual"),
+                                       # widths that 192 divides and 256 does not: the 256x192 form and its ragged rows
+                                       (257, 192, 2048, "residual"), (1000, 768, 640, "none")])
 def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     """All tile shapes and both LDS feeding schemes walk K in the same order with the same
     MFMA instruction, so the implementation choice (which the profile makes per operation
