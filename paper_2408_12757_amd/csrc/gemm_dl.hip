@@ -477,9 +477,10 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
 // and 3.  The w rows so have two K-steps to arrive (measured against two stages of both on one
 // device: 2-2.5 % on Up/Gate and KQV, 5 % on O, 6 % on the 70B KQV).  TM = 4: 256x256 tiles; TM = 2: 128x256
 // tiles with 64x128 shares (for shapes whose 256x256 tiles leave CUs idle, and for the
-// remainder of a launch beyond its last whole round of tiles).  TN = 3: 256x192 tiles with
-// 128x96 shares (N = 6144, the 8B layer's KQV: 8 x 32 = 256 tiles, one per CU, where 256x256
-// gives 192; not for SwiGLU, whose epilogue pairs 32-column groups).  Same MFMA and K order as
+// remainder of a launch beyond its last whole round of tiles).  TN = 3: 192 columns with
+// 96-column shares (N = 6144, the 8B layer's KQV: 8 x 32 = 256 tiles of 256x192 at 2048 rows,
+// of 128x192 at 1024 rows, one per CU, where 256 columns give 192 tiles; not for SwiGLU, whose
+// epilogue pairs 32-column groups).  Same MFMA and K order as
 // the other loops, hence the same output bits.  Requires K % 128 == 0 and 64 * TN | N.
 template <int EPI, bool GROUPED = false, int TM = 4, int TN = 4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
   constexpr int WM = 32 * TM, BM = 2 * WM, BN = 64 * TN, NW = 4, WN = 32 * TN;
   static_assert(TM == 4 || TM == 2, "256x256 tiles, or 128x256 tiles with 64x128 wavefront shares");
-  static_assert(TN == 4 || (TN == 3 && TM == 4 && EPI != EPI_SWIGLU), "or 256x192 tiles with 128x96 shares");
+  static_assert(TN == 4 || (TN == 3 && EPI != EPI_SWIGLU), "or 192 columns with 96-column shares");
   constexpr int BKT = 64, RB = 128, CPR = 8, RPI = 8;
   constexpr int ROWS = BM + BN;
   constexpr int LOADS = ROWS / RPI / NW;  // per K-step: BM / 32 of x, then 8 of w
@@ -1028,6 +1029,9 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     case 23:  // the four-wavefront loop with 256x192 tiles
       if (K % 128 != 0 || N % 192 != 0 || epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
       return launch_w4_columns<false, 4, 3>(x, w, out, residual, M, N, K, epilogue, s, none, 0, N / 192);
+    case 24:  // and with 128x192 tiles
+      if (K % 128 != 0 || N % 192 != 0 || epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
+      return launch_w4_columns<false, 2, 3>(x, w, out, residual, M, N, K, epilogue, s, none, 0, N / 192);
     default: return hipErrorInvalidValue;
   }
 }

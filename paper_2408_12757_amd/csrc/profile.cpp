@@ -27,7 +27,7 @@ void nf_profile_free(nf_ctx* ctx) {
 
 namespace {
 
-constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19, 20, 21, 22, 23};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
+constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19, 20, 21, 22, 23, 24};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
 constexpr int kAttnWgSettings[] = {64, 96, 128, 160, 192, 256, 512};
 
 struct Scratch {
