@@ -916,7 +916,8 @@ hipError_t nf_launch_gemm_dl_two_sums(const void* x, const void* w, void* out, c
 // Two-segment operation with the segments on different workgroups: twice the workgroups of
 // the one-launch form, for row counts that would leave most of the chip idle.  partial holds
 // the two [M, N] fp32 sums seg_stride floats apart; a second kernel adds them (+ residual).
-// variant: 7 = 128x128, 12 = 256x128, 13 = 256x256 (N % 256 == 0), 19 = 256x128 second main loop.
+// variant: 7 = 128x128, 12 = 256x128, 13 = 256x256 (N % 256 == 0), 19 = 256x128 second main loop,
+// 21 / 22 = the four-wavefront loop with 256x256 / 128x256 tiles (K % 256 == 0, N % 256 == 0).
 hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, const void* residual, int M, int N,
                                     int K, float* partial, long long seg_stride, int variant, hipStream_t s) {
   const KRange kr{K, partial, seg_stride};
@@ -964,7 +965,8 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
 
 // Grouped mode of the two-segment operation (the experts' down projection): the fp32 sums of
 // the two halves of K go to partial and partial + seg_stride, rows at their sorted positions;
-// the consumer (the combine kernel) adds them.  variant: 12 / 19 = 256x128 tiles, 13 = 256x256.
+// the consumer (the combine kernel) adds them.  variant: 12 / 19 = 256x128 tiles, 13 = 256x256,
+// 21 = 256x256 with the four-wavefront loop.
 hipError_t nf_launch_gemm_dl_grouped_halves(const void* x, const void* w, int rows, int N, int K, float* partial,
                                             long long seg_stride, const int32_t* expert_offset,
                                             const int32_t* row_index, int n_experts, long long w_stride, int variant,
@@ -1036,7 +1038,7 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
   }
 }
 
-// Grouped mode (see GroupedArgs): 7 / 11 = 128x128 tiles, 9 / 12 / 19 = 256x128 tiles, 13 = 256x256 tiles.
+// Grouped mode (see GroupedArgs): 7 / 11 = 128x128 tiles, 9 / 12 / 19 = 256x128 tiles, 13 / 21 = 256x256 tiles.
 hipError_t nf_launch_gemm_dl_grouped(const void* x, const void* w, void* out, int rows, int N, int K, int epilogue,
                                      const int32_t* expert_offset, const int32_t* row_index, int n_experts,
                                      long long w_stride, int variant, hipStream_t s) {
