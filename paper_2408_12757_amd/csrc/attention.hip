@@ -330,9 +330,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void attention_kernel(const bf
 }
 
 // Merge the partial results of one row group in chunk order and write bf16 output.
-// grid (n_groups, Hkv), DH threads: thread d owns output dimension d of every row.
+// grid (n_groups, Hkv), block (DH, 4): thread (d, y) owns output dimension d of the rows
+// y, y + 4, ... (the rows are independent chains of dependent loads: four run side by side).
 template <int DH>
-__global__ __launch_bounds__(DH) void attention_merge_kernel(const float* __restrict__ parts,
+__global__ __launch_bounds__(DH * 4) void attention_merge_kernel(const float* __restrict__ parts,
                                                              const NfAttnGroup* __restrict__ groups, int Hq, int Hkv,
                                                              bf16_t* __restrict__ out) {
   const NfAttnGroup gr = groups[blockIdx.x];
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(DH) void attention_merge_kernel(const float* __rest
   const int n_rows = gr.n_tok * G;
   const size_t stride = (size_t)Hkv * (16 * DH + 32);
   const float* base = parts + ((size_t)gr.part0 * Hkv + kvh) * (16 * DH + 32);
-  for (int r = 0; r < n_rows; ++r) {
+  for (int r = threadIdx.y; r < n_rows; r += 4) {
     float M = -INFINITY;
     for (int j = 0; j < gr.n_parts; ++j) M = fmaxf(M, base[j * stride + 16 * DH + r]);
     float L = 0.f, acc = 0.f;
@@ -437,10 +438,10 @@ hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* grou
   if (n_groups <= 0) return hipSuccess;
   const dim3 grid(n_groups, shp.n_kv_heads);
   if (shp.head_dim == 128) {
-    attention_merge_kernel<128><<<grid, dim3(128), 0, s>>>(parts, groups, shp.n_q_heads, shp.n_kv_heads,
+    attention_merge_kernel<128><<<grid, dim3(128, 4), 0, s>>>(parts, groups, shp.n_q_heads, shp.n_kv_heads,
                                                            (bf16_t*)attn_out);
   } else if (shp.head_dim == 64) {
-    attention_merge_kernel<64><<<grid, dim3(64), 0, s>>>(parts, groups, shp.n_q_heads, shp.n_kv_heads,
+    attention_merge_kernel<64><<<grid, dim3(64, 4), 0, s>>>(parts, groups, shp.n_q_heads, shp.n_kv_heads,
                                                          (bf16_t*)attn_out);
   } else {
     return hipErrorInvalidValue;
