@@ -166,6 +166,9 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
       double best = 1e300;
       int best_tile = 1;
       for (int tile : kTiles) {
+        // the 192-column forms have no SwiGLU epilogue and need 192 | N: such an operation would
+        // run (and be listed under) the implementation they fall back to
+        if ((tile == 20 || tile == 23 || tile == 24) && (shp[o].epi == NF_EPI_SWIGLU || shp[o].N % 192 != 0)) continue;
         int flip = 0;
         double ms = 0;
         rc = time_ms(ctx, sg, 6, [&] {
