@@ -101,12 +101,17 @@ def silu(a: np.ndarray) -> np.ndarray:
     return a / (1.0 + np.exp(-a))
 
 
-def swiglu_ffn(h: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray) -> np.ndarray:
-    """down( silu(gate(h)) * up(h) ); w_gate_up[2I, D] holds gate rows then up rows."""
+def swiglu_inner(h: np.ndarray, w_gate_up: np.ndarray) -> np.ndarray:
+    """silu(gate(h)) * up(h); w_gate_up[2I, D] holds gate rows then up rows."""
     inner = w_gate_up.shape[0] // 2
     og = dense(h, w_gate_up[:inner])
     ou = dense(h, w_gate_up[inner:])
-    return dense(silu(og) * ou, w_down)
+    return silu(og) * ou
+
+
+def swiglu_ffn(h: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray) -> np.ndarray:
+    """down( silu(gate(h)) * up(h) )."""
+    return dense(swiglu_inner(h, w_gate_up), w_down)
 
 
 def softmax_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
@@ -189,6 +194,45 @@ def gather_kv(pages, page_list, n_tokens: int, n_kv_heads: int, head_dim: int, p
     return K, V
 
 
+def attention_stage(model, batch, pages, q, k, v):
+    """Position embedding, KV concatenation and attention of the whole dense batch
+    (Sec. 2.1: "Key and Value [are] concatenated into the existing KV-cache.  The Query
+    is then multiplied with the existing Keys", normalised, and used to average the Values).
+
+    q[B, Hq, dh], k[B, Hkv, dh], v[B, Hkv, dh]: this iteration's projections BEFORE the
+    rotary embedding.  pages: the KV pool before the iteration.  The token with index t of
+    request r sits at position ctx_len[r] + (t - q_indptr[r]) and reads keys 0 .. position.
+
+    Returns (q after rotary embedding, k after rotary embedding, attn[B, Hq, dh]).
+    """
+    Hq, Hkv, dh, P = model.n_q_heads, model.n_kv_heads, model.head_dim, model.page_size
+    G = Hq // Hkv
+    B = q.shape[0]
+    n_reqs = len(batch.ctx_len)
+    pos = np.zeros(B, np.int64)
+    for r in range(n_reqs):
+        t0, t1 = int(batch.q_indptr[r]), int(batch.q_indptr[r + 1])
+        pos[t0:t1] = int(batch.ctx_len[r]) + np.arange(t1 - t0)
+    q = rope(q, pos, model.rope_theta)
+    k = rope(k, pos, model.rope_theta)
+
+    attn = np.zeros((B, Hq, dh))
+    for r in range(n_reqs):
+        t0, t1 = int(batch.q_indptr[r]), int(batch.q_indptr[r + 1])
+        c = int(batch.ctx_len[r])
+        plist = batch.page_ids[int(batch.page_indptr[r]): int(batch.page_indptr[r + 1])]
+        Kc, Vc = gather_kv(pages, plist, c, Hkv, dh, P)
+        # cached prefix + this iteration's rows of the request
+        Kall = np.concatenate([Kc, k[t0:t1]], axis=0)
+        Vall = np.concatenate([Vc, v[t0:t1]], axis=0)
+        for t in range(t0, t1):
+            n_keys = c + (t - t0) + 1
+            for hq in range(Hq):
+                hk = hq // G
+                attn[t, hq] = softmax_attention(q[t, hq], Kall[:n_keys, hk], Vall[:n_keys, hk])
+    return q, k, attn
+
+
 # ----------------------------------------------------------------------------
 # the layer
 # ----------------------------------------------------------------------------
@@ -209,11 +253,8 @@ def layer_forward(model, weights, pages, batch, x, expert_choice=None, return_pa
     (k_new[B, Hkv, dh] after rotary embedding, v_new[B, Hkv, dh]).
     """
     D, Hq, Hkv, dh = model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim
-    G = Hq // Hkv
-    P = model.page_size
     x = widen(x)
     B = x.shape[0]
-    n_reqs = len(batch.ctx_len)
 
     # attention stage
     h = rmsnorm(x, widen(weights["g_attn_norm"]), model.rms_eps)
@@ -222,28 +263,7 @@ def layer_forward(model, weights, pages, batch, x, expert_choice=None, return_pa
     k = qkv[:, Hq * dh: (Hq + Hkv) * dh].reshape(B, Hkv, dh)
     v = qkv[:, (Hq + Hkv) * dh:].reshape(B, Hkv, dh)
 
-    pos = np.zeros(B, np.int64)
-    for r in range(n_reqs):
-        t0, t1 = int(batch.q_indptr[r]), int(batch.q_indptr[r + 1])
-        pos[t0:t1] = int(batch.ctx_len[r]) + np.arange(t1 - t0)
-    q = rope(q, pos, model.rope_theta)
-    k = rope(k, pos, model.rope_theta)
-
-    attn = np.zeros((B, Hq, dh))
-    for r in range(n_reqs):
-        t0, t1 = int(batch.q_indptr[r]), int(batch.q_indptr[r + 1])
-        c = int(batch.ctx_len[r])
-        plist = batch.page_ids[int(batch.page_indptr[r]): int(batch.page_indptr[r + 1])]
-        Kc, Vc = gather_kv(pages, plist, c, Hkv, dh, P)
-        # Key and Value are concatenated into the existing cache, then the Query
-        # is multiplied with the keys (Sec. 2.1): cached prefix + this iteration.
-        Kall = np.concatenate([Kc, k[t0:t1]], axis=0)
-        Vall = np.concatenate([Vc, v[t0:t1]], axis=0)
-        for t in range(t0, t1):
-            n_keys = c + (t - t0) + 1
-            for hq in range(Hq):
-                hk = hq // G
-                attn[t, hq] = softmax_attention(q[t, hq], Kall[:n_keys, hk], Vall[:n_keys, hk])
+    q, k, attn = attention_stage(model, batch, pages, q, k, v)
 
     y = x + dense(attn.reshape(B, Hq * dh), widen(weights["w_o"]))
 
@@ -252,15 +272,17 @@ def layer_forward(model, weights, pages, batch, x, expert_choice=None, return_pa
     wgu = weights["w_gate_up"]
     wd = weights["w_down"]
     route = None
+    inner = None
     if model.n_experts > 1:
         f, idx, wts, logits = moe_ffn(h2, widen(weights["w_router"]), wgu, wd,
                                       model.top_k, expert_choice)
         route = (idx, wts, logits)
     else:
-        f = swiglu_ffn(h2, widen(wgu[0]), widen(wd[0]))
+        inner = swiglu_inner(h2, widen(wgu[0]))
+        f = dense(inner, widen(wd[0]))
     z = y + f
     if return_parts:
-        return z, k, v, dict(h=h, q=q, attn=attn, y=y, h2=h2, route=route)
+        return z, k, v, dict(h=h, q=q, attn=attn, y=y, h2=h2, inner=inner, route=route)
     return z, k, v
 
 

@@ -8,17 +8,30 @@ from paper_2408_12757_amd import binding as nf
 from paper_2408_12757_amd import harness as hz
 from paper_2408_12757_amd import workloads as wl
 
-# the benchmark spec tolerance for bf16 with fp32 accumulation: max |gpu - ref| / max |ref| per tensor
-REL_TOL = 2e-2
+from parity_metrics import REL_TOL, check_intermediates, tensor_rel_err
+
+# REL_TOL: tolerance for bf16 with fp32 accumulation, max |gpu - ref| / max |ref| per tensor
 DEV = "cuda:0"
-
-
-def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
-    return float(np.max(np.abs(gpu.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30))
+rel_err = tensor_rel_err
 
 
 def f64(bits: np.ndarray) -> np.ndarray:
     return orc.widen(bits)
+
+
+def regions_from_workspace(ws: torch.Tensor, plan, model, B: int, rows=None):
+    """bf16 bits of the attention output, y and (dense models) SiLU(gate)*up that the last
+    call with this plan's layout left in the workspace; rows: optional row subset."""
+    got = {}
+    for name, cols in (("attn", model.q_dim), ("y", model.hidden), ("f", model.ffn_inner)):
+        if name == "f" and model.is_moe:
+            continue        # rows sorted by expert: compared through z only
+        off, nb = plan.workspace_region(name)
+        t = ws[off:off + nb].view(torch.bfloat16).view(B, cols)
+        if rows is not None:
+            t = t[torch.as_tensor(np.asarray(rows), device=t.device)]
+        got[name] = hz.bf16_bits(t)
+    return got
 
 
 class Case:
@@ -40,11 +53,25 @@ class Case:
         self.pages.copy_(hz.bf16_tensor(self.pages_bits, DEV))
 
     def run(self, plan=None):
-        """Returns (z bits [B, D], pages bits after the call)."""
+        """Returns (z bits [B, D], pages bits after the call); keeps the bf16 bits of the
+        intermediates the call left in the workspace (attention output, y, SiLU(gate)*up)."""
         self.reset_pages()
         out = self.runner.forward(self.args, self.x, plan)
         torch.cuda.synchronize()
+        self.last_regions = self.read_regions(plan)
         return hz.bf16_bits(out), hz.bf16_bits(self.pages)
+
+    def read_regions(self, plan=None):
+        """The activation regions lie in front of everything whose size depends on the plan,
+        so an unsplit plan of the same batch names the offsets of any run."""
+        m, B = self.model, self.batch.n_tokens
+        if B == 0:
+            return {}
+        tmp = plan if plan is not None else nf.nf_plan_manual(self.ctx, m, self.args, [0, B])
+        got = regions_from_workspace(self.runner.workspace, tmp, m, B)
+        if plan is None:
+            tmp.close()
+        return got
 
     def oracle(self, reqs=None):
         b, x, pages = self.batch, self.x_bits, self.pages_bits
@@ -52,18 +79,23 @@ class Case:
         if reqs is not None:
             b, tok, phys = wl.subset_batch(self.batch, reqs)
             x, pages = x[tok], pages[phys]
-        z, k, v = orc.layer_forward(self.model, self.weights, pages, b, x)
-        return z, k, v, tok
+        z, k, v, parts = orc.layer_forward(self.model, self.weights, pages, b, x, return_parts=True)
+        parts["x"] = orc.widen(x)
+        return z, k, v, tok, parts
 
-    def check(self, z_bits, pages_bits, reqs=None, tol=REL_TOL):
-        z, k, v, tok = self.oracle(reqs)
+    def check(self, z_bits, pages_bits, reqs=None, tol=REL_TOL, regions=None):
+        """Layer output, appended K/V rows and every intermediate the call left in the
+        workspace against the oracle, each on its own scale (see parity_metrics)."""
+        z, k, v, tok, parts = self.oracle(reqs)
         e_z = rel_err(f64(z_bits[tok]), z)
         kg, vg = hz.read_kv_rows(pages_bits, self.model, self.batch, tok)
         e_k = rel_err(f64(kg), k)
         e_v = rel_err(f64(vg), v)
         assert np.all(np.isfinite(f64(z_bits))), "non-finite output"
         assert e_z <= tol and e_k <= tol and e_v <= tol, (e_z, e_k, e_v)
-        return e_z, e_k, e_v
+        regions = self.last_regions if regions is None else regions
+        report = check_intermediates(self.model, regions, z_bits, tok, z, parts, tol)
+        return (e_z, e_k, e_v), report
 
 
 def untouched_pages_equal(case: Case, pages_after: np.ndarray) -> bool:

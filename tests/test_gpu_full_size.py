@@ -11,7 +11,9 @@ from paper_2408_12757_amd import binding as nf
 from paper_2408_12757_amd import harness as hz
 from paper_2408_12757_amd import workloads as wl
 
-from gpu_util import REL_TOL, f64, rel_err
+from gpu_util import REL_TOL, f64, regions_from_workspace, rel_err
+from parity_metrics import check_intermediates
+import test_gpu_attention as ta
 
 pytestmark = pytest.mark.gpu
 
@@ -28,11 +30,17 @@ def c2():
     case.ctx.close()
 
 
-def sample_check(cfg, case, out_bits, pages_before, reqs):
+def sample_check(cfg, case, out_bits, pages_before, reqs, plan):
+    """Output, appended rows and the intermediates left in the workspace (attention output
+    per row, attention block, SiLU(gate)*up, FFN block) of the sampled requests."""
     b, m = case.batch, cfg.model
     sub, tok, phys = wl.subset_batch(b, reqs)
-    z, k, v = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok])
+    z, k, v, parts = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok], return_parts=True)
+    parts["x"] = f64(case.x_bits[tok])
     e_z = rel_err(f64(out_bits[tok]), z)
+    regions = regions_from_workspace(case._ws, plan, m, b.n_tokens, rows=tok)
+    report = check_intermediates(m, regions, out_bits[tok], np.arange(len(tok)), z, parts)
+    say("intermediates", report)
     # appended K/V rows, read back from the device pool
     pages_after = case.pages_of_requests(reqs)
     kg, vg = hz.read_kv_rows(pages_after, m, sub, np.arange(sub.n_tokens))
@@ -41,15 +49,27 @@ def sample_check(cfg, case, out_bits, pages_before, reqs):
     return e_z, e_k, e_v
 
 
+def sample_requests(b, rng, n_random):
+    """The prefill request, n random decode requests, the longest and the shortest context
+    and the contexts nearest above the attention chunk edges (2048, 4096 keys)."""
+    dec_ids = np.arange(b.n_prefill_reqs, b.n_reqs)
+    ctx = b.ctx_len[dec_ids]
+    picks = [dec_ids[int(np.argmax(ctx))], dec_ids[int(np.argmin(ctx))]]
+    for edge in (2048, 4096):
+        above = np.where(ctx >= edge)[0]
+        if above.size:
+            picks.append(dec_ids[above[int(np.argmin(ctx[above]))]])
+    dec = rng.choice(dec_ids, size=n_random, replace=False)
+    return np.unique(np.concatenate([[0], dec, picks])).astype(np.int64)
+
+
 def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
     cfg, case = c2
     b, m = case.batch, cfg.model
     assert b.n_tokens == 2048 and b.n_decode_reqs == 1792
     rng = np.random.default_rng(11)
-    dec = np.sort(rng.choice(np.arange(b.n_prefill_reqs, b.n_reqs), size=20, replace=False))
-    longest = b.n_prefill_reqs + int(np.argmax(b.ctx_len[b.n_prefill_reqs:]))
-    reqs = np.unique(np.concatenate([[0], dec, [longest]]))
-    say("sampled requests", len(reqs), "longest ctx", int(b.ctx_len[longest]))
+    reqs = sample_requests(b, rng, 20)
+    say("sampled requests", len(reqs), "contexts", sorted(int(c) for c in b.ctx_len[reqs]))
     pages_before = case.pages_of_requests(reqs)
 
     say("unsplit run")
@@ -57,7 +77,7 @@ def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
     out1 = hz.bf16_bits(case.forward(plan1))
     torch.cuda.synchronize()
     say("oracle on the sample")
-    errs = sample_check(cfg, case, out1, pages_before, reqs)
+    errs = sample_check(cfg, case, out1, pages_before, reqs, plan1)
     say("C2 sampled rel err z/k/v", errs)
     assert np.all(np.isfinite(f64(out1)))
 
@@ -105,6 +125,46 @@ def test_c2_attention_rows_are_convex_combinations(c2):
         expect = 0.25 * (hq // G + 1)
         assert np.max(np.abs(got[:, hq, :] - expect)) <= 2e-2 * expect, hq
     pages[:, 1] = saved
+
+
+def test_c2_attention_ops_full_size_match_oracle_on_sampled_rows(c2):
+    """The attention path alone at the bench's size and launch configuration (all 2048 rows,
+    the unsplit plan the search returns, automatic grid): seeded random Q/K/V rows, needles
+    planted in the sampled requests' keys, compared per row with the oracle's attention
+    stage on the sampled requests - among them the longest context of the batch."""
+    cfg, case = c2
+    b, m = case.batch, cfg.model
+    rng = np.random.default_rng(21)
+    reqs = sample_requests(b, rng, 12)
+    sub, tok, phys = wl.subset_batch(b, reqs)
+    say("sampled contexts", sorted(int(c) for c in sub.ctx_len))
+    phys_t = torch.from_numpy(phys).to(case.device)
+    saved = case.pages.index_select(0, phys_t)
+    try:
+        for rnd in range(2):
+            qkv_bits = wl.f32_to_bf16_bits(rng.standard_normal((b.n_tokens, m.n_qkv)).astype(np.float32))
+            sub_pages = hz.bf16_bits(saved).copy()
+            sub_qkv = qkv_bits[tok].copy()
+            expect = ta.plant_needles(m, sub, sub_qkv, sub_pages, rnd)
+            qkv_bits[tok] = sub_qkv
+            case.pages.index_copy_(0, phys_t, hz.bf16_tensor(sub_pages, case.device))
+            plan = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
+            qkv = hz.bf16_tensor(qkv_bits, case.device)
+            attn = torch.empty((b.n_tokens, m.q_dim), dtype=torch.bfloat16, device=case.device)
+            ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=case.device)
+            nf.nf_op_rope_append(case.ctx, m, case.pages.data_ptr(), b.num_pages, case.args, plan, qkv.data_ptr(),
+                                 0, b.n_tokens)
+            nf.nf_op_attention(case.ctx, m, case.pages.data_ptr(), b.num_pages, case.args, plan, qkv.data_ptr(),
+                               attn.data_ptr(), ws.data_ptr(), ws.numel(), 0)
+            torch.cuda.synchronize()
+            tok_t = torch.from_numpy(tok).to(case.device)
+            got_pages = hz.bf16_bits(case.pages.index_select(0, phys_t))
+            fig = ta.compare_with_oracle(m, sub, sub_qkv, sub_pages, hz.bf16_bits(qkv[tok_t]), hz.bf16_bits(attn[tok_t]),
+                                         got_pages, expect)
+            say("C2 attention ops, round", rnd, "needles", len(expect), fig)
+            plan.close()
+    finally:
+        case.pages.index_copy_(0, phys_t, saved)
 
 
 @pytest.mark.timeout(600)
@@ -190,8 +250,7 @@ def test_other_configs_full_size_sampled_parity(name):
     case = hz.DeviceCase(cfg, n_weight_copies=1)
     b, m = case.batch, cfg.model
     rng = np.random.default_rng(13)
-    dec = np.sort(rng.choice(np.arange(b.n_prefill_reqs, b.n_reqs), size=8, replace=False))
-    reqs = np.unique(np.concatenate([[0], dec]))
+    reqs = sample_requests(b, rng, 6)
     pages_before = case.pages_of_requests(reqs)
     plan1 = nf.nf_plan_manual(case.ctx, m, case.args, [0, b.n_tokens])
     out1 = hz.bf16_bits(case.forward(plan1))
@@ -210,6 +269,9 @@ def test_other_configs_full_size_sampled_parity(name):
     z, k, v, parts = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok],
                                        expert_choice=choice, return_parts=True)
     e_z = rel_err(f64(out1[tok]), z)
+    parts["x"] = f64(case.x_bits[tok])
+    regions = regions_from_workspace(case._ws, plan1, m, b.n_tokens, rows=tok)
+    say(name, "intermediates", check_intermediates(m, regions, out1[tok], np.arange(len(tok)), z, parts))
     pages_after = case.pages_of_requests(reqs)
     kg, vg = hz.read_kv_rows(pages_after, m, sub, np.arange(sub.n_tokens))
     e_k, e_v = rel_err(f64(kg), k), rel_err(f64(vg), v)
