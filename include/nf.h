@@ -46,7 +46,9 @@ typedef enum nf_status {
   NF_EHIP = -5,       /* a HIP call failed; see nf_last_hip_error                 */
   NF_EPLAN = -6,      /* plan does not match the batch, or is malformed           */
   NF_ENOMEM = -7,     /* host allocation failed                                   */
-  NF_EIO = -8         /* profile cache file could not be read or written          */
+  NF_EIO = -8,        /* profile cache file could not be read or written          */
+  NF_ESCRATCH = -9    /* nf_op_attention_static: the plan needs more partial-result
+                         space than the library's built-in array holds             */
 } nf_status;
 
 /* Model shape of one decoder layer (Sec. 3.1 "Model configuration"). */
@@ -378,6 +380,26 @@ int nf_op_rope_append(nf_ctx *ctx, const nf_model_desc *model, nf_kv_cache *kv, 
 int nf_op_attention(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *kv,
                     const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
                     void *workspace, size_t workspace_bytes, int nano_index, void *hip_stream);
+
+/*
+ * nf_op_attention for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same result bits as nf_op_attention, but the partial results of
+ * rows whose keys span several 2048-key chunks live in an array built into the library
+ * (nf_attention_static_bytes() = 64 MiB per device, held from library load to process exit)
+ * instead of a caller workspace.  The call itself allocates and frees nothing (the plan was
+ * built beforehand).  A plan that needs more than the array holds -
+ *   plan partial slots * n_kv_heads * (16 * head_dim + 32) * 4 bytes; the LLaMA-3-8B layer at
+ *   dense batch 2048 with lognormal contexts up to 8192 needs 53 MiB -
+ * is rejected with NF_ESCRATCH before anything is launched.  Nothing in the array has to start
+ * at zero (every slot a merge reads was written by the attention kernel of the same call).
+ * All calls on one device share the array: two calls whose kernels may overlap in time on one
+ * GPU (different streams, or different threads) race and must be serialised by the caller.
+ */
+size_t nf_attention_static_bytes(void);
+int nf_op_attention_static(nf_ctx *ctx, const nf_model_desc *model, const nf_kv_cache *kv,
+                           const nf_batch *batch, const nf_plan *plan, const void *qkv, void *attn_out,
+                           int nano_index, void *hip_stream);
 
 /* ---- the ends of the iteration (Sec. 2.1: tokens enter through the embedding and leave through
  * the LM head and sampling; Sec. 2.2 counts them among the "other operations") ------------- */

@@ -17,7 +17,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnanoflow.so")
 
-NF_OK, NF_EINVAL, NF_ESHAPE, NF_EWORKSPACE, NF_EPAGES, NF_EHIP, NF_EPLAN, NF_ENOMEM, NF_EIO = 0, -1, -2, -3, -4, -5, -6, -7, -8
+NF_OK, NF_EINVAL, NF_ESHAPE, NF_EWORKSPACE, NF_EPAGES, NF_EHIP, NF_EPLAN, NF_ENOMEM, NF_EIO, NF_ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7, -8, -9
 NF_EPI_NONE, NF_EPI_RESIDUAL, NF_EPI_SWIGLU = 0, 1, 2
 
 EXPORTS = [
@@ -28,7 +28,8 @@ EXPORTS = [
     "nf_op_rmsnorm", "nf_op_gemm", "nf_gemm_segments", "nf_op_rope_append", "nf_op_attention", "nf_measure_peaks",
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
-    "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax",
+    "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
+    "nf_attention_static_bytes",
 ]
 
 
@@ -131,6 +132,9 @@ def lib() -> C.CDLL:
     L.nf_gemm_segments.restype = i32
     L.nf_op_rope_append.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, i32, i32, vp]
     L.nf_op_attention.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, vp, vp, sz, i32, vp]
+    L.nf_op_attention_static.argtypes = [vp, P(nf_model_desc), P(nf_kv_cache), P(nf_batch), vp, vp, vp, i32, vp]
+    L.nf_attention_static_bytes.argtypes = []
+    L.nf_attention_static_bytes.restype = sz
     _lib = L
     return L
 
@@ -410,6 +414,18 @@ def nf_op_attention(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Pl
     _check(lib().nf_op_attention(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle, qkv_ptr,
                                  attn_out_ptr, workspace_ptr, int(workspace_bytes), int(nano_index), stream),
            "nf_op_attention", ctx)
+
+
+def nf_attention_static_bytes() -> int:
+    return int(lib().nf_attention_static_bytes())
+
+
+def nf_op_attention_static(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Plan, qkv_ptr, attn_out_ptr,
+                           nano_index=0, stream=0):
+    md = model_desc(model)
+    kv = nf_kv_cache(pages_ptr, int(num_pages))
+    _check(lib().nf_op_attention_static(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle,
+                                        qkv_ptr, attn_out_ptr, int(nano_index), stream), "nf_op_attention_static", ctx)
 
 
 # ------------------------------------------------------------ continuous batching ---

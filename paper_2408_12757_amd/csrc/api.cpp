@@ -28,6 +28,12 @@ extern "C" int nf_ctx_create(int device, nf_ctx** out) try {
     return NF_EHIP;
   }
   c->num_cus = prop.multiProcessorCount;
+  // the device address of the static scratch array, looked up with this device current
+  e = nf_attention_static_scratch(device, &c->static_parts, &c->static_parts_bytes);
+  if (e != hipSuccess) {
+    delete c;
+    return NF_EHIP;
+  }
   *out = c;
   return NF_OK;
 } catch (const std::bad_alloc&) {
@@ -64,6 +70,7 @@ extern "C" const char* nf_strerror(int status) {
     case NF_EPLAN: return "plan does not match the batch or is malformed";
     case NF_ENOMEM: return "host allocation failed";
     case NF_EIO: return "profile cache i/o failed";
+    case NF_ESCRATCH: return "problem exceeds the built-in scratch of the allocation-free entry point";
     default: return "unknown status";
   }
 }
@@ -716,10 +723,14 @@ extern "C" int nf_op_rope_append(nf_ctx* ctx, const nf_model_desc* model, nf_kv_
   return NF_OK;
 }
 
-extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv, const nf_batch* batch,
-                               const nf_plan* plan, const void* qkv, void* attn_out, void* workspace,
-                               size_t workspace_bytes, int nano_index, void* hip_stream) {
-  if (!ctx || !kv || !batch || !plan || !qkv || !attn_out || !workspace) return NF_EINVAL;
+namespace {
+
+// Shared body of nf_op_attention and nf_op_attention_static: validation on the host mirrors,
+// then the attention kernel and the merge kernel with `parts` as the partial-result buffer.
+int op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv, const nf_batch* batch,
+                 const nf_plan* plan, const void* qkv, void* attn_out, float* parts, size_t parts_bytes,
+                 int too_small, int nano_index, hipStream_t s) {
+  if (!ctx || !kv || !batch || !plan || !qkv || !attn_out || !parts) return NF_EINVAL;
   int rc = nf_validate_model(model);
   if (rc) return rc;
   rc = nf_validate_batch(model, batch, kv->num_pages);
@@ -728,16 +739,35 @@ extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf
   if (nano_index < 0 || nano_index + 1 >= (int)plan->bounds.size()) return NF_EINVAL;
   const size_t need = nf_align256((size_t)std::max(1, plan->total_parts) * model->n_kv_heads *
                                   nf_attn_part_floats(model->head_dim) * sizeof(float));
-  if (workspace_bytes < need) return NF_EWORKSPACE;
+  if (parts_bytes < need) return too_small;
   const int32_t nqkv = (model->n_q_heads + 2 * model->n_kv_heads) * model->head_dim;
   const NfAttnShape shp{model->n_q_heads, model->n_kv_heads, model->head_dim, nqkv};
-  hipStream_t s = (hipStream_t)hip_stream;
   NF_HIP(ctx, nf_launch_attention(qkv, kv->pages, batch->page_indptr, batch->page_ids,
                                   plan->d_items + plan->item_off[nano_index], plan->item_cnt[nano_index], shp,
-                                  (float*)workspace, attn_out, plan->attn_wgs, s, plan->item_pages[nano_index]));
-  NF_HIP(ctx, nf_launch_attention_merge((const float*)workspace, plan->d_groups + plan->group_off[nano_index],
+                                  parts, attn_out, plan->attn_wgs, s, plan->item_pages[nano_index]));
+  NF_HIP(ctx, nf_launch_attention_merge(parts, plan->d_groups + plan->group_off[nano_index],
                                         plan->group_cnt[nano_index], shp, attn_out, s));
   return NF_OK;
+}
+
+}  // namespace
+
+extern "C" int nf_op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv, const nf_batch* batch,
+                               const nf_plan* plan, const void* qkv, void* attn_out, void* workspace,
+                               size_t workspace_bytes, int nano_index, void* hip_stream) {
+  return op_attention(ctx, model, kv, batch, plan, qkv, attn_out, (float*)workspace, workspace_bytes, NF_EWORKSPACE,
+                      nano_index, (hipStream_t)hip_stream);
+}
+
+extern "C" size_t nf_attention_static_bytes(void) { return NF_ATTN_STATIC_BYTES; }
+
+extern "C" int nf_op_attention_static(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv,
+                                      const nf_batch* batch, const nf_plan* plan, const void* qkv, void* attn_out,
+                                      int nano_index, void* hip_stream) {
+  if (!ctx) return NF_EINVAL;
+  // ctx->static_parts is the address hipGetSymbolAddress returned for ctx->device at nf_ctx_create
+  return op_attention(ctx, model, kv, batch, plan, qkv, attn_out, ctx->static_parts, ctx->static_parts_bytes,
+                      NF_ESCRATCH, nano_index, (hipStream_t)hip_stream);
 }
 
 extern "C" int nf_op_embedding(const int32_t* token_ids, const int32_t* from_slot, const int32_t* slot_tokens,

@@ -448,3 +448,32 @@ hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* grou
   }
   return hipGetLastError();
 }
+
+// ---- partial results in a static device array (for callers that cannot allocate) ----------
+//
+// nf_op_attention_static keeps the partial results of multi-chunk rows here instead of in a
+// caller-provided workspace.  Every device the library runs on holds its own copy of the array
+// (at its own address) until the process ends.  Host code never uses the array's name as an
+// address: nf_attention_static_scratch() asks the runtime for the device address once per
+// device, with that device current, and hands that pointer to the kernels.
+static __device__ __align__(256) unsigned char scratch[NF_ATTN_STATIC_BYTES];
+
+hipError_t nf_attention_static_scratch(int device, float** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static float* per_device[kMaxDevices] = {};
+  if (!ptr || !bytes || device < 0 || device >= kMaxDevices) return hipErrorInvalidValue;
+  if (!per_device[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device) return hipErrorInvalidDevice;   // the caller makes the device current first
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[device] = (float*)p;
+  }
+  *ptr = per_device[device];
+  *bytes = NF_ATTN_STATIC_BYTES;
+  return hipSuccess;
+}

@@ -48,6 +48,9 @@ struct nf_ctx {
   size_t offload_layer_stride = 0;
   hipStream_t offload_stream = nullptr;
   std::vector<hipEvent_t> offload_events;  // reused from call to call
+  // this device's copy of the static attention-partials array (nf_op_attention_static)
+  float* static_parts = nullptr;
+  size_t static_parts_bytes = 0;
 };
 
 struct nf_plan {

@@ -81,6 +81,11 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
                                hipStream_t s, long long item_pages = 0);
+// Size of the static device array that holds attention partials for nf_op_attention_static,
+// and the device address of that array on `device` (which must be the current device on the
+// first call for it; the address is looked up once per device and kept).
+constexpr size_t NF_ATTN_STATIC_BYTES = (size_t)64 << 20;
+hipError_t nf_attention_static_scratch(int device, float** ptr, size_t* bytes);
 hipError_t nf_launch_attention_merge(const float* parts, const NfAttnGroup* groups, int n_groups,
                                      const NfAttnShape& shp, void* attn_out, hipStream_t s);
 // Fills a bf16 buffer with pseudo-random, roughly normal values (timing buffers only).
