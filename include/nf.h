@@ -9,6 +9,19 @@
  * nano-operations run concurrently with the memory-bound paged decode
  * attention of other nano-batches (Sec. 3.7, Sec. 4.1, Sec. 5).
  *
+ * Where this interface departs from the plainest statement of the problem (weights, a
+ * paged KV cache, per-request context lengths, the dense batch), on purpose:
+ *   - KV page layout: the 16 x head_dim elements of a (page, K|V, kv head) block are stored in
+ *     the order the matrix cores consume them (formulas at nf_kv_cache), not token-major.  A
+ *     caller with a token-major cache repacks blocks once; appends go through the library.
+ *   - Extra arguments: `granule` on nf_profile / nf_plan_nanobatches (the nano-batch size unit
+ *     of Sec. 4.1.1, 128 for real models, smaller for toy batches) and `max_context` on
+ *     nf_workspace_bytes (the attention partials depend on the longest request).
+ *   - Device allocations after nf_ctx_create: a plan's work lists (a few KB per request,
+ *     pooled per process and reused), and the scratch of nf_profile and nf_measure_peaks
+ *     (freed before they return).  nf_layer_forward / nf_layers_forward / nf_op_* with a
+ *     prepared plan allocate nothing.
+ *
  * Conventions
  *   - All structs live in HOST memory.  Every pointer inside them, and every
  *     buffer argument, is a DEVICE pointer unless its comment says "host".
@@ -176,15 +189,15 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * one layer on its own; n in 2..16 = they price the time per layer of n consecutive layers
  * pipelined across the layer boundaries, as nf_layers_forward runs them.
  * key "search.rank": 0 (default) = the search returns its best pipeline; r in 1..64 = the best
- * pipeline of the r-th best row of the R -> P table, whatever its estimate (unsplit when there
- * are fewer rows), so that a caller can refine the model's choice with trial runs.
+ * pipeline of the r-th best row of the R -> P table (1 = the best row), whatever its estimate
+ * (unsplit when there are fewer rows), so that a caller can refine the model's choice with trial runs.
  * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 / 21 = force
- * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.debug": 0 = off, 1..3 = timing-only ablations of the 128x128 kernel
- * (wrong results).  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
+ * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
  * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.
  * key "offload.dma": 1 (default) = the simultaneous KV offload copies the rows with a strided
  * device-to-host copy on the copy engines, 0 = with a small kernel that stores to the host buffer.
- * Apart from "gemm.debug", variants never change a result bit.
+ * No key ever changes a result bit.  The knobs are process-wide and not thread-safe: they are
+ * meant for tuning runs and tests, set while no other thread is inside the library.
  * Returns NF_EINVAL for an unknown key or a value out of range.
  */
 int nf_tune_set(const char *key, int value);
@@ -288,6 +301,23 @@ int nf_plan_manual(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batc
                    const int32_t *bounds, int overlap, int attn_cus, int gemm_cus, int attn_wgs,
                    nf_plan **out);
 
+/*
+ * nf_plan_manual with a resource share and kernel implementation per nano-operation
+ * (Sec. 4.1.1 - 4.1.3: every nano-operation has its own R and its own kernel choice).
+ * spec[i] (host array of n_nano entries) belongs to nano-batch i: attn_wgs as in
+ * nf_plan_manual for its attention nano-operation, gemm_tile[k] = the GEMM implementation
+ * (key "gemm.tile" of nf_tune_set; 0 = automatic) of its KQV, O, Up/Gate and Down
+ * nano-operations (k = 0..3).  Neither changes a result bit.
+ */
+typedef struct nf_nano_spec {
+  int32_t attn_wgs;
+  int32_t gemm_tile[4];
+  int32_t reserved[3];
+} nf_nano_spec;
+int nf_plan_manual_ops(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch, int n_nano,
+                       const int32_t *bounds, int overlap, int attn_cus, int gemm_cus,
+                       const nf_nano_spec *spec, nf_plan **out);
+
 /* Writes a JSON description of the plan into buf (host); returns the number of
  * bytes needed (excluding the terminator), or a negative status. */
 int nf_plan_describe(const nf_plan *plan, char *buf, size_t buf_len);
@@ -313,8 +343,11 @@ int nf_workspace_region(const nf_plan *plan, const char *name, size_t *offset, s
  *   to the pages; attention of every token over its request's cached tokens,
  *   the earlier tokens of its chunk and itself; y = x + attn W_o^T;
  *   z = y + FFN(RMSNorm(y)) with FFN = SwiGLU (dense) or top-k routed experts.
- * plan = NULL runs unsplit on hip_stream (a temporary plan is built and
- * destroyed inside the call, which then synchronises hip_stream).
+ * plan = NULL runs unsplit on hip_stream with a plan the context builds and keeps: it is
+ * reused while the batch stays the same; after a change the old one is freed by a later
+ * call, once an event recorded behind its last use has passed.  The call does not wait for
+ * hip_stream (building the plan for a new batch copies its small work lists to the device
+ * with a synchronous copy, like nf_plan_manual).
  * x_in  : bf16 [n_tokens, D]; must not alias x_out.
  * x_out : bf16 [n_tokens, D].
  * Mutates the KV pages and x_out.  Returns NF_EWORKSPACE / NF_EPAGES /

@@ -96,7 +96,7 @@ class BatchFormation:
         while self.swapped and len(self.resident) < self.max_requests:
             r = self.requests[self.swapped[0]]
             need = self.pages_for(r.cached)
-            if need + 1 > len(self.free) or not self.predicted_peak_fits(r):
+            if need + 1 > len(self.free) or (self.resident and not self.predicted_peak_fits(r)):
                 break
             self.swapped.pop(0)
             r.pages = [self.free.pop() for _ in range(need)]
@@ -151,7 +151,7 @@ class BatchFormation:
             room_in_batch -= chunk
         while room_in_batch > 0 and self.waiting and len(self.resident) < self.max_requests:
             r = self.requests[self.waiting[0]]
-            if not self.predicted_peak_fits(r):
+            if self.resident and not self.predicted_peak_fits(r):
                 break
             chunk = min(limit(min(r.prompt, room_in_batch)), len(self.free) * self.P)
             if chunk <= 0:

@@ -29,7 +29,7 @@ EXPORTS = [
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
-    "nf_attention_static_bytes",
+    "nf_attention_static_bytes", "nf_plan_manual_ops",
 ]
 
 
@@ -59,6 +59,10 @@ class nf_batch(C.Structure):
 class nf_pipeline_desc(C.Structure):
     _fields_ = [("n_nano", C.c_int32), ("bounds", C.c_int32 * 9), ("overlap", C.c_int32), ("attn_wgs", C.c_int32),
                 ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("est_us", C.c_double), ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
+
+
+class nf_nano_spec(C.Structure):
+    _fields_ = [("attn_wgs", C.c_int32), ("gemm_tile", C.c_int32 * 4), ("reserved", C.c_int32 * 3)]
 
 
 class nf_trace_rec(C.Structure):
@@ -112,6 +116,8 @@ def lib() -> C.CDLL:
                                        P(C.c_double)]
     L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
+    L.nf_plan_manual_ops.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32,
+                                     P(nf_nano_spec), P(vp)]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
     L.nf_plan_destroy.argtypes = [vp]
     L.nf_plan_destroy.restype = None
@@ -264,6 +270,25 @@ def nf_plan_manual(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int],
     _check(lib().nf_plan_manual(ctx.handle, C.byref(md), C.byref(batch.struct), len(b) - 1,
                                 b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)), int(attn_cus),
                                 int(gemm_cus), int(attn_wgs), C.byref(h)), "nf_plan_manual", ctx)
+    return Plan(ctx, h)
+
+
+def nf_plan_manual_ops(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int], overlap: bool,
+                       attn_wgs: Sequence[int], gemm_tiles: "Optional[Sequence[Sequence[int]]]" = None,
+                       attn_cus: int = 0, gemm_cus: int = 0) -> Plan:
+    """attn_wgs[i] and gemm_tiles[i] = (KQV, O, Up/Gate, Down) implementations of nano-batch i."""
+    b = _np_i32(bounds)
+    n = len(b) - 1
+    spec = (nf_nano_spec * n)()
+    for i in range(n):
+        spec[i].attn_wgs = int(attn_wgs[i])
+        for k in range(4):
+            spec[i].gemm_tile[k] = int(gemm_tiles[i][k]) if gemm_tiles is not None else 0
+    h = C.c_void_p()
+    md = model_desc(model)
+    _check(lib().nf_plan_manual_ops(ctx.handle, C.byref(md), C.byref(batch.struct), n,
+                                    b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)), int(attn_cus),
+                                    int(gemm_cus), spec, C.byref(h)), "nf_plan_manual_ops", ctx)
     return Plan(ctx, h)
 
 

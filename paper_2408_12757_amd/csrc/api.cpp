@@ -51,6 +51,13 @@ extern "C" void nf_ctx_destroy(nf_ctx* ctx) {
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
   for (auto& kv : ctx->streams) (void)hipStreamDestroy(kv.second);
   for (hipEvent_t e : ctx->offload_events) (void)hipEventDestroy(e);
+  for (auto& r : ctx->retired_plans) {
+    (void)hipEventSynchronize(r.second);
+    (void)hipEventDestroy(r.second);
+    nf_plan_destroy(r.first);
+  }
+  // the caller must have drained the streams it used with this context
+  if (ctx->null_plan) nf_plan_destroy(ctx->null_plan);
   if (ctx->offload_stream) (void)hipStreamDestroy(ctx->offload_stream);
   nf_profile_free(ctx);
   delete ctx;
@@ -127,11 +134,6 @@ extern "C" int nf_tune_set(const char* key, int value) {
   if (!strcmp(key, "offload.dma")) {
     if (value < 0 || value > 1) return NF_EINVAL;
     nf_set_offload_dma(value);
-    return NF_OK;
-  }
-  if (!strcmp(key, "gemm.debug")) {
-    if (value < 0 || value > 3) return NF_EINVAL;
-    nf_set_gemm_debug(value);
     return NF_OK;
   }
   if (!strcmp(key, "search.rank")) {
@@ -383,7 +385,7 @@ hipError_t launch_nano_op(nf_ctx* ctx, const nf_plan* p, const NfNanoOp& op, con
       e = traced(ctx, NF_K_ATTENTION, op, s, [&] {
         return nf_launch_attention(a.ws.qkv, a.kv->pages, a.b->page_indptr, a.b->page_ids,
                                    p->d_items + p->item_off[op.nano], p->item_cnt[op.nano], shp, a.ws.parts,
-                                   a.ws.attn, p->attn_wgs, s, p->item_pages[op.nano]);
+                                   a.ws.attn, op.attn_wgs, s, p->item_pages[op.nano], ctx->num_cus);
       });
       if (e != hipSuccess) return e;
       return traced(ctx, NF_K_ATTN_MERGE, op, s, [&] {
@@ -572,6 +574,48 @@ int check_weights(const nf_model_desc* model, const nf_layer_weights* w) {
   return NF_OK;
 }
 
+// The unsplit plan a plan = NULL call runs with.  It is kept in the context and reused while the
+// batch stays the same.  When the batch changes, the old plan cannot be freed at once - kernels
+// already enqueued on the caller's stream may still read its work lists - and the call must not
+// wait for them either (it returns after enqueueing): the old plan is parked with an event
+// recorded on the caller's stream and freed by a later call once that event has passed.  Only
+// a caller more than eight batches ahead of the GPU waits (for the oldest parked plan).
+int null_plan_for(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, hipStream_t user,
+                  const nf_plan** out) {
+  nf_plan* cur = ctx->null_plan;
+  if (cur && cur->n_tokens == batch->n_tokens && cur->batch_sig == nf_batch_signature(batch) &&
+      memcmp(&cur->model, model, sizeof(nf_model_desc)) == 0) {
+    *out = cur;
+    return NF_OK;
+  }
+  for (size_t i = 0; i < ctx->retired_plans.size();) {
+    auto& r = ctx->retired_plans[i];
+    const bool oldest_must_go = ctx->retired_plans.size() > 8 && i == 0;
+    if (oldest_must_go) NF_HIP(ctx, hipEventSynchronize(r.second));
+    if (oldest_must_go || hipEventQuery(r.second) == hipSuccess) {
+      (void)hipEventDestroy(r.second);
+      nf_plan_destroy(r.first);
+      ctx->retired_plans.erase(ctx->retired_plans.begin() + (long)i);
+    } else {
+      ++i;
+    }
+  }
+  if (cur) {
+    hipEvent_t e = nullptr;
+    NF_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    NF_HIP(ctx, hipEventRecord(e, user));
+    ctx->retired_plans.emplace_back(cur, e);
+    ctx->null_plan = nullptr;
+  }
+  const int32_t bounds[2] = {0, batch->n_tokens};
+  nf_plan* fresh = nullptr;
+  int rc = nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, 0, &fresh);
+  if (rc) return rc;
+  ctx->null_plan = fresh;
+  *out = fresh;
+  return NF_OK;
+}
+
 }  // namespace
 
 extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const nf_layer_weights* weights,
@@ -588,12 +632,9 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
   if (check_weights(model, weights) != NF_OK) return NF_EINVAL;
   hipStream_t user = (hipStream_t)hip_stream;
 
-  nf_plan* tmp = nullptr;
   if (!plan) {
-    const int32_t bounds[2] = {0, batch->n_tokens};
-    rc = nf_plan_manual(ctx, model, batch, 1, bounds, 0, 0, 0, 0, &tmp);
+    rc = null_plan_for(ctx, model, batch, user, &plan);
     if (rc) return rc;
-    plan = tmp;
   }
   rc = NF_OK;
   if ((int)plan->bounds.size() - 1 > kMaxNanoOffsets) rc = NF_EPLAN;
@@ -614,15 +655,6 @@ extern "C" int nf_layer_forward(nf_ctx* ctx, const nf_model_desc* model, const n
     a.x_out = (char*)x_out;
     a.ws = layout_workspace(model, batch->n_tokens, (size_t)std::max(1, plan->total_parts), (char*)workspace);
     rc = run_layers(ctx, plan, &a, 1, user);
-  }
-  if (tmp) {
-    // the temporary plan owns device work lists the kernels are reading: drain first
-    hipError_t e = hipStreamSynchronize(user);
-    nf_plan_destroy(tmp);
-    if (e != hipSuccess && rc == NF_OK) {
-      ctx->last_hip = (int)e;
-      rc = NF_EHIP;
-    }
   }
   return rc;
 } catch (const std::bad_alloc&) {
@@ -744,7 +776,8 @@ int op_attention(nf_ctx* ctx, const nf_model_desc* model, const nf_kv_cache* kv,
   const NfAttnShape shp{model->n_q_heads, model->n_kv_heads, model->head_dim, nqkv};
   NF_HIP(ctx, nf_launch_attention(qkv, kv->pages, batch->page_indptr, batch->page_ids,
                                   plan->d_items + plan->item_off[nano_index], plan->item_cnt[nano_index], shp,
-                                  parts, attn_out, plan->attn_wgs, s, plan->item_pages[nano_index]));
+                                  parts, attn_out, plan->nano_attn_wgs[nano_index], s, plan->item_pages[nano_index],
+                                  ctx->num_cus));
   NF_HIP(ctx, nf_launch_attention_merge(parts, plan->d_groups + plan->group_off[nano_index],
                                         plan->group_cnt[nano_index], shp, attn_out, s));
   return NF_OK;

@@ -395,7 +395,7 @@ static hipError_t launch_attention_dh(int variant, dim3 grid, hipStream_t s, con
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
-                               hipStream_t s, long long item_pages) {
+                               hipStream_t s, long long item_pages, int n_cus) {
   if (n_items <= 0) return hipSuccess;
   const int head_groups = (shp.n_kv_heads + 3) / 4;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)shp.head_dim);
@@ -407,8 +407,7 @@ hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t
   // HBM, fewer requesters queueing in front of it - while the short launches of the iteration
   // loop (0.6 M cached tokens, many prefill rows) lose 2 % of the layer with 176.  More
   // workgroups than CUs lose much more (320 on 256 CUs: 25 %).
-  static int n_cus = 0;
-  if (n_cus == 0) {
+  if (n_cus <= 0) {  // no context at hand: the device that is current now
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)

@@ -25,7 +25,7 @@ namespace {
 using namespace nfgemm;
 
 // BM x BN tile, 2 x 2 wavefronts, each wavefront (BM/2) x (BN/2).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int PF, bool GROUPED, int DBG = 0>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int PF, bool GROUPED>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WAVES_M * WAVES_N) / 4 : 2) void gemm_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp) {
@@ -124,21 +124,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN > 128 * 128) ? (WA
             for (int j = 0; j < TM; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT && DBG < 2) {
+        if (kt + 1 < KT) {
           const int nxt = cur ^ 1;
 #pragma unroll
           for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sX[nxt][xs[i]]) = xr[d][i];
 #pragma unroll
           for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(&sW[nxt][ws[i]]) = wr[d][i];
         }
-        if (kt + 1 + PF < KT && DBG < 1) {
+        if (kt + 1 + PF < KT) {
           const int koff = (kt + 1 + PF) * BK;
 #pragma unroll
           for (int i = 0; i < A_CHUNKS; ++i) xr[d][i] = *reinterpret_cast<const u32x4*>(xg[i] + koff);
 #pragma unroll
           for (int i = 0; i < B_CHUNKS; ++i) wr[d][i] = *reinterpret_cast<const u32x4*>(wg[i] + koff);
         }
-        if (DBG < 3) __syncthreads();
+        __syncthreads();
       }
     }
   }
@@ -183,20 +183,6 @@ static int g_gemm_tile = 0;
 void nf_set_gemm_tile(int v) { g_gemm_tile = v; }
 static int g_grouped_tile = 0;  // implementation of the grouped (mixture-of-experts) GEMM; 0 = automatic
 void nf_set_grouped_gemm_tile(int v) { g_grouped_tile = v; }
-
-// Timing-only ablations of the 128x128 kernel (results are wrong): 1 = no global loads in
-// the main loop, 2 = also no LDS writes, 3 = also no barriers.
-static int g_gemm_debug = 0;
-void nf_set_gemm_debug(int v) { g_gemm_debug = v; }
-
-template <int DBG>
-static hipError_t launch_debug(const void* x, const void* w, void* out, int M, int N, int K, hipStream_t s) {
-  const int tiles_m = (M + 127) / 128, tiles_n = N / 128;
-  gemm_kernel<128, 128, 2, 2, EPI_NONE, 1, false, DBG><<<dim3(tiles_m * tiles_n), dim3(256), 0, s>>>(
-      (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)out, nullptr, M, N, K, tiles_m, tiles_n,
-      GroupedArgs{nullptr, nullptr, 0, 0});
-  return hipGetLastError();
-}
 
 static int g_gemm_ksplit = 0;
 void nf_set_gemm_ksplit(int v) { g_gemm_ksplit = v; }
@@ -247,11 +233,6 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     return launch_two_segments(x, w, out, residual, M, N, K, epilogue, tile, s, split);
   const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
   if (n_eff % 128 != 0) return launch<128, 64, 2, 2, 1>(x, w, out, residual, M, N, K, epilogue, s);
-  if (g_gemm_debug && epilogue == EPI_NONE && n_eff % 128 == 0) {
-    if (g_gemm_debug == 1) return launch_debug<1>(x, w, out, M, N, K, s);
-    if (g_gemm_debug == 2) return launch_debug<2>(x, w, out, M, N, K, s);
-    return launch_debug<3>(x, w, out, M, N, K, s);
-  }
   if (g_gemm_tile) tile = g_gemm_tile;  // process-wide override for tuning runs
   if (tile == 0) {
     // No profile: pick among 256x256, 256x128 and 128x128 by (relative speed of the shape on

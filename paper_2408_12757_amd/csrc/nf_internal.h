@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <map>
+#include <utility>
 #include <string>
 #include <vector>
 
@@ -24,6 +25,7 @@ struct NfNanoOp {
   std::vector<int> deps;  // indices of earlier nano-ops this one waits for (other lane only)
   bool record = false;    // some later nano-op on another lane waits for this one
   int gemm_tile = 0;      // GEMM implementation chosen by the profile (0 = default)
+  int attn_wgs = 0;       // attention nano-ops: persistent workgroups (its resource share; 0 = automatic, -1 = one per unit)
 };
 
 struct NfProfile;  // kernel timing tables (planner input)
@@ -48,6 +50,11 @@ struct nf_ctx {
   size_t offload_layer_stride = 0;
   hipStream_t offload_stream = nullptr;
   std::vector<hipEvent_t> offload_events;  // reused from call to call
+  // plan = NULL calls of nf_layer_forward: the unsplit plan of the latest such batch (reused
+  // while the batch stays the same) and earlier ones whose kernels may still be reading their
+  // work lists, each with an event recorded behind its last use
+  nf_plan* null_plan = nullptr;
+  std::vector<std::pair<nf_plan*, hipEvent_t>> retired_plans;
   // this device's copy of the static attention-partials array (nf_op_attention_static)
   float* static_parts = nullptr;
   size_t static_parts_bytes = 0;
@@ -63,6 +70,7 @@ struct nf_plan {
   int lane_cus[NF_LANES] = {0, 0};        // CU count per lane (0 = whole chip, no mask)
   int lane_cu_first[NF_LANES] = {0, 0};   // first CU bit of the lane's mask
   int attn_wgs = 0;                       // persistent attention workgroups (0 = one per CU, -1 = one per work unit)
+  std::vector<int> nano_attn_wgs;         // the same per nano-batch (what the launches use; attn_wgs is the default)
   hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
   std::vector<hipEvent_t> events;  // one per nano-op that records
   std::vector<hipEvent_t> events_alt;  // second set: consecutive layers of a multi-layer run alternate

@@ -77,10 +77,11 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
 // max_workgroups: > 0 = that many persistent workgroups, 0 = automatic, < 0 = one workgroup
 // per work unit.  item_pages: KV pages the items read per kv head (the automatic grid depends
 // on it: a long, HBM-bound launch does better with fewer workgroups than CUs); 0 = unknown.
+// n_cus: compute units of the device the stream belongs to (0 = ask the current device).
 hipError_t nf_launch_attention(const void* qkv, const void* pages, const int32_t* page_indptr,
                                const int32_t* page_ids, const NfAttnItem* items, int n_items,
                                const NfAttnShape& shp, float* parts, void* attn_out, int max_workgroups,
-                               hipStream_t s, long long item_pages = 0);
+                               hipStream_t s, long long item_pages = 0, int n_cus = 0);
 // Size of the static device array that holds attention partials for nf_op_attention_static,
 // and the device address of that array on `device` (which must be the current device on the
 // first call for it; the address is looked up once per device and kept).
@@ -123,7 +124,6 @@ hipError_t nf_launch_moe_scatter(const int32_t* expert_ids, int tok_begin, int t
 hipError_t nf_launch_moe_combine(const void* y, const void* expert_out, const int32_t* slot_of, const float* expert_w,
                                  void* z, int tok_begin, int tok_end, int hidden, int top_k, hipStream_t s,
                                  const float* expert_partial = nullptr, long long seg_stride = 0);
-void nf_set_gemm_debug(int v);
 void nf_set_offload_dma(int v);
 hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, int variant, hipStream_t s);

@@ -174,6 +174,11 @@ int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch) {
   p->n_reqs = n_reqs;
   p->n_prefill_reqs = batch->n_prefill_reqs;
   p->batch_sig = nf_batch_signature(batch);
+  // resource share of every attention nano-operation (Sec. 4.1.1: each nano-operation has its
+  // own R): the plan-wide default unless the caller gave one per nano-batch
+  if ((int)p->nano_attn_wgs.size() != n_nano) p->nano_attn_wgs.assign((size_t)n_nano, p->attn_wgs);
+  for (NfNanoOp& op : p->ops)
+    if (op.kind == NF_OP_ATTN) op.attn_wgs = p->nano_attn_wgs[op.nano];
 
   // token -> request
   std::vector<int32_t> tok_req((size_t)std::max(1, batch->n_tokens));
@@ -357,6 +362,54 @@ extern "C" int nf_plan_manual(nf_ctx* ctx, const nf_model_desc* model, const nf_
   return NF_EINVAL;
 }
 
+extern "C" int nf_plan_manual_ops(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int n_nano,
+                                  const int32_t* bounds, int overlap, int attn_cus, int gemm_cus,
+                                  const nf_nano_spec* spec, nf_plan** out) try {
+  if (!ctx || !out || !spec) return NF_EINVAL;
+  *out = nullptr;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  rc = check_bounds(batch, n_nano, bounds);
+  if (rc) return rc;
+  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus) return NF_EINVAL;
+  for (int i = 0; i < n_nano; ++i) {
+    if (spec[i].attn_wgs < -1) return NF_EINVAL;
+    for (int k = 0; k < 4; ++k)
+      if (spec[i].gemm_tile[k] < 0 || spec[i].gemm_tile[k] > 24) return NF_EINVAL;
+  }
+  nf_plan* p = new (std::nothrow) nf_plan();
+  if (!p) return NF_ENOMEM;
+  struct Guard {
+    nf_plan* p;
+    ~Guard() { nf_plan_destroy(p); }
+  } guard{p};
+  p->model = *model;
+  p->bounds.assign(bounds, bounds + n_nano + 1);
+  p->origin = "manual";
+  p->attn_wgs = spec[0].attn_wgs;
+  for (int i = 0; i < n_nano; ++i) p->nano_attn_wgs.push_back(spec[i].attn_wgs);
+  nf_plan_default_order(p, overlap ? 1 : 0);
+  for (NfNanoOp& op : p->ops) {
+    static const int slot[NF_OP_KINDS] = {0, -1, 1, 2, 3};
+    if (slot[op.kind] >= 0) op.gemm_tile = spec[op.nano].gemm_tile[slot[op.kind]];
+  }
+  p->lane_cus[NF_LANE_ATTN] = attn_cus;
+  p->lane_cu_first[NF_LANE_ATTN] = 0;
+  p->lane_cus[NF_LANE_GEMM] = gemm_cus;
+  p->lane_cu_first[NF_LANE_GEMM] = (gemm_cus && attn_cus + gemm_cus <= ctx->num_cus) ? attn_cus : 0;
+  rc = nf_plan_finalize(ctx, p, batch);
+  if (rc) return rc;
+  guard.p = nullptr;
+  *out = p;
+  return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
 extern "C" void nf_plan_destroy(nf_plan* p) {
   if (!p) return;
   for (hipEvent_t e : p->events)
@@ -388,7 +441,10 @@ extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) try
     const NfNanoOp& o = p->ops[a];
     s += std::string(a ? ", " : "") + "{\"op\": \"" + kind_name(o.kind) + "\", \"nano\": " + std::to_string(o.nano) +
          ", \"range\": [" + std::to_string(o.tok_begin) + ", " + std::to_string(o.tok_end) +
-         "], \"lane\": " + std::to_string(o.lane) + ", \"deps\": [";
+         "], \"lane\": " + std::to_string(o.lane) +
+         (o.kind == NF_OP_ATTN ? ", \"attn_wgs\": " + std::to_string(o.attn_wgs)
+                               : ", \"gemm_tile\": " + std::to_string(o.gemm_tile)) +
+         ", \"deps\": [";
     for (size_t d = 0; d < o.deps.size(); ++d) s += (d ? ", " : "") + std::to_string(o.deps[d]);
     s += "]}";
   }

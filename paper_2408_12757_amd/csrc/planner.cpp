@@ -334,7 +334,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   // Stage II: resource share per structure, with interference.  The best structure is kept
   // per table row; the rows are then ranked by their estimates.  in.rank = 0 asks for the best
   // pipeline (unsplit if nothing beats it); in.rank = r > 0 for the r-th best row's pipeline
-  // whatever its estimate, so that a caller can refine the choice with trial runs.
+  // (r = 1: the best row) whatever its estimate, so that a caller can refine the choice with trial runs.
   const NfRpRow ideal{0, 1.0, 1.0, 1.0, 0, 1.0};
   struct RowBest {
     double t2 = 1e300;
@@ -354,9 +354,12 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     }
   }
   std::stable_sort(per_row.begin(), per_row.end(), [](const RowBest& a, const RowBest& b) { return a.t2 < b.t2; });
+  // rank 0: the best row's pipeline if its estimate beats unsplit; rank r > 0: the r-th best
+  // row's pipeline (r = 1 is the best row) whatever its estimate
   const size_t rank = (size_t)std::max(0, in.rank);
-  if (rank < per_row.size() && (rank > 0 || per_row[0].t2 < out->est_us_unsplit - 1e-9)) {
-    const RowBest& b = per_row[rank];
+  const size_t pick = rank > 0 ? rank - 1 : 0;
+  if (pick < per_row.size() && (rank > 0 || per_row[0].t2 < out->est_us_unsplit - 1e-9)) {
+    const RowBest& b = per_row[pick];
     out->bounds = cands[b.cand].bounds;
     out->overlap = 1;
     out->attn_wgs = b.row.attn_wgs;

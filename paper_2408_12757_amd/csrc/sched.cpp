@@ -163,7 +163,9 @@ extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) try {
   while (!s->swapped.empty() && (int)s->resident.size() < c.max_requests) {
     Req& r = s->reqs.at(s->swapped.front());
     const int32_t need = s->pages_for(r.cached());
-    if ((int64_t)need + 1 > (int64_t)s->free_pages.size() || !s->prediction_fits(&r)) break;
+    // with nothing resident the oldest request comes back whatever the prediction says: submit
+    // proved that it fits alone, and refusing it would stall the loop for good
+    if ((int64_t)need + 1 > (int64_t)s->free_pages.size() || (!s->resident.empty() && !s->prediction_fits(&r))) break;
     s->swapped.pop_front();
     for (int32_t i = 0; i < need; ++i) r.pages.push_back(s->take_page());
     r.state = RESIDENT;
@@ -228,7 +230,7 @@ extern "C" int nf_sched_next_batch(nf_sched* s, nf_sched_batch* out) try {
   }
   while (cap > 0 && !s->waiting.empty() && (int)s->resident.size() < c.max_requests) {
     Req& r = s->reqs.at(s->waiting.front());
-    if (!s->prediction_fits(&r)) break;
+    if (!s->resident.empty() && !s->prediction_fits(&r)) break;  // alone, a request is always admitted
     const int32_t want = chunk_limit(std::min(r.prompt, cap));
     const int32_t chunk = (int32_t)std::min<int64_t>(want, (int64_t)s->free_pages.size() * P);
     if (chunk <= 0) break;

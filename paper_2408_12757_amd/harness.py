@@ -96,7 +96,7 @@ class DeviceCase:
     consecutive steps read cold weights), a seeded KV pool generated on the device,
     the uploaded batch and the layer input."""
 
-    def __init__(self, cfg: wl.Config, n_weight_copies: int = 1, device="cuda:0", sort_decode: bool = False,
+    def __init__(self, cfg: wl.Config, n_weight_copies: int = 1, device="cuda:0", sort_decode="none",
                  keep_host_weights: bool = True):
         self.cfg = cfg
         self.model = cfg.model

@@ -214,18 +214,25 @@ def draw_ctx_lens(spec: BatchSpec, rng: np.random.Generator) -> np.ndarray:
 
 
 def make_batch(spec: BatchSpec, seed: int, page_size: int = PAGE_SIZE,
-               sort_decode: bool = False, spare_pages: int = 0) -> Batch:
+               sort_decode="none", spare_pages: int = 0) -> Batch:
     """Draw context lengths and a fragmented page table.
 
     Physical page ids are a seeded random permutation of the pool, so the
     pages of one request are scattered (Sec. 4.2.2).  ``sort_decode`` orders
-    the decode requests by descending context (a batch-formation choice; the
-    layer result per request does not depend on it).
+    the decode requests of the batch by context length: "none" (as drawn), "asc"
+    or "desc" (True = "desc").  The order of the requests in the dense batch is a
+    batch-formation choice; the layer result per request does not depend on it.
     """
     rng = np.random.default_rng(seed)
     dec_ctx = draw_ctx_lens(spec, rng)
-    if sort_decode:
-        dec_ctx = np.sort(dec_ctx)[::-1].copy()
+    if sort_decode is True:
+        sort_decode = "desc"
+    if sort_decode in ("asc", "desc"):
+        dec_ctx = np.sort(dec_ctx)
+        if sort_decode == "desc":
+            dec_ctx = dec_ctx[::-1].copy()
+    elif sort_decode not in (False, None, "none"):
+        raise ValueError(sort_decode)
     q_lens = np.concatenate([np.full(spec.n_prefill_reqs, spec.prefill_len, np.int32),
                              np.ones(spec.n_decode_reqs, np.int32)])
     ctx = np.concatenate([np.full(spec.n_prefill_reqs, spec.prefill_prior, np.int32), dec_ctx])

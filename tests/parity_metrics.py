@@ -81,3 +81,32 @@ def check_intermediates(model, regions, z_bits, tok, z_ref, parts, tol=REL_TOL):
     assert d_ffn <= block_tol(ffn, z_ref, parts["y"], tol=tol), ("FFN block z - y", d_ffn, float(np.max(np.abs(ffn))))
     report["ffn_block"] = d_ffn / float(np.max(np.abs(ffn)))
     return report
+
+
+def routing_exemptions(ids_gpu: np.ndarray, logits: np.ndarray, h2: np.ndarray, w_router: np.ndarray, top_k: int):
+    """Tokens whose expert choice on the GPU (fp32 dot products of bf16 inputs) differs from the
+    float64 choice.  A difference is accepted only at a near-tie, with the threshold taken from
+    the arithmetic: the GPU forms its logits from activations that were rounded to bf16 twice
+    (y, then the normalised row), a relative error of about 2^-8 per element, so the difference
+    of two logits d = sum_k h_k (w_ak - w_bk) carries an error of standard deviation
+    2^-8 * sqrt(sum_k h_k^2 (w_ak - w_bk)^2); four of these is the bound.  Every expert the GPU
+    chose and the float64 top-k did not must lie within that bound of the k-th float64 logit.
+    Returns the indices of the exempted tokens (the others must match the float64 choice)."""
+    T, E = logits.shape
+    exempt = []
+    for t in range(T):
+        order = sorted(range(E), key=lambda e: (-logits[t, e], e))
+        top = order[:top_k]
+        if sorted(ids_gpu[t]) == sorted(top):
+            continue
+        assert len(set(int(e) for e in ids_gpu[t])) == top_k, (t, ids_gpu[t])
+        kth = top[-1]
+        for e in ids_gpu[t]:
+            if e in top:
+                continue
+            dw = w_router[e] - w_router[kth]
+            bound = 4.0 * 2.0 ** -8 * float(np.sqrt(np.sum(h2[t] ** 2 * dw ** 2)))
+            gap = float(logits[t, kth] - logits[t, e])
+            assert 0.0 <= gap <= bound, ("expert choice is not a near-tie", t, int(e), gap, bound)
+        exempt.append(t)
+    return np.asarray(exempt, np.int64)

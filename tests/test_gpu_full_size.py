@@ -12,7 +12,7 @@ from paper_2408_12757_amd import harness as hz
 from paper_2408_12757_amd import workloads as wl
 
 from gpu_util import REL_TOL, f64, regions_from_workspace, rel_err
-from parity_metrics import check_intermediates
+from parity_metrics import check_intermediates, routing_exemptions
 import test_gpu_attention as ta
 
 pytestmark = pytest.mark.gpu
@@ -266,30 +266,33 @@ def test_other_configs_full_size_sampled_parity(name):
         say("expert load", counts.tolist())
         assert counts.sum() == b.n_tokens * m.top_k and np.all(counts > 0)
     say(name, "oracle on", len(reqs), "requests /", sub.n_tokens, "tokens")
-    z, k, v, parts = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok],
-                                       expert_choice=choice, return_parts=True)
-    e_z = rel_err(f64(out1[tok]), z)
+    # the oracle under its OWN expert choice; tokens whose GPU choice differs must be near-ties
+    # by the bound of parity_metrics.routing_exemptions and are compared under the GPU's choice
+    z, k, v, parts = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok], return_parts=True)
+    rows = np.arange(sub.n_tokens)
+    exempt = np.zeros(0, np.int64)
+    if m.is_moe:
+        exempt = routing_exemptions(choice, parts["route"][2], parts["h2"], f64(case.host_weights[0]["w_router"]),
+                                    m.top_k)
+        say("routing: tokens exempted as near-ties", len(exempt), "of", sub.n_tokens)
+        assert len(exempt) <= max(2, sub.n_tokens // 20)
+        rows = np.setdiff1d(rows, exempt)
+    scale = np.max(np.abs(z))
+    e_z = float(np.max(np.abs(f64(out1[tok])[rows] - z[rows])) / scale)
+    if len(exempt):
+        z2, _, _ = orc.layer_forward(m, case.host_weights[0], pages_before, sub, case.x_bits[tok], expert_choice=choice)
+        e_z = max(e_z, float(np.max(np.abs(f64(out1[tok])[exempt] - z2[exempt])) / scale))
     parts["x"] = f64(case.x_bits[tok])
-    regions = regions_from_workspace(case._ws, plan1, m, b.n_tokens, rows=tok)
-    say(name, "intermediates", check_intermediates(m, regions, out1[tok], np.arange(len(tok)), z, parts))
+    regions = regions_from_workspace(case._ws, plan1, m, b.n_tokens, rows=tok[rows])
+    z_keep = z[rows]
+    parts_keep = {key: (val[rows] if isinstance(val, np.ndarray) and val.shape[:1] == (sub.n_tokens,) else val)
+                  for key, val in parts.items()}
+    say(name, "intermediates", check_intermediates(m, regions, out1[tok[rows]], np.arange(len(rows)), z_keep, parts_keep))
     pages_after = case.pages_of_requests(reqs)
     kg, vg = hz.read_kv_rows(pages_after, m, sub, np.arange(sub.n_tokens))
     e_k, e_v = rel_err(f64(kg), k), rel_err(f64(vg), v)
     say(name, "sampled rel err z/k/v", (e_z, e_k, e_v))
     assert e_z <= REL_TOL and e_k <= REL_TOL and e_v <= REL_TOL
-    if m.is_moe:
-        # the GPU's fp32 routing choice against the oracle's float64 logits
-        free = orc.route_topk(parts["route"][2], m.top_k)[0]
-        logits = parts["route"][2]
-        scale = np.max(np.abs(logits))
-        n_diff = 0
-        for t in range(sub.n_tokens):
-            if list(choice[t]) != list(free[t]):
-                n_diff += 1
-                kth = np.sort(logits[t])[::-1][m.top_k - 1]
-                assert all(logits[t, e] >= kth - 2e-2 * scale for e in choice[t])
-        say("routing decisions differing from float64 argmax (near-ties):", n_diff, "of", sub.n_tokens)
-        assert n_diff <= max(2, sub.n_tokens // 20)
     plan2 = nf.nf_plan_manual(case.ctx, m, case.args, [0, 768, b.n_tokens], True, 0, 0, 256)
     out2 = hz.bf16_bits(case.forward(plan2))
     torch.cuda.synchronize()

@@ -13,6 +13,7 @@ from paper_2408_12757_amd import workloads as wl
 
 from cases import EDGE_CASES, edge_case_batch, small_gqa_model
 from gpu_util import DEV, REL_TOL, Case, ChainCase, f64, rel_err, untouched_pages_equal
+from parity_metrics import routing_exemptions
 
 pytestmark = pytest.mark.gpu
 
@@ -392,30 +393,33 @@ def read_routing(case, plan, B, k):
 
 
 def check_moe_case(case, plan):
+    """The routing decision is taken in the kernel's precision (fp32).  Tokens on which it agrees
+    with the oracle's own float64 decision - all but the near-ties, whose bound comes from the
+    arithmetic (parity_metrics.routing_exemptions) - are compared with the oracle under ITS OWN
+    choice; the exempted tokens with the oracle under the GPU's choice."""
     m, b = case.model, case.batch
     z_bits, pages = case.run(plan)
     ids, wts = read_routing(case, plan, b.n_tokens, m.top_k)
-    # The argmax decision is taken in the kernel's precision (fp32): the oracle is given the
-    # GPU's choice, and the choice itself is checked against the oracle's float64 logits.
-    z, k, v, parts = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, expert_choice=ids,
-                                       return_parts=True)
+    z_own, k, v, parts = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, return_parts=True)
     idx64, w64, logits = parts["route"]
-    _, _, _, parts_free = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, return_parts=True)
-    top64 = parts_free["route"][0]
-    scale = np.max(np.abs(logits))
-    n_diff = 0
-    for t in range(b.n_tokens):
-        if list(ids[t]) != list(top64[t]):
-            n_diff += 1
-            # a different choice is valid only at a near-tie of the float64 logits
-            lg = logits[t]
-            kth = np.sort(lg)[::-1][m.top_k - 1]
-            assert all(lg[e] >= kth - 2e-2 * scale for e in ids[t]), (t, ids[t], top64[t])
-        assert len(set(ids[t])) == m.top_k
-    assert n_diff <= max(2, b.n_tokens // 20), n_diff
-    assert rel_err(wts, w64) <= 2e-2
-    e = rel_err(f64(z_bits), z)
-    assert np.all(np.isfinite(f64(z_bits))) and e <= REL_TOL, e
+    exempt = routing_exemptions(ids, logits, parts["h2"], f64(case.weights["w_router"]), m.top_k)
+    say("routing: tokens exempted as near-ties", len(exempt), "of", b.n_tokens)
+    assert len(exempt) <= max(2, b.n_tokens // 20), len(exempt)
+    keep = np.setdiff1d(np.arange(b.n_tokens), exempt)
+    got = f64(z_bits)
+    assert np.all(np.isfinite(got))
+    scale = np.max(np.abs(z_own))
+    e = float(np.max(np.abs(got[keep] - z_own[keep])) / scale)
+    assert e <= REL_TOL, e
+    # the order of the k experts may differ between the two sides: compare weights per expert
+    for t in keep:
+        for j in range(m.top_k):
+            jj = list(idx64[t]).index(ids[t, j])
+            assert abs(wts[t, j] - w64[t, jj]) <= 2e-2, (t, wts[t], w64[t])
+    if len(exempt):
+        z_gpu_choice, _, _ = orc.layer_forward(m, case.weights, case.pages_bits, b, case.x_bits, expert_choice=ids)
+        e2 = float(np.max(np.abs(got[exempt] - z_gpu_choice[exempt])) / scale)
+        assert e2 <= REL_TOL, e2
     return z_bits, pages, e
 
 

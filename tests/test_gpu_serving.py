@@ -145,7 +145,7 @@ def test_tokens_flow_through_embedding_layers_lm_head_and_sampling(ctx):
     """Token path: embedding -> layers -> final norm -> LM head -> greedy sampling, the sampled
     token feeding the request's next iteration on the device.  The sampling decision is taken
     in the kernel's precision: the oracle is handed the GPU's tokens as the next inputs, and
-    every choice must be the float64 argmax or within the tolerance of it (a near-tie)."""
+    every choice must be the float64 argmax or a near-tie within a bound taken from the arithmetic."""
     m = wl.CONFIGS["C1"].model
     n_layers, B, num_pages, vocab, lag, seed = 2, 64, 300, 512, 1, 91
     weights = [wl.make_weights(m, seed + 10 * l) for l in range(n_layers)]
@@ -163,6 +163,7 @@ def test_tokens_flow_through_embedding_layers_lm_head_and_sampling(ctx):
     last_token = {}     # request -> token the GPU sampled for it last
     exact = total = 0
     worst_z = worst_gap = 0.0
+    near_ties = 0
     it = 0
     while True:
         fb, z = eng.step()
@@ -193,11 +194,22 @@ def test_tokens_flow_through_embedding_layers_lm_head_and_sampling(ctx):
             if rows:
                 logits = otp.lm_head_logits(zo[rows], tw["g_final"], tw["w_lm"], m.rms_eps)
                 best = otp.greedy(logits)
-                scale = np.max(np.abs(logits))
+                hn = orc.rmsnorm(zo[rows], f64(tw["g_final"]), m.rms_eps)
+                w_lm = f64(tw["w_lm"])
                 for r, rid in enumerate(owners):
                     tok = int(slot_tokens[tp.slot_of[rid]]) if rid in tp.slot_of else None
                     assert tok is not None and 0 <= tok < vocab
-                    gap = float(logits[r, best[r]] - logits[r, tok]) / scale
+                    gap = float(logits[r, best[r]] - logits[r, tok])
+                    if tok != best[r]:
+                        # A deviation is accepted only at a near-tie, bounded from the arithmetic: the
+                        # kernel compares bf16 logits (half an ulp, 2^-8 relative, on each of the two)
+                        # formed from rows that were rounded to bf16 twice (the layer output, then the
+                        # normalised row: four standard deviations of 2^-8 per element on the difference).
+                        dw = w_lm[best[r]] - w_lm[tok]
+                        bound = 2.0 ** -8 * (abs(logits[r, best[r]]) + abs(logits[r, tok])) + 4.0 * 2.0 ** -8 * float(
+                            np.sqrt(np.sum(hn[r] ** 2 * dw ** 2)))
+                        assert 0.0 <= gap <= bound, ("sampled token is not a near-tie", it, rid, gap, bound)
+                        near_ties += 1
                     worst_gap = max(worst_gap, gap)
                     exact += int(tok == best[r])
                     total += 1
@@ -208,8 +220,8 @@ def test_tokens_flow_through_embedding_layers_lm_head_and_sampling(ctx):
             break
         assert it < 1000
     eng.drain()
-    print("iterations", it, "sampled", total, "equal to the float64 argmax", exact, "worst gap", worst_gap,
-          "worst z err", worst_z, flush=True)
-    assert worst_z <= REL_TOL and worst_gap <= REL_TOL
+    print("iterations", it, "sampled", total, "equal to the float64 argmax", exact, "exempted as near-ties", near_ties,
+          "worst logit gap", worst_gap, "worst z err", worst_z, flush=True)
+    assert worst_z <= REL_TOL
     assert total == sum(o for _, o in reqs) + st["wasted_decode_tokens"] and exact >= 0.9 * total
     eng.close()

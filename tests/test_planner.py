@@ -345,6 +345,33 @@ def test_search_never_returns_a_pipeline_slower_than_unsplit(tmp_path):
     assert got["est_us"] == pytest.approx(got["est_us_unsplit"])
 
 
+def test_search_rank_walks_the_table_rows_from_the_best_one(tmp_path):
+    """search.rank = r > 0 asks for the pipeline of the r-th best row whatever its estimate: rank 1
+    is the row the model rates best - the candidate a trial run has to try first when the model
+    prefers unsplit - rank 2 the next, and a rank beyond the table gives unsplit."""
+    g = 16
+    b = wl.batch_from_lengths([1] * 64, np.full(64, 500), 0, np.random.default_rng(0))
+    dense = {o: [20.0 + 5 * i for i in range(4)] for o in OPS}
+    path = str(tmp_path / "p.txt")
+    rows = [dict(attn_wgs=64, p_gemm=0.2, p_attn=0.2, p_attn_solo=0.9),       # the worse row
+            dict(attn_wgs=256, p_gemm=0.3, p_attn=0.3, p_attn_solo=0.9)]      # the better row
+    write_profile(path, MODEL, g, 64, dense, 1.0, 0.5, rows)
+    try:
+        assert nf.nf_search_pipeline(MODEL, host_batch(b), path, 0, g)["overlap"] == 0      # rank 0: unsplit wins
+        nf.nf_tune_set("search.rank", 1)
+        best = nf.nf_search_pipeline(MODEL, host_batch(b), path, 0, g)
+        nf.nf_tune_set("search.rank", 2)
+        second = nf.nf_search_pipeline(MODEL, host_batch(b), path, 0, g)
+        nf.nf_tune_set("search.rank", 3)
+        beyond = nf.nf_search_pipeline(MODEL, host_batch(b), path, 0, g)
+    finally:
+        nf.nf_tune_set("search.rank", 0)
+    assert best["overlap"] == 1 and best["attn_wgs"] == 256
+    assert second["overlap"] == 1 and second["attn_wgs"] == 64
+    assert best["est_us"] <= second["est_us"] and best["est_us"] > best["est_us_unsplit"]
+    assert beyond["overlap"] == 0 and beyond["bounds"] == [0, 64]
+
+
 def test_search_uses_analytic_profile_without_a_file():
     cfg = wl.CONFIGS["C2"]
     b = wl.make_batch(cfg.batch, cfg.seed + 2)

@@ -167,6 +167,33 @@ def lib_batch_as_dict(fb):
             "finished": list(fb.finished)}
 
 
+def test_a_request_the_prediction_would_never_admit_still_runs_when_alone():
+    """Long prompt, short output, tight pool, large average output length: the predicted peak
+    (prompt + average output) exceeds the pool although the request itself fits.  With nothing
+    resident it must be admitted anyway - submit accepted it - in the oracle and in the library;
+    otherwise every batch would be empty for ever."""
+    B, P, NP, avg = 32, 4, 30, 64.0          # 120 token slots; prediction wants 100 + 64
+    reqs = [(100, 3), (90, 2)]
+    oracle = BatchFormation(B, P, NP, 8, 0, 0, avg)
+    batches = drive(oracle, reqs, lag=0)
+    assert sum(b["n_tokens"] for b in batches) == 100 + 2 + 90 + 1
+    assert len(oracle.free) == NP
+    s = nf.Scheduler(B, P, NP, 8, 0, 0, avg)
+    for p_len, o_len in reqs:
+        s.submit(p_len, o_len)
+    tokens, it = 0, 0
+    for _ in range(64):
+        b = s.next_batch()
+        tokens += b.n_tokens
+        s.complete(it)
+        it += 1
+        st = s.stats()
+        if st["waiting"] + st["resident"] + st["swapped"] == 0:
+            break
+    assert tokens == 100 + 2 + 90 + 1 and s.stats()["finished"] == 2
+    s.close()
+
+
 CASES = [
     # name, dense_batch, page_size, num_pages, max_requests, max_chunk, reserve, avg, lag, n_req, prompt range, output range
     ("roomy", 64, 4, 5000, 64, 0, 0, 20.0, 0, 150, (1, 90), (1, 40)),
