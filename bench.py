@@ -59,6 +59,11 @@ def parse_args():
                     help="also time this many consecutive layers (distinct weights and KV pools) in one "
                          "nf_layers_forward call and report the time per layer; 0 = skip")
     ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA / HBM ceiling measurement")
+    ap.add_argument("--other-steps", type=int, default=5,
+                    help="with the headline configuration: also time this many steps of C3 and C4 and a short window "
+                         "of the C5 loop and report them under other_configs (0 = skip)")
+    ap.add_argument("--other-loop-iterations", type=int, default=400,
+                    help="iterations of the short C5 window under other_configs")
     return ap.parse_args()
 
 
@@ -190,7 +195,7 @@ def run_rp_sensitivity(args):
                               "size combinations (A100)"}))
 
 
-def run_loop(args):
+def run_loop(args, emit=True):
     """Configuration C5: LLaMA-3-8B layers in sequence, continuous batching at a dense batch of
     2048 tokens over a synthetic request stream; steady-state tokens/s."""
     import numpy as np
@@ -272,8 +277,45 @@ def run_loop(args):
         out_json["iteration_roofline"] = {"t_ms_per_layer": t_roof * 1e3, "frac": t_roof * 1e3 / (it_ms / L),
                                           "note": "weights + K/V of the mean cached-token count per layer; "
                                                   "activations left out"}
-    print(json.dumps(out_json))
     eng.close()
+    if emit:
+        print(json.dumps(out_json))
+    return out_json
+
+
+def run_other_layer_config(name: str, steps: int, weight_copies: int):
+    """One of the other single-layer configurations, briefly: kernel profile, pipeline search with
+    the trial run that keeps a split pipeline only if it beats unsplit, then `steps` timed steps."""
+    import torch
+
+    from paper_2408_12757_amd import binding as nf
+    from paper_2408_12757_amd import costmodel as cm
+    from paper_2408_12757_amd import harness as hz
+    from paper_2408_12757_amd import workloads as wl
+
+    cfg = wl.CONFIGS[name]
+    case = hz.DeviceCase(cfg, n_weight_copies=weight_copies, keep_host_weights=False)
+    b, m = case.batch, cfg.model
+    roof = cm.iteration_roofline(cm.layer_costs(m, b))
+    if not m.is_moe:      # the kernel profile covers dense layers: it picks the GEMM implementations
+        nf.nf_profile(case.ctx, m, b.n_tokens, cfg.granule, None)
+    unsplit = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
+    plan, t = unsplit, hz.time_plan(case, unsplit, 4, steps)
+    if not m.is_moe:
+        cand = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
+        if len(cand.describe()["bounds"]) > 2:
+            t_c = hz.time_plan(case, cand, 4, steps)
+            if t_c < t:
+                plan, t = cand, t_c
+    d = plan.describe()
+    out = {"ms_per_step": t, "tokens_per_s": b.n_tokens / (t * 1e-3), "steps": steps,
+           "iteration_frac": roof["t_roofline"] * 1e3 / t, "iteration_roofline_ms": roof["t_roofline"] * 1e3,
+           "bound": roof["bound"], "plan": {k: d[k] for k in ("bounds", "overlap", "attn_wgs")},
+           "workload": cfg.description}
+    case.ctx.close()
+    del case
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -332,19 +374,42 @@ def main():
     seq_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, False, 0, 0, 0)
     ovl_plan = nf.nf_plan_manual(case.ctx, m, case.args, abl_bounds, True, 0, 0, args.ablation_attn_wgs)
 
-    # A searched pipeline that splits the batch is kept only if a short trial run on this batch
-    # confirms the model (Sec. 4.1.3 refines the pipeline with measured interference); else the
-    # unsplit pipeline is timed.
-    verify = None
-    if len(best_desc["bounds"]) > 2:
-        t_s = hz.time_plan(case, best_plan, 3, 8)
-        t_u = hz.time_plan(case, unsplit_plan, 3, 8)
-        verify = {"searched_ms": t_s, "unsplit_ms": t_u}
-        if t_u < t_s:
-            best_plan = unsplit_plan
-            d = unsplit_plan.describe()
-            best_c = {k: d[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
-            best_c["origin"] += "; searched pipeline rejected by the trial run"
+    # The model's choice and the pipelines of its best R -> P rows are refined by short trial runs
+    # on this batch (Sec. 4.1.3 refines the pipeline with measured interference): a pipeline that
+    # splits the batch is kept only if it beats the unsplit one on the device.
+    t_u = hz.time_plan(case, unsplit_plan, 3, 8)
+    verify = {"unsplit_ms": t_u, "trials": []}
+    kept_ms = t_u
+    kept_plan = unsplit_plan
+    for rank in range(0, 6):
+        nf.nf_tune_set("search.rank", rank)
+        try:
+            pl = best_plan if rank == 0 else nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
+        finally:
+            nf.nf_tune_set("search.rank", 0)
+        d = pl.describe()
+        rec = {k: d[k] for k in ("bounds", "overlap", "attn_wgs", "est_time_us")}
+        if len(d["bounds"]) <= 2 or any(t["bounds"] == rec["bounds"] and t["attn_wgs"] == rec["attn_wgs"]
+                                        for t in verify["trials"]):
+            if pl is not best_plan:
+                pl.close()
+            continue
+        rec["ms"] = hz.time_plan(case, pl, 3, 8)
+        verify["trials"].append(rec)
+        if rec["ms"] < kept_ms:
+            if kept_plan not in (unsplit_plan, best_plan):
+                kept_plan.close()
+            kept_ms, kept_plan = rec["ms"], pl
+        elif pl is not best_plan:
+            pl.close()
+    if kept_plan is not best_plan:
+        d = kept_plan.describe()
+        best_c = {k: d[k] for k in ("origin", "bounds", "overlap", "attn_wgs", "est_time_us")}
+        if kept_plan is unsplit_plan and verify["trials"]:
+            best_c["origin"] += "; every split pipeline lost its trial run"
+        if len(best_desc["bounds"]) > 2 or kept_plan is not unsplit_plan:
+            best_plan_searched = best_plan
+        best_plan = kept_plan
 
     step_marks = []
 
@@ -452,7 +517,7 @@ def main():
         # the auto-search with the time per layer of L consecutive layers as its objective; the
         # model's ranking of the R -> P rows is then refined by trial runs of its best candidates
         trials, best_chain = [], None
-        for rank in range(6):
+        for rank in range(7):
             nf.nf_tune_set("search.layers", L)
             nf.nf_tune_set("search.rank", rank)
             try:
@@ -542,6 +607,29 @@ def main():
                                      attention_frac=achieved / peaks["hbm_read_gbs"])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, case)
+    if cfg.name == "C2" and args.other_steps > 0:
+        # the other configurations, briefly, on the same device in the same run
+        for pl in {id(q): q for q in (best_plan, unsplit_plan, seq_plan, ovl_plan)}.values():
+            pl.close()
+        case.ctx.close()
+        del case, pl, best_plan, unsplit_plan, seq_plan, ovl_plan, host_rows, kept_plan
+        torch.cuda.empty_cache()
+        others = {}
+        for name in ("C3", "C4"):
+            others[name] = run_other_layer_config(name, args.other_steps, 2)
+        loop_args = argparse.Namespace(**vars(args))
+        loop_args.loop_max_iterations = args.other_loop_iterations
+        lj = run_loop(loop_args, emit=False)
+        others["C5"] = {"tokens_per_s": lj["value"], "ms_per_iteration": lj["ms_per_step"],
+                        "iterations_timed": lj["steps"], "iterations_run": lj["loop"]["iterations"],
+                        "mean_decode_requests": lj["loop"]["mean_decode_requests"],
+                        "mean_cached_tokens": lj["loop"]["mean_cached_tokens"],
+                        "iteration_frac": lj.get("iteration_roofline", {}).get("frac"),
+                        "note": f"first {args.other_loop_iterations} iterations of the loop only (the last nine tenths of "
+                                "them are timed): the decode population is still growing, so this is a window of the "
+                                "ramp-up, not the steady state that `--config C5` runs to the end",
+                        "workload": lj["config"]["workload"]}
+        out["other_configs"] = others
     print(json.dumps(out))
 
 

@@ -26,7 +26,11 @@ Readings where the paper is silent (the C++ scheduler takes the same ones):
     not been given its page yet (possibly the request that needs the page); swapped
     requests return oldest first, once their pages plus one are free and the prediction
     allows; pages are handed out from a stack whose top is initially page 0, and freed
-    pages go back on top in the order of the owner's page list.
+    pages go back on top in the order of the owner's page list;
+  * progress: the prediction only guards admission beside other requests.  When no request
+    is resident, the oldest swapped-out (else waiting) request is taken whatever the
+    prediction says - it fits the pool alone (submission checks that) - so a long-prompt
+    request under a large average output length cannot starve.
 """
 import math
 

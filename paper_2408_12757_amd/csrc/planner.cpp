@@ -49,7 +49,7 @@ void nf_profile_analytic(NfProfile* p, const nf_model_desc* m, int max_tokens, i
   const int steps = std::max(1, (max_tokens + granule - 1) / granule);
   for (int o = 0; o < NF_DENSE_OPS; ++o) {
     p->dense_us[o].assign(steps, 0.0);
-    p->dense_tile[o].assign(steps, 1);
+    p->dense_tile[o].assign(steps, 0);  // nothing measured: leave the implementation to the launcher
     for (int i = 0; i < steps; ++i) {
       const double M = (double)(i + 1) * granule;
       const double flops = 2.0 * M * NK[o][0] * NK[o][1];
