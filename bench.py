@@ -55,6 +55,9 @@ def parse_args():
     ap.add_argument("--rp-sensitivity", action="store_true",
                     help="instead of the benchmark: measure the GEMM || attention resource mapping for every dense "
                          "operation and several batch sizes and print its spread (Sec. 4.1.1, sensitivity analysis)")
+    ap.add_argument("--corun-report", action="store_true",
+                    help="instead of the benchmark: print the co-run report (load latency beside the attention kernel, "
+                         "fixed-work overlap of GEMM groups and attention, kernel timelines of overlapped pipelines)")
     ap.add_argument("--chained-layers", type=int, default=8,
                     help="also time this many consecutive layers (distinct weights and KV pools) in one "
                          "nf_layers_forward call and report the time per layer; 0 = skip")
@@ -326,6 +329,10 @@ def main():
         sys.exit(2)
     if args.rp_sensitivity:
         run_rp_sensitivity(args)
+        return
+    if args.corun_report:
+        from paper_2408_12757_amd import corun_report
+        corun_report.run(args.config if args.config in ("C2", "C3") else "C2")
         return
     if args.config == "C5":
         run_loop(args)

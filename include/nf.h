@@ -222,6 +222,18 @@ typedef struct {
 int nf_measure_peaks(nf_ctx *ctx, nf_peaks *out /* host */);
 
 /*
+ * Interference probe (Sec. 4.1.1 profiles how co-running kernels disturb one another): launches
+ * n_workgroups (1..4096) single-wavefront workgroups on hip_stream; each follows `iters`
+ * dependent loads through a 256 KiB buffer built into the library (it misses the per-CU cache
+ * and stays in the L2).  out (DEVICE, 2 * n_workgroups floats): out[2b] = nanoseconds per load
+ * seen by workgroup b, out[2b + 1] = the bits of the hardware id register of the compute unit it
+ * ran on.  Run alone it gives the L2 hit latency; run beside another kernel it gives what a
+ * GEMM's operand loads wait for on a compute unit they share with that kernel's wavefronts (or on
+ * a free one).  Asynchronous; allocates nothing.
+ */
+int nf_probe_load_latency(nf_ctx *ctx, int n_workgroups, int iters, float *out, void *hip_stream);
+
+/*
  * Kernel profiling for the auto-search (Sec. 4.1.1): times every dense
  * operation of `model` alone for batch sizes granule, 2*granule, ... max_tokens
  * with every GEMM tile shape (keeping the best: the kernel -> implementation map),

@@ -29,7 +29,7 @@ EXPORTS = [
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
-    "nf_attention_static_bytes", "nf_plan_manual_ops",
+    "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency",
 ]
 
 
@@ -118,6 +118,7 @@ def lib() -> C.CDLL:
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_manual_ops.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32,
                                      P(nf_nano_spec), P(vp)]
+    L.nf_probe_load_latency.argtypes = [vp, i32, i32, vp, vp]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
     L.nf_plan_destroy.argtypes = [vp]
     L.nf_plan_destroy.restype = None
@@ -439,6 +440,11 @@ def nf_op_attention(ctx, model, pages_ptr, num_pages, batch: BatchArgs, plan: Pl
     _check(lib().nf_op_attention(ctx.handle, C.byref(md), C.byref(kv), C.byref(batch.struct), plan.handle, qkv_ptr,
                                  attn_out_ptr, workspace_ptr, int(workspace_bytes), int(nano_index), stream),
            "nf_op_attention", ctx)
+
+
+def nf_probe_load_latency(ctx: Context, n_workgroups: int, iters: int, out_ptr: int, stream=0):
+    _check(lib().nf_probe_load_latency(ctx.handle, int(n_workgroups), int(iters), out_ptr, stream),
+           "nf_probe_load_latency", ctx)
 
 
 def nf_attention_static_bytes() -> int:

@@ -132,3 +132,61 @@ extern "C" int nf_measure_peaks(nf_ctx* ctx, nf_peaks* out) try {
 } catch (...) {
   return NF_EINVAL;
 }
+
+// ---- interference probe: latency of cache-resident loads (Sec. 4.1.1 profiles how kernels
+// disturb one another; this measures what a GEMM's operand loads wait for while another kernel
+// streams from HBM) ------------------------------------------------------------------------
+namespace {
+
+constexpr uint32_t kChaseLines = 2048;  // 256 KiB of 128-byte lines: misses the 32 KiB L1, fits any L2
+static __device__ __align__(256) uint32_t chase_buf[kChaseLines * 32];
+
+// Every word of line i holds the word index of the line that follows i in one cycle through
+// all lines (an odd multiplier modulo a power of two walks every line before it repeats).
+__global__ void chase_init_kernel(uint32_t* __restrict__ buf) {
+  const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= kChaseLines * 32) return;
+  const uint32_t line = w / 32;
+  buf[w] = ((line * 1229u + 977u) & (kChaseLines - 1)) * 32u;
+}
+
+// One wavefront per workgroup; lane 0 follows the chain with device-scope loads (they bypass
+// the per-CU cache), everything else idles.  out[2b] = nanoseconds per load of workgroup b,
+// out[2b + 1] = the hardware id register of the CU it ran on.
+__global__ __launch_bounds__(64) void chase_kernel(const uint32_t* __restrict__ buf, int iters,
+                                                   float* __restrict__ out) {
+  uint32_t idx = ((blockIdx.x * 131u + 7u) & (kChaseLines - 1)) * 32u;
+  for (int i = 0; i < 64; ++i) idx = __hip_atomic_load(buf + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long t0 = wall_clock64();
+  if (threadIdx.x == 0)
+    for (int i = 0; i < iters; ++i) idx = __hip_atomic_load(buf + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long t1 = wall_clock64();
+  if (threadIdx.x == 0) {
+    uint32_t hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    // wall_clock64 ticks at 100 MHz; idx enters the result so that the chain cannot be dropped
+    out[2 * blockIdx.x] = (float)(t1 - t0) * 10.0f / (float)iters + (idx == 0xffffffffu ? 1.0f : 0.0f);
+    out[2 * blockIdx.x + 1] = __uint_as_float(hw);
+  }
+}
+
+}  // namespace
+
+extern "C" int nf_probe_load_latency(nf_ctx* ctx, int n_workgroups, int iters, float* out, void* hip_stream) {
+  if (!ctx || !out || n_workgroups < 1 || n_workgroups > 4096 || iters < 1 || iters > (1 << 24)) return NF_EINVAL;
+  constexpr int kMaxDevices = 64;
+  static uint32_t* per_device[kMaxDevices] = {};
+  if (ctx->device < 0 || ctx->device >= kMaxDevices) return NF_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (!per_device[ctx->device]) {
+    NF_HIP(ctx, hipSetDevice(ctx->device));
+    void* p = nullptr;
+    NF_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(chase_buf)));
+    chase_init_kernel<<<dim3(kChaseLines * 32 / 256), dim3(256), 0, s>>>((uint32_t*)p);
+    NF_HIP(ctx, hipGetLastError());
+    per_device[ctx->device] = (uint32_t*)p;
+  }
+  chase_kernel<<<dim3(n_workgroups), dim3(64), 0, s>>>(per_device[ctx->device], iters, out);
+  NF_HIP(ctx, hipGetLastError());
+  return NF_OK;
+}
