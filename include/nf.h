@@ -183,7 +183,7 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
 /*
  * Process-wide kernel-variant knobs for tuning runs (Sec. 4.1.1: several implementations
  * per kernel are profiled).  key "attention.variant": 0..7 = pages in flight / occupancy /
- * load-hint trade-off of the attention kernel.  key "gemm.tile": 0 = automatic, 1..24 = force
+ * load-hint trade-off of the attention kernel.  key "gemm.tile": 0 = automatic, 1..25 = force
  * one GEMM implementation (tile shape, LDS feeding scheme, main loop) for every dense
  * operation.  key "search.layers": 1 (default) = the auto-search and nf_simulate_pipeline price
  * one layer on its own; n in 2..16 = they price the time per layer of n consecutive layers

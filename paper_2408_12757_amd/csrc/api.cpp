@@ -159,7 +159,7 @@ extern "C" int nf_tune_set(const char* key, int value) {
     return NF_OK;
   }
   if (!strcmp(key, "gemm.tile")) {
-    if (value < 0 || value > 24) return NF_EINVAL;
+    if (value < 0 || value > 25) return NF_EINVAL;
     nf_set_gemm_tile(value);
     return NF_OK;
   }

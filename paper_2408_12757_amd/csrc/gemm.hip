@@ -217,8 +217,8 @@ static hipError_t launch_two_segments(const void* x, const void* w, void* out, c
                   (tile == 21 || (tile == 0 && round_fill(units21) >= 0.9));
   if (w4) return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, 21, s);
   // the same loop with 128x256 tiles, when the profile asks for it (few rows)
-  if (tile == 22 && split.partial && K % 256 == 0 && N % 256 == 0 && g_gemm_ksplit != 1)
-    return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, 22, s);
+  if ((tile == 22 || tile == 25) && split.partial && K % 256 == 0 && N % 256 == 0 && g_gemm_ksplit != 1)
+    return nf_launch_gemm_dl_halves(x, w, out, residual, M, N, K, split.partial, split.seg_stride, tile, s);
   if (!halves) return nf_launch_gemm_dl_two_sums(x, w, out, residual, M, N, K, epilogue, s);
   int variant = (tile == 7 || tile == 11) ? 7 : (tile == 13 || tile == 10 || tile == 17) ? 13 : tile == 12 ? 12 : 19;
   if (variant == 13 && N % 256 != 0) variant = 12;
@@ -265,10 +265,10 @@ hipError_t nf_launch_gemm(const void* x, const void* w, void* out, const void* r
     const double s24 = s23 > 0.0 ? score(128, 192, 1.05) : 0.0;
     if (s24 > s23 && s24 > s22 && s24 > s21 && s24 > s20 && s24 > s12 && s24 > s7 && s24 > s13) tile = 24;
   }
-  if (tile >= 7 && tile <= 24) {
+  if (tile >= 7 && tile <= 25) {
     if (tile == 24 && (K % 128 != 0 || n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 22;
     if (tile == 23 && (K % 128 != 0 || n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 21;
-    if ((tile == 21 || tile == 22) && (K % 128 != 0 || n_eff % 256 != 0)) tile = 13;
+    if ((tile == 21 || tile == 22 || tile == 25) && (K % 128 != 0 || n_eff % 256 != 0)) tile = 13;
     if (tile == 20 && (n_eff % 192 != 0 || epilogue == EPI_SWIGLU)) tile = 19;
     if (tile == 10 && n_eff % 256 != 0) tile = 9;
     if (tile == 13 && n_eff % 256 != 0) tile = 12;

@@ -482,7 +482,11 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[TN][TM], bf1
 // of 128x192 at 1024 rows, one per CU, where 256 columns give 192 tiles; not for SwiGLU, whose
 // epilogue pairs 32-column groups).  Same MFMA and K order as
 // the other loops, hence the same output bits.  Requires K % 128 == 0 and 64 * TN | N.
-template <int EPI, bool GROUPED = false, int TM = 4, int TN = 4>
+// XS = 3 (128x256 tiles only): three stages of x rows as well, so that the x rows are requested
+// two K-steps ahead like the w rows.  Alone it changes little; on a CU shared with wavefronts
+// that stream from HBM, where a cache hit waits about a microsecond behind their misses (the
+// per-CU memory path returns in order), a K-step of lead is not enough and two are.
+template <int EPI, bool GROUPED = false, int TM = 4, int TN = 4, int XS = 2>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_w4_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, bf16_t* __restrict__ Y, const bf16_t* __restrict__ R,
     int M, int N, int K, int tiles_m, int tiles_n, GroupedArgs grp, KRange kr) {
@@ -494,7 +498,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   constexpr int LOADS = ROWS / RPI / NW;  // per K-step: BM / 32 of x, then 8 of w
   constexpr int XLOADS = BM / RPI / NW, WLOADS = BN / RPI / NW;
   // LDS: two stages of x rows, then three stages of w rows (a third stage of both would not fit)
-  constexpr int XSTAGE = BM * RB, WSTAGE = BN * RB, WBASE = 2 * XSTAGE;
+  static_assert(XS == 2 || (XS == 3 && TM == 2), "a third stage of x rows fits beside 128-row tiles only");
+  constexpr int XSTAGE = BM * RB, WSTAGE = BN * RB, WBASE = XS * XSTAGE;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   int m0, n0;
@@ -527,13 +532,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   // load I of the K-step its pointer stands at: an x load into x stage xs, a w load to byte
   // offset wf of the w region
-  auto load_one = [&](const int I, const int xs, const int wf) __attribute__((always_inline)) {
+  auto load_one = [&](const int I, const uint32_t xf, const uint32_t wf) __attribute__((always_inline)) {
     // weight rows are used by the few tiles of one tile column and then never again: loaded
     // non-temporal they do not push the x rows, which every tile column re-reads, out of the
     // L2 (measured: 2-3 % on Up/Gate; non-temporal x rows or both: no gain; with 128x256 tiles,
     // where twice as many tiles share a weight row, it costs 15 %, so those load normally)
     if (I < XLOADS)
-      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + xs * XSTAGE + (I * NW + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)src[I], (lptr_t)(lds + xf + (I * NW + wave) * 1024), 16, 0, 0);
     else if (TM != 4)
       __builtin_amdgcn_global_load_lds((gptr_t)src[I],
                                        (lptr_t)(lds + WBASE + wf + ((I - XLOADS) * NW + wave) * 1024), 16, 0, 0);
@@ -574,13 +579,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) load_one(i, 0, 0);
 #pragma unroll
-  for (int i = 0; i < LOADS; ++i) load_one(i, 1, WSTAGE);
+  for (int i = 0; i < LOADS; ++i) load_one(i, XSTAGE, WSTAGE);
   if (2 < KT) {
+    // K-step 2: its w rows, and with three x stages its x rows too
 #pragma unroll
-    for (int i = XLOADS; i < LOADS; ++i) load_one(i, 0, 2 * WSTAGE);
+    for (int i = (XS == 3 ? 0 : XLOADS); i < LOADS; ++i) load_one(i, 2 * XSTAGE, 2 * WSTAGE);
   }
   if (2 < KT)
-    wait_vmcnt<LOADS + WLOADS>();
+    wait_vmcnt<LOADS + (XS == 3 ? LOADS : WLOADS)>();
   else
     wait_vmcnt<LOADS>();
   __builtin_amdgcn_s_barrier();
@@ -594,7 +600,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         0);                                                                                                     \
   __builtin_amdgcn_sched_barrier(0)
 #define NF_W4_LOAD(I)                                                                                           \
-  if constexpr ((I) < XLOADS ? XRELOAD : (WRELOAD && (I) < LOADS)) load_one(I, STAGE, w_cur);                    \
+  if constexpr (XS == 3 ? (WRELOAD && (I) < LOADS) : ((I) < XLOADS ? XRELOAD : (WRELOAD && (I) < LOADS)))        \
+    load_one(I, CUR, w_cur);                                                                                    \
   __builtin_amdgcn_sched_barrier(0)
   // fragment I (0..3: w, 4..7: x) of K-slice KK from the stage at BASE, if ON
 #define NF_W4_RD1(ON, KK, XB, WB, I)                                                                            \
@@ -635,12 +642,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // a K-step k + 2; WRELOAD: a K-step k + 3.  The loads of a K-step are issued x rows first:
   // waiting until only WLOADS loads are outstanding leaves the w rows of K-step k + 2 in flight
   // and has everything of K-step k + 1 in LDS.
+  // With three x stages the x rows rotate like the w rows: x_cur / x_next are the byte offsets
+  // of the x stages of K-steps k and k + 1, and the x rows of K-step k + 3 are requested together
+  // with its w rows (into the stages K-step k has left); the wait in front of the barrier then
+  // leaves all loads of K-step k + 2 in flight.
   auto k_step = [&](auto stage_c, auto more_c, auto xreload_c, auto wreload_c, const uint32_t w_cur,
-                    const uint32_t w_next) {
+                    const uint32_t w_next, const uint32_t x_cur, const uint32_t x_next) {
     constexpr int STAGE = decltype(stage_c)::value;
     constexpr bool MORE = decltype(more_c)::value, XRELOAD = decltype(xreload_c)::value,
                    WRELOAD = decltype(wreload_c)::value;
-    constexpr int CUR = STAGE * XSTAGE, NEXT = (1 - STAGE) * XSTAGE;
+    const uint32_t CUR = XS == 3 ? x_cur : (uint32_t)(STAGE * XSTAGE);
+    const uint32_t NEXT = XS == 3 ? x_next : (uint32_t)((1 - STAGE) * XSTAGE);
     wait_frags<TN + TM, TN, TM>(fw[0], fx[0]);
     NF_W4_SLICE_READS(0, true, 2, CUR, w_cur);
     wait_frags<TN + TM, TN, TM>(fw[1], fx[1]);
@@ -650,7 +662,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     wait_frags<0, TN, TM>(fw[3], fx[3]);
     if (MORE) {
       if (XRELOAD)
-        wait_vmcnt<WLOADS>();  // the w rows of K-step k + 2 stay in flight
+        wait_vmcnt<(XS == 3 ? LOADS : WLOADS)>();  // the w rows (and third-stage x rows) of K-step k + 2 stay in flight
       else
         wait_vmcnt<0>();
     }
@@ -662,27 +674,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   using F = std::false_type;
   using C0 = std::integral_constant<int, 0>;
   using C1 = std::integral_constant<int, 1>;
-  uint32_t w_cur = 0, w_next = WSTAGE;
+  uint32_t w_cur = 0, w_next = WSTAGE, x_cur = 0, x_next = XSTAGE;
   auto advance = [&]() {
     w_cur = w_next;
     w_next = w_next == 2 * WSTAGE ? 0 : w_next + WSTAGE;
+    x_cur = x_next;
+    x_next = x_next == 2 * XSTAGE ? 0 : x_next + XSTAGE;
   };
   int k = 0;
   for (; k + 4 < KT; k += 2) {
-    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next);
+    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next, x_cur, x_next);
     advance();
-    k_step(C1{}, T{}, T{}, T{}, w_cur, w_next);
+    k_step(C1{}, T{}, T{}, T{}, w_cur, w_next, x_cur, x_next);
     advance();
   }
   if (k + 2 < KT) {  // K-steps KT - 4 and KT - 3
-    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next);
+    k_step(C0{}, T{}, T{}, T{}, w_cur, w_next, x_cur, x_next);
     advance();
-    k_step(C1{}, T{}, T{}, F{}, w_cur, w_next);
+    k_step(C1{}, T{}, T{}, F{}, w_cur, w_next, x_cur, x_next);
     advance();
   }
-  k_step(C0{}, T{}, F{}, F{}, w_cur, w_next);
+  k_step(C0{}, T{}, F{}, F{}, w_cur, w_next, x_cur, x_next);
   advance();
-  k_step(C1{}, F{}, F{}, F{}, w_cur, w_next);
+  k_step(C1{}, F{}, F{}, F{}, w_cur, w_next, x_cur, x_next);
 #undef NF_W4_MFMA
 #undef NF_W4_LOAD
 #undef NF_W4_SLICE_READS
@@ -764,19 +778,19 @@ hipError_t launch_dl2(const void* x, const void* w, void* out, const void* resid
 
 // One launch of the four-wavefront loop with tiles of 64 * TM rows over the tile columns
 // [n_first, n_first + n_tiles).
-template <bool GROUPED, int TM, int TN = 4>
+template <bool GROUPED, int TM, int TN = 4, int XS = 2>
 hipError_t launch_w4_columns(const void* x, const void* w, void* out, const void* residual, int M, int N, int K,
                              int epilogue, hipStream_t s, GroupedArgs grp, int n_first, int n_tiles) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   const int tiles_m = GROUPED ? (M + BM - 1) / BM + grp.n_experts : (M + BM - 1) / BM;
   const dim3 grid(tiles_m * n_tiles), block(256);
   // two x stages and three w stages; the epilogue reuses them as 4 regions of (BM / 2) rows x 272 bytes
-  const size_t lds_bytes = std::max((size_t)(2 * BM + 3 * BN) * 128, (size_t)4 * (BM / 2) * (BN + 16));
+  const size_t lds_bytes = std::max((size_t)(XS * BM + 3 * BN) * 128, (size_t)4 * (BM / 2) * (BN + 16));
   KRange kr{K, nullptr, 0};
   kr.n_first = n_first;
 #define NF_W4_LAUNCH(E)                                                                                            \
   do {                                                                                                             \
-    auto kern = gemm_w4_kernel<E, GROUPED, TM, TN>;                                                                 \
+    auto kern = gemm_w4_kernel<E, GROUPED, TM, TN, XS>;                                                             \
     static bool attr_set = false;                                                                                  \
     hipError_t e = allow_lds(kern, lds_bytes, attr_set);                                                           \
     if (e != hipSuccess) return e;                                                                                 \
@@ -954,6 +968,19 @@ hipError_t nf_launch_gemm_dl_halves(const void* x, const void* w, void* out, con
       e = hipGetLastError();
       break;
     }
+    case 25: {  // 128x256 tiles with three stages of x rows
+      if (K % 256 != 0 || N % 256 != 0) return hipErrorInvalidValue;
+      const int tiles_m = (M + 127) / 128, tiles_n = N / 256;
+      const size_t lds_bytes = (size_t)(3 * 128 + 3 * 256) * 128;
+      static bool attr_set = false;
+      e = allow_lds(gemm_w4_kernel<EPI_PARTIAL, false, 2, 4, 3>, lds_bytes, attr_set);
+      if (e != hipSuccess) return e;
+      gemm_w4_kernel<EPI_PARTIAL, false, 2, 4, 3><<<dim3(tiles_m * tiles_n, 2), dim3(256), lds_bytes, s>>>(
+          (const bf16_t*)x, (const bf16_t*)w, nullptr, nullptr, M, N, K / 2, tiles_m, tiles_n,
+          GroupedArgs{nullptr, nullptr, 0, 0}, kr);
+      e = hipGetLastError();
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
@@ -1034,6 +1061,11 @@ hipError_t nf_launch_gemm_dl(const void* x, const void* w, void* out, const void
     case 24:  // and with 128x192 tiles
       if (K % 128 != 0 || N % 192 != 0 || epilogue == EPI_SWIGLU) return hipErrorInvalidValue;
       return launch_w4_columns<false, 2, 3>(x, w, out, residual, M, N, K, epilogue, s, none, 0, N / 192);
+    case 25: {  // 128x256 tiles with three stages of x rows: the form for CUs shared with streaming wavefronts
+      const int n_eff = epilogue == EPI_SWIGLU ? 2 * N : N;
+      if (K % 128 != 0 || n_eff % 256 != 0) return hipErrorInvalidValue;
+      return launch_w4_columns<false, 2, 4, 3>(x, w, out, residual, M, N, K, epilogue, s, none, 0, n_eff / 256);
+    }
     default: return hipErrorInvalidValue;
   }
 }

@@ -377,7 +377,7 @@ extern "C" int nf_plan_manual_ops(nf_ctx* ctx, const nf_model_desc* model, const
   for (int i = 0; i < n_nano; ++i) {
     if (spec[i].attn_wgs < -1) return NF_EINVAL;
     for (int k = 0; k < 4; ++k)
-      if (spec[i].gemm_tile[k] < 0 || spec[i].gemm_tile[k] > 24) return NF_EINVAL;
+      if (spec[i].gemm_tile[k] < 0 || spec[i].gemm_tile[k] > 25) return NF_EINVAL;
   }
   nf_plan* p = new (std::nothrow) nf_plan();
   if (!p) return NF_ENOMEM;

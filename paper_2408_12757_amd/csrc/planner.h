@@ -8,7 +8,7 @@
 
 #include "../../include/nf.h"
 
-constexpr int NF_MAX_TILE = 24;
+constexpr int NF_MAX_TILE = 25;
 enum { NF_DENSE_KQV = 0, NF_DENSE_O = 1, NF_DENSE_UG = 2, NF_DENSE_D = 3, NF_DENSE_OPS = 4 };
 
 // One row of the resource-mapping table (Sec. 4.1.1, Table 3) for the memory-bound kernel:

@@ -27,7 +27,7 @@ void nf_profile_free(nf_ctx* ctx) {
 
 namespace {
 
-constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19, 20, 21, 22, 23, 24};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
+constexpr int kTiles[] = {1, 7, 11, 12, 13, 17, 19, 20, 21, 22, 23, 24, 25};  // GEMM implementations (see gemm.hip / gemm_dl.hip)
 constexpr int kAttnWgSettings[] = {64, 96, 128, 160, 192, 256, 512};
 
 struct Scratch {
@@ -283,7 +283,7 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     const int M = half_steps * granule;
     double g_best_ms = 0;
     for (int o = 0; o < NF_DENSE_OPS; ++o) g_best_ms += p->dense_us[o][half_steps - 1] / 1e3;
-    const int kPairTiles[] = {7, 12, 13, 19, 21};
+    const int kPairTiles[] = {7, 12, 13, 19, 21, 22, 25};
     p->rp.clear();
     for (int tile : kPairTiles) {
       if (rc) break;

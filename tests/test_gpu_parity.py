@@ -104,7 +104,7 @@ def test_every_gemm_implementation_gives_the_same_bits(M, N, K, epi):
     res_ptr = rt.data_ptr() if epi == "residual" else None
     outs = {}
     try:
-        for tile in range(1, 25):
+        for tile in range(1, 26):
             nf.nf_tune_set("gemm.tile", tile)
             out = torch.full((M + 1, N), 7.0, dtype=torch.bfloat16, device=DEV)
             nf.nf_op_gemm(xt.data_ptr(), wt.data_ptr(), out.data_ptr(), res_ptr, M, N, K, code)
