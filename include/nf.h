@@ -277,6 +277,8 @@ typedef struct nf_pipeline_desc {
   int32_t attn_wgs;       /* attention kernel's persistent workgroups (its share R)      */
   int32_t gemm_tile;      /* GEMM implementation of the chosen R -> P pair (0 = per-op best) */
   int32_t reserved;
+  int32_t nano_attn_wgs[8]; /* the share per attention nano-operation (Sec. 4.1.1: R per nano-operation) */
+  int32_t order[8];       /* launch order: order[k] = index of the nano-batch launched k-th    */
   double est_us;          /* modelled makespan with interference                         */
   double est_us_stage1;   /* same structure without interference                         */
   double est_us_unsplit;  /* the unsplit sequential layer                                */
@@ -285,6 +287,13 @@ int nf_search_pipeline(const nf_model_desc *model, const nf_batch *batch, const 
                        int max_nano, int granule, nf_pipeline_desc *out);
 int nf_simulate_pipeline(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
                          int n_nano, const int32_t *bounds, int overlap, int rp_row, double *est_us);
+/* The overlapped pipeline with a table row per nano-batch (rp_rows[i] holds while the attention
+ * nano-operation of nano-batch i runs; the rows must share one GEMM implementation) and a launch
+ * order (order[k] = nano-batch launched k-th; NULL = index order).  NF_EPLAN for an order that
+ * launches an attention nano-operation before a KQV nano-operation it depends on. */
+int nf_simulate_pipeline_ops(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
+                             int n_nano, const int32_t *bounds, const int32_t *rp_rows, const int32_t *order,
+                             double *est_us);
 
 /* Dependency rule of Sec. 4.1.2: 1 iff the parent operations are dependent (kinds: 0 KQV,
  * 1 ATTN, 2 O, 3 UG, 4 D; KQV -> ATTN -> O -> UG -> D) and the token ranges [b0,e0) and
@@ -324,7 +333,10 @@ int nf_plan_manual(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batc
 typedef struct nf_nano_spec {
   int32_t attn_wgs;
   int32_t gemm_tile[4];
-  int32_t reserved[3];
+  int32_t launch_pos;   /* position of this nano-batch in the launch order (a permutation of
+                           0..n_nano-1; all zero = index order).  NF_EPLAN if an attention
+                           nano-operation would be launched before a KQV it depends on. */
+  int32_t reserved[2];
 } nf_nano_spec;
 int nf_plan_manual_ops(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch, int n_nano,
                        const int32_t *bounds, int overlap, int attn_cus, int gemm_cus,

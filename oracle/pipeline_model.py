@@ -13,6 +13,12 @@ attention kernel overlap, the GEMM runs at P = R_gemm and attention at P = P_att
 (the R -> P table, with the R of overlapping kernels summing to 1); a kernel that runs alone
 runs at the stand-alone speed of the implementation the table row names.
 
+Every nano-operation has its own resource share (Sec. 4.1.1: "R" belongs to the nano-operation),
+so ``rows`` may name one table row per nano-batch - the row in force is that of the attention
+nano-operation currently on the memory resource - and the nano-batches may be launched in any
+``order`` whose dependencies can be met (Sec. 4.1.2: number, size and order of the
+nano-operations are what the search decides).
+
 It is written as a fixed-step time integration - slow and plain - so that it can check the
 event-driven C++ implementation.
 """
@@ -35,7 +41,8 @@ def interp_dense(table: Sequence[float], granule: int, m: int) -> float:
 
 
 def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, overlap,
-             row: Optional[dict], dt: float = 0.02, misc=None, layers: int = 1) -> float:
+             row: Optional[dict], dt: float = 0.02, misc=None, layers: int = 1, rows: Optional[list] = None,
+             order: Optional[list] = None) -> Optional[float]:
     """dense: dict op -> table of the best implementation; row: dict(p_gemm, p_attn,
     p_attn_solo[, p_gemm_solo][, dense]) or None.  A row that carries its own "dense" tables
     (the times of the GEMM implementation it was measured with) makes every GEMM of an
@@ -46,12 +53,22 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
     layers > 1: that many consecutive layers (the output of a layer is the next layer's input,
     Sec. 2.1), pipelined across the layer boundary: on the compute resource the KQV
     nano-operation of a range in layer l + 1 is launched right behind the O/Up/Gate/Down
-    nano-operation of that range in layer l; the total time is returned."""
+    nano-operation of that range in layer l; the total time is returned.
+    rows: one row per nano-batch (the row of the attention nano-operation that is running decides the
+    speeds; all rows belong to one GEMM implementation, so rows[0] supplies the GEMM tables).
+    order: order[k] = index of the nano-batch launched k-th; None (the function's result) when
+    an attention nano-operation would be launched before a KQV nano-operation it needs."""
+    if rows is not None:
+        row = rows[0]
     if overlap and row is not None and row.get("dense") is not None:
         dense = row["dense"]
         solo = row.get("p_gemm_solo", 1.0)
         row = dict(row, p_gemm=row["p_gemm"] / solo, p_gemm_solo=1.0)
+        if rows is not None:
+            rows = [dict(r, p_gemm=r["p_gemm"] / r.get("p_gemm_solo", 1.0), p_gemm_solo=1.0) for r in rows]
     n = len(bounds) - 1
+    order = list(order) if order is not None else list(range(n))
+    position = {i: k for k, i in enumerate(order)}
     kqv, att, rest = [], [], []
     for i in range(n):
         m = bounds[i + 1] - bounds[i]
@@ -66,14 +83,18 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
         return (sum(kqv) + sum(att) + sum(rest)) * layers
     # launch order on the compute resource: all KQV nano-ops of the first layer, then per layer
     # O+UG+D of every nano-batch, each followed by the next layer's KQV of the same range
-    compute = [("kqv", i, 0) for i in range(n)]
+    compute = [("kqv", i, 0) for i in order]
     memory = []
     for l in range(layers):
-        for i in range(n):
+        for i in order:
             compute.append(("rest", i, l))
             if l + 1 < layers:
                 compute.append(("kqv", i, l + 1))
-        memory += [("att", i, l) for i in range(n)]
+        memory += [("att", i, l) for i in order]
+    for i in range(n):
+        lo = req_start[bounds[i]]
+        if any(bounds[j + 1] > lo and position[j] > position[i] for j in range(i + 1)):
+            return None
     work = {}
     for l in range(layers):
         for i in range(n):
@@ -99,13 +120,16 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
         m = memory[mi] if mi < len(memory) and ready(memory[mi]) else None
         assert c is not None or m is not None, "deadlock"
         sc = sm = 1.0
-        if row is not None:
+        cur = row
+        if rows is not None and mi < len(memory):
+            cur = rows[memory[mi][1]]       # the attention nano-operation at the head of the memory resource
+        if cur is not None:
             if c is not None and m is not None:
-                sc, sm = row["p_gemm"], row["p_attn"]
+                sc, sm = cur["p_gemm"], cur["p_attn"]
             elif m is not None:
-                sm = row["p_attn_solo"]
+                sm = cur["p_attn_solo"]
             else:
-                sc = row.get("p_gemm_solo", 1.0)
+                sc = cur.get("p_gemm_solo", 1.0)
         if c is not None:
             left[c] -= sc * dt
             if left[c] <= 0:
@@ -123,6 +147,20 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
 def all_bounds(n_tokens: int, granule: int, n_nano: int) -> List[List[int]]:
     cuts = list(range(granule, n_tokens, granule))
     return [[0, *c, n_tokens] for c in itertools.combinations(cuts, n_nano - 1)]
+
+
+def brute_force_ops(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, rows, dt: float = 0.02):
+    """Minimum makespan of ONE structure over every assignment of table rows to its nano-batches
+    and every launch order."""
+    n = len(bounds) - 1
+    best = None
+    for assign in itertools.product(rows, repeat=n):
+        for order in itertools.permutations(range(n)):
+            t = makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, True, None, dt,
+                         rows=list(assign), order=list(order))
+            if t is not None and (best is None or t < best[0]):
+                best = (t, assign, order)
+    return best
 
 
 def brute_force(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, n_tokens, rows, max_nano,

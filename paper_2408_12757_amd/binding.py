@@ -29,7 +29,7 @@ EXPORTS = [
     "nf_layers_workspace_bytes", "nf_layers_forward",
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
-    "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency",
+    "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency", "nf_simulate_pipeline_ops",
 ]
 
 
@@ -58,11 +58,14 @@ class nf_batch(C.Structure):
 
 class nf_pipeline_desc(C.Structure):
     _fields_ = [("n_nano", C.c_int32), ("bounds", C.c_int32 * 9), ("overlap", C.c_int32), ("attn_wgs", C.c_int32),
-                ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("est_us", C.c_double), ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
+                ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("nano_attn_wgs", C.c_int32 * 8),
+                ("order", C.c_int32 * 8), ("est_us", C.c_double), ("est_us_stage1", C.c_double),
+                ("est_us_unsplit", C.c_double)]
 
 
 class nf_nano_spec(C.Structure):
-    _fields_ = [("attn_wgs", C.c_int32), ("gemm_tile", C.c_int32 * 4), ("reserved", C.c_int32 * 3)]
+    _fields_ = [("attn_wgs", C.c_int32), ("gemm_tile", C.c_int32 * 4), ("launch_pos", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class nf_trace_rec(C.Structure):
@@ -114,6 +117,8 @@ def lib() -> C.CDLL:
     L.nf_search_pipeline.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, i32, P(nf_pipeline_desc)]
     L.nf_simulate_pipeline.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, P(C.c_int32), i32, i32,
                                        P(C.c_double)]
+    L.nf_simulate_pipeline_ops.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, P(C.c_int32), P(C.c_int32),
+                                           P(C.c_int32), P(C.c_double)]
     L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_manual_ops.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32,
@@ -276,13 +281,15 @@ def nf_plan_manual(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int],
 
 def nf_plan_manual_ops(ctx: Context, model, batch: BatchArgs, bounds: Sequence[int], overlap: bool,
                        attn_wgs: Sequence[int], gemm_tiles: "Optional[Sequence[Sequence[int]]]" = None,
-                       attn_cus: int = 0, gemm_cus: int = 0) -> Plan:
-    """attn_wgs[i] and gemm_tiles[i] = (KQV, O, Up/Gate, Down) implementations of nano-batch i."""
+                       attn_cus: int = 0, gemm_cus: int = 0, launch_pos: "Optional[Sequence[int]]" = None) -> Plan:
+    """attn_wgs[i] and gemm_tiles[i] = (KQV, O, Up/Gate, Down) implementations of nano-batch i;
+    launch_pos[i] = its position in the launch order (None = index order)."""
     b = _np_i32(bounds)
     n = len(b) - 1
     spec = (nf_nano_spec * n)()
     for i in range(n):
         spec[i].attn_wgs = int(attn_wgs[i])
+        spec[i].launch_pos = int(launch_pos[i]) if launch_pos is not None else 0
         for k in range(4):
             spec[i].gemm_tile[k] = int(gemm_tiles[i][k]) if gemm_tiles is not None else 0
     h = C.c_void_p()
@@ -309,7 +316,8 @@ def nf_search_pipeline(model, batch: BatchArgs, profile_path: Optional[str] = No
                                     int(max_nano), int(granule), C.byref(out)), "nf_search_pipeline")
     return dict(bounds=[int(out.bounds[i]) for i in range(out.n_nano + 1)], overlap=int(out.overlap),
                 attn_wgs=int(out.attn_wgs), gemm_tile=int(out.gemm_tile), est_us=out.est_us, est_us_stage1=out.est_us_stage1,
-                est_us_unsplit=out.est_us_unsplit)
+                est_us_unsplit=out.est_us_unsplit, nano_attn_wgs=[int(out.nano_attn_wgs[i]) for i in range(out.n_nano)],
+                order=[int(out.order[i]) for i in range(out.n_nano)])
 
 
 def nf_simulate_pipeline(model, batch: BatchArgs, bounds: Sequence[int], overlap: bool, rp_row: int = -1,
@@ -320,6 +328,19 @@ def nf_simulate_pipeline(model, batch: BatchArgs, bounds: Sequence[int], overlap
     _check(lib().nf_simulate_pipeline(C.byref(md), C.byref(batch.struct), profile_path.encode() if profile_path else None,
                                       len(b) - 1, b.ctypes.data_as(C.POINTER(C.c_int32)), int(bool(overlap)),
                                       int(rp_row), C.byref(est)), "nf_simulate_pipeline")
+    return est.value
+
+
+def nf_simulate_pipeline_ops(model, batch: BatchArgs, bounds: Sequence[int], rp_rows: Sequence[int],
+                             order: Optional[Sequence[int]], profile_path: str) -> float:
+    md = model_desc(model)
+    b, r = _np_i32(bounds), _np_i32(rp_rows)
+    o = _np_i32(order) if order is not None else None
+    est = C.c_double()
+    _check(lib().nf_simulate_pipeline_ops(C.byref(md), C.byref(batch.struct), profile_path.encode(), len(b) - 1,
+                                          b.ctypes.data_as(C.POINTER(C.c_int32)), r.ctypes.data_as(C.POINTER(C.c_int32)),
+                                          o.ctypes.data_as(C.POINTER(C.c_int32)) if o is not None else None,
+                                          C.byref(est)), "nf_simulate_pipeline_ops")
     return est.value
 
 

@@ -71,6 +71,7 @@ struct nf_plan {
   int lane_cu_first[NF_LANES] = {0, 0};   // first CU bit of the lane's mask
   int attn_wgs = 0;                       // persistent attention workgroups (0 = one per CU, -1 = one per work unit)
   std::vector<int> nano_attn_wgs;         // the same per nano-batch (what the launches use; attn_wgs is the default)
+  std::vector<int> nano_order;            // launch order of the nano-batches (empty = index order)
   hipStream_t lane_stream[NF_LANES] = {nullptr, nullptr};
   std::vector<hipEvent_t> events;  // one per nano-op that records
   std::vector<hipEvent_t> events_alt;  // second set: consecutive layers of a multi-layer run alternate
@@ -114,6 +115,7 @@ extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan);
 int nf_plan_finalize(nf_ctx* ctx, nf_plan* p, const nf_batch* batch);
 // Default launch order for given nano-batch bounds (used by nf_plan_manual and as the
 // search's starting point).
-void nf_plan_default_order(nf_plan* p, int overlap);
+// order (optional, n_nano entries): order[k] = index of the nano-batch launched k-th.
+void nf_plan_default_order(nf_plan* p, int overlap, const int* order = nullptr);
 
 size_t nf_align256(size_t v);

@@ -137,10 +137,14 @@ extern "C" int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, in
   return std::max(b0, b1) < std::min(e0, e1) ? 1 : 0;
 }
 
-void nf_plan_default_order(nf_plan* p, int overlap) {
+void nf_plan_default_order(nf_plan* p, int overlap, const int* order) {
   const int n = (int)p->bounds.size() - 1;
   p->ops.clear();
-  auto add = [&](int kind, int i) {
+  p->nano_order.clear();
+  if (order)
+    for (int k = 0; k < n; ++k) p->nano_order.push_back(order[k]);
+  auto add = [&](int kind, int k) {
+    const int i = order ? order[k] : k;
     NfNanoOp op;
     op.kind = kind;
     op.nano = i;
@@ -374,6 +378,20 @@ extern "C" int nf_plan_manual_ops(nf_ctx* ctx, const nf_model_desc* model, const
   rc = check_bounds(batch, n_nano, bounds);
   if (rc) return rc;
   if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus) return NF_EINVAL;
+  // launch order: spec[i].launch_pos = position of nano-batch i (all zero = index order); it must
+  // be a permutation, and nf_plan_finalize refuses one that launches an attention nano-operation
+  // before a KQV nano-operation it depends on
+  std::vector<int> order;
+  bool any_pos = false;
+  for (int i = 0; i < n_nano; ++i) any_pos = any_pos || spec[i].launch_pos != 0;
+  if (any_pos) {
+    order.assign((size_t)n_nano, -1);
+    for (int i = 0; i < n_nano; ++i) {
+      const int k = spec[i].launch_pos;
+      if (k < 0 || k >= n_nano || order[k] >= 0) return NF_EPLAN;
+      order[k] = i;
+    }
+  }
   for (int i = 0; i < n_nano; ++i) {
     if (spec[i].attn_wgs < -1) return NF_EINVAL;
     for (int k = 0; k < 4; ++k)
@@ -390,7 +408,7 @@ extern "C" int nf_plan_manual_ops(nf_ctx* ctx, const nf_model_desc* model, const
   p->origin = "manual";
   p->attn_wgs = spec[0].attn_wgs;
   for (int i = 0; i < n_nano; ++i) p->nano_attn_wgs.push_back(spec[i].attn_wgs);
-  nf_plan_default_order(p, overlap ? 1 : 0);
+  nf_plan_default_order(p, overlap ? 1 : 0, order.empty() ? nullptr : order.data());
   for (NfNanoOp& op : p->ops) {
     static const int slot[NF_OP_KINDS] = {0, -1, 1, 2, 3};
     if (slot[op.kind] >= 0) op.gemm_tile = spec[op.nano].gemm_tile[slot[op.kind]];
@@ -423,6 +441,12 @@ extern "C" void nf_plan_destroy(nf_plan* p) {
   delete p;
 }
 
+static std::string list_json(const std::vector<int>& v) {
+  std::string s = "[";
+  for (size_t i = 0; i < v.size(); ++i) s += (i ? ", " : "") + std::to_string(v[i]);
+  return s + "]";
+}
+
 static const char* kind_name(int k) {
   static const char* n[] = {"KQV", "ATTN", "O", "UG", "D"};
   return (k >= 0 && k < NF_OP_KINDS) ? n[k] : "?";
@@ -435,7 +459,8 @@ extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) try
   for (size_t i = 0; i < p->bounds.size(); ++i) s += (i ? ", " : "") + std::to_string(p->bounds[i]);
   s += "], \"attn_cus\": " + std::to_string(p->lane_cus[NF_LANE_ATTN]) +
        ", \"gemm_cus\": " + std::to_string(p->lane_cus[NF_LANE_GEMM]) +
-       ", \"attn_wgs\": " + std::to_string(p->attn_wgs) + ", \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
+       ", \"attn_wgs\": " + std::to_string(p->attn_wgs) + ", \"nano_attn_wgs\": " + list_json(p->nano_attn_wgs) +
+       ", \"order\": " + list_json(p->nano_order) + ", \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
        ", \"ops\": [";
   for (size_t a = 0; a < p->ops.size(); ++a) {
     const NfNanoOp& o = p->ops[a];

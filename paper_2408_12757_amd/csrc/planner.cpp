@@ -172,11 +172,13 @@ struct SimOp {
 
 }  // namespace
 
-double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
-                   const NfRpRow* row, int n_layers) {
+static double simulate_impl(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
+                            const NfRpRow* row, const std::vector<const NfRpRow*>* rows, const std::vector<int>* order,
+                            int n_layers) {
   const int n = (int)bounds.size() - 1;
   const int L = std::max(1, n_layers);
   std::vector<double> kqv(n), att(n), rest(n);
+  if (rows && !rows->empty()) row = (*rows)[0];  // the GEMM implementation is common to all rows
   // With a table row, every GEMM runs in the row's implementation: its own interference-free
   // time is the work, and its overlapped speed is relative to that implementation alone.
   const bool use_row_tile = overlap && row && row->gemm_tile > 0;
@@ -197,6 +199,14 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
     for (int i = 0; i < n; ++i) t += kqv[i] + att[i] + rest[i];
     return t * L;
   }
+  // launch order of the nano-batches (index order unless given)
+  std::vector<int> ord(n);
+  for (int k = 0; k < n; ++k) ord[k] = (order && (int)order->size() == n) ? (*order)[k] : k;
+  std::vector<int> pos(n, -1);
+  for (int k = 0; k < n; ++k) {
+    if (ord[k] < 0 || ord[k] >= n || pos[ord[k]] >= 0) return -1.0;
+    pos[ord[k]] = k;
+  }
   // ops of layer l: KQV_i = 3nl + i, ATTN_i = 3nl + n + i, REST_i (O, Up/Gate, Down) = 3nl + 2n + i.
   // Consecutive layers are pipelined as the executor does it: the KQV nano-operation of a range
   // in layer l + 1 is launched right behind the O/Up/Gate/Down of that range in layer l.
@@ -212,15 +222,18 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
       // request it starts inside of
       const int lo = in.req_start_of_tok.empty() ? bounds[i] : in.req_start_of_tok[bounds[i]];
       for (int j = 0; j <= i; ++j)
-        if (bounds[j + 1] > lo) ops[base + n + i].deps.push_back(base + j);
+        if (bounds[j + 1] > lo) {
+          if (pos[j] > pos[i]) return -1.0;  // its KQV would be launched after this attention
+          ops[base + n + i].deps.push_back(base + j);
+        }
     }
     if (l == 0)
-      for (int i = 0; i < n; ++i) q[0].push_back(i);
-    for (int i = 0; i < n; ++i) {
-      q[0].push_back(base + 2 * n + i);
-      if (l + 1 < L) q[0].push_back(base + 3 * n + i);
+      for (int k = 0; k < n; ++k) q[0].push_back(ord[k]);
+    for (int k = 0; k < n; ++k) {
+      q[0].push_back(base + 2 * n + ord[k]);
+      if (l + 1 < L) q[0].push_back(base + 3 * n + ord[k]);
     }
-    for (int i = 0; i < n; ++i) q[1].push_back(base + n + i);
+    for (int k = 0; k < n; ++k) q[1].push_back(base + n + ord[k]);
   }
   std::vector<char> done(ops.size(), 0);
   size_t head[2] = {0, 0};
@@ -239,15 +252,18 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
       }
     }
     if (!running[0] && !running[1]) break;  // all done (a valid structure cannot deadlock)
+    // the row in force: that of the attention nano-operation at the head of its lane
+    const NfRpRow* r = row;
+    if (rows && !rows->empty() && head[1] < q[1].size()) r = (*rows)[(size_t)((q[1][head[1]] % (3 * n)) - n)];
     double sp[2] = {1.0, 1.0};
-    if (row) {
+    if (r) {
       // GEMM work is in units of the row's implementation when its table is used
-      const double g_solo = use_row_tile ? 1.0 : row->p_gemm_solo;
+      const double g_solo = use_row_tile ? 1.0 : r->p_gemm_solo;
       if (running[0] && running[1]) {
-        sp[0] = use_row_tile ? row->p_gemm / std::max(row->p_gemm_solo, 1e-6) : row->p_gemm;
-        sp[1] = row->p_attn;
+        sp[0] = use_row_tile ? r->p_gemm / std::max(r->p_gemm_solo, 1e-6) : r->p_gemm;
+        sp[1] = r->p_attn;
       } else if (running[1]) {
-        sp[1] = row->p_attn_solo;
+        sp[1] = r->p_attn_solo;
       } else {
         sp[0] = g_solo;
       }
@@ -269,6 +285,21 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
   return t;
 }
 
+double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
+                   const NfRpRow* row, int n_layers) {
+  return simulate_impl(prof, in, bounds, overlap, row, nullptr, nullptr, n_layers);
+}
+
+double nf_simulate_ops(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
+                       const std::vector<const NfRpRow*>& rows, const std::vector<int>& order, int n_layers) {
+  if (!rows.empty()) {
+    if (rows.size() + 1 != bounds.size()) return -1.0;
+    for (const NfRpRow* r : rows)
+      if (!r || r->gemm_tile != rows[0]->gemm_tile) return -1.0;
+  }
+  return simulate_impl(prof, in, bounds, 1, nullptr, &rows, &order, n_layers);
+}
+
 // Time per layer of a long run of consecutive layers: the increment between one layer and
 // in.layers layers (the ramp-up of the first layer and the drain of the last drop out).
 double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
@@ -276,6 +307,14 @@ double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, con
   if (in.layers <= 1) return nf_simulate(prof, in, bounds, overlap, row, 1);
   const double t1 = nf_simulate(prof, in, bounds, overlap, row, 1);
   const double tl = nf_simulate(prof, in, bounds, overlap, row, in.layers);
+  return (tl - t1) / (in.layers - 1);
+}
+
+static double simulate_ops_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
+                                     const std::vector<const NfRpRow*>& rows, const std::vector<int>& order) {
+  const double t1 = nf_simulate_ops(prof, in, bounds, rows, order, 1);
+  if (t1 < 0 || in.layers <= 1) return t1;
+  const double tl = nf_simulate_ops(prof, in, bounds, rows, order, in.layers);
   return (tl - t1) / (in.layers - 1);
 }
 
@@ -306,6 +345,8 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   out->bounds = whole;
   out->overlap = 0;
   out->attn_wgs = 0;
+  out->nano_attn_wgs.clear();
+  out->order.clear();
   out->est_us_unsplit = in.n_tokens ? nf_simulate_per_layer(prof, in, whole, 0, nullptr) : 0.0;
   out->est_us = out->est_us_stage1 = out->est_us_unsplit;
   const int max_n = in.max_nano > 0 ? std::min(in.max_nano, NF_MAX_NANO) : NF_MAX_NANO;
@@ -366,6 +407,61 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     out->gemm_tile = b.row.gemm_tile;
     out->est_us = b.t2;
     out->est_us_stage1 = cands[b.cand].t1;
+    // Stage II, second pass (Sec. 4.1.2 - 4.1.3: R is chosen per nano-operation, and the order of the
+    // nano-batches belongs to the pipeline): starting from the uniform share, every attention
+    // nano-operation in turn tries the other rows measured with the same GEMM implementation, and
+    // the launch order tries every permutation the dependencies allow; changes that shorten the
+    // estimate are kept until none does.  A few hundred simulations at most.
+    if (!prof.rp.empty()) {
+      const int n = (int)out->bounds.size() - 1;
+      std::vector<const NfRpRow*> same_tile;
+      const NfRpRow* start = nullptr;
+      for (const NfRpRow& r : prof.rp)
+        if (r.gemm_tile == b.row.gemm_tile) {
+          same_tile.push_back(&r);
+          if (r.attn_wgs == b.row.attn_wgs && fabs(r.p_gemm - b.row.p_gemm) < 1e-12) start = &r;
+        }
+      if (start && n >= 2 && n <= NF_MAX_NANO) {
+        std::vector<const NfRpRow*> rows((size_t)n, start);
+        std::vector<int> order(n);
+        for (int i = 0; i < n; ++i) order[i] = i;
+        double best = simulate_ops_per_layer(prof, in, out->bounds, rows, order);
+        bool improved = best >= 0;
+        for (int pass = 0; pass < 4 && improved; ++pass) {
+          improved = false;
+          for (int i = 0; i < n; ++i)
+            for (const NfRpRow* r : same_tile) {
+              if (r == rows[i]) continue;
+              const NfRpRow* keep = rows[i];
+              rows[i] = r;
+              const double t = simulate_ops_per_layer(prof, in, out->bounds, rows, order);
+              if (t >= 0 && t < best - 1e-9) {
+                best = t;
+                improved = true;
+              } else {
+                rows[i] = keep;
+              }
+            }
+          std::vector<int> perm = order, best_perm = order;
+          std::sort(perm.begin(), perm.end());
+          do {
+            const double t = simulate_ops_per_layer(prof, in, out->bounds, rows, perm);
+            if (t >= 0 && t < best - 1e-9) {
+              best = t;
+              best_perm = perm;
+              improved = true;
+            }
+          } while (std::next_permutation(perm.begin(), perm.end()));
+          order = best_perm;
+        }
+        if (best >= 0 && best < out->est_us - 1e-9) {
+          out->est_us = best;
+          out->nano_attn_wgs.clear();
+          for (const NfRpRow* r : rows) out->nano_attn_wgs.push_back(r->attn_wgs);
+          out->order = order;
+        }
+      }
+    }
   }
   return NF_OK;
 }

@@ -69,6 +69,12 @@ struct NfSearchInput {
 struct NfPipeline {
   std::vector<int> bounds;   // nano-batch boundaries
   int overlap = 0;
+  // Per nano-batch (Sec. 4.1.1 - 4.1.3: every nano-operation has its own resource share, and the
+  // order of the nano-batches is part of the pipeline): the persistent workgroups of its attention
+  // nano-operation, and the launch order (order[k] = index of the nano-batch launched k-th).
+  // Empty = the uniform share `attn_wgs` / index order.
+  std::vector<int> nano_attn_wgs;
+  std::vector<int> order;
   int attn_wgs = 0;          // chosen row of the R -> P table (0 = unrestricted)
   int gemm_tile = 0;         // GEMM implementation of the chosen row (0 = per-op best)
   double est_us = 0.0;       // simulated makespan
@@ -83,6 +89,12 @@ constexpr int NF_MAX_NANO = 4;
 // p_attn of their stand-alone speeds and attention alone at p_attn_solo (Stage II).
 double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds, int overlap,
                    const NfRpRow* row, int n_layers = 1);
+// The same with a table row per nano-batch (rows[i] holds while the attention nano-operation of
+// nano-batch i runs; all rows must name the same GEMM implementation) and a launch order.  Returns
+// a negative value for an order that launches an attention nano-operation before the KQV
+// nano-operations it depends on.
+double nf_simulate_ops(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
+                       const std::vector<const NfRpRow*>& rows, const std::vector<int>& order, int n_layers = 1);
 // The objective of the search: the makespan of one layer, or (in.layers > 1) the time per layer
 // of a run of consecutive layers pipelined across the layer boundaries.
 double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,

@@ -466,6 +466,10 @@ extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* ba
   out->overlap = pl.overlap;
   out->attn_wgs = pl.attn_wgs;
   out->gemm_tile = pl.gemm_tile;
+  for (int i = 0; i < out->n_nano && i < 8; ++i) {
+    out->nano_attn_wgs[i] = pl.nano_attn_wgs.empty() ? pl.attn_wgs : pl.nano_attn_wgs[(size_t)i];
+    out->order[i] = pl.order.empty() ? i : pl.order[(size_t)i];
+  }
   out->est_us = pl.est_us;
   out->est_us_stage1 = pl.est_us_stage1;
   out->est_us_unsplit = pl.est_us_unsplit;
@@ -505,6 +509,42 @@ extern "C" int nf_simulate_pipeline(const nf_model_desc* model, const nf_batch* 
   return NF_EINVAL;
 }
 
+extern "C" int nf_simulate_pipeline_ops(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
+                                        int n_nano, const int32_t* bounds, const int32_t* rp_rows,
+                                        const int32_t* order, double* est_us) try {
+  if (!est_us || !bounds || !rp_rows || n_nano < 1 || n_nano > 8) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  NfProfile prof;
+  if (!profile_path) return NF_EINVAL;  // per-row simulation needs a table
+  rc = nf_profile_load(&prof, profile_path);
+  if (rc) return rc;
+  if (bounds[0] != 0 || bounds[n_nano] != batch->n_tokens) return NF_EPLAN;
+  for (int i = 0; i < n_nano; ++i)
+    if (bounds[i + 1] <= bounds[i]) return NF_EPLAN;
+  std::vector<const NfRpRow*> rows;
+  std::vector<int> ord;
+  for (int i = 0; i < n_nano; ++i) {
+    if (rp_rows[i] < 0 || rp_rows[i] >= (int)prof.rp.size()) return NF_EINVAL;
+    rows.push_back(&prof.rp[(size_t)rp_rows[i]]);
+    if (order) ord.push_back(order[i]);
+  }
+  NfSearchInput in;
+  build_search_input(model, batch, 0, prof.granule, &in);
+  const std::vector<int> b(bounds, bounds + n_nano + 1);
+  double t = nf_simulate_ops(prof, in, b, rows, ord, 1);
+  if (t >= 0 && in.layers > 1) t = (nf_simulate_ops(prof, in, b, rows, ord, in.layers) - t) / (in.layers - 1);
+  if (t < 0) return NF_EPLAN;
+  *est_us = t;
+  return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
 extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
                                    int granule, nf_plan** out) try {
   if (!ctx || !out || granule < 1 || max_nano < 0) return NF_EINVAL;
@@ -521,7 +561,19 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   rc = nf_search(*prof, in, &pl);
   if (rc) return rc;
   std::vector<int32_t> b32(pl.bounds.begin(), pl.bounds.end());
-  rc = nf_plan_manual(ctx, model, batch, (int)b32.size() - 1, b32.data(), pl.overlap, 0, 0, pl.attn_wgs, out);
+  const int n_nano = (int)b32.size() - 1;
+  if (pl.nano_attn_wgs.empty() && pl.order.empty()) {
+    rc = nf_plan_manual(ctx, model, batch, n_nano, b32.data(), pl.overlap, 0, 0, pl.attn_wgs, out);
+  } else {
+    std::vector<nf_nano_spec> spec((size_t)n_nano);
+    for (int i = 0; i < n_nano; ++i) {
+      memset(&spec[(size_t)i], 0, sizeof(nf_nano_spec));
+      spec[(size_t)i].attn_wgs = pl.nano_attn_wgs.empty() ? pl.attn_wgs : pl.nano_attn_wgs[(size_t)i];
+    }
+    for (int k = 0; k < n_nano && !pl.order.empty(); ++k) spec[(size_t)pl.order[(size_t)k]].launch_pos = k;
+    rc = nf_plan_manual_ops(ctx, model, batch, n_nano, b32.data(), pl.overlap, 0, 0, spec.data(), out);
+    if (rc == NF_OK) (*out)->attn_wgs = pl.attn_wgs;
+  }
   if (rc) return rc;
   (*out)->origin = prof->measured ? "search(measured profile)" : "search(analytic profile)";
   (*out)->est_time_us = pl.est_us;

@@ -226,6 +226,42 @@ def test_nano_batched_and_overlapped_are_bit_exact_with_unsplit(ctx):
             plan.close()
 
 
+def test_per_nano_operation_shares_and_launch_order_are_bit_exact(ctx):
+    """Every attention nano-operation with its own workgroup count, every nano-operation with its
+    own GEMM implementation, the nano-batches launched in another order (Sec. 4.1.1 - 4.1.3): the
+    same bits as unsplit, for one layer and for a chain of layers; an order that would launch an
+    attention nano-operation before the KQV of the earlier part of its prefill request is refused."""
+    cfg = wl.CONFIGS["C1"]
+    b = wl.make_batch(cfg.batch, cfg.seed + 2)
+    case = Case(cfg.model, b, cfg.seed, ctx=ctx)
+    z0, p0 = case.run(None)
+    bounds = [0, 20, 41, 64]                     # 20 cuts the third prefill request (tokens 16..23)
+    tiles = [[7, 22, 21, 19], [0, 0, 0, 0], [24, 25, 22, 13]]
+    for wgs, pos in (([0, 3, -1], None), ([5, 0, 2], [0, 2, 1]), ([0, 0, 0], [1, 2, 0]), ([2, 7, 1], [1, 2, 0])):
+        plan = nf.nf_plan_manual_ops(case.ctx, cfg.model, case.args, bounds, True, wgs, tiles, launch_pos=pos)
+        d = plan.describe()
+        say("plan", d["nano_attn_wgs"], d["order"])
+        assert d["nano_attn_wgs"] == wgs
+        for rep in range(2):
+            z, p = case.run(plan)
+            assert np.array_equal(z, z0) and np.array_equal(p, p0), (wgs, pos)
+        plan.close()
+    with pytest.raises(nf.NfError) as e:       # nano-batch 1 first: its attention needs the KQV of nano-batch 0
+        nf.nf_plan_manual_ops(case.ctx, cfg.model, case.args, bounds, True, [0, 0, 0], None, launch_pos=[1, 0, 2])
+    assert e.value.status == nf.NF_EPLAN
+    with pytest.raises(nf.NfError) as e:       # not a permutation
+        nf.nf_plan_manual_ops(case.ctx, cfg.model, case.args, bounds, True, [0, 0, 0], None, launch_pos=[1, 1, 2])
+    assert e.value.status == nf.NF_EPLAN
+    chain = ChainCase(cfg.model, b, cfg.seed, 3, ctx=ctx)
+    z_ref, pools_ref = chain.run_layer_by_layer()
+    plan = nf.nf_plan_manual_ops(chain.ctx, cfg.model, chain.args, bounds, True, [4, 0, 9], tiles, launch_pos=[0, 2, 1])
+    z, pools = chain.run_chain(plan)
+    assert np.array_equal(z, z_ref)
+    for l in range(3):
+        assert np.array_equal(pools[l], pools_ref[l]), l
+    plan.close()
+
+
 def test_two_segment_down_projection_is_bit_exact_in_both_launch_forms(ctx):
     """A model whose down projection has a long K (ffn_inner 8192 over hidden 512) sums the two
     halves of K separately.  With the layer's workspace the halves may run on different
