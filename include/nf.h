@@ -191,6 +191,9 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * key "search.rank": 0 (default) = the search returns its best pipeline; r in 1..64 = the best
  * pipeline of the r-th best row of the R -> P table (1 = the best row), whatever its estimate
  * (unsplit when there are fewer rows), so that a caller can refine the model's choice with trial runs.
+ * key "search.refine": 1 (default) = after the search over (structure, one R -> P row) the share of
+ * every attention nano-operation and the launch order of the nano-batches are refined; 0 = one row
+ * for all nano-operations, index order.
  * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 / 21 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
  * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.

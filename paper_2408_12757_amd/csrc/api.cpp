@@ -141,6 +141,11 @@ extern "C" int nf_tune_set(const char* key, int value) {
     nf_set_search_rank(value);
     return NF_OK;
   }
+  if (!strcmp(key, "search.refine")) {
+    if (value < 0 || value > 1) return NF_EINVAL;
+    nf_set_search_refine(value);
+    return NF_OK;
+  }
   if (!strcmp(key, "search.layers")) {
     if (value < 1 || value > 16) return NF_EINVAL;
     nf_set_search_layers(value);

@@ -106,6 +106,7 @@ int nf_get_lane_stream(nf_ctx* ctx, int lane, int first_cu, int n_cus, hipStream
 void nf_profile_free(nf_ctx* ctx);
 void nf_set_search_layers(int n);
 void nf_set_search_rank(int r);
+void nf_set_search_refine(int v);
 int nf_search_layers();
 extern "C" int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b1, int e1);
 extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan);

@@ -412,7 +412,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     // nano-operation in turn tries the other rows measured with the same GEMM implementation, and
     // the launch order tries every permutation the dependencies allow; changes that shorten the
     // estimate are kept until none does.  A few hundred simulations at most.
-    if (!prof.rp.empty()) {
+    if (!prof.rp.empty() && in.refine) {
       const int n = (int)out->bounds.size() - 1;
       std::vector<const NfRpRow*> same_tile;
       const NfRpRow* start = nullptr;

@@ -62,6 +62,7 @@ struct NfSearchInput {
   int max_nano = 0;                  // 0 = search up to NF_MAX_NANO
   int layers = 1;                    // > 1: minimise the time per layer of that many consecutive layers
   int rank = 0;                      // 0: the best pipeline; r > 0: the r-th best table row's pipeline
+  int refine = 1;                    // second pass of Stage II: share per attention nano-operation and launch order
   std::vector<double> attn_mb_prefix;  // [n_tokens + 1] prefix sums of attention megabytes per token
   std::vector<int> req_start_of_tok;   // [n_tokens] first token of the request that owns token t
 };

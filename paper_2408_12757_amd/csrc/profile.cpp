@@ -19,6 +19,8 @@ int nf_search_layers() { return g_search_layers; }
 // Which of the ranked candidates the search returns (tuning knob "search.rank").
 static int g_search_rank = 0;
 void nf_set_search_rank(int r) { g_search_rank = r; }
+static int g_search_refine = 1;
+void nf_set_search_refine(int v) { g_search_refine = v; }
 
 void nf_profile_free(nf_ctx* ctx) {
   delete ctx->profile;
@@ -387,6 +389,7 @@ void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano,
   in->max_nano = max_nano;
   in->layers = nf_search_layers();
   in->rank = g_search_rank;
+  in->refine = g_search_refine;
   in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
   in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
   const double tok_mb = 2.0 * m->n_kv_heads * m->head_dim * 2 / 1e6;
