@@ -389,7 +389,7 @@ def main():
     verify = {"unsplit_ms": t_u, "trials": []}
     kept_ms = t_u
     kept_plan = unsplit_plan
-    for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 7) for f in (1, 0)]:
+    for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 11) for f in (1, 0)]:
         nf.nf_tune_set("search.rank", rank)
         nf.nf_tune_set("search.refine", refine)
         try:
@@ -528,7 +528,7 @@ def main():
         # the auto-search with the time per layer of L consecutive layers as its objective; the
         # model's ranking of the R -> P rows is then refined by trial runs of its best candidates
         trials, best_chain = [], None
-        for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 7) for f in (1, 0)]:
+        for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 11) for f in (1, 0)]:
             nf.nf_tune_set("search.layers", L)
             nf.nf_tune_set("search.rank", rank)
             nf.nf_tune_set("search.refine", refine)

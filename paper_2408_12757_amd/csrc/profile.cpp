@@ -359,14 +359,15 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
       }
       for (auto& e : ev) (void)hipEventDestroy(e);
     }
-    // discard dominated pairs: another pair is at least as good for both kernels
-    // (Sec. 4.1.1, the greyed-out pairs)
+    // discard dominated pairs: another pair is better for both kernels (Sec. 4.1.1, the
+    // greyed-out pairs) - by more than the few per cent that two measurements of one pair differ
+    // by, so that a pair within the noise of its neighbour stays a candidate of the search
+    constexpr double kNoise = 1.03;
     std::vector<NfRpRow> keep;
     for (const NfRpRow& r : p->rp) {
       bool dominated = false;
       for (const NfRpRow& q : p->rp)
-        if (&q != &r && q.p_gemm >= r.p_gemm && q.p_attn >= r.p_attn && (q.p_gemm > r.p_gemm || q.p_attn > r.p_attn))
-          dominated = true;
+        if (&q != &r && q.p_gemm >= kNoise * r.p_gemm && q.p_attn >= kNoise * r.p_attn) dominated = true;
       if (!dominated) keep.push_back(r);
     }
     p->rp = keep;
