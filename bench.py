@@ -372,7 +372,7 @@ def main():
     best_plan = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
     t_search = time.perf_counter() - t0
     best_desc = best_plan.describe()
-    plan_keys = ("origin", "bounds", "overlap", "attn_wgs", "nano_attn_wgs", "order", "est_time_us")
+    plan_keys = ("origin", "bounds", "overlap", "attn_wgs", "nano_attn_wgs", "order", "partitions", "est_time_us")
     best_c = {k: best_desc[k] for k in plan_keys}
     searched_c = dict(best_c)
     # the ablation of Sec. 6.4 on a fixed two-nano-batch structure
@@ -389,18 +389,18 @@ def main():
     verify = {"unsplit_ms": t_u, "trials": []}
     kept_ms = t_u
     kept_plan = unsplit_plan
-    for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 11) for f in (1, 0)]:
+    for rank, refine in [(0, 2)] + [(r, f) for r in range(1, 11) for f in (2, 1, 0)]:
         nf.nf_tune_set("search.rank", rank)
         nf.nf_tune_set("search.refine", refine)
         try:
             pl = best_plan if rank == 0 else nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
         finally:
             nf.nf_tune_set("search.rank", 0)
-            nf.nf_tune_set("search.refine", 1)
+            nf.nf_tune_set("search.refine", 2)
         d = pl.describe()
-        rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "est_time_us")}
+        rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "partitions", "est_time_us")}
         rec["gemm_tiles"] = sorted({o["gemm_tile"] for o in d["ops"] if o["op"] != "ATTN"})
-        if len(d["bounds"]) <= 2 or any(all(t[k] == rec[k] for k in ("bounds", "nano_attn_wgs", "order", "gemm_tiles"))
+        if len(d["bounds"]) <= 2 or any(all(t[k] == rec[k] for k in ("bounds", "nano_attn_wgs", "order", "partitions", "gemm_tiles"))
                                         for t in verify["trials"]):
             if pl is not best_plan:
                 pl.close()
@@ -528,7 +528,7 @@ def main():
         # the auto-search with the time per layer of L consecutive layers as its objective; the
         # model's ranking of the R -> P rows is then refined by trial runs of its best candidates
         trials, best_chain = [], None
-        for rank, refine in [(0, 1)] + [(r, f) for r in range(1, 11) for f in (1, 0)]:
+        for rank, refine in [(0, 2)] + [(r, f) for r in range(1, 11) for f in (2, 1, 0)]:
             nf.nf_tune_set("search.layers", L)
             nf.nf_tune_set("search.rank", rank)
             nf.nf_tune_set("search.refine", refine)
@@ -537,11 +537,11 @@ def main():
             finally:
                 nf.nf_tune_set("search.layers", 1)
                 nf.nf_tune_set("search.rank", 0)
-                nf.nf_tune_set("search.refine", 1)
+                nf.nf_tune_set("search.refine", 2)
             d = pl.describe()
-            rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "est_time_us")}
+            rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "partitions", "est_time_us")}
             rec["gemm_tiles"] = sorted({o["gemm_tile"] for o in d["ops"] if o["op"] != "ATTN"})
-            if any(all(t[k] == rec[k] for k in ("bounds", "nano_attn_wgs", "order", "gemm_tiles")) for t in trials):
+            if any(all(t[k] == rec[k] for k in ("bounds", "nano_attn_wgs", "order", "partitions", "gemm_tiles")) for t in trials):
                 pl.close()
                 continue
             rec["ms_per_layer"] = chain_ms(pl, reps=3)

@@ -191,9 +191,11 @@ int nf_ctx_mask_stream(nf_ctx *ctx, const uint32_t *mask, int words, void **out)
  * key "search.rank": 0 (default) = the search returns its best pipeline; r in 1..64 = the best
  * pipeline of the r-th best row of the R -> P table (1 = the best row), whatever its estimate
  * (unsplit when there are fewer rows), so that a caller can refine the model's choice with trial runs.
- * key "search.refine": 1 (default) = after the search over (structure, one R -> P row) the share of
- * every attention nano-operation and the launch order of the nano-batches are refined; 0 = one row
- * for all nano-operations, index order.
+ * key "search.refine": after the search over (structure, one R -> P row), 1 = the share of every
+ * attention nano-operation and the launch order of the nano-batches are refined; 2 (default) = then
+ * also the number of nano-operations of every operation (a partition per operation, at most
+ * "search.max_parts" = 1..8 nano-operations each, 0 = 8); 0 = one row for all nano-operations, index
+ * order, common boundaries.
  * key "gemm.grouped_tile": 0 = automatic, 1 / 7 / 9 / 11 / 12 / 13 / 19 / 21 = force
  * the implementation of the grouped (mixture-of-experts) GEMM.  key "gemm.ksplit": 0 = automatic, 1 / 2 = run a dense operation whose K is
  * summed in two segments (see nf_op_gemm) always with one / with two workgroups per output tile.
@@ -273,6 +275,15 @@ int nf_plan_nanobatches(nf_ctx *ctx, const nf_model_desc *model, const nf_batch 
  * of a row of the profile's R -> P table (Stage II: overlapped kernels run at p_gemm and
  * p_attn of their stand-alone speed, so a nano-operation takes D_best / P, Sec. 4.1.3).
  */
+/* A token partition per operation (Sec. 4.1.2: the number of nano-operations and their sizes are
+ * decided per operation).  Index k: 0 KQV, 1 attention, 2 O, 3 Up/Gate, 4 Down.  Operation k has
+ * n[k] nano-operations (1..8) with token boundaries bounds[k][0] = 0 < ... < bounds[k][n[k]] =
+ * n_tokens.  Nano-operations depend on each other by the rule of nf_nano_ops_dependent. */
+typedef struct nf_partitions {
+  int32_t n[5];
+  int32_t bounds[5][9];
+} nf_partitions;
+
 typedef struct nf_pipeline_desc {
   int32_t n_nano;
   int32_t bounds[9];      /* n_nano + 1 token boundaries                                */
@@ -282,6 +293,9 @@ typedef struct nf_pipeline_desc {
   int32_t reserved;
   int32_t nano_attn_wgs[8]; /* the share per attention nano-operation (Sec. 4.1.1: R per nano-operation) */
   int32_t order[8];       /* launch order: order[k] = index of the nano-batch launched k-th    */
+  nf_partitions parts;    /* n[] all zero: every operation is split at `bounds`; otherwise the partition
+                             of every operation (then bounds / nano_attn_wgs are the attention
+                             operation's, and the order is that of nf_plan_manual_parts)           */
   double est_us;          /* modelled makespan with interference                         */
   double est_us_stage1;   /* same structure without interference                         */
   double est_us_unsplit;  /* the unsplit sequential layer                                */
@@ -297,6 +311,13 @@ int nf_simulate_pipeline(const nf_model_desc *model, const nf_batch *batch, cons
 int nf_simulate_pipeline_ops(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
                              int n_nano, const int32_t *bounds, const int32_t *rp_rows, const int32_t *order,
                              double *est_us);
+
+/* The pipeline with a partition per operation, launched in the order of nf_plan_manual_parts.
+ * overlap as in nf_simulate_pipeline; rp_rows: one row index of the profile's R -> P table per
+ * attention nano-operation (rows of one GEMM implementation), or NULL for no interference
+ * (profile_path may then be NULL too).  NF_EPLAN for invalid partitions. */
+int nf_simulate_pipeline_parts(const nf_model_desc *model, const nf_batch *batch, const char *profile_path,
+                               const nf_partitions *parts, int overlap, const int32_t *rp_rows, double *est_us);
 
 /* Dependency rule of Sec. 4.1.2: 1 iff the parent operations are dependent (kinds: 0 KQV,
  * 1 ATTN, 2 O, 3 UG, 4 D; KQV -> ATTN -> O -> UG -> D) and the token ranges [b0,e0) and
@@ -344,6 +365,24 @@ typedef struct nf_nano_spec {
 int nf_plan_manual_ops(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch, int n_nano,
                        const int32_t *bounds, int overlap, int attn_cus, int gemm_cus,
                        const nf_nano_spec *spec, nf_plan **out);
+
+/*
+ * Explicit pipeline structure with a partition per operation (Sec. 4.1.2; Fig. 6 shows such
+ * pipelines: the operations near a bubble are split into more nano-operations than the others).
+ * Launch order of a layer: the KQV nano-operations in range order, each attention nano-operation
+ * right behind the KQV nano-operation that launches the last of its tokens; then the O, Up/Gate
+ * and Down nano-operations, always the one with the smallest last token among those whose input
+ * rows have all been launched (ties: O, then Up/Gate, then Down).  Equal partitions give the order
+ * of nf_plan_manual.  overlap, attn_cus, gemm_cus as in nf_plan_manual.
+ * attn_wgs : host array, one entry per attention nano-operation (NULL = 0 for all).
+ * gemm_tile: host array of 4 (KQV, O, Up/Gate, Down; NULL = automatic).
+ * Mixture-of-experts layers need equal Up/Gate and Down partitions (NF_EPLAN otherwise): the rows
+ * of a Down nano-operation are the (token, expert) rows its Up/Gate nano-operation grouped.
+ * Results do not depend on the partitions by a single bit.
+ */
+int nf_plan_manual_parts(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch,
+                         const nf_partitions *parts, int overlap, int attn_cus, int gemm_cus,
+                         const int32_t *attn_wgs, const int32_t *gemm_tile, nf_plan **out);
 
 /* Writes a JSON description of the plan into buf (host); returns the number of
  * bytes needed (excluding the terminator), or a negative status. */

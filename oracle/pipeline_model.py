@@ -19,6 +19,11 @@ nano-operation currently on the memory resource - and the nano-batches may be la
 ``order`` whose dependencies can be met (Sec. 4.1.2: number, size and order of the
 nano-operations are what the search decides).
 
+Sec. 4.1.2 also lets every operation have its own number of nano-operations (Fig. 6: the
+operations near a bubble are split further than the others).  ``makespan_parts`` models that:
+one token partition per operation, the dependency rule above between the pieces, and the launch
+order stated in ``launch_order``.
+
 It is written as a fixed-step time integration - slow and plain - so that it can check the
 event-driven C++ implementation.
 """
@@ -176,3 +181,140 @@ def brute_force(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_sta
                 if t < best[0]:
                     best = (t, b, r)
     return best, unsplit
+
+
+KINDS = ("KQV", "ATTN", "O", "UG", "D")
+FEEDS = {"ATTN": "KQV", "O": "ATTN", "UG": "O", "D": "UG"}      # child operation -> parent operation
+
+
+def launch_order(parts: dict) -> list:
+    """Order in which one layer's nano-operations are handed to the device when every operation
+    has its own partition ``parts[kind]`` (boundaries from 0 to the number of tokens).
+    KQV pieces go first, in token order, and an attention piece is launched as soon as the KQV
+    piece holding its last token has been launched.  Then the O, Up/Gate and Down pieces: among
+    the pieces whose input rows have all been launched, the one that ends at the smallest token
+    goes next, and O goes before Up/Gate before Down when they end at the same token."""
+    seq = []
+    attn_left = list(range(len(parts["ATTN"]) - 1))
+    for k in range(len(parts["KQV"]) - 1):
+        seq.append(("KQV", k))
+        while attn_left and parts["ATTN"][attn_left[0] + 1] <= parts["KQV"][k + 1]:
+            seq.append(("ATTN", attn_left.pop(0)))
+    waiting = {kind: list(range(len(parts[kind]) - 1)) for kind in ("O", "UG", "D")}
+    launched_up_to = {"ATTN": parts["ATTN"][-1], "O": 0, "UG": 0, "D": 0}
+    while any(waiting.values()):
+        ready = []
+        for rank, kind in enumerate(("O", "UG", "D")):
+            if waiting[kind]:
+                end = parts[kind][waiting[kind][0] + 1]
+                if launched_up_to[FEEDS[kind]] >= end:
+                    ready.append((end, rank, kind))
+        end, _, kind = min(ready)
+        seq.append((kind, waiting[kind].pop(0)))
+        launched_up_to[kind] = end
+    return seq
+
+
+def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, parts: dict, overlap,
+                   rows: Optional[list] = None, dt: float = 0.02, misc=None, layers: int = 1) -> float:
+    """``makespan`` with a partition per operation.  rows: one table row per attention piece (the
+    row of the attention piece at the head of the memory resource decides the speeds; all rows
+    belong to one GEMM implementation) or None for no interference.  The small kernels of ``misc``
+    are charged to the KQV pieces, to the Up/Gate pieces (the norm in front of them) and to the
+    attention pieces.  layers > 1: the KQV piece of the next layer is launched right behind the
+    Down piece of this layer that completes its tokens."""
+    if rows is not None and overlap and rows[0].get("dense") is not None:
+        dense = rows[0]["dense"]
+        rows = [dict(r, p_gemm=r["p_gemm"] / r.get("p_gemm_solo", 1.0), p_gemm_solo=1.0) for r in rows]
+    table = {"KQV": "KQV", "O": "O", "UG": "UG", "D": "D"}
+    extra = {"KQV": 0, "UG": 1, "ATTN": 2}
+    work, span = {}, {}
+    for kind in KINDS:
+        for j in range(len(parts[kind]) - 1):
+            lo, hi = parts[kind][j], parts[kind][j + 1]
+            span[(kind, j)] = (lo, hi)
+            if kind == "ATTN":
+                w = attn_fixed + attn_per_mb * (attn_mb_prefix[hi] - attn_mb_prefix[lo])
+            else:
+                w = interp_dense(dense[table[kind]], granule, hi - lo)
+            if misc is not None and kind in extra:
+                w += misc[extra[kind]][0] + misc[extra[kind]][1] * (hi - lo)
+            work[(kind, j)] = w
+    seq = launch_order(parts)
+    if not overlap:
+        return sum(work[p] for p in seq) * layers
+    compute, memory = [(kind, j, 0) for kind, j in seq if kind == "KQV"], []
+    for l in range(layers):
+        next_layer_kqv = [(kind, j) for kind, j in seq if kind == "KQV"]
+        for kind, j in seq:
+            if kind in ("O", "UG", "D"):
+                compute.append((kind, j, l))
+            if kind == "D" and l + 1 < layers:
+                while next_layer_kqv and span[next_layer_kqv[0]][1] <= span[(kind, j)][1]:
+                    compute.append((*next_layer_kqv.pop(0), l + 1))
+        memory += [(kind, j, l) for kind, j in seq if kind == "ATTN"]
+    done = set()
+
+    def ready(op):
+        kind, j, l = op
+        if kind == "KQV":
+            return True                       # queued behind the Down pieces that complete its rows
+        lo, hi = span[(kind, j)]
+        if kind == "ATTN":
+            lo = req_start[lo]                # it also reads K/V appended by the request's earlier tokens
+        parent = FEEDS[kind]
+        return all((parent, i, l) in done for i in range(len(parts[parent]) - 1)
+                   if max(lo, parts[parent][i]) < min(hi, parts[parent][i + 1]))
+
+    left = {(kind, j, l): work[(kind, j)] for (kind, j) in work for l in range(layers)}
+    t = 0.0
+    ci = mi = 0
+    while ci < len(compute) or mi < len(memory):
+        c = compute[ci] if ci < len(compute) and ready(compute[ci]) else None
+        m = memory[mi] if mi < len(memory) and ready(memory[mi]) else None
+        assert c is not None or m is not None, "deadlock"
+        sc = sm = 1.0
+        if rows is not None:
+            cur = rows[memory[mi][1]] if mi < len(memory) else rows[-1]
+            if c is not None and m is not None:
+                sc, sm = cur["p_gemm"], cur["p_attn"]
+            elif m is not None:
+                sm = cur["p_attn_solo"]
+            else:
+                sc = cur.get("p_gemm_solo", 1.0)
+        if c is not None:
+            left[c] -= sc * dt
+            if left[c] <= 0:
+                done.add(c)
+                ci += 1
+        if m is not None:
+            left[m] -= sm * dt
+            if left[m] <= 0:
+                done.add(m)
+                mi += 1
+        t += dt
+    return t
+
+
+def all_partitions(n_tokens: int, granule: int, max_pieces: int) -> List[List[int]]:
+    out = []
+    for n in range(1, max_pieces + 1):
+        out += all_bounds(n_tokens, granule, n) if n > 1 else [[0, n_tokens]]
+    return out
+
+
+def brute_force_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, n_tokens, rows, max_pieces,
+                      dt: float = 0.05, misc=None):
+    """Minimum makespan over every choice of a partition per operation (at most max_pieces pieces
+    each) and of a table row per attention piece."""
+    options = all_partitions(n_tokens, granule, max_pieces)
+    best = None
+    for combo in itertools.product(options, repeat=len(KINDS)):
+        parts = dict(zip(KINDS, combo))
+        n_attn = len(parts["ATTN"]) - 1
+        for assign in (itertools.product(rows, repeat=n_attn) if rows else [None]):
+            t = makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, parts, True,
+                               list(assign) if assign is not None else None, dt, misc)
+            if best is None or t < best[0]:
+                best = (t, parts, assign)
+    return best

@@ -30,6 +30,7 @@ EXPORTS = [
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
     "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency", "nf_simulate_pipeline_ops",
+    "nf_plan_manual_parts", "nf_simulate_pipeline_parts",
 ]
 
 
@@ -56,11 +57,15 @@ class nf_batch(C.Structure):
                 ("host_page_indptr", C.c_void_p), ("host_page_ids", C.c_void_p)]
 
 
+class nf_partitions(C.Structure):
+    _fields_ = [("n", C.c_int32 * 5), ("bounds", (C.c_int32 * 9) * 5)]
+
+
 class nf_pipeline_desc(C.Structure):
     _fields_ = [("n_nano", C.c_int32), ("bounds", C.c_int32 * 9), ("overlap", C.c_int32), ("attn_wgs", C.c_int32),
                 ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("nano_attn_wgs", C.c_int32 * 8),
-                ("order", C.c_int32 * 8), ("est_us", C.c_double), ("est_us_stage1", C.c_double),
-                ("est_us_unsplit", C.c_double)]
+                ("order", C.c_int32 * 8), ("parts", nf_partitions), ("est_us", C.c_double),
+                ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
 
 
 class nf_nano_spec(C.Structure):
@@ -123,6 +128,10 @@ def lib() -> C.CDLL:
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_manual_ops.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32,
                                      P(nf_nano_spec), P(vp)]
+    L.nf_plan_manual_parts.argtypes = [vp, P(nf_model_desc), P(nf_batch), P(nf_partitions), i32, i32, i32,
+                                       P(C.c_int32), P(C.c_int32), P(vp)]
+    L.nf_simulate_pipeline_parts.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, P(nf_partitions), i32,
+                                             P(C.c_int32), P(C.c_double)]
     L.nf_probe_load_latency.argtypes = [vp, i32, i32, vp, vp]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
     L.nf_plan_destroy.argtypes = [vp]
@@ -300,6 +309,62 @@ def nf_plan_manual_ops(ctx: Context, model, batch: BatchArgs, bounds: Sequence[i
     return Plan(ctx, h)
 
 
+PART_KINDS = ("KQV", "ATTN", "O", "UG", "D")
+
+
+def _partitions(parts) -> nf_partitions:
+    """parts: five boundary lists (KQV, attention, O, Up/Gate, Down) or a dict keyed by PART_KINDS."""
+    if isinstance(parts, dict):
+        parts = [parts[k] for k in PART_KINDS]
+    c = nf_partitions()
+    for k in range(5):
+        b = [int(v) for v in parts[k]]
+        if not 2 <= len(b) <= 9:
+            raise ValueError("an operation has 1..8 nano-operations")
+        c.n[k] = len(b) - 1
+        for i, v in enumerate(b):
+            c.bounds[k][i] = v
+    return c
+
+
+def nf_plan_manual_parts(ctx: Context, model, batch: BatchArgs, parts, overlap: bool,
+                         attn_wgs: "Optional[Sequence[int]]" = None, gemm_tile: "Optional[Sequence[int]]" = None,
+                         attn_cus: int = 0, gemm_cus: int = 0) -> Plan:
+    """A partition per operation; attn_wgs[i] = share of attention nano-operation i; gemm_tile = (KQV, O,
+    Up/Gate, Down) implementations."""
+    c = _partitions(parts)
+    w = _np_i32(attn_wgs) if attn_wgs is not None else None
+    g = _np_i32(gemm_tile) if gemm_tile is not None else None
+    if w is not None and len(w) != c.n[1]:
+        raise ValueError("attn_wgs needs one entry per attention nano-operation")
+    if g is not None and len(g) != 4:
+        raise ValueError("gemm_tile needs four entries")
+    h = C.c_void_p()
+    md = model_desc(model)
+    _check(lib().nf_plan_manual_parts(ctx.handle, C.byref(md), C.byref(batch.struct), C.byref(c), int(bool(overlap)),
+                                      int(attn_cus), int(gemm_cus),
+                                      w.ctypes.data_as(C.POINTER(C.c_int32)) if w is not None else None,
+                                      g.ctypes.data_as(C.POINTER(C.c_int32)) if g is not None else None, C.byref(h)),
+           "nf_plan_manual_parts", ctx)
+    return Plan(ctx, h)
+
+
+def nf_simulate_pipeline_parts(model, batch: BatchArgs, parts, overlap: bool,
+                               rp_rows: "Optional[Sequence[int]]" = None, profile_path: Optional[str] = None) -> float:
+    md = model_desc(model)
+    c = _partitions(parts)
+    r = _np_i32(rp_rows) if rp_rows is not None else None
+    if r is not None and len(r) != c.n[1]:
+        raise ValueError("rp_rows needs one entry per attention nano-operation")
+    est = C.c_double()
+    _check(lib().nf_simulate_pipeline_parts(C.byref(md), C.byref(batch.struct),
+                                            profile_path.encode() if profile_path else None, C.byref(c),
+                                            int(bool(overlap)),
+                                            r.ctypes.data_as(C.POINTER(C.c_int32)) if r is not None else None,
+                                            C.byref(est)), "nf_simulate_pipeline_parts")
+    return est.value
+
+
 def nf_plan_nanobatches(ctx: Context, model, batch: BatchArgs, max_nano: int = 0, granule: int = 128) -> Plan:
     h = C.c_void_p()
     md = model_desc(model)
@@ -317,7 +382,9 @@ def nf_search_pipeline(model, batch: BatchArgs, profile_path: Optional[str] = No
     return dict(bounds=[int(out.bounds[i]) for i in range(out.n_nano + 1)], overlap=int(out.overlap),
                 attn_wgs=int(out.attn_wgs), gemm_tile=int(out.gemm_tile), est_us=out.est_us, est_us_stage1=out.est_us_stage1,
                 est_us_unsplit=out.est_us_unsplit, nano_attn_wgs=[int(out.nano_attn_wgs[i]) for i in range(out.n_nano)],
-                order=[int(out.order[i]) for i in range(out.n_nano)])
+                order=[int(out.order[i]) for i in range(out.n_nano)],
+                parts=[[int(out.parts.bounds[k][i]) for i in range(out.parts.n[k] + 1)] for k in range(5)]
+                if out.parts.n[0] > 0 else None)
 
 
 def nf_simulate_pipeline(model, batch: BatchArgs, bounds: Sequence[int], overlap: bool, rp_row: int = -1,

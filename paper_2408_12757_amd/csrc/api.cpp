@@ -142,8 +142,13 @@ extern "C" int nf_tune_set(const char* key, int value) {
     return NF_OK;
   }
   if (!strcmp(key, "search.refine")) {
-    if (value < 0 || value > 1) return NF_EINVAL;
+    if (value < 0 || value > 2) return NF_EINVAL;
     nf_set_search_refine(value);
+    return NF_OK;
+  }
+  if (!strcmp(key, "search.max_parts")) {
+    if (value < 0 || value > 8) return NF_EINVAL;
+    nf_set_search_max_parts(value);
     return NF_OK;
   }
   if (!strcmp(key, "search.layers")) {
@@ -506,21 +511,26 @@ struct Offload {
 
 int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, hipStream_t user) {
   Offload off{ctx};
-  std::vector<hipEvent_t> copied(p->ops.size(), nullptr);  // per KQV nano-op: its latest offload copy
-  // the KQV nano-op that produced the qkv rows of an attention nano-op (same nano-batch)
-  auto kqv_of = [&](const NfNanoOp& attn) -> size_t {
-    for (size_t j = 0; j < p->ops.size(); ++j)
-      if (p->ops[j].kind == NF_OP_KQV && p->ops[j].nano == attn.nano) return j;
-    return 0;
+  // per attention nano-op: the latest offload copy of its qkv rows.  A KQV nano-op overwrites qkv
+  // rows, so it waits for the copies of the attention nano-ops whose rows it shares.
+  std::vector<hipEvent_t> copied(p->ops.size(), nullptr);
+  auto wait_for_copies = [&](const NfNanoOp& kqv, hipStream_t s) -> hipError_t {
+    for (size_t j = 0; j < p->ops.size(); ++j) {
+      const NfNanoOp& at = p->ops[j];
+      if (at.kind != NF_OP_ATTN || !copied[j]) continue;
+      if (std::max(at.tok_begin, kqv.tok_begin) >= std::min(at.tok_end, kqv.tok_end)) continue;
+      hipError_t e = hipStreamWaitEvent(s, copied[j], 0);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   };
   if (!p->overlap) {
     for (int l = 0; l < n_layers; ++l)
       for (size_t i = 0; i < p->ops.size(); ++i) {
         const NfNanoOp& op = p->ops[i];
-        if (op.kind == NF_OP_KQV && copied[i]) NF_HIP(ctx, hipStreamWaitEvent(user, copied[i], 0));
+        if (op.kind == NF_OP_KQV) NF_HIP(ctx, wait_for_copies(op, user));
         NF_HIP(ctx, launch_nano_op(ctx, p, op, a[l], user));
-        if (op.kind == NF_OP_ATTN && off.on())
-          NF_HIP(ctx, off.after_attention(op, a[l], l, user, &copied[kqv_of(op)]));
+        if (op.kind == NF_OP_ATTN && off.on()) NF_HIP(ctx, off.after_attention(op, a[l], l, user, &copied[i]));
       }
     for (hipEvent_t e : copied)
       if (e) NF_HIP(ctx, hipStreamWaitEvent(user, e, 0));
@@ -538,26 +548,35 @@ int run_layers(nf_ctx* ctx, const nf_plan* p, const LayerArgs* a, int n_layers, 
       const std::vector<hipEvent_t>& pev = ((layer - 1) & 1) ? p->events_alt : p->events;
       NF_HIP(ctx, hipStreamWaitEvent(s, pev[after_prev_layer_op], 0));
     }
-    if (op.kind == NF_OP_KQV && copied[i]) NF_HIP(ctx, hipStreamWaitEvent(s, copied[i], 0));
+    if (op.kind == NF_OP_KQV) NF_HIP(ctx, wait_for_copies(op, s));
     NF_HIP(ctx, launch_nano_op(ctx, p, op, a[layer], s));
-    if (op.kind == NF_OP_ATTN && off.on())
-      NF_HIP(ctx, off.after_attention(op, a[layer], layer, s, &copied[kqv_of(op)]));
+    if (op.kind == NF_OP_ATTN && off.on()) NF_HIP(ctx, off.after_attention(op, a[layer], layer, s, &copied[i]));
     if (op.record) NF_HIP(ctx, hipEventRecord(ev[i], s));
     return NF_OK;
   };
+  std::vector<char> down_done((size_t)std::max(1, p->n_tokens));  // rows whose Down nano-op of this layer is issued
+  std::vector<char> hoisted(p->ops.size());                       // next layer's KQV nano-ops already issued
   for (int l = 0; l < n_layers; ++l) {
+    std::fill(down_done.begin(), down_done.end(), 0);
+    std::fill(hoisted.begin(), hoisted.end(), 0);
     for (size_t i = 0; i < p->ops.size(); ++i) {
       const NfNanoOp& op = p->ops[i];
       if (l > 0 && op.kind == NF_OP_KQV) continue;  // issued behind the previous layer's Down
       int rc = emit(l, i, -1);
       if (rc) return rc;
       if (op.kind == NF_OP_D && l + 1 < n_layers) {
+        // the next layer's KQV nano-ops whose rows are now all complete (with equal partitions:
+        // the one of the same range)
+        for (int t = op.tok_begin; t < op.tok_end; ++t) down_done[(size_t)t] = 1;
         for (size_t j = 0; j < p->ops.size(); ++j) {
           const NfNanoOp& nx = p->ops[j];
-          if (nx.kind == NF_OP_KQV && nx.tok_begin == op.tok_begin && nx.tok_end == op.tok_end) {
-            rc = emit(l + 1, j, (int)i);
-            if (rc) return rc;
-          }
+          if (nx.kind != NF_OP_KQV || hoisted[j]) continue;
+          bool complete = true;
+          for (int t = nx.tok_begin; t < nx.tok_end && complete; ++t) complete = down_done[(size_t)t] != 0;
+          if (!complete) continue;
+          hoisted[j] = 1;
+          rc = emit(l + 1, j, (int)i);
+          if (rc) return rc;
         }
       }
     }

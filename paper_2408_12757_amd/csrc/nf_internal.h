@@ -64,7 +64,8 @@ struct nf_plan {
   nf_model_desc model;
   int n_tokens = 0, n_reqs = 0, n_prefill_reqs = 0;
   uint64_t batch_sig = 0;
-  std::vector<int> bounds;  // nano-batch token boundaries, size n_nano + 1
+  std::vector<int> bounds;  // nano-batch token boundaries, size n_nano + 1 (the attention operation's when `parts` is set)
+  std::vector<int> parts[NF_OP_KINDS];  // a partition per operation (Sec. 4.1.2); all empty = `bounds` for every operation
   std::vector<NfNanoOp> ops;  // launch order
   int overlap = 0;
   int lane_cus[NF_LANES] = {0, 0};        // CU count per lane (0 = whole chip, no mask)
@@ -107,6 +108,7 @@ void nf_profile_free(nf_ctx* ctx);
 void nf_set_search_layers(int n);
 void nf_set_search_rank(int r);
 void nf_set_search_refine(int v);
+void nf_set_search_max_parts(int v);
 int nf_search_layers();
 extern "C" int nf_nano_ops_dependent(int parent_kind, int child_kind, int b0, int e0, int b1, int e1);
 extern "C" size_t nf_plan_workspace_bytes(const nf_plan* plan);

@@ -9,6 +9,7 @@
 #include <new>
 
 #include "nf_internal.h"
+#include "planner.h"
 
 // Device buffers of destroyed plans are kept for the next plans instead of being returned to
 // the driver: hipFree waits for the whole device, which would stall a caller that forms the
@@ -428,6 +429,74 @@ extern "C" int nf_plan_manual_ops(nf_ctx* ctx, const nf_model_desc* model, const
   return NF_EINVAL;
 }
 
+extern "C" int nf_plan_manual_parts(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch,
+                                    const nf_partitions* parts, int overlap, int attn_cus, int gemm_cus,
+                                    const int32_t* attn_wgs, const int32_t* gemm_tile, nf_plan** out) try {
+  if (!ctx || !out || !parts) return NF_EINVAL;
+  *out = nullptr;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  if (attn_cus < 0 || gemm_cus < 0 || attn_cus > ctx->num_cus || gemm_cus > ctx->num_cus) return NF_EINVAL;
+  if (batch->n_tokens == 0) {  // nothing to split
+    const int32_t none[2] = {0, 0};
+    return nf_plan_manual(ctx, model, batch, 1, none, overlap, attn_cus, gemm_cus, 0, out);
+  }
+  NfParts pp;
+  for (int k = 0; k < NF_OP_KINDS; ++k) {
+    if (parts->n[k] < 1 || parts->n[k] > NF_MAX_PARTS) return NF_EPLAN;
+    rc = check_bounds(batch, parts->n[k], parts->bounds[k]);
+    if (rc) return rc;
+    pp[(size_t)k].assign(parts->bounds[k], parts->bounds[k] + parts->n[k] + 1);
+  }
+  // the (token, expert) rows of a Down nano-operation are those its Up/Gate nano-operation grouped
+  if (model->n_experts > 1 && pp[NF_OP_UG] != pp[NF_OP_D]) return NF_EPLAN;
+  for (int i = 0; attn_wgs && i < parts->n[NF_OP_ATTN]; ++i)
+    if (attn_wgs[i] < -1) return NF_EINVAL;
+  for (int k = 0; gemm_tile && k < 4; ++k)
+    if (gemm_tile[k] < 0 || gemm_tile[k] > NF_MAX_TILE) return NF_EINVAL;
+  std::vector<NfEmitOp> emit;
+  if (!nf_emission_order(pp, &emit)) return NF_EPLAN;
+  nf_plan* p = new (std::nothrow) nf_plan();
+  if (!p) return NF_ENOMEM;
+  struct Guard {
+    nf_plan* p;
+    ~Guard() { nf_plan_destroy(p); }
+  } guard{p};
+  p->model = *model;
+  p->origin = "manual";
+  p->bounds = pp[NF_OP_ATTN];  // the attention work lists and shares are per attention nano-operation
+  for (int k = 0; k < NF_OP_KINDS; ++k) p->parts[k] = pp[(size_t)k];
+  p->attn_wgs = attn_wgs ? attn_wgs[0] : 0;
+  for (int i = 0; i < parts->n[NF_OP_ATTN]; ++i) p->nano_attn_wgs.push_back(attn_wgs ? attn_wgs[i] : 0);
+  p->overlap = overlap ? 1 : 0;
+  for (const NfEmitOp& e : emit) {
+    static const int slot[NF_OP_KINDS] = {0, -1, 1, 2, 3};
+    NfNanoOp op;
+    op.kind = e.kind;
+    op.nano = e.index;
+    op.tok_begin = e.tok_begin;
+    op.tok_end = e.tok_end;
+    op.lane = (p->overlap && e.kind == NF_OP_ATTN) ? NF_LANE_ATTN : NF_LANE_GEMM;
+    if (gemm_tile && slot[e.kind] >= 0) op.gemm_tile = gemm_tile[slot[e.kind]];
+    p->ops.push_back(op);
+  }
+  p->lane_cus[NF_LANE_ATTN] = attn_cus;
+  p->lane_cu_first[NF_LANE_ATTN] = 0;
+  p->lane_cus[NF_LANE_GEMM] = gemm_cus;
+  p->lane_cu_first[NF_LANE_GEMM] = (gemm_cus && attn_cus + gemm_cus <= ctx->num_cus) ? attn_cus : 0;
+  rc = nf_plan_finalize(ctx, p, batch);
+  if (rc) return rc;
+  guard.p = nullptr;
+  *out = p;
+  return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
 extern "C" void nf_plan_destroy(nf_plan* p) {
   if (!p) return;
   for (hipEvent_t e : p->events)
@@ -460,7 +529,9 @@ extern "C" int nf_plan_describe(const nf_plan* p, char* buf, size_t buf_len) try
   s += "], \"attn_cus\": " + std::to_string(p->lane_cus[NF_LANE_ATTN]) +
        ", \"gemm_cus\": " + std::to_string(p->lane_cus[NF_LANE_GEMM]) +
        ", \"attn_wgs\": " + std::to_string(p->attn_wgs) + ", \"nano_attn_wgs\": " + list_json(p->nano_attn_wgs) +
-       ", \"order\": " + list_json(p->nano_order) + ", \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
+       ", \"order\": " + list_json(p->nano_order) + ", \"partitions\": [" + list_json(p->parts[0]) + ", " +
+       list_json(p->parts[1]) + ", " + list_json(p->parts[2]) + ", " + list_json(p->parts[3]) + ", " +
+       list_json(p->parts[4]) + "], \"attn_parts\": " + std::to_string(p->total_parts) + ", \"est_time_us\": " + std::to_string(p->est_time_us) +
        ", \"ops\": [";
   for (size_t a = 0; a < p->ops.size(); ++a) {
     const NfNanoOp& o = p->ops[a];

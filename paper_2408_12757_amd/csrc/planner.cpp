@@ -300,6 +300,188 @@ double nf_simulate_ops(const NfProfile& prof, const NfSearchInput& in, const std
   return simulate_impl(prof, in, bounds, 1, nullptr, &rows, &order, n_layers);
 }
 
+bool nf_emission_order(const NfParts& parts, std::vector<NfEmitOp>* out) {
+  out->clear();
+  const int end = parts[0].empty() ? -1 : parts[0].back();
+  for (const std::vector<int>& b : parts) {
+    if (b.size() < 2 || b.front() != 0 || b.back() != end) return false;
+    for (size_t i = 0; i + 1 < b.size(); ++i)
+      if (b[i + 1] <= b[i]) return false;
+  }
+  auto op = [&](int kind, int j) { return NfEmitOp{kind, j, parts[kind][j], parts[kind][j + 1]}; };
+  // KQV in range order; an attention nano-operation follows the KQV nano-operation that launches
+  // the last of its tokens (its earlier tokens, and the earlier tokens of a request it starts
+  // inside of, belong to KQV nano-operations launched before)
+  size_t a = 0;
+  for (size_t k = 0; k + 1 < parts[0].size(); ++k) {
+    out->push_back(op(0, (int)k));
+    for (; a + 1 < parts[1].size() && parts[1][a + 1] <= parts[0][k + 1]; ++a) out->push_back(op(1, (int)a));
+  }
+  // O, Up/Gate, Down: launched[k] = tokens [0, launched[k]) of operation k have been launched
+  int launched[NF_PART_KINDS] = {end, end, 0, 0, 0};
+  size_t next[NF_PART_KINDS] = {0, 0, 0, 0, 0};
+  for (;;) {
+    int pick = -1;
+    for (int k = 2; k < NF_PART_KINDS; ++k) {
+      if (next[k] + 1 >= parts[k].size()) continue;
+      const int e = parts[k][next[k] + 1];
+      if (launched[k - 1] < e) continue;  // an input row has not been launched yet
+      if (pick < 0 || e < parts[pick][next[pick] + 1]) pick = k;
+    }
+    if (pick < 0) break;
+    out->push_back(op(pick, (int)next[pick]));
+    launched[pick] = parts[pick][next[pick] + 1];
+    ++next[pick];
+  }
+  return true;
+}
+
+// The general form of simulate_impl: one partition per operation, launch order by
+// nf_emission_order, O / Up-Gate / Down as nano-operations of their own.  For equal partitions
+// it gives simulate_impl's result.
+double nf_simulate_parts(const NfProfile& prof, const NfSearchInput& in, const NfParts& parts, int overlap,
+                         const std::vector<const NfRpRow*>& rows, int n_layers) {
+  std::vector<NfEmitOp> emit;
+  if (!nf_emission_order(parts, &emit) || parts[0].back() != in.n_tokens) return -1.0;
+  const int L = std::max(1, n_layers);
+  const int n_attn = (int)parts[1].size() - 1;
+  if (!rows.empty()) {
+    if ((int)rows.size() != n_attn) return -1.0;
+    for (const NfRpRow* r : rows)
+      if (!r || r->gemm_tile != rows[0]->gemm_tile) return -1.0;
+  }
+  const NfRpRow* row0 = rows.empty() ? nullptr : rows[0];
+  const bool use_row_tile = overlap && row0 && row0->gemm_tile > 0;
+  auto dense = [&](int op, int m) {
+    return use_row_tile ? nf_profile_tile_us(prof, row0->gemm_tile, row0->p_gemm_solo, op, m)
+                        : nf_profile_dense_us(prof, op, m);
+  };
+  auto work_of = [&](const NfEmitOp& e) {
+    const int m = e.tok_end - e.tok_begin;
+    switch (e.kind) {
+      case 0: return dense(NF_DENSE_KQV, m) + prof.misc_kqv[0] + prof.misc_kqv[1] * m;
+      case 1:
+        return prof.attn_fixed_us +
+               prof.attn_us_per_mb * (in.attn_mb_prefix[(size_t)e.tok_end] - in.attn_mb_prefix[(size_t)e.tok_begin]) +
+               prof.misc_attn[0] + prof.misc_attn[1] * m;
+      case 2: return dense(NF_DENSE_O, m);
+      case 3: return dense(NF_DENSE_UG, m) + prof.misc_rest[0] + prof.misc_rest[1] * m;
+      default: return dense(NF_DENSE_D, m);
+    }
+  };
+  const size_t per_layer = emit.size();
+  if (!overlap) {
+    double t = 0;
+    for (const NfEmitOp& e : emit) t += work_of(e);
+    return t * L;
+  }
+  // ops of layer l: index l * per_layer + position in `emit`
+  struct Op {
+    int lane;
+    double work;
+    int attn_index;  // attention nano-operations: index into rows
+    std::vector<int> deps;
+  };
+  std::vector<Op> ops(per_layer * (size_t)L);
+  std::vector<int> q[2];
+  for (int l = 0; l < L; ++l) {
+    const size_t base = per_layer * (size_t)l;
+    for (size_t i = 0; i < per_layer; ++i) {
+      const NfEmitOp& e = emit[i];
+      Op& o = ops[base + i];
+      o.lane = e.kind == 1 ? 1 : 0;
+      o.work = work_of(e);
+      o.attn_index = e.kind == 1 ? e.index : -1;
+      // cross-lane dependencies (same-lane ones are met by the launch order): attention needs the
+      // KQV nano-operations of its tokens and of the earlier tokens of a prefill request it starts
+      // inside of; O needs the attention nano-operations of its tokens
+      if (e.kind == 1 || e.kind == 2) {
+        int lo = e.tok_begin;
+        if (e.kind == 1 && !in.req_start_of_tok.empty()) lo = in.req_start_of_tok[(size_t)e.tok_begin];
+        for (size_t j = 0; j < per_layer; ++j)
+          if (emit[j].kind == e.kind - 1 && std::max(lo, emit[j].tok_begin) < std::min(e.tok_end, emit[j].tok_end))
+            o.deps.push_back((int)(base + j));
+      }
+    }
+    // lanes: KQV of the first layer up front; later layers' KQV nano-operations right behind the
+    // Down nano-operation of the previous layer that completes their tokens
+    size_t next_kqv = 0;
+    std::vector<size_t> kqv_pos, attn_pos;
+    for (size_t i = 0; i < per_layer; ++i)
+      if (emit[i].kind == 0)
+        kqv_pos.push_back(i);
+      else if (emit[i].kind == 1)
+        attn_pos.push_back(i);
+    if (l == 0)
+      for (size_t i : kqv_pos) q[0].push_back((int)i);
+    for (size_t i = 0; i < per_layer; ++i) {
+      if (emit[i].kind < 2) continue;
+      q[0].push_back((int)(base + i));
+      if (emit[i].kind == 4 && l + 1 < L)
+        for (; next_kqv < kqv_pos.size() && emit[kqv_pos[next_kqv]].tok_end <= emit[i].tok_end; ++next_kqv)
+          q[0].push_back((int)(base + per_layer + kqv_pos[next_kqv]));
+    }
+    for (size_t i : attn_pos) q[1].push_back((int)(base + i));
+  }
+  std::vector<char> done(ops.size(), 0);
+  size_t head[2] = {0, 0};
+  double rem[2] = {0, 0};
+  bool running[2] = {false, false};
+  double t = 0;
+  for (;;) {
+    for (int l = 0; l < 2; ++l) {
+      if (running[l] || head[l] >= q[l].size()) continue;
+      const Op& o = ops[(size_t)q[l][head[l]]];
+      bool ready = true;
+      for (int d : o.deps) ready = ready && done[(size_t)d];
+      if (ready) {
+        running[l] = true;
+        rem[l] = o.work;
+      }
+    }
+    if (!running[0] && !running[1]) break;
+    // the row in force: that of the attention nano-operation at the head of its lane
+    const NfRpRow* r = nullptr;
+    if (!rows.empty()) r = head[1] < q[1].size() ? rows[(size_t)ops[(size_t)q[1][head[1]]].attn_index] : rows.back();
+    double sp[2] = {1.0, 1.0};
+    if (r) {
+      const double g_solo = use_row_tile ? 1.0 : r->p_gemm_solo;
+      if (running[0] && running[1]) {
+        sp[0] = use_row_tile ? r->p_gemm / std::max(r->p_gemm_solo, 1e-6) : r->p_gemm;
+        sp[1] = r->p_attn;
+      } else if (running[1]) {
+        sp[1] = r->p_attn_solo;
+      } else {
+        sp[0] = g_solo;
+      }
+    }
+    double dt = 1e300;
+    for (int l = 0; l < 2; ++l)
+      if (running[l]) dt = std::min(dt, rem[l] / std::max(sp[l], 1e-6));
+    t += dt;
+    for (int l = 0; l < 2; ++l) {
+      if (!running[l]) continue;
+      rem[l] -= dt * std::max(sp[l], 1e-6);
+      if (rem[l] <= 1e-9) {
+        running[l] = false;
+        done[(size_t)q[l][head[l]]] = 1;
+        ++head[l];
+      }
+    }
+  }
+  for (int l = 0; l < 2; ++l)
+    if (head[l] < q[l].size()) return -1.0;  // a nano-operation never became ready
+  return t;
+}
+
+static double simulate_parts_per_layer(const NfProfile& prof, const NfSearchInput& in, const NfParts& parts,
+                                       const std::vector<const NfRpRow*>& rows) {
+  const double t1 = nf_simulate_parts(prof, in, parts, 1, rows, 1);
+  if (t1 < 0 || in.layers <= 1) return t1;
+  const double tl = nf_simulate_parts(prof, in, parts, 1, rows, in.layers);
+  return tl < 0 ? tl : (tl - t1) / (in.layers - 1);
+}
+
 // Time per layer of a long run of consecutive layers: the increment between one layer and
 // in.layers layers (the ramp-up of the first layer and the drain of the last drop out).
 double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
@@ -339,6 +521,120 @@ void enumerate(int n_left, int pos, int n_tokens, int granule, std::vector<int>&
 
 }  // namespace
 
+// Stage II, third pass (Sec. 4.1.2: the number of nano-operations is decided per operation, more
+// of them where a bubble is): starting from the common boundaries, every operation's partition
+// in turn tries one more boundary (any multiple of the granule) or one fewer, attention
+// nano-operations that are split inherit their share and then try the other rows of the same
+// GEMM implementation; the single change that shortens the estimate most is kept, until none
+// shortens it by a thousandth.  Runs only from the index launch order.
+static void refine_partitions(const NfProfile& prof, const NfSearchInput& in, const NfRpRow& picked, NfPipeline* out) {
+  const int n = (int)out->bounds.size() - 1;
+  for (size_t k = 0; k < out->order.size(); ++k)
+    if (out->order[k] != (int)k) return;
+  if (n < 2) return;
+  const int max_parts = in.max_parts > 0 ? std::min(in.max_parts, NF_MAX_PARTS) : NF_MAX_PARTS;
+  std::vector<const NfRpRow*> same_tile, rows;
+  if (!prof.rp.empty()) {
+    for (const NfRpRow& r : prof.rp)
+      if (r.gemm_tile == picked.gemm_tile) same_tile.push_back(&r);
+    for (int i = 0; i < n; ++i) {
+      const int wgs = out->nano_attn_wgs.empty() ? picked.attn_wgs : out->nano_attn_wgs[(size_t)i];
+      const NfRpRow* found = nullptr;
+      for (const NfRpRow* r : same_tile)
+        if (r->attn_wgs == wgs && (!found || fabs(r->p_gemm - picked.p_gemm) < fabs(found->p_gemm - picked.p_gemm)))
+          found = r;
+      if (!found) return;
+      rows.push_back(found);
+    }
+  }
+  NfParts parts;
+  for (auto& b : parts) b = out->bounds;
+  double best = simulate_parts_per_layer(prof, in, parts, rows);
+  if (best < 0) return;
+  bool changed = false;
+  for (int pass = 0; pass < 24; ++pass) {
+    NfParts best_parts;
+    std::vector<const NfRpRow*> best_rows;
+    double best_t = best * (1.0 - 1e-3);
+    bool found = false;
+    auto consider = [&](const NfParts& p, const std::vector<const NfRpRow*>& r) {
+      const double t = simulate_parts_per_layer(prof, in, p, r);
+      if (t >= 0 && t < best_t) {
+        best_t = t;
+        best_parts = p;
+        best_rows = r;
+        found = true;
+      }
+    };
+    // one boundary more or fewer, in one operation or in a group of consecutive operations at once
+    // (a bubble behind the first KQV needs KQV and attention split together to close)
+    static const int kGroups[][NF_PART_KINDS] = {{1, 0, 0, 0, 0}, {0, 1, 0, 0, 0}, {0, 0, 1, 0, 0}, {0, 0, 0, 1, 0},
+                                                 {0, 0, 0, 0, 1}, {1, 1, 0, 0, 0}, {0, 0, 0, 1, 1}, {0, 0, 1, 1, 1},
+                                                 {1, 1, 1, 0, 0}, {1, 1, 1, 1, 1}};
+    for (const auto& group : kGroups)
+      for (int cut = in.granule; cut < in.n_tokens; cut += in.granule)
+        for (int add = 0; add < 2; ++add) {
+          NfParts p = parts;
+          std::vector<const NfRpRow*> r = rows;
+          bool any = false, ok = true;
+          long split_attn = -1;  // index of the right half of an attention nano-operation split by this move
+          for (int k = 0; k < NF_PART_KINDS; ++k) {
+            if (!group[k]) continue;
+            std::vector<int>& b = p[(size_t)k];
+            const auto at = std::lower_bound(b.begin(), b.end(), cut);
+            const size_t j = (size_t)(at - b.begin());  // b[j - 1] < cut <= b[j]
+            if (add && *at != cut) {
+              if ((int)b.size() - 1 >= max_parts) ok = false;
+              b.insert(at, cut);
+              if (k == 1 && !r.empty()) {
+                r.insert(r.begin() + (long)j, r[j - 1]);
+                split_attn = (long)j;
+              }
+              any = true;
+            } else if (!add && *at == cut) {
+              b.erase(at);
+              if (k == 1 && !r.empty()) r.erase(r.begin() + (long)j);
+              any = true;
+            }
+          }
+          if (in.tie_ffn && p[3] != p[4]) ok = false;
+          if (!any || !ok) continue;
+          consider(p, r);
+          // the halves of a split attention nano-operation may want different shares (one runs
+          // beside GEMMs, the other alone): neither change pays on its own
+          for (long half = split_attn - 1; split_attn > 0 && half <= split_attn; ++half)
+            for (const NfRpRow* alt : same_tile) {
+              if (alt == r[(size_t)half]) continue;
+              std::vector<const NfRpRow*> r2 = r;
+              r2[(size_t)half] = alt;
+              consider(p, r2);
+            }
+        }
+    // another share for one attention nano-operation
+    for (size_t i = 0; i < rows.size(); ++i)
+      for (const NfRpRow* alt : same_tile) {
+        if (alt == rows[i]) continue;
+        std::vector<const NfRpRow*> r = rows;
+        r[i] = alt;
+        consider(parts, r);
+      }
+    if (!found) break;
+    parts = best_parts;
+    rows = best_rows;
+    best = best_t;
+    changed = true;
+  }
+  if (!changed || best >= out->est_us - 1e-9) return;
+  bool uniform = true;
+  for (const auto& b : parts) uniform = uniform && b == parts[0];
+  out->est_us = best;
+  out->bounds = parts[1];
+  out->order.clear();
+  out->nano_attn_wgs.clear();
+  for (const NfRpRow* r : rows) out->nano_attn_wgs.push_back(r->attn_wgs);
+  if (!uniform) out->parts = parts;
+}
+
 int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   if (in.n_tokens < 0 || in.granule <= 0 || (int)in.attn_mb_prefix.size() != in.n_tokens + 1) return NF_EINVAL;
   const std::vector<int> whole = {0, in.n_tokens};
@@ -347,6 +643,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   out->attn_wgs = 0;
   out->nano_attn_wgs.clear();
   out->order.clear();
+  for (auto& b : out->parts) b.clear();
   out->est_us_unsplit = in.n_tokens ? nf_simulate_per_layer(prof, in, whole, 0, nullptr) : 0.0;
   out->est_us = out->est_us_stage1 = out->est_us_unsplit;
   const int max_n = in.max_nano > 0 ? std::min(in.max_nano, NF_MAX_NANO) : NF_MAX_NANO;
@@ -395,11 +692,11 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     }
   }
   std::stable_sort(per_row.begin(), per_row.end(), [](const RowBest& a, const RowBest& b) { return a.t2 < b.t2; });
-  // rank 0: the best row's pipeline if its estimate beats unsplit; rank r > 0: the r-th best
-  // row's pipeline (r = 1 is the best row) whatever its estimate
+  // rank 0: the best row's pipeline, refined, if its estimate beats unsplit; rank r > 0: the r-th
+  // best row's pipeline (r = 1 is the best row) whatever its estimate
   const size_t rank = (size_t)std::max(0, in.rank);
   const size_t pick = rank > 0 ? rank - 1 : 0;
-  if (pick < per_row.size() && (rank > 0 || per_row[0].t2 < out->est_us_unsplit - 1e-9)) {
+  if (pick < per_row.size()) {
     const RowBest& b = per_row[pick];
     out->bounds = cands[b.cand].bounds;
     out->overlap = 1;
@@ -461,6 +758,18 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
           out->order = order;
         }
       }
+    }
+    if (in.refine >= 2) refine_partitions(prof, in, b.row, out);
+    if (rank == 0 && out->est_us >= out->est_us_unsplit - 1e-9) {
+      // nothing beats running unsplit
+      out->bounds = whole;
+      out->overlap = 0;
+      out->attn_wgs = 0;
+      out->gemm_tile = 0;
+      out->nano_attn_wgs.clear();
+      out->order.clear();
+      for (auto& pb : out->parts) pb.clear();
+      out->est_us = out->est_us_stage1 = out->est_us_unsplit;
     }
   }
   return NF_OK;

@@ -3,6 +3,7 @@
 #pragma once
 #include <stdint.h>
 
+#include <array>
 #include <string>
 #include <vector>
 
@@ -62,13 +63,26 @@ struct NfSearchInput {
   int max_nano = 0;                  // 0 = search up to NF_MAX_NANO
   int layers = 1;                    // > 1: minimise the time per layer of that many consecutive layers
   int rank = 0;                      // 0: the best pipeline; r > 0: the r-th best table row's pipeline
-  int refine = 1;                    // second pass of Stage II: share per attention nano-operation and launch order
+  int refine = 1;                    // second pass of Stage II: share per attention nano-operation, launch order,
+                                     // and the number of nano-operations per operation
+  int max_parts = 0;                 // nano-operations per operation in that pass (0 = NF_MAX_PARTS)
+  bool tie_ffn = false;              // Up/Gate and Down must share one partition (mixture-of-experts layers)
   std::vector<double> attn_mb_prefix;  // [n_tokens + 1] prefix sums of attention megabytes per token
   std::vector<int> req_start_of_tok;   // [n_tokens] first token of the request that owns token t
 };
 
+// The token partition of every operation (Sec. 4.1.2: the number and the sizes of the
+// nano-operations are decided per operation): parts[k] holds the boundaries of the nano-operations
+// of operation k, in the order KQV, attention, O, Up/Gate, Down.
+constexpr int NF_PART_KINDS = 5;
+constexpr int NF_MAX_PARTS = 8;
+using NfParts = std::array<std::vector<int>, NF_PART_KINDS>;
+
 struct NfPipeline {
-  std::vector<int> bounds;   // nano-batch boundaries
+  std::vector<int> bounds;   // nano-batch boundaries (of the attention operation when `parts` is set)
+  // per-operation partitions; all empty = every operation is split at `bounds`.  With partitions
+  // nano_attn_wgs has one entry per attention nano-operation and `order` is empty.
+  NfParts parts;
   int overlap = 0;
   // Per nano-batch (Sec. 4.1.1 - 4.1.3: every nano-operation has its own resource share, and the
   // order of the nano-batches is part of the pipeline): the persistent workgroups of its attention
@@ -96,6 +110,23 @@ double nf_simulate(const NfProfile& prof, const NfSearchInput& in, const std::ve
 // nano-operations it depends on.
 double nf_simulate_ops(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
                        const std::vector<const NfRpRow*>& rows, const std::vector<int>& order, int n_layers = 1);
+// One nano-operation in launch order: operation kind (index into NfParts), its index within the
+// operation's partition, its token range.
+struct NfEmitOp {
+  int kind, index, tok_begin, tok_end;
+};
+// Launch order of one layer's nano-operations when every operation has its own partition:
+// the KQV nano-operations in range order, each attention nano-operation right behind the KQV
+// nano-operation that completes its tokens; then O, Up/Gate and Down nano-operations, always the
+// one with the smallest last token among those whose inputs have been launched (ties: O before
+// Up/Gate before Down).  For equal partitions this is KQV0 ATTN0 KQV1 ATTN1 .. O0 UG0 D0 O1 UG1 D1 ..
+// Returns false for partitions that are not increasing sequences from 0 to one common end.
+bool nf_emission_order(const NfParts& parts, std::vector<NfEmitOp>* out);
+// Simulated makespan with a partition per operation.  rows: one table row per attention
+// nano-operation (all of one GEMM implementation), or empty for no interference.  overlap = 0:
+// every nano-operation back to back.  Negative for invalid partitions.
+double nf_simulate_parts(const NfProfile& prof, const NfSearchInput& in, const NfParts& parts, int overlap,
+                         const std::vector<const NfRpRow*>& rows, int n_layers = 1);
 // The objective of the search: the makespan of one layer, or (in.layers > 1) the time per layer
 // of a run of consecutive layers pipelined across the layer boundaries.
 double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,

@@ -19,8 +19,10 @@ int nf_search_layers() { return g_search_layers; }
 // Which of the ranked candidates the search returns (tuning knob "search.rank").
 static int g_search_rank = 0;
 void nf_set_search_rank(int r) { g_search_rank = r; }
-static int g_search_refine = 1;
+static int g_search_refine = 2;
 void nf_set_search_refine(int v) { g_search_refine = v; }
+static int g_search_max_parts = 0;
+void nf_set_search_max_parts(int v) { g_search_max_parts = v; }
 
 void nf_profile_free(nf_ctx* ctx) {
   delete ctx->profile;
@@ -391,6 +393,8 @@ void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano,
   in->layers = nf_search_layers();
   in->rank = g_search_rank;
   in->refine = g_search_refine;
+  in->max_parts = g_search_max_parts;
+  in->tie_ffn = m->n_experts > 1;
   in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
   in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
   const double tok_mb = 2.0 * m->n_kv_heads * m->head_dim * 2 / 1e6;
@@ -474,6 +478,11 @@ extern "C" int nf_search_pipeline(const nf_model_desc* model, const nf_batch* ba
     out->nano_attn_wgs[i] = pl.nano_attn_wgs.empty() ? pl.attn_wgs : pl.nano_attn_wgs[(size_t)i];
     out->order[i] = pl.order.empty() ? i : pl.order[(size_t)i];
   }
+  if (!pl.parts[0].empty())
+    for (int k = 0; k < NF_PART_KINDS; ++k) {
+      out->parts.n[k] = (int32_t)pl.parts[(size_t)k].size() - 1;
+      for (size_t i = 0; i < pl.parts[(size_t)k].size() && i < 9; ++i) out->parts.bounds[k][i] = pl.parts[(size_t)k][i];
+    }
   out->est_us = pl.est_us;
   out->est_us_stage1 = pl.est_us_stage1;
   out->est_us_unsplit = pl.est_us_unsplit;
@@ -549,6 +558,54 @@ extern "C" int nf_simulate_pipeline_ops(const nf_model_desc* model, const nf_bat
   return NF_EINVAL;
 }
 
+// nf_partitions -> NfParts; false unless every operation has 1..8 nano-operations
+static bool parts_from_c(const nf_partitions* c, NfParts* out) {
+  for (int k = 0; k < NF_PART_KINDS; ++k) {
+    if (c->n[k] < 1 || c->n[k] > NF_MAX_PARTS) return false;
+    (*out)[(size_t)k].assign(c->bounds[k], c->bounds[k] + c->n[k] + 1);
+  }
+  return true;
+}
+
+extern "C" int nf_simulate_pipeline_parts(const nf_model_desc* model, const nf_batch* batch, const char* profile_path,
+                                          const nf_partitions* parts, int overlap, const int32_t* rp_rows,
+                                          double* est_us) try {
+  if (!est_us || !parts) return NF_EINVAL;
+  int rc = nf_validate_model(model);
+  if (rc) return rc;
+  rc = nf_validate_batch(model, batch, INT64_MAX);
+  if (rc) return rc;
+  NfProfile prof;
+  if (profile_path) {
+    rc = nf_profile_load(&prof, profile_path);
+    if (rc) return rc;
+  } else {
+    if (rp_rows) return NF_EINVAL;  // rows need a table
+    nf_profile_analytic(&prof, model, std::max(batch->n_tokens, 128), 128);
+  }
+  NfParts p;
+  if (!parts_from_c(parts, &p)) return NF_EPLAN;
+  std::vector<const NfRpRow*> rows;
+  for (int i = 0; rp_rows && i < parts->n[1]; ++i) {
+    if (rp_rows[i] < 0 || rp_rows[i] >= (int)prof.rp.size()) return NF_EINVAL;
+    rows.push_back(&prof.rp[(size_t)rp_rows[i]]);
+  }
+  NfSearchInput in;
+  build_search_input(model, batch, 0, prof.granule, &in);
+  double t = nf_simulate_parts(prof, in, p, overlap, rows, 1);
+  if (t >= 0 && in.layers > 1) {
+    const double tl = nf_simulate_parts(prof, in, p, overlap, rows, in.layers);
+    t = tl < 0 ? tl : (tl - t) / (in.layers - 1);
+  }
+  if (t < 0) return NF_EPLAN;
+  *est_us = t;
+  return NF_OK;
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
 extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
                                    int granule, nf_plan** out) try {
   if (!ctx || !out || granule < 1 || max_nano < 0) return NF_EINVAL;
@@ -566,7 +623,18 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   if (rc) return rc;
   std::vector<int32_t> b32(pl.bounds.begin(), pl.bounds.end());
   const int n_nano = (int)b32.size() - 1;
-  if (pl.nano_attn_wgs.empty() && pl.order.empty()) {
+  if (!pl.parts[0].empty()) {
+    nf_partitions c;
+    memset(&c, 0, sizeof c);
+    for (int k = 0; k < NF_PART_KINDS; ++k) {
+      c.n[k] = (int32_t)pl.parts[(size_t)k].size() - 1;
+      for (size_t i = 0; i < pl.parts[(size_t)k].size(); ++i) c.bounds[k][i] = pl.parts[(size_t)k][i];
+    }
+    std::vector<int32_t> wgs((size_t)c.n[1], pl.attn_wgs);
+    for (size_t i = 0; i < wgs.size() && i < pl.nano_attn_wgs.size(); ++i) wgs[i] = pl.nano_attn_wgs[i];
+    rc = nf_plan_manual_parts(ctx, model, batch, &c, pl.overlap, 0, 0, wgs.data(), nullptr, out);
+    if (rc == NF_OK) (*out)->attn_wgs = pl.attn_wgs;
+  } else if (pl.nano_attn_wgs.empty() && pl.order.empty()) {
     rc = nf_plan_manual(ctx, model, batch, n_nano, b32.data(), pl.overlap, 0, 0, pl.attn_wgs, out);
   } else {
     std::vector<nf_nano_spec> spec((size_t)n_nano);
@@ -581,6 +649,25 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   if (rc) return rc;
   (*out)->origin = prof->measured ? "search(measured profile)" : "search(analytic profile)";
   (*out)->est_time_us = pl.est_us;
+  // Nano-operations that cannot have an attention kernel beside them in a single layer: the first
+  // KQV nano-operation (every attention nano-operation waits for it) and everything launched
+  // from the O nano-operation that waits for the last attention nano-operation on.  They take the
+  // implementation that is fastest alone, not the one of the chosen R -> P pair.
+  std::vector<char> runs_alone((*out)->ops.size(), 0);
+  if (pl.overlap && nf_search_layers() <= 1) {
+    int last_attn = -1, first_kqv = -1;
+    for (size_t i = 0; i < (*out)->ops.size(); ++i) {
+      if ((*out)->ops[i].kind == NF_OP_ATTN) last_attn = (int)i;
+      if ((*out)->ops[i].kind == NF_OP_KQV && first_kqv < 0) first_kqv = (int)i;
+    }
+    if (first_kqv >= 0) runs_alone[(size_t)first_kqv] = 1;
+    bool tail = false;
+    for (size_t i = 0; i < (*out)->ops.size(); ++i) {
+      const NfNanoOp& op = (*out)->ops[i];
+      if (op.kind == NF_OP_O && std::find(op.deps.begin(), op.deps.end(), last_attn) != op.deps.end()) tail = true;
+      if (tail && op.kind != NF_OP_ATTN) runs_alone[i] = 1;
+    }
+  }
   // implementation map (Sec. 4.1.1): best GEMM tile per (operation, batch size)
   for (NfNanoOp& op : (*out)->ops) {
     const int dense = op.kind == NF_OP_KQV ? NF_DENSE_KQV
@@ -591,7 +678,8 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
     if (dense < 0 || prof->dense_tile[dense].empty()) continue;
     const int m = op.tok_end - op.tok_begin;
     const int idx = std::min((int)prof->dense_tile[dense].size() - 1, std::max(0, (m + granule - 1) / granule - 1));
-    op.gemm_tile = (pl.overlap && pl.gemm_tile) ? pl.gemm_tile : prof->dense_tile[dense][idx];
+    const bool alone = runs_alone[(size_t)(&op - (*out)->ops.data())] != 0;
+    op.gemm_tile = (pl.overlap && pl.gemm_tile && !alone) ? pl.gemm_tile : prof->dense_tile[dense][idx];
   }
   return NF_OK;
 } catch (const std::bad_alloc&) {

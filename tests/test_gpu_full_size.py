@@ -87,7 +87,11 @@ def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
     plans = [nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule),
              nf.nf_plan_manual(case.ctx, m, case.args, [0, 1024, 2048], True, 0, 0, 256),
              nf.nf_plan_manual(case.ctx, m, case.args, [0, 128, 1152, 2048], True, 0, 0, 0),
-             nf.nf_plan_manual(case.ctx, m, case.args, [0, 100, 2048], False)]     # cuts the prefill request
+             nf.nf_plan_manual(case.ctx, m, case.args, [0, 100, 2048], False),     # cuts the prefill request
+             # a partition per operation: attention in four pieces with alternating shares, the rest in two
+             nf.nf_plan_manual_parts(case.ctx, m, case.args,
+                                     dict(KQV=[0, 1024, 2048], ATTN=[0, 512, 1024, 1536, 2048], O=[0, 1024, 2048],
+                                          UG=[0, 1024, 2048], D=[0, 1024, 2048]), True, [128, 256, 128, 256])]
     for p in plans:
         d = p.describe()
         say("plan", d["origin"], d["bounds"], "overlap", d["overlap"], "attn_wgs", d["attn_wgs"])

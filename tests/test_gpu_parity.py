@@ -262,6 +262,84 @@ def test_per_nano_operation_shares_and_launch_order_are_bit_exact(ctx):
     plan.close()
 
 
+PARTITION_CASES = [
+    # KQV and attention in more pieces than the rest (the shape of the paper's pipelines, Fig. 6)
+    dict(KQV=[0, 12, 20, 41, 64], ATTN=[0, 12, 20, 41, 64], O=[0, 41, 64], UG=[0, 41, 64], D=[0, 41, 64]),
+    # attention pieces that span several KQV pieces and cut prefill requests; Up/Gate finer than Down
+    dict(KQV=[0, 7, 20, 33, 50, 64], ATTN=[0, 20, 50, 64], O=[0, 64], UG=[0, 16, 17, 40, 64], D=[0, 17, 64]),
+    # everything different
+    dict(KQV=[0, 64], ATTN=[0, 5, 64], O=[0, 30, 31, 64], UG=[0, 50, 64], D=[0, 10, 20, 30, 40, 50, 60, 63, 64]),
+]
+
+
+def test_a_partition_per_operation_is_bit_exact(ctx):
+    """Every operation with its own number of nano-operations (Sec. 4.1.2): the plan launches
+    them in the stated order with the dependencies of the range rule, and one layer, a chain of
+    layers and a chain with the simultaneous KV offload give the bits of the unsplit run."""
+    from oracle import pipeline_model as pm
+    cfg = wl.CONFIGS["C1"]
+    m = cfg.model
+    b = wl.make_batch(cfg.batch, cfg.seed + 2, spare_pages=5)
+    case = Case(m, b, cfg.seed, ctx=ctx)
+    z0, p0 = case.run(None)
+    for parts in PARTITION_CASES:
+        n_attn = len(parts["ATTN"]) - 1
+        for overlap, wgs, tiles in ((True, list(range(1, n_attn + 1)), [22, 0, 21, 25]), (False, None, None),
+                                    (True, None, None)):
+            plan = nf.nf_plan_manual_parts(case.ctx, m, case.args, parts, overlap, wgs, tiles)
+            d = plan.describe()
+            say("partitions", d["partitions"], "overlap", overlap)
+            assert d["partitions"] == [parts[k] for k in pm.KINDS] and d["bounds"] == parts["ATTN"]
+            assert [(o["op"], o["nano"]) for o in d["ops"]] == pm.launch_order(parts)
+            for i, o in enumerate(d["ops"]):
+                assert o["range"] == [parts[o["op"]][o["nano"]], parts[o["op"]][o["nano"] + 1]]
+                # waits: the earlier nano-operations on the other lane that the range rule names
+                lo = o["range"][0]
+                if o["op"] == "ATTN":
+                    lo = int(b.q_indptr[np.searchsorted(b.q_indptr, lo, side="right") - 1])
+                want = [j for j, q in enumerate(d["ops"][:i]) if q["lane"] != o["lane"] and
+                        nf.lib().nf_nano_ops_dependent(pm.KINDS.index(q["op"]), pm.KINDS.index(o["op"]), q["range"][0],
+                                                 q["range"][1], lo, o["range"][1])]
+                assert o["deps"] == want, (parts, o)
+            if wgs is not None:
+                assert d["nano_attn_wgs"] == wgs
+            for rep in range(2):
+                z, p = case.run(plan)
+                assert np.array_equal(z, z0) and np.array_equal(p, p0), (parts, overlap)
+            plan.close()
+    bad = dict(PARTITION_CASES[0], O=[0, 41, 63])
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_plan_manual_parts(case.ctx, m, case.args, bad, True)
+    assert e.value.status == nf.NF_EPLAN
+    # a chain of layers: the next layer's KQV pieces go behind the Down piece that completes their rows
+    n_layers = 3
+    chain = ChainCase(m, b, cfg.seed, n_layers, ctx=ctx)
+    z_ref, pools_ref = chain.run_layer_by_layer()
+    row = 2 * m.n_kv_heads * m.head_dim
+    tok = np.arange(b.n_tokens)
+    for parts in PARTITION_CASES:
+        plan = nf.nf_plan_manual_parts(chain.ctx, m, chain.args, parts, True)
+        for rep in range(2):
+            z, pools = chain.run_chain(plan)
+            assert np.array_equal(z, z_ref), parts
+            for l in range(n_layers):
+                assert np.array_equal(pools[l], pools_ref[l]), (parts, l)
+        host = torch.full((n_layers, b.n_tokens, row), 7.0, dtype=torch.bfloat16).pin_memory()
+        nf.nf_ctx_set_kv_offload(chain.ctx, host.data_ptr(), b.n_tokens * row * 2)
+        try:
+            z, pools = chain.run_chain(plan)
+        finally:
+            nf.nf_ctx_set_kv_offload(chain.ctx, None)
+        assert np.array_equal(z, z_ref)
+        got = hz.bf16_bits(host)
+        for l in range(n_layers):
+            assert np.array_equal(pools[l], pools_ref[l]), (parts, l)
+            kg, vg = hz.read_kv_rows(pools[l], m, b, tok)
+            assert np.array_equal(got[l], np.concatenate([kg.reshape(b.n_tokens, -1), vg.reshape(b.n_tokens, -1)],
+                                                         axis=1)), (parts, l)
+        plan.close()
+
+
 def test_two_segment_down_projection_is_bit_exact_in_both_launch_forms(ctx):
     """A model whose down projection has a long K (ffn_inner 8192 over hidden 512) sums the two
     halves of K separately.  With the layer's workspace the halves may run on different
@@ -473,6 +551,16 @@ def test_moe_layer_matches_oracle_and_is_split_invariant(ctx):
         z, p = case.run(plan)
         assert np.array_equal(z, z0) and np.array_equal(p, p0), bounds
         plan.close()
+    # a partition per operation: Up/Gate and Down must share theirs (the expert rows are grouped per Up/Gate piece)
+    parts = dict(KQV=[0, 30, 45, 100, 128], ATTN=[0, 45, 100, 128], O=[0, 128], UG=[0, 50, 90, 128], D=[0, 50, 90, 128])
+    for overlap in (True, False):
+        plan = nf.nf_plan_manual_parts(case.ctx, m, case.args, parts, overlap)
+        z, p = case.run(plan)
+        assert np.array_equal(z, z0) and np.array_equal(p, p0), parts
+        plan.close()
+    with pytest.raises(nf.NfError) as err:
+        nf.nf_plan_manual_parts(case.ctx, m, case.args, dict(parts, D=[0, 50, 128]), True)
+    assert err.value.status == nf.NF_EPLAN
     plan1.close()
 
 
@@ -484,8 +572,10 @@ def test_moe_layer_chain_is_bit_exact_with_separate_calls(ctx):
                               np.random.default_rng(4), spare_pages=2)
     chain = ChainCase(m, b, 4200, 3, ctx=ctx)
     z_ref, pools_ref = chain.run_layer_by_layer()
-    for bounds, overlap in (([0, b.n_tokens], False), ([0, 64, 128], True), ([0, 16, 50, 128], True)):
-        plan = nf.nf_plan_manual(chain.ctx, m, chain.args, bounds, overlap)
+    parts = dict(KQV=[0, 30, 45, 100, 128], ATTN=[0, 45, 100, 128], O=[0, 128], UG=[0, 50, 90, 128], D=[0, 50, 90, 128])
+    for bounds, overlap in (([0, b.n_tokens], False), ([0, 64, 128], True), ([0, 16, 50, 128], True), (parts, True)):
+        plan = (nf.nf_plan_manual_parts(chain.ctx, m, chain.args, bounds, overlap) if isinstance(bounds, dict)
+                else nf.nf_plan_manual(chain.ctx, m, chain.args, bounds, overlap))
         for rep in range(2):
             z, pools = chain.run_chain(plan)
             assert np.array_equal(z, z_ref), (bounds, overlap, rep)

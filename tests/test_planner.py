@@ -58,6 +58,16 @@ def attn_prefix(model, b: wl.Batch):
 MODEL = wl.ModelDesc(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_inner=1024)
 
 
+@pytest.fixture(autouse=True)
+def common_boundaries_unless_asked():
+    """The tests of the nano-batch model (one set of boundaries for every operation) run the search
+    without its last pass; the tests of that pass (a partition per operation) switch it on."""
+    nf.nf_tune_set("search.refine", 1)
+    yield
+    nf.nf_tune_set("search.refine", 2)
+    nf.nf_tune_set("search.max_parts", 0)
+
+
 def table3_rows():
     rows = []
     for line in open(GOLD):
@@ -468,3 +478,207 @@ def test_bad_profile_file_is_an_io_error(tmp_path):
     with pytest.raises(nf.NfError) as e:
         nf.nf_search_pipeline(MODEL, host_batch(b), str(p), 0, 16)
     assert e.value.status == nf.NF_EIO
+
+
+# ---- a partition per operation (Sec. 4.1.2: the number of nano-operations is decided per operation) ----
+
+def random_instance(seed, n_gran=6, g=8, prefill=20, misc=None):
+    r = np.random.default_rng(seed)
+    n_tok = g * n_gran
+    q_lens = ([prefill] if prefill else []) + [1] * (n_tok - prefill)
+    ctxs = ([0] if prefill else []) + list(r.integers(50, 3000, size=len(q_lens) - (1 if prefill else 0)))
+    b = wl.batch_from_lengths(q_lens, ctxs, 1 if prefill else 0, r)
+    dense = {o: list(np.cumsum(r.uniform(4, 12, size=n_gran)) * s + r.uniform(2, 6))
+             for o, s in zip(OPS, (1.0, 0.7, 3.0, 1.5))}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = r.uniform(0.8, 2.5) * sum(sum(v) for v in dense.values()) / n_gran / pre[-1]
+    return r, b, dense, pre, start, per_mb
+
+
+def test_launch_order_of_partitioned_operations():
+    """The stated launch order, by hand: equal partitions give the nano-batch order; with KQV and
+    attention in four pieces and the other operations in two, an O piece follows once the attention
+    pieces of its rows are launched, and Up/Gate / Down pieces with the smaller last token go first."""
+    same = {k: [0, 32, 64] for k in pm.KINDS}
+    assert pm.launch_order(same) == [("KQV", 0), ("ATTN", 0), ("KQV", 1), ("ATTN", 1), ("O", 0), ("UG", 0), ("D", 0),
+                                     ("O", 1), ("UG", 1), ("D", 1)]
+    parts = dict(same, KQV=[0, 16, 32, 48, 64], ATTN=[0, 16, 32, 48, 64], UG=[0, 16, 32, 64])
+    assert pm.launch_order(parts) == [("KQV", 0), ("ATTN", 0), ("KQV", 1), ("ATTN", 1), ("KQV", 2), ("ATTN", 2),
+                                      ("KQV", 3), ("ATTN", 3), ("O", 0), ("UG", 0), ("UG", 1), ("D", 0), ("O", 1),
+                                      ("UG", 2), ("D", 1)]
+    # an attention piece that spans two KQV pieces waits for the second one
+    parts = dict(same, KQV=[0, 16, 64], ATTN=[0, 32, 64])
+    assert pm.launch_order(parts)[:4] == [("KQV", 0), ("KQV", 1), ("ATTN", 0), ("ATTN", 1)]
+
+
+def test_partition_model_closed_forms():
+    """Without interference and with one attention piece nothing overlaps but the KQV pieces:
+    KQV + attention + O + Up/Gate + Down whatever the other partitions; with attention and KQV in
+    two pieces the first attention piece hides the second KQV piece."""
+    g = 10
+    dense = {"KQV": [3.0, 6.0, 9.0, 12.0], "O": [2.0, 4.0, 6.0, 8.0], "UG": [5.0, 10.0, 15.0, 20.0],
+             "D": [4.0, 8.0, 12.0, 16.0]}
+    pre = [0.5 * t for t in range(41)]               # attention: 0.5 per token -> 20 for the batch
+    start = list(range(40))
+    parts = {"KQV": [0, 20, 40], "ATTN": [0, 40], "O": [0, 10, 40], "UG": [0, 40], "D": [0, 30, 40]}
+    t = pm.makespan_parts(dense, g, 0.0, 1.0, pre, start, parts, True, None, dt=0.01)
+    assert t == pytest.approx(12.0 + 20.0 + 8.0 + 20.0 + 16.0, abs=0.1)
+    parts["ATTN"] = [0, 20, 40]
+    t = pm.makespan_parts(dense, g, 0.0, 1.0, pre, start, parts, True, None, dt=0.01)
+    # KQV0 6, then attention 10 + 10 on its lane (KQV1 hidden), O waits for the attention of its rows:
+    # O[0,10) after the first attention piece (at 16) takes 2, O[10,40) needs the second piece (at 26)
+    assert t == pytest.approx(6.0 + 10.0 + 10.0 + 6.0 + 20.0 + 16.0, abs=0.1)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_partition_model_matches_the_oracle(tmp_path, seed):
+    """Random partitions per operation, a random table row per attention piece, small kernels, a
+    prefill request cut by some of the boundaries, one layer and a run of layers, overlapped and
+    back to back: the event-driven C++ model against the oracle's time stepping."""
+    misc = ((1.0, 0.01), (0.5, 0.02), (0.7, 0.03))
+    r, b, dense, pre, start, per_mb = random_instance(200 + seed)
+    g, n_tok = 8, b.n_tokens
+    rows = table3_rows()
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows, misc=misc)
+
+    def random_partition():
+        cuts = sorted(int(c) * g for c in r.choice(np.arange(1, n_tok // g), size=int(r.integers(0, 4)), replace=False))
+        return [0, *cuts, n_tok]
+
+    cases = [{k: random_partition() for k in pm.KINDS} for _ in range(5)]
+    # the shape of the paper's pipelines: KQV and attention in more pieces than the rest
+    cases.append({"KQV": [0, 8, 24, 32, 48], "ATTN": [0, 8, 24, 32, 48], "O": [0, 24, 48], "UG": [0, 24, 48],
+                  "D": [0, 24, 48]})
+    for parts in cases:
+        idx = [int(x) for x in r.integers(0, len(rows), size=len(parts["ATTN"]) - 1)]
+        chosen = [rows[i] for i in idx]
+        want_seq = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, False, None, 0.01, misc)
+        assert nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, False, None, path) == \
+            pytest.approx(want_seq, rel=1e-6)        # the profile file keeps four to eight decimals
+        t1 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc)
+        assert nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, True, idx, path) == \
+            pytest.approx(t1, rel=2e-3, abs=0.2), parts
+        t4 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc, layers=4)
+        nf.nf_tune_set("search.layers", 4)
+        try:
+            got = nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, True, idx, path)
+        finally:
+            nf.nf_tune_set("search.layers", 1)
+        assert got == pytest.approx((t4 - t1) / 3, rel=2e-3, abs=0.2), parts
+    # the last case does pipeline across the layer boundary
+    assert t4 < 4 * t1 - 1.0
+
+
+def test_equal_partitions_give_the_nano_batch_model(tmp_path):
+    r, b, dense, pre, start, per_mb = random_instance(300)
+    g, n_tok = 8, b.n_tokens
+    rows = table3_rows()
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows)
+    for bounds, idx in (([0, 24, 48], [0, 2]), ([0, 16, 24, 48], [3, 1, 2]), ([0, 8, 16, 24, 48], [1, 1, 0, 3])):
+        same = {k: bounds for k in pm.KINDS}
+        for layers in (1, 3):
+            nf.nf_tune_set("search.layers", layers)
+            try:
+                a = nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), same, True, idx, path)
+                c = nf.nf_simulate_pipeline_ops(MODEL, host_batch(b), bounds, idx, None, path)
+            finally:
+                nf.nf_tune_set("search.layers", 1)
+            assert a == pytest.approx(c, rel=1e-12)
+        chosen = [rows[i] for i in idx]
+        assert pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, same, True, chosen, 0.01) == \
+            pytest.approx(pm.makespan(dense, g, 2.0, per_mb, pre, start, bounds, True, None, 0.01, rows=chosen), abs=0.1)
+
+
+def test_invalid_partitions_are_refused(tmp_path):
+    r, b, dense, pre, start, per_mb = random_instance(301)
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, 8, b.n_tokens, dense, 2.0, per_mb, table3_rows())
+    good = {k: [0, 24, 48] for k in pm.KINDS}
+    for bad in (dict(good, O=[0, 24, 40]), dict(good, UG=[0, 24, 24, 48]), dict(good, D=[8, 24, 48])):
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), bad, True, [0, 0], path)
+        assert e.value.status == nf.NF_EPLAN
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_search_over_partitions_against_brute_force(tmp_path, seed):
+    """At most two pieces per operation on four granules, two table rows: the search with its last
+    pass is never worse than without it and never better than the optimum over every partition per
+    operation and every row per attention piece; its estimate is the model's for what it reports."""
+    r = np.random.default_rng(400 + seed)
+    g, n_gran = 8, 4
+    n_tok = g * n_gran
+    b = wl.batch_from_lengths([1] * n_tok, list(r.integers(50, 3000, size=n_tok)), 0, r)
+    dense = {o: list((np.cumsum(r.uniform(0.5, 1.5, size=n_gran)) * s + r.uniform(0.2, 0.8)))
+             for o, s in zip(OPS, (1.0, 0.7, 3.0, 1.5))}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = r.uniform(0.8, 2.5) * sum(sum(v) for v in dense.values()) / n_gran / pre[-1]
+    rows = [dict(attn_wgs=256, p_gemm=0.35, p_attn=0.8, p_attn_solo=1.0),
+            dict(attn_wgs=128, p_gemm=0.7, p_attn=0.55, p_attn_solo=0.85)]
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, n_tok, dense, 0.5, per_mb, rows)
+    before = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=2, granule=g)
+    nf.nf_tune_set("search.refine", 2)
+    nf.nf_tune_set("search.max_parts", 2)
+    got = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=2, granule=g)
+    assert got["est_us"] <= before["est_us"] + 1e-9
+    floor = pm.brute_force_parts(dense, g, 0.5, per_mb, pre, start, n_tok, rows, 2, dt=0.02)
+    assert got["est_us"] >= floor[0] * (1 - 5e-3) - 0.1
+    assert got["est_us"] <= got["est_us_unsplit"] + 1e-9
+    if got["overlap"]:
+        parts = got["parts"] or [got["bounds"]] * 5
+        assert all(len(p) - 1 <= 2 for p in parts)
+        wgs = [x["attn_wgs"] for x in rows]
+        idx = [wgs.index(w) for w in got["nano_attn_wgs"]]
+        assert nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, True, idx, path) == \
+            pytest.approx(got["est_us"], rel=1e-9)
+        want = pm.makespan_parts(dense, g, 0.5, per_mb, pre, start, dict(zip(pm.KINDS, parts)), True,
+                                 [rows[i] for i in idx], 0.01)
+        assert got["est_us"] == pytest.approx(want, rel=2e-3, abs=0.1)
+
+
+def test_search_splits_attention_where_its_company_changes(tmp_path):
+    """A run of layers, attention longer than the GEMMs, O / Up/Gate / Down losing efficiency when
+    split (a fixed cost per piece), and the two rows of the per-nano-operation share test.  In the
+    steady state each attention nano-operation has the other nano-batch's GEMMs beside it for its
+    first part only: with common boundaries it keeps the sharing-friendly, slow-alone row to its
+    end.  The last pass cuts the attention operation alone - four pieces, alternately the sharing
+    row and the fast-alone row - and leaves the other operations in two pieces, which no common
+    structure with a share per nano-batch reaches."""
+    g, layers = 16, 8
+    b = wl.batch_from_lengths([1] * 64, np.full(64, 1000), 0, np.random.default_rng(0))
+    dense = {"KQV": [4.0, 5.0, 6.0, 7.0], "O": [8.0, 13.0, 18.0, 23.0], "UG": [30.0, 50.0, 70.0, 90.0],
+             "D": [16.0, 26.0, 36.0, 46.0]}
+    pre, start = attn_prefix(MODEL, b)
+    per_mb = 400.0 / pre[-1]
+    rows = [dict(attn_wgs=256, p_gemm=0.10, p_attn=0.50, p_attn_solo=1.0),
+            dict(attn_wgs=128, p_gemm=0.80, p_attn=0.70, p_attn_solo=0.75)]
+    path = str(tmp_path / "p.txt")
+    write_profile(path, MODEL, g, 64, dense, 0.0, per_mb, rows)
+    nf.nf_tune_set("search.layers", layers)
+    try:
+        before = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=4, granule=g)
+        nf.nf_tune_set("search.refine", 2)
+        got = nf.nf_search_pipeline(MODEL, host_batch(b), path, max_nano=4, granule=g)
+    finally:
+        nf.nf_tune_set("search.layers", 1)
+    assert got["parts"] == [[0, 32, 64], [0, 16, 32, 48, 64], [0, 32, 64], [0, 32, 64], [0, 32, 64]], got
+    assert got["nano_attn_wgs"] == [128, 256, 128, 256] and got["bounds"] == [0, 16, 32, 48, 64]
+    assert got["est_us"] < 0.9 * before["est_us"]
+
+    def per_layer(parts, chosen, dt):
+        t1 = pm.makespan_parts(dense, g, 0.0, per_mb, pre, start, parts, True, chosen, dt)
+        tl = pm.makespan_parts(dense, g, 0.0, per_mb, pre, start, parts, True, chosen, dt, layers=layers)
+        return (tl - t1) / (layers - 1)
+
+    X, Y = rows
+    assert got["est_us"] == pytest.approx(per_layer(dict(zip(pm.KINDS, got["parts"])), [Y, X, Y, X], 0.02),
+                                          rel=2e-3, abs=0.2)
+    # every common structure of two or three nano-batches with every row assignment, index order
+    import itertools
+    best_common = min(per_layer({k: bounds for k in pm.KINDS}, list(assign), 0.2)
+                      for n in (2, 3) for bounds in pm.all_bounds(64, g, n)
+                      for assign in itertools.product(rows, repeat=n))
+    assert got["est_us"] < 0.95 * best_common
