@@ -413,11 +413,22 @@ def main():
             kept_ms, kept_plan = rec["ms"], pl
         elif pl is not best_plan:
             pl.close()
+    # The short trials differ by less than their own scatter near the top: the best split pipeline
+    # is timed again, alternating with the unsplit one, and replaces it only if it is at least
+    # 1 % faster (otherwise the headline would change hands from box to box on noise).
+    if kept_plan is not unsplit_plan:
+        rounds = [(hz.time_plan(case, unsplit_plan, 2, 12), hz.time_plan(case, kept_plan, 2, 12)) for _ in range(3)]
+        u_ms, s_ms = (float(np.median([r[i] for r in rounds])) for i in (0, 1))
+        verify["confirm"] = {"unsplit_ms": u_ms, "split_ms": s_ms, "rounds": rounds, "kept_split": s_ms < 0.99 * u_ms}
+        if not verify["confirm"]["kept_split"]:
+            if kept_plan is not best_plan:
+                kept_plan.close()
+            kept_plan, kept_ms = unsplit_plan, u_ms
     if kept_plan is not best_plan:
         d = kept_plan.describe()
         best_c = {k: d[k] for k in plan_keys}
         if kept_plan is unsplit_plan and verify["trials"]:
-            best_c["origin"] += "; every split pipeline lost its trial run"
+            best_c["origin"] += "; no split pipeline beat it by 1 % in its trial run"
         if len(best_desc["bounds"]) > 2 or kept_plan is not unsplit_plan:
             best_plan_searched = best_plan
         best_plan = kept_plan
