@@ -142,8 +142,21 @@ def run(config: str = "C2", out=print):
              ("two nano-batches overlapped, attention of the second on 128 workgroups", [0, B // 2, B], [0, 128], None, True),
              ("two nano-batches overlapped, 256 attention workgroups, 128x256 GEMM tiles beside them", [0, B // 2, B],
               [0, 256], [[22] * 4, [0] * 4], True)]
+    # a partition per operation (the shape the search's last pass proposes for this layer): KQV and
+    # Down whole, attention / O / Up-Gate cut at three quarters of the batch, so that only the
+    # second attention nano-operation has GEMMs (O and Up/Gate of the first rows) beside it
+    cut = max(1, B * 3 // 4)
+    split = [0, cut, B] if cut < B else [0, B]
+    specs.append(("a partition per operation: attention, O and Up/Gate cut at 3/4 of the batch, KQV and Down whole; "
+                  "attention on 192 then 128 workgroups, O and Up/Gate as 128x256 tiles (with O as 256x256 tiles, which take whole CUs and "
+                  "start together with the second attention piece, that piece lands two workgroups to a CU: 980 instead of 615 us)",
+                  dict(KQV=[0, B], ATTN=split, O=split, UG=split, D=[0, B]), [192, 128][:len(split) - 1], [0, 21, 21, 0],
+                  True))
     for name, bounds, wgs, tiles, overlap in specs:
-        p = nf.nf_plan_manual_ops(ctx, m, case.args, bounds, overlap, wgs, tiles)
+        if isinstance(bounds, dict):
+            p = nf.nf_plan_manual_parts(ctx, m, case.args, bounds, overlap, wgs, tiles)
+        else:
+            p = nf.nf_plan_manual_ops(ctx, m, case.args, bounds, overlap, wgs, tiles)
         t = hz.time_plan(case, p, 3, 10)
         out(f"   -- {name}: bounds {bounds}, {t:.3f} ms per step untraced")
         ctx.set_trace(2)
@@ -153,6 +166,7 @@ def run(config: str = "C2", out=print):
         ctx.set_trace(0)
         for r in recs:
             st, ms = r["start_ms"] * 1e3, r["ms"] * 1e3
-            out("      %8.1f %8.1f %7.1f  %-12s %-4s nano-batch %d" % (st, st + ms, ms, r["kernel"], r["op"], r["nano"]))
+            out("      %8.1f %8.1f %7.1f  %-12s %-4s piece %d, tokens [%d, %d)" % (st, st + ms, ms, r["kernel"], r["op"],
+                                                                              r["nano"], r["tok_begin"], r["tok_end"]))
         p.close()
     case.ctx.close()
