@@ -534,6 +534,20 @@ int nf_op_argmax(const void *logits, int n_rows, int vocab, const int32_t *out_i
  */
 int nf_ctx_set_kv_offload(nf_ctx *ctx, void *host_rows /* host */, size_t layer_stride_bytes);
 
+/*
+ * KV loading and scattering (Sec. 4.2.2; also the swap-out and reload of Sec. 4.2.1): the cache
+ * of a request crosses the bus as one contiguous copy, and on the device its pages are gathered
+ * from, or scattered to, the places the page allocator gave them.
+ * scatter = 0: staging page i = pool page page_ids[i];  scatter = 1: pool page page_ids[i] =
+ * staging page i, for i < n_pages.  pool (num_pages pages of page_bytes bytes: the pages of
+ * nf_kv_cache), staging (n_pages contiguous pages) and page_ids are DEVICE pointers;
+ * page_bytes % 16 == 0 (NF_ESHAPE).  Ids outside [0, num_pages) are skipped.  Ids must be
+ * distinct when scattering.  Enqueues one kernel on hip_stream; the copy between staging and
+ * host memory is the caller's.
+ */
+int nf_op_move_pages(void *pool, size_t page_bytes, int64_t num_pages, const int32_t *page_ids, int n_pages,
+                     void *staging, int scatter, void *hip_stream);
+
 /* ---- continuous batching (Sec. 4.2.1 "Request scheduling"), host only ---------------------- */
 
 /*

@@ -30,7 +30,7 @@ EXPORTS = [
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
     "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency", "nf_simulate_pipeline_ops",
-    "nf_plan_manual_parts", "nf_simulate_pipeline_parts",
+    "nf_plan_manual_parts", "nf_simulate_pipeline_parts", "nf_op_move_pages",
 ]
 
 
@@ -132,6 +132,7 @@ def lib() -> C.CDLL:
                                        P(C.c_int32), P(C.c_int32), P(vp)]
     L.nf_simulate_pipeline_parts.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, P(nf_partitions), i32,
                                              P(C.c_int32), P(C.c_double)]
+    L.nf_op_move_pages.argtypes = [vp, sz, C.c_int64, vp, i32, vp, i32, vp]
     L.nf_probe_load_latency.argtypes = [vp, i32, i32, vp, vp]
     L.nf_plan_describe.argtypes = [vp, C.c_char_p, sz]
     L.nf_plan_destroy.argtypes = [vp]
@@ -437,6 +438,12 @@ def nf_op_embedding(token_ids_ptr, from_slot_ptr, slot_tokens_ptr, table_ptr, ta
     f.argtypes = [C.c_void_p] * 4 + [C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     _check(f(token_ids_ptr, from_slot_ptr, slot_tokens_ptr, table_ptr, int(table_rows), out_ptr, int(n_rows),
              int(width), stream), "nf_op_embedding")
+
+
+def nf_op_move_pages(pool_ptr, page_bytes, num_pages, page_ids_ptr, n_pages, staging_ptr, scatter, stream=0):
+    """Gather (scatter = False) pool pages into a contiguous device buffer, or scatter them back."""
+    _check(lib().nf_op_move_pages(pool_ptr, int(page_bytes), int(num_pages), page_ids_ptr, int(n_pages), staging_ptr,
+                                  int(bool(scatter)), stream), "nf_op_move_pages")
 
 
 def nf_op_argmax(logits_ptr, n_rows, vocab, out_index_ptr, out_ptr, stream=0):

@@ -846,3 +846,13 @@ extern "C" int nf_op_argmax(const void* logits, int n_rows, int vocab, const int
   return nf_launch_argmax(logits, n_rows, vocab, out_index, out, (hipStream_t)hip_stream) == hipSuccess ? NF_OK
                                                                                                         : NF_EHIP;
 }
+
+extern "C" int nf_op_move_pages(void* pool, size_t page_bytes, int64_t num_pages, const int32_t* page_ids, int n_pages,
+                                void* staging, int scatter, void* hip_stream) {
+  if (!pool || !staging || n_pages < 0 || num_pages < 0 || (n_pages > 0 && !page_ids)) return NF_EINVAL;
+  if (page_bytes == 0 || page_bytes % 16) return NF_ESHAPE;
+  return nf_launch_move_pages(pool, page_bytes, (long)num_pages, page_ids, n_pages, staging, scatter ? 1 : 0,
+                              (hipStream_t)hip_stream) == hipSuccess
+             ? NF_OK
+             : NF_EHIP;
+}

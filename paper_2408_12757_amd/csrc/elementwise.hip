@@ -205,6 +205,26 @@ hipError_t nf_launch_fill_random(void* p, size_t n_elems, uint32_t seed, float s
 
 namespace {
 
+// Moves whole KV pages between their scattered places in a pool and a contiguous buffer
+// (Sec. 4.2.2, loading and scattering: a request's cache crosses the bus as one contiguous
+// copy; on the device its pages are gathered from / scattered to wherever the allocator put
+// them).  One 16-byte element per thread and step; ids outside the pool are skipped.
+__global__ __launch_bounds__(256) void move_pages_kernel(char* __restrict__ pool, const int32_t* __restrict__ ids,
+                                                         int n, long chunks_per_page, long num_pages,
+                                                         char* __restrict__ staging, int scatter) {
+  const long total = (long)n * chunks_per_page;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    const long id = ids[i / chunks_per_page];
+    if (id < 0 || id >= num_pages) continue;
+    u32x4* in_pool = reinterpret_cast<u32x4*>(pool) + id * chunks_per_page + i % chunks_per_page;
+    u32x4* in_line = reinterpret_cast<u32x4*>(staging) + i;
+    if (scatter)
+      *in_pool = *in_line;
+    else
+      *in_line = *in_pool;
+  }
+}
+
 // Copies the K and V part of the qkv rows of tokens [tok_begin, tok_begin + n_tok) to rows
 // tok_begin.. of a host buffer the device can write (Sec. 4.2.2: the fresh K/V vectors are
 // contiguous right after KQV generation and leave the GPU through a copy the GPU itself
@@ -248,5 +268,16 @@ hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin,
   const int blocks = (int)std::min<long>(64, (total + 255) / 256);
   kv_offload_kernel<<<dim3(blocks), dim3(256), 0, s>>>((const bf16_t*)qkv, (bf16_t*)host_rows, tok_begin,
                                                        tok_end - tok_begin, n_qkv, n_q_heads * head_dim, row_elems);
+  return hipGetLastError();
+}
+
+hipError_t nf_launch_move_pages(void* pool, size_t page_bytes, long num_pages, const int32_t* page_ids, int n,
+                                void* staging, int scatter, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const long chunks = (long)(page_bytes / 16);
+  const long total = (long)n * chunks;
+  const int blocks = (int)std::min<long>(4096, (total + 255) / 256);
+  move_pages_kernel<<<dim3(blocks), dim3(256), 0, s>>>((char*)pool, page_ids, n, chunks, num_pages, (char*)staging,
+                                                       scatter);
   return hipGetLastError();
 }

@@ -48,6 +48,8 @@ hipError_t nf_launch_rope_append(void* qkv, void* pages, const int32_t* tok_req,
                                  float rope_theta, int write_k_back, hipStream_t s);
 // Copies the (rotated) K and V parts of qkv rows [tok_begin, tok_end) to the same rows of a
 // device-writable host buffer of 2 * n_kv_heads * head_dim elements per row.
+hipError_t nf_launch_move_pages(void* pool, size_t page_bytes, long num_pages, const int32_t* page_ids, int n,
+                                void* staging, int scatter, hipStream_t s);
 hipError_t nf_launch_kv_offload(const void* qkv, void* host_rows, int tok_begin, int tok_end, int n_q_heads,
                                 int n_kv_heads, int head_dim, hipStream_t s);
 // Number of K segments of a dense operation: 1, or 2 for the long-K, narrow-N operations

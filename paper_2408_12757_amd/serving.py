@@ -142,20 +142,28 @@ class ServingEngine:
     def _swap(self, fb: nf.FormedBatch):
         for rid in fb.released:
             self.host_store.pop(rid, None)
+        # pages are gathered into / scattered from a contiguous device buffer by the library
+        # (nf_op_move_pages); torch only allocates the buffers and copies them across the bus
         with torch.cuda.stream(self.stream):
+            s = self.stream.cuda_stream
             for rid, pages in fb.swap_out:
-                idx = torch.from_numpy(pages.astype(np.int64)).to(self.device)
+                idx = torch.from_numpy(np.ascontiguousarray(pages, dtype=np.int32)).to(self.device)
                 saved = []
                 for pool in self.pools:
+                    line = torch.empty((len(pages), pool.shape[1]), dtype=pool.dtype, device=self.device)
+                    nf.nf_op_move_pages(pool.data_ptr(), pool.shape[1] * pool.element_size(), pool.shape[0],
+                                        idx.data_ptr(), len(pages), line.data_ptr(), False, s)
                     host = torch.empty((len(pages), pool.shape[1]), dtype=pool.dtype, pin_memory=True)
-                    host.copy_(pool.index_select(0, idx), non_blocking=True)
+                    host.copy_(line, non_blocking=True)
                     saved.append(host)
                 self.host_store[rid] = saved
             for rid, pages in fb.swap_in:
-                idx = torch.from_numpy(pages.astype(np.int64)).to(self.device)
+                idx = torch.from_numpy(np.ascontiguousarray(pages, dtype=np.int32)).to(self.device)
                 saved = self.host_store.pop(rid)
                 for pool, host in zip(self.pools, saved):
-                    pool.index_copy_(0, idx, host.to(self.device, non_blocking=True))
+                    line = host.to(self.device, non_blocking=True)
+                    nf.nf_op_move_pages(pool.data_ptr(), pool.shape[1] * pool.element_size(), pool.shape[0],
+                                        idx.data_ptr(), len(pages), line.data_ptr(), True, s)
 
     def _upload(self, fb: nf.FormedBatch) -> nf.BatchArgs:
         # pinned staging + a copy stream of its own: the arrays of iteration k + 1 cross the bus

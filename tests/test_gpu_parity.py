@@ -466,6 +466,42 @@ def test_kv_offload_delivers_the_appended_rows_and_changes_nothing_else(ctx):
         plan.close()
 
 
+def test_pages_are_gathered_and_scattered_bit_for_bit():
+    """KV loading and scattering (Sec. 4.2.2): pool pages named by an id list land in a contiguous
+    buffer in list order and go back to (other) places in the pool; ids outside the pool are
+    skipped; nothing else in the pool or in the buffer changes."""
+    r = np.random.default_rng(11)
+    num_pages, elems, n = 300, 2 * 8 * 16 * 128, 37          # a C2 page: K and V blocks of 8 kv heads
+    pool_h = r.integers(0, 1 << 16, size=(num_pages, elems), dtype=np.uint16)
+    pool = hz.bf16_tensor(pool_h, DEV)
+    ids = r.choice(num_pages, size=n, replace=False).astype(np.int32)
+    ids_bad = ids.copy()
+    ids_bad[5], ids_bad[20] = -1, num_pages
+    line = torch.full((n, elems), 3.0, dtype=torch.bfloat16, device=DEV)
+    before = hz.bf16_bits(line).copy()
+    d_ids = torch.from_numpy(ids_bad).to(DEV)
+    nf.nf_op_move_pages(pool.data_ptr(), elems * 2, num_pages, d_ids.data_ptr(), n, line.data_ptr(), False)
+    torch.cuda.synchronize()
+    got = hz.bf16_bits(line)
+    for i in range(n):
+        want = before[i] if i in (5, 20) else pool_h[ids[i]]
+        assert np.array_equal(got[i], want), i
+    assert np.array_equal(hz.bf16_bits(pool), pool_h)
+    # scatter the gathered pages to a disjoint set of places
+    free = np.setdiff1d(np.arange(num_pages), ids)
+    dst = r.choice(free, size=n, replace=False).astype(np.int32)
+    d_dst = torch.from_numpy(dst).to(DEV)
+    nf.nf_op_move_pages(pool.data_ptr(), elems * 2, num_pages, d_dst.data_ptr(), n, line.data_ptr(), True)
+    torch.cuda.synchronize()
+    want_pool = pool_h.copy()
+    want_pool[dst] = got
+    assert np.array_equal(hz.bf16_bits(pool), want_pool)
+    nf.nf_op_move_pages(pool.data_ptr(), elems * 2, num_pages, d_dst.data_ptr(), 0, line.data_ptr(), True)   # nothing to move
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_op_move_pages(pool.data_ptr(), 24, num_pages, d_dst.data_ptr(), n, line.data_ptr(), True)
+    assert e.value.status == nf.NF_ESHAPE
+
+
 def test_plan_mismatch_and_workspace_errors(ctx):
     cfg = wl.CONFIGS["C1"]
     b = wl.make_batch(cfg.batch, cfg.seed + 2)
