@@ -390,13 +390,8 @@ def main():
     kept_ms = t_u
     kept_plan = unsplit_plan
     for rank, refine in [(0, 2)] + [(r, f) for r in range(1, 11) for f in (2, 1, 0)]:
-        nf.nf_tune_set("search.rank", rank)
-        nf.nf_tune_set("search.refine", refine)
-        try:
-            pl = best_plan if rank == 0 else nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
-        finally:
-            nf.nf_tune_set("search.rank", 0)
-            nf.nf_tune_set("search.refine", 2)
+        pl = best_plan if rank == 0 else nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, rank=rank,
+                                                           refine=refine)
         d = pl.describe()
         rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "partitions", "est_time_us")}
         rec["gemm_tiles"] = sorted({o["gemm_tile"] for o in d["ops"] if o["op"] != "ATTN"})
@@ -540,15 +535,7 @@ def main():
         # model's ranking of the R -> P rows is then refined by trial runs of its best candidates
         trials, best_chain = [], None
         for rank, refine in [(0, 2)] + [(r, f) for r in range(1, 11) for f in (2, 1, 0)]:
-            nf.nf_tune_set("search.layers", L)
-            nf.nf_tune_set("search.rank", rank)
-            nf.nf_tune_set("search.refine", refine)
-            try:
-                pl = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
-            finally:
-                nf.nf_tune_set("search.layers", 1)
-                nf.nf_tune_set("search.rank", 0)
-                nf.nf_tune_set("search.refine", 2)
+            pl = nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, layers=L, rank=rank, refine=refine)
             d = pl.describe()
             rec = {k: d[k] for k in ("bounds", "overlap", "nano_attn_wgs", "order", "partitions", "est_time_us")}
             rec["gemm_tiles"] = sorted({o["gemm_tile"] for o in d["ops"] if o["op"] != "ATTN"})

@@ -266,6 +266,26 @@ int nf_plan_nanobatches(nf_ctx *ctx, const nf_model_desc *model, const nf_batch 
                         int max_nano, int granule, nf_plan **out);
 
 /*
+ * nf_plan_nanobatches with the knobs of the search passed by the caller instead of taken from the
+ * process-wide keys of nf_tune_set (two engines in one process do not disturb each other):
+ * max_nano, granule as above; layers = 1: the makespan of one layer is minimised, n in 2..16: the
+ * time per layer of a run of n consecutive layers pipelined across the layer boundaries (what
+ * nf_layers_forward runs); rank, refine, max_parts: keys "search.rank", "search.refine",
+ * "search.max_parts".  NF_EINVAL for a value outside its key's range.
+ */
+typedef struct nf_search_options {
+  int32_t max_nano;
+  int32_t granule;
+  int32_t layers;
+  int32_t rank;
+  int32_t refine;
+  int32_t max_parts;
+  int32_t reserved[2];
+} nf_search_options;
+int nf_plan_search(nf_ctx *ctx, const nf_model_desc *model, const nf_batch *batch,
+                   const nf_search_options *options /* host */, nf_plan **out);
+
+/*
  * Host-only forms of the search (no GPU needed; used by CPU tests and offline planning).
  * profile_path: text file written by nf_profile, or NULL for built-in analytic estimates.
  * nf_search_pipeline returns the structure nf_plan_nanobatches would pick from that profile.

@@ -30,7 +30,7 @@ EXPORTS = [
     "nf_sched_create", "nf_sched_destroy", "nf_sched_submit", "nf_sched_next_batch", "nf_sched_complete",
     "nf_sched_get_stats", "nf_ctx_set_kv_offload", "nf_op_embedding", "nf_op_argmax", "nf_op_attention_static",
     "nf_attention_static_bytes", "nf_plan_manual_ops", "nf_probe_load_latency", "nf_simulate_pipeline_ops",
-    "nf_plan_manual_parts", "nf_simulate_pipeline_parts", "nf_op_move_pages",
+    "nf_plan_manual_parts", "nf_simulate_pipeline_parts", "nf_op_move_pages", "nf_plan_search",
 ]
 
 
@@ -66,6 +66,11 @@ class nf_pipeline_desc(C.Structure):
                 ("gemm_tile", C.c_int32), ("reserved", C.c_int32), ("nano_attn_wgs", C.c_int32 * 8),
                 ("order", C.c_int32 * 8), ("parts", nf_partitions), ("est_us", C.c_double),
                 ("est_us_stage1", C.c_double), ("est_us_unsplit", C.c_double)]
+
+
+class nf_search_options(C.Structure):
+    _fields_ = [("max_nano", C.c_int32), ("granule", C.c_int32), ("layers", C.c_int32), ("rank", C.c_int32),
+                ("refine", C.c_int32), ("max_parts", C.c_int32), ("reserved", C.c_int32 * 2)]
 
 
 class nf_nano_spec(C.Structure):
@@ -125,6 +130,7 @@ def lib() -> C.CDLL:
     L.nf_simulate_pipeline_ops.argtypes = [P(nf_model_desc), P(nf_batch), C.c_char_p, i32, P(C.c_int32), P(C.c_int32),
                                            P(C.c_int32), P(C.c_double)]
     L.nf_plan_nanobatches.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, i32, P(vp)]
+    L.nf_plan_search.argtypes = [vp, P(nf_model_desc), P(nf_batch), P(nf_search_options), P(vp)]
     L.nf_plan_manual.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32, i32, P(vp)]
     L.nf_plan_manual_ops.argtypes = [vp, P(nf_model_desc), P(nf_batch), i32, P(C.c_int32), i32, i32, i32,
                                      P(nf_nano_spec), P(vp)]
@@ -371,6 +377,17 @@ def nf_plan_nanobatches(ctx: Context, model, batch: BatchArgs, max_nano: int = 0
     md = model_desc(model)
     _check(lib().nf_plan_nanobatches(ctx.handle, C.byref(md), C.byref(batch.struct), int(max_nano), int(granule),
                                      C.byref(h)), "nf_plan_nanobatches", ctx)
+    return Plan(ctx, h)
+
+
+def nf_plan_search(ctx: Context, model, batch: BatchArgs, max_nano: int = 0, granule: int = 128, layers: int = 1,
+                   rank: int = 0, refine: int = 2, max_parts: int = 0) -> Plan:
+    """nf_plan_nanobatches with the search's knobs given here instead of through nf_tune_set."""
+    h = C.c_void_p()
+    md = model_desc(model)
+    opt = nf_search_options(int(max_nano), int(granule), int(layers), int(rank), int(refine), int(max_parts))
+    _check(lib().nf_plan_search(ctx.handle, C.byref(md), C.byref(batch.struct), C.byref(opt), C.byref(h)),
+           "nf_plan_search", ctx)
     return Plan(ctx, h)
 
 

@@ -696,7 +696,10 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   // best row's pipeline (r = 1 is the best row) whatever its estimate
   const size_t rank = (size_t)std::max(0, in.rank);
   const size_t pick = rank > 0 ? rank - 1 : 0;
-  if (pick < per_row.size()) {
+  // the refinement passes have gained up to an eighth in the cases seen; a best row that is
+  // further than that from unsplit is not worth their time (they run per batch in a serving loop)
+  const bool hopeless = rank == 0 && !per_row.empty() && per_row[0].t2 > 1.15 * out->est_us_unsplit;
+  if (pick < per_row.size() && !hopeless) {
     const RowBest& b = per_row[pick];
     out->bounds = cands[b.cand].bounds;
     out->overlap = 1;

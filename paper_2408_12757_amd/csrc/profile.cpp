@@ -385,15 +385,23 @@ bool same_shape(const nf_model_desc& a, const nf_model_desc& b) {
          a.head_dim == b.head_dim && a.ffn_inner == b.ffn_inner;
 }
 
-void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano, int granule, NfSearchInput* in) {
+// The search's knobs: the process-wide ones of nf_tune_set, or those a caller passes with
+// nf_plan_search.
+struct SearchKnobs {
+  int layers, rank, refine, max_parts;
+};
+SearchKnobs process_knobs() { return SearchKnobs{nf_search_layers(), g_search_rank, g_search_refine, g_search_max_parts}; }
+
+void build_search_input(const nf_model_desc* m, const nf_batch* b, int max_nano, int granule, NfSearchInput* in,
+                        const SearchKnobs& knobs = process_knobs()) {
   const int n_reqs = b->n_prefill_reqs + b->n_decode_reqs;
   in->n_tokens = b->n_tokens;
   in->granule = granule;
   in->max_nano = max_nano;
-  in->layers = nf_search_layers();
-  in->rank = g_search_rank;
-  in->refine = g_search_refine;
-  in->max_parts = g_search_max_parts;
+  in->layers = knobs.layers;
+  in->rank = knobs.rank;
+  in->refine = knobs.refine;
+  in->max_parts = knobs.max_parts;
   in->tie_ffn = m->n_experts > 1;
   in->attn_mb_prefix.assign((size_t)b->n_tokens + 1, 0.0);
   in->req_start_of_tok.assign((size_t)b->n_tokens, 0);
@@ -606,8 +614,34 @@ extern "C" int nf_simulate_pipeline_parts(const nf_model_desc* model, const nf_b
   return NF_EINVAL;
 }
 
+static int plan_search(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano, int granule,
+                       const SearchKnobs& knobs, nf_plan** out);
+
 extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano,
                                    int granule, nf_plan** out) try {
+  return plan_search(ctx, model, batch, max_nano, granule, process_knobs(), out);
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
+extern "C" int nf_plan_search(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch,
+                              const nf_search_options* opt, nf_plan** out) try {
+  if (!opt) return NF_EINVAL;
+  if (opt->layers < 1 || opt->layers > 16 || opt->rank < 0 || opt->rank > 64 || opt->refine < 0 || opt->refine > 2 ||
+      opt->max_parts < 0 || opt->max_parts > NF_MAX_PARTS)
+    return NF_EINVAL;
+  return plan_search(ctx, model, batch, opt->max_nano, opt->granule,
+                     SearchKnobs{opt->layers, opt->rank, opt->refine, opt->max_parts}, out);
+} catch (const std::bad_alloc&) {
+  return NF_ENOMEM;
+} catch (...) {
+  return NF_EINVAL;
+}
+
+static int plan_search(nf_ctx* ctx, const nf_model_desc* model, const nf_batch* batch, int max_nano, int granule,
+                       const SearchKnobs& knobs, nf_plan** out) {
   if (!ctx || !out || granule < 1 || max_nano < 0) return NF_EINVAL;
   *out = nullptr;
   int rc = nf_validate_model(model);
@@ -617,7 +651,7 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   NfProfile tmp;
   const NfProfile* prof = pick_profile(ctx, model, batch->n_tokens, granule, &tmp);
   NfSearchInput in;
-  build_search_input(model, batch, max_nano, granule, &in);
+  build_search_input(model, batch, max_nano, granule, &in, knobs);
   NfPipeline pl;
   rc = nf_search(*prof, in, &pl);
   if (rc) return rc;
@@ -654,7 +688,7 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
   // from the O nano-operation that waits for the last attention nano-operation on.  They take the
   // implementation that is fastest alone, not the one of the chosen R -> P pair.
   std::vector<char> runs_alone((*out)->ops.size(), 0);
-  if (pl.overlap && nf_search_layers() <= 1) {
+  if (pl.overlap && knobs.layers <= 1) {
     int last_attn = -1, first_kqv = -1;
     for (size_t i = 0; i < (*out)->ops.size(); ++i) {
       if ((*out)->ops[i].kind == NF_OP_ATTN) last_attn = (int)i;
@@ -682,8 +716,4 @@ extern "C" int nf_plan_nanobatches(nf_ctx* ctx, const nf_model_desc* model, cons
     op.gemm_tile = (pl.overlap && pl.gemm_tile && !alone) ? pl.gemm_tile : prof->dense_tile[dense][idx];
   }
   return NF_OK;
-} catch (const std::bad_alloc&) {
-  return NF_ENOMEM;
-} catch (...) {
-  return NF_EINVAL;
 }

@@ -248,11 +248,8 @@ class ServingEngine:
                 x = x(fb)
             args = self._upload(fb)
             if self.auto_search and fb.n_tokens >= 2 * self.granule:
-                nf.nf_tune_set("search.layers", max(1, min(16, self.n_layers)))
-                try:
-                    plan = nf.nf_plan_nanobatches(self.ctx, self.model, args, 0, self.granule)
-                finally:
-                    nf.nf_tune_set("search.layers", 1)
+                plan = nf.nf_plan_search(self.ctx, self.model, args, 0, self.granule,
+                                         layers=max(1, min(16, self.n_layers)))
             else:
                 bounds = self.bounds_fn(fb.n_tokens) if self.bounds_fn else [0, fb.n_tokens]
                 plan = nf.nf_plan_manual(self.ctx, self.model, args, bounds, self.overlap and len(bounds) > 2, 0, 0,

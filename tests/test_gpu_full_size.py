@@ -88,6 +88,10 @@ def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
              nf.nf_plan_manual(case.ctx, m, case.args, [0, 1024, 2048], True, 0, 0, 256),
              nf.nf_plan_manual(case.ctx, m, case.args, [0, 128, 1152, 2048], True, 0, 0, 0),
              nf.nf_plan_manual(case.ctx, m, case.args, [0, 100, 2048], False),     # cuts the prefill request
+             # the search with its knobs passed by the caller: the best row's pipeline for a run of layers,
+             # and the third best row's without the refinement passes
+             nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, layers=8, rank=1, refine=2),
+             nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, rank=3, refine=0),
              # a partition per operation: attention in four pieces with alternating shares, the rest in two
              nf.nf_plan_manual_parts(case.ctx, m, case.args,
                                      dict(KQV=[0, 1024, 2048], ATTN=[0, 512, 1024, 1536, 2048], O=[0, 1024, 2048],
@@ -98,6 +102,13 @@ def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
         out = hz.bf16_bits(case.forward(p))
         torch.cuda.synchronize()
         assert np.array_equal(out, out1), d["bounds"]
+    for p in plans[4:6]:                                # rank > 0: a split pipeline whatever its estimate
+        d = p.describe()
+        assert max(len(x) for x in d["partitions"] + [d["bounds"]]) > 2, d
+    for bad in (dict(layers=0), dict(layers=17), dict(refine=3), dict(rank=-1), dict(max_parts=9)):
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, **bad)
+        assert e.value.status == nf.NF_EINVAL
     # the profile file round-trips through the host-only search
     got = nf.nf_search_pipeline(m, case.args, str(tmp_path / "profile.txt"), 0, cfg.granule)
     assert got["bounds"] == plans[0].describe()["bounds"]
