@@ -461,6 +461,29 @@ def main():
     attn_bytes_step = costs["DecAttn"].bytes + costs["PfAttn"].bytes
     attn_ms_step = sum(attn_ms) / args.steps
     achieved = attn_bytes_step / (attn_ms_step * 1e-3) / 1e9
+    # ---- every kernel of the unsplit layer against its own roofline (a short traced run: HIP events
+    # around each kernel on its stream; the events cost a few microseconds per kernel, so this run
+    # is not the timed one) ----
+    n_tr = 10
+    _, krecs = timed(unsplit_plan, n_tr, 3, trace=2)
+    by_kernel = {}
+    for r in krecs:
+        by_kernel.setdefault((r["kernel"], r["op"]), []).append(r["ms"])
+    kernel_rooflines = []
+    gemm_cost = {"KQV": "KQV", "O": "O", "UG": "UG", "D": "D"}
+    for (kname, op), ms_list in by_kernel.items():
+        us = 1e3 * sum(ms_list) / n_tr              # per step (an operation may take several launches)
+        rec = {"kernel": kname, "op": op, "us_per_step": us, "launches_per_step": len(ms_list) / n_tr}
+        if kname == "gemm" and op in gemm_cost:
+            fl = costs[gemm_cost[op]].flops
+            rec.update(bound="mfma", achieved=fl / (us * 1e-6) / 1e12, peak=cm.MI355X_PEAK_BF16_FLOPS / 1e12,
+                       unit="TFLOP/s")
+        elif kname == "attention":
+            rec.update(bound="hbm", achieved=attn_bytes_step / (us * 1e-6) / 1e9, peak=cm.MI355X_PEAK_HBM_BPS / 1e9,
+                       unit="GB/s")
+        if "achieved" in rec:
+            rec["frac"] = rec["achieved"] / rec["peak"]
+        kernel_rooflines.append(rec)
     # ---- ablation (Sec. 6.4): unsplit, nano-batched sequential, nano-batched overlapped ----
     n_abl = max(10, args.steps // 4)
     unsplit_ms, _ = timed(unsplit_plan, n_abl, 3)
@@ -591,6 +614,9 @@ def main():
                                "frac": roof["t_roofline"] * 1e3 / ms_step,
                                "peaks": {"bf16_mfma_flops": cm.MI355X_PEAK_BF16_FLOPS,
                                          "hbm_bytes_per_s": cm.MI355X_PEAK_HBM_BPS}},
+        "kernel_rooflines": {"note": "unsplit layer, traced run (HIP events around every kernel); dense operations "
+                                     "against the bf16 MFMA peak, attention against the HBM peak, algorithmic flops / bytes",
+                             "kernels": kernel_rooflines},
         "ablation_ms": {"structure": abl_bounds, "unsplit": unsplit_ms, "nano_sequential": seq_ms,
                         "nano_overlapped": ovl_ms, "overlapped_attn_wgs": best_trial["attn_wgs"],
                         "overlapped_gemm_tile": ovl_tile, "overlapped_trials": ovl_trials,
