@@ -85,11 +85,13 @@ def test_argument_errors_are_reported_before_anything_touches_the_gpu():
         nf.nf_op_argmax(1, 4, 60, None, 1)
     assert e.value.status == nf.NF_ESHAPE
     for key, value in (("no.such.key", 1), ("gemm.tile", 99), ("gemm.tile", 26), ("gemm.tile", -1), ("search.layers", 0), ("search.rank", -1),
-                       ("gemm.grouped_tile", 3), ("attention.variant", 8)):
+                       ("gemm.grouped_tile", 3), ("attention.variant", 8), ("search.refine", 3), ("search.refine", -1),
+                       ("search.max_parts", 9), ("search.max_parts", -1)):
         with pytest.raises(nf.NfError) as e:
             nf.nf_tune_set(key, value)
         assert e.value.status == nf.NF_EINVAL, key
-    for key, value in (("gemm.tile", 25), ("gemm.tile", 0), ("search.layers", 1), ("search.rank", 0), ("gemm.grouped_tile", 0)):
+    for key, value in (("gemm.tile", 25), ("gemm.tile", 0), ("search.layers", 1), ("search.rank", 0), ("gemm.grouped_tile", 0),
+                       ("search.refine", 0), ("search.refine", 2), ("search.max_parts", 8), ("search.max_parts", 0)):
         nf.nf_tune_set(key, value)
 
 
