@@ -62,6 +62,9 @@ def parse_args():
                     help="also time this many consecutive layers (distinct weights and KV pools) in one "
                          "nf_layers_forward call and report the time per layer; 0 = skip")
     ap.add_argument("--no-measured-peaks", action="store_true", help="skip the MFMA / HBM ceiling measurement")
+    ap.add_argument("--confirm-margin", type=float, default=0.99,
+                    help="the best split pipeline of the trial runs becomes the timed plan if its confirmation run takes "
+                         "less than this fraction of the unsplit time")
     ap.add_argument("--other-steps", type=int, default=5,
                     help="with the headline configuration: also time this many steps of C3 and C4 and a short window "
                          "of the C5 loop and report them under other_configs (0 = skip)")
@@ -387,7 +390,7 @@ def main():
     # splits the batch is kept only if it beats the unsplit one on the device.
     t_u = hz.time_plan(case, unsplit_plan, 3, 8)
     verify = {"unsplit_ms": t_u, "trials": []}
-    kept_ms = t_u
+    kept_ms = float("inf")          # the best split pipeline of the trials goes on to the confirmation run
     kept_plan = unsplit_plan
     for rank, refine in [(0, 2)] + [(r, f) for r in range(1, 11) for f in (2, 1, 0)]:
         pl = best_plan if rank == 0 else nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, rank=rank,
@@ -408,13 +411,17 @@ def main():
             kept_ms, kept_plan = rec["ms"], pl
         elif pl is not best_plan:
             pl.close()
-    # The short trials differ by less than their own scatter near the top: the best split pipeline
-    # is timed again, alternating with the unsplit one, and replaces it only if it is at least
-    # 1 % faster (otherwise the headline would change hands from box to box on noise).
-    if kept_plan is not unsplit_plan:
+    # The short trials differ by less than their own scatter near the top (and the first of them,
+    # the unsplit one, runs on a device that has just been profiling): the best split pipeline is
+    # timed again, alternating with the unsplit one, and replaces it only if it is at least 1 %
+    # faster (otherwise the headline would change hands from box to box on noise).
+    if kept_plan is unsplit_plan:
+        kept_ms = t_u
+    else:
         rounds = [(hz.time_plan(case, unsplit_plan, 2, 12), hz.time_plan(case, kept_plan, 2, 12)) for _ in range(3)]
         u_ms, s_ms = (float(np.median([r[i] for r in rounds])) for i in (0, 1))
-        verify["confirm"] = {"unsplit_ms": u_ms, "split_ms": s_ms, "rounds": rounds, "kept_split": s_ms < 0.99 * u_ms}
+        verify["confirm"] = {"unsplit_ms": u_ms, "split_ms": s_ms, "rounds": rounds, "kept_split": s_ms < args.confirm_margin * u_ms,
+                             "margin": args.confirm_margin}
         if not verify["confirm"]["kept_split"]:
             if kept_plan is not best_plan:
                 kept_plan.close()
@@ -423,7 +430,7 @@ def main():
         d = kept_plan.describe()
         best_c = {k: d[k] for k in plan_keys}
         if kept_plan is unsplit_plan and verify["trials"]:
-            best_c["origin"] += "; no split pipeline beat it by 1 % in its trial run"
+            best_c["origin"] += "; no split pipeline beat it by the confirmation margin in its trial run"
         if len(best_desc["bounds"]) > 2 or kept_plan is not unsplit_plan:
             best_plan_searched = best_plan
         best_plan = kept_plan
@@ -452,14 +459,24 @@ def main():
 
     # ---- the timed run: exactly --steps layer iterations, attention kernel traced with
     # HIP events on the stream it is launched on ----
-    ms_step, recs = timed(best_plan, args.steps, args.warmup, trace=1, marks=step_marks)
+    # An overlapped pipeline is timed without the events: a record in front of the attention kernel
+    # lets the GEMM that starts at the same moment on the other lane take its CUs first, and the
+    # persistent attention workgroups then stay where they landed (seen on the 70B layer: 4.89
+    # instead of 4.54 ms per step).  Its attention launches are measured in a traced run of the same
+    # plan right after, and the roofline object says so.
+    headline_overlapped = bool(best_plan.describe()["overlap"])
+    ms_step, recs = timed(best_plan, args.steps, args.warmup, trace=0 if headline_overlapped else 1, marks=step_marks)
     per_step = np.array([step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(len(step_marks) - 1)])
+    traced_steps = args.steps
+    if headline_overlapped:
+        traced_steps = max(5, args.steps // 4)
+        _, recs = timed(best_plan, traced_steps, 2, trace=1)
     attn_ms = [r["ms"] for r in recs if r["kernel"] == "attention"]
-    launches_per_step = max(1, len(attn_ms) // args.steps)
+    launches_per_step = max(1, len(attn_ms) // traced_steps)
     # algorithmic bytes of the attention kernel per step: K and V of every key read once per
     # kv head, plus q in / out once (decode + prefill rows)
     attn_bytes_step = costs["DecAttn"].bytes + costs["PfAttn"].bytes
-    attn_ms_step = sum(attn_ms) / args.steps
+    attn_ms_step = sum(attn_ms) / traced_steps
     achieved = attn_bytes_step / (attn_ms_step * 1e-3) / 1e9
     # ---- every kernel of the unsplit layer against its own roofline (a short traced run: HIP events
     # around each kernel on its stream; the events cost a few microseconds per kernel, so this run
@@ -631,7 +648,10 @@ def main():
                      "frac": achieved / (cm.MI355X_PEAK_HBM_BPS / 1e9),
                      "traffic": measured_traffic(f"attention_{cfg.name.lower()}"),
                      "launches_per_step": launches_per_step, "avg_launch_ms": attn_ms_step / launches_per_step,
-                     "algorithmic_bytes_per_step": attn_bytes_step},
+                     "algorithmic_bytes_per_step": attn_bytes_step,
+                     "measured_in": ("a traced run of the same overlapped plan right after the timed region (events in "
+                                     "front of the attention kernel disturb the placement of the two lanes' kernels)"
+                                     if headline_overlapped else "the timed region")},
     }
     if chained is not None:
         out["chained"] = chained
