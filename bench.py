@@ -307,17 +307,20 @@ def run_other_layer_config(name: str, steps: int, weight_copies: int):
         nf.nf_profile(case.ctx, m, b.n_tokens, cfg.granule, None)
     unsplit = nf.nf_plan_nanobatches(case.ctx, m, case.args, 1, cfg.granule)
     plan, t = unsplit, hz.time_plan(case, unsplit, 4, steps)
+    t_unsplit, t_searched = t, None
     if not m.is_moe:
         cand = nf.nf_plan_nanobatches(case.ctx, m, case.args, 0, cfg.granule)
-        if len(cand.describe()["bounds"]) > 2:
-            t_c = hz.time_plan(case, cand, 4, steps)
-            if t_c < t:
-                plan, t = cand, t_c
+        dc = cand.describe()
+        if max(len(x) for x in dc["partitions"] + [dc["bounds"]]) > 2:
+            t_searched = hz.time_plan(case, cand, 4, steps)
+            if t_searched < t:
+                plan, t = cand, t_searched
     d = plan.describe()
     out = {"ms_per_step": t, "tokens_per_s": b.n_tokens / (t * 1e-3), "steps": steps,
            "iteration_frac": roof["t_roofline"] * 1e3 / t, "iteration_roofline_ms": roof["t_roofline"] * 1e3,
-           "bound": roof["bound"], "plan": {k: d[k] for k in ("bounds", "overlap", "attn_wgs")},
-           "workload": cfg.description}
+           "bound": roof["bound"],
+           "plan": {k: d[k] for k in ("bounds", "overlap", "attn_wgs", "nano_attn_wgs", "partitions")},
+           "unsplit_ms": t_unsplit, "searched_split_ms": t_searched, "workload": cfg.description}
     case.ctx.close()
     del case
     torch.cuda.empty_cache()
