@@ -362,9 +362,10 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
       for (auto& e : ev) (void)hipEventDestroy(e);
     }
     // discard dominated pairs: another pair is better for both kernels (Sec. 4.1.1, the
-    // greyed-out pairs) - by more than the few per cent that two measurements of one pair differ
-    // by, so that a pair within the noise of its neighbour stays a candidate of the search
-    constexpr double kNoise = 1.03;
+    // greyed-out pairs) - by more than two measurements of one pair differ by (a tenth: how the
+    // hardware happens to place the persistent workgroups decides that much), so that a pair within
+    // the scatter of its neighbour stays a candidate of the search
+    constexpr double kNoise = 1.10;
     std::vector<NfRpRow> keep;
     for (const NfRpRow& r : p->rp) {
       bool dominated = false;
