@@ -284,7 +284,7 @@ extern "C" int nf_workspace_region(const nf_plan* plan, const char* name, size_t
              {"moe.slot_of", w.slot_of, m->n_experts > 1 ? B * k * 4 : 0}};
   for (auto& t : tab) {
     if (!strcmp(t.n, name)) {
-      *offset = (size_t)((const char*)t.p - (const char*)nullptr);
+      *offset = (size_t)reinterpret_cast<uintptr_t>(t.p);  // laid out from a null base: the address is the offset
       *bytes = t.b;
       return NF_OK;
     }
