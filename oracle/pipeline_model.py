@@ -19,6 +19,10 @@ nano-operation currently on the memory resource - and the nano-batches may be la
 ``order`` whose dependencies can be met (Sec. 4.1.2: number, size and order of the
 nano-operations are what the search decides).
 
+The two resources are two streams of the device: a nano-operation that waits for one on the
+other stream starts ``sync`` later than that one ends (a measured latency of the device; the
+paper's model has no such term, and ``sync`` = 0 gives the paper's model).
+
 Sec. 4.1.2 also lets every operation have its own number of nano-operations (Fig. 6: the
 operations near a bubble are split further than the others).  ``makespan_parts`` models that:
 one token partition per operation, the dependency rule above between the pieces, and the launch
@@ -47,7 +51,7 @@ def interp_dense(table: Sequence[float], granule: int, m: int) -> float:
 
 def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, bounds, overlap,
              row: Optional[dict], dt: float = 0.02, misc=None, layers: int = 1, rows: Optional[list] = None,
-             order: Optional[list] = None) -> Optional[float]:
+             order: Optional[list] = None, sync: float = 0.0) -> Optional[float]:
     """dense: dict op -> table of the best implementation; row: dict(p_gemm, p_attn,
     p_attn_solo[, p_gemm_solo][, dense]) or None.  A row that carries its own "dense" tables
     (the times of the GEMM implementation it was measured with) makes every GEMM of an
@@ -62,7 +66,9 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
     rows: one row per nano-batch (the row of the attention nano-operation that is running decides the
     speeds; all rows belong to one GEMM implementation, so rows[0] supplies the GEMM tables).
     order: order[k] = index of the nano-batch launched k-th; None (the function's result) when
-    an attention nano-operation would be launched before a KQV nano-operation it needs."""
+    an attention nano-operation would be launched before a KQV nano-operation it needs.
+    sync: a nano-operation that waits for one on the other resource starts that much later than
+    the moment the last of them ends (the latency of a dependency across two streams)."""
     if rows is not None:
         row = rows[0]
     if overlap and row is not None and row.get("dense") is not None:
@@ -106,16 +112,18 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
             work[("kqv", i, l)] = kqv[i]
             work[("att", i, l)] = att[i]
             work[("rest", i, l)] = rest[i]
-    done = set()
+    done = {}                               # nano-operation -> the time it ended
 
     def ready(op):
         kind, i, l = op
         if kind == "kqv":
             return True                     # the launch order already puts it behind its predecessor
         if kind == "rest":
-            return ("att", i, l) in done
-        lo = req_start[bounds[i]]           # attention also reads K/V appended by earlier ranges
-        return all(("kqv", j, l) in done for j in range(i + 1) if bounds[j + 1] > lo)
+            needs = [("att", i, l)]
+        else:
+            lo = req_start[bounds[i]]       # attention also reads K/V appended by earlier ranges
+            needs = [("kqv", j, l) for j in range(i + 1) if bounds[j + 1] > lo]
+        return all(p in done and t >= done[p] + sync - 1e-9 for p in needs)
 
     t = 0.0
     ci = mi = 0
@@ -123,7 +131,10 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
     while ci < len(compute) or mi < len(memory):
         c = compute[ci] if ci < len(compute) and ready(compute[ci]) else None
         m = memory[mi] if mi < len(memory) and ready(memory[mi]) else None
-        assert c is not None or m is not None, "deadlock"
+        if c is None and m is None:         # both resources wait out a synchronisation latency
+            assert sync > 0, "deadlock"
+            t += dt
+            continue
         sc = sm = 1.0
         cur = row
         if rows is not None and mi < len(memory):
@@ -138,12 +149,12 @@ def makespan(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start,
         if c is not None:
             left[c] -= sc * dt
             if left[c] <= 0:
-                done.add(c)
+                done[c] = t + dt
                 ci += 1
         if m is not None:
             left[m] -= sm * dt
             if left[m] <= 0:
-                done.add(m)
+                done[m] = t + dt
                 mi += 1
         t += dt
     return t
@@ -216,7 +227,8 @@ def launch_order(parts: dict) -> list:
 
 
 def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_start, parts: dict, overlap,
-                   rows: Optional[list] = None, dt: float = 0.02, misc=None, layers: int = 1) -> float:
+                   rows: Optional[list] = None, dt: float = 0.02, misc=None, layers: int = 1,
+                   sync: float = 0.0) -> float:
     """``makespan`` with a partition per operation.  rows: one table row per attention piece (the
     row of the attention piece at the head of the memory resource decides the speeds; all rows
     belong to one GEMM implementation) or None for no interference.  The small kernels of ``misc``
@@ -253,7 +265,7 @@ def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_
                 while next_layer_kqv and span[next_layer_kqv[0]][1] <= span[(kind, j)][1]:
                     compute.append((*next_layer_kqv.pop(0), l + 1))
         memory += [(kind, j, l) for kind, j in seq if kind == "ATTN"]
-    done = set()
+    done = {}                                 # piece -> the time it ended
 
     def ready(op):
         kind, j, l = op
@@ -263,7 +275,11 @@ def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_
         if kind == "ATTN":
             lo = req_start[lo]                # it also reads K/V appended by the request's earlier tokens
         parent = FEEDS[kind]
-        return all((parent, i, l) in done for i in range(len(parts[parent]) - 1)
+        # a piece on the other resource must have ended `sync` ago (attention after KQV, O after
+        # attention); pieces of the same resource follow each other without it
+        wait = sync if kind in ("ATTN", "O") else 0.0
+        return all((parent, i, l) in done and t >= done[(parent, i, l)] + wait - 1e-9
+                   for i in range(len(parts[parent]) - 1)
                    if max(lo, parts[parent][i]) < min(hi, parts[parent][i + 1]))
 
     left = {(kind, j, l): work[(kind, j)] for (kind, j) in work for l in range(layers)}
@@ -272,7 +288,10 @@ def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_
     while ci < len(compute) or mi < len(memory):
         c = compute[ci] if ci < len(compute) and ready(compute[ci]) else None
         m = memory[mi] if mi < len(memory) and ready(memory[mi]) else None
-        assert c is not None or m is not None, "deadlock"
+        if c is None and m is None:
+            assert sync > 0, "deadlock"
+            t += dt
+            continue
         sc = sm = 1.0
         if rows is not None:
             cur = rows[memory[mi][1]] if mi < len(memory) else rows[-1]
@@ -285,12 +304,12 @@ def makespan_parts(dense, granule, attn_fixed, attn_per_mb, attn_mb_prefix, req_
         if c is not None:
             left[c] -= sc * dt
             if left[c] <= 0:
-                done.add(c)
+                done[c] = t + dt
                 ci += 1
         if m is not None:
             left[m] -= sm * dt
             if left[m] <= 0:
-                done.add(m)
+                done[m] = t + dt
                 mi += 1
         t += dt
     return t

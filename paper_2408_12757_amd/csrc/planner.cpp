@@ -59,6 +59,7 @@ void nf_profile_analytic(NfProfile* p, const nf_model_desc* m, int max_tokens, i
   }
   p->attn_fixed_us = 8.0;
   p->attn_us_per_mb = 1.0 / 5.8;
+  p->sync_us = 0.0;
   for (int t = 0; t <= NF_MAX_TILE; ++t)
     for (int o = 0; o < NF_DENSE_OPS; ++o) p->tile_us[t][o].clear();
   p->rp.clear();
@@ -82,6 +83,7 @@ int nf_profile_save(const NfProfile& p, const char* path) {
   fprintf(f, "misc %.4f %.6f %.4f %.6f %.4f %.6f\n", p.misc_kqv[0], p.misc_kqv[1], p.misc_rest[0], p.misc_rest[1],
           p.misc_attn[0], p.misc_attn[1]);
   fprintf(f, "attn %.6f %.8f\n", p.attn_fixed_us, p.attn_us_per_mb);
+  fprintf(f, "sync %.4f\n", p.sync_us);
   for (const NfRpRow& r : p.rp)
     fprintf(f, "rp %d %.6f %.6f %.6f %d %.6f\n", r.attn_wgs, r.p_gemm, r.p_attn, r.p_attn_solo, r.gemm_tile,
             r.p_gemm_solo);
@@ -133,6 +135,8 @@ int nf_profile_load(NfProfile* p, const char* path) {
     } else if (sscanf(line, "attn %lf %lf", &x, &y) == 2) {
       q.attn_fixed_us = x;
       q.attn_us_per_mb = y;
+    } else if (sscanf(line, "sync %lf", &x) == 1) {
+      q.sync_us = x;
     } else if (!strncmp(line, "rp ", 3)) {
       NfRpRow r{};
       const int nf = sscanf(line, "rp %d %lf %lf %lf %d %lf", &r.attn_wgs, &r.p_gemm, &r.p_attn, &r.p_attn_solo,
@@ -236,22 +240,38 @@ static double simulate_impl(const NfProfile& prof, const NfSearchInput& in, cons
     for (int k = 0; k < n; ++k) q[1].push_back(base + n + ord[k]);
   }
   std::vector<char> done(ops.size(), 0);
+  std::vector<double> done_at(ops.size(), 0.0);
   size_t head[2] = {0, 0};
   double rem[2] = {0, 0};
   bool running[2] = {false, false};
   double t = 0;
   for (;;) {
+    // a nano-operation starts once its dependencies (all on the other lane) are done and the
+    // synchronisation latency behind the last of them has passed
+    double wake = 1e300;
     for (int l = 0; l < 2; ++l) {
       if (running[l] || head[l] >= q[l].size()) continue;
       const SimOp& o = ops[q[l][head[l]]];
       bool ready = true;
-      for (int d : o.deps) ready = ready && done[d];
-      if (ready) {
+      double at = 0.0;
+      for (int d : o.deps) {
+        ready = ready && done[d];
+        at = std::max(at, done_at[d] + prof.sync_us);
+      }
+      if (ready && t + 1e-9 >= at) {
         running[l] = true;
         rem[l] = o.work;
+      } else if (ready) {
+        wake = std::min(wake, at);
       }
     }
-    if (!running[0] && !running[1]) break;  // all done (a valid structure cannot deadlock)
+    if (!running[0] && !running[1]) {
+      if (wake < 1e299) {
+        t = wake;
+        continue;
+      }
+      break;  // all done (a valid structure cannot deadlock)
+    }
     // the row in force: that of the attention nano-operation at the head of its lane
     const NfRpRow* r = row;
     if (rows && !rows->empty() && head[1] < q[1].size()) r = (*rows)[(size_t)((q[1][head[1]] % (3 * n)) - n)];
@@ -271,6 +291,7 @@ static double simulate_impl(const NfProfile& prof, const NfSearchInput& in, cons
     double dt = 1e300;
     for (int l = 0; l < 2; ++l)
       if (running[l]) dt = std::min(dt, rem[l] / std::max(sp[l], 1e-6));
+    if (wake < 1e299) dt = std::min(dt, wake - t);  // the idle lane's nano-operation joins then
     t += dt;
     for (int l = 0; l < 2; ++l) {
       if (!running[l]) continue;
@@ -278,6 +299,7 @@ static double simulate_impl(const NfProfile& prof, const NfSearchInput& in, cons
       if (rem[l] <= 1e-9) {
         running[l] = false;
         done[q[l][head[l]]] = 1;
+        done_at[q[l][head[l]]] = t;
         ++head[l];
       }
     }
@@ -424,22 +446,36 @@ double nf_simulate_parts(const NfProfile& prof, const NfSearchInput& in, const N
     for (size_t i : attn_pos) q[1].push_back((int)(base + i));
   }
   std::vector<char> done(ops.size(), 0);
+  std::vector<double> done_at(ops.size(), 0.0);
   size_t head[2] = {0, 0};
   double rem[2] = {0, 0};
   bool running[2] = {false, false};
   double t = 0;
   for (;;) {
+    double wake = 1e300;  // as in simulate_impl: the synchronisation latency behind a cross-lane dependency
     for (int l = 0; l < 2; ++l) {
       if (running[l] || head[l] >= q[l].size()) continue;
       const Op& o = ops[(size_t)q[l][head[l]]];
       bool ready = true;
-      for (int d : o.deps) ready = ready && done[(size_t)d];
-      if (ready) {
+      double at = 0.0;
+      for (int d : o.deps) {
+        ready = ready && done[(size_t)d];
+        at = std::max(at, done_at[(size_t)d] + prof.sync_us);
+      }
+      if (ready && t + 1e-9 >= at) {
         running[l] = true;
         rem[l] = o.work;
+      } else if (ready) {
+        wake = std::min(wake, at);
       }
     }
-    if (!running[0] && !running[1]) break;
+    if (!running[0] && !running[1]) {
+      if (wake < 1e299) {
+        t = wake;
+        continue;
+      }
+      break;
+    }
     // the row in force: that of the attention nano-operation at the head of its lane
     const NfRpRow* r = nullptr;
     if (!rows.empty()) r = head[1] < q[1].size() ? rows[(size_t)ops[(size_t)q[1][head[1]]].attn_index] : rows.back();
@@ -458,6 +494,7 @@ double nf_simulate_parts(const NfProfile& prof, const NfSearchInput& in, const N
     double dt = 1e300;
     for (int l = 0; l < 2; ++l)
       if (running[l]) dt = std::min(dt, rem[l] / std::max(sp[l], 1e-6));
+    if (wake < 1e299) dt = std::min(dt, wake - t);
     t += dt;
     for (int l = 0; l < 2; ++l) {
       if (!running[l]) continue;
@@ -465,6 +502,7 @@ double nf_simulate_parts(const NfProfile& prof, const NfSearchInput& in, const N
       if (rem[l] <= 1e-9) {
         running[l] = false;
         done[(size_t)q[l][head[l]]] = 1;
+        done_at[(size_t)q[l][head[l]]] = t;
         ++head[l];
       }
     }
@@ -491,6 +529,7 @@ double nf_simulate_per_layer(const NfProfile& prof, const NfSearchInput& in, con
   const double tl = nf_simulate(prof, in, bounds, overlap, row, in.layers);
   return (tl - t1) / (in.layers - 1);
 }
+
 
 static double simulate_ops_per_layer(const NfProfile& prof, const NfSearchInput& in, const std::vector<int>& bounds,
                                      const std::vector<const NfRpRow*>& rows, const std::vector<int>& order) {
@@ -635,7 +674,12 @@ static void refine_partitions(const NfProfile& prof, const NfSearchInput& in, co
   if (!uniform) out->parts = parts;
 }
 
-int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
+int nf_search(const NfProfile& prof, const NfSearchInput& input, NfPipeline* out) {
+  // The time per layer of a run of layers is the increment between one layer and `layers`
+  // layers; the pipeline is in its steady state after two or three, so six price a longer run
+  // just as well at a fraction of the simulations' cost.
+  NfSearchInput in = input;
+  in.layers = std::min(input.layers, 6);
   if (in.n_tokens < 0 || in.granule <= 0 || (int)in.attn_mb_prefix.size() != in.n_tokens + 1) return NF_EINVAL;
   const std::vector<int> whole = {0, in.n_tokens};
   out->bounds = whole;
@@ -667,7 +711,7 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
     if (fabs(a.t1 - b.t1) > 1e-9) return a.t1 < b.t1;
     return a.bounds.size() < b.bounds.size();
   });
-  const size_t keep = std::min<size_t>(cands.size(), 64);
+  const size_t keep = std::min<size_t>(cands.size(), 24);
 
   // Stage II: resource share per structure, with interference.  The best structure is kept
   // per table row; the rows are then ranked by their estimates.  in.rank = 0 asks for the best
@@ -699,8 +743,12 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
   // the refinement passes have gained up to an eighth in the cases seen; a best row that is
   // further than that from unsplit is not worth their time (they run per batch in a serving loop)
   const bool hopeless = rank == 0 && !per_row.empty() && per_row[0].t2 > 1.15 * out->est_us_unsplit;
-  if (pick < per_row.size() && !hopeless) {
-    const RowBest& b = per_row[pick];
+  // the pipeline of one row, refined; rank 0 refines the three best rows and keeps the best result
+  // (the refinement is a local search: the best uniform row is not always its best start)
+  auto build = [&](const RowBest& b, NfPipeline* out) {
+    out->nano_attn_wgs.clear();
+    out->order.clear();
+    for (auto& pb : out->parts) pb.clear();
     out->bounds = cands[b.cand].bounds;
     out->overlap = 1;
     out->attn_wgs = b.row.attn_wgs;
@@ -763,6 +811,14 @@ int nf_search(const NfProfile& prof, const NfSearchInput& in, NfPipeline* out) {
       }
     }
     if (in.refine >= 2) refine_partitions(prof, in, b.row, out);
+  };
+  if (pick < per_row.size() && !hopeless) {
+    build(per_row[pick], out);
+    for (size_t alt = 1; rank == 0 && in.refine && alt < 3 && alt < per_row.size(); ++alt) {
+      NfPipeline other = *out;
+      build(per_row[alt], &other);
+      if (other.est_us < out->est_us - 1e-9) *out = other;
+    }
     if (rank == 0 && out->est_us >= out->est_us_unsplit - 1e-9) {
       // nothing beats running unsplit
       out->bounds = whole;

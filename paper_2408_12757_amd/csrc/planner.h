@@ -41,6 +41,9 @@ struct NfProfile {
   // the small row-wise kernels, as fixed + per-token microseconds: norm + rotary/append before
   // the KQV GEMM's consumers, norm before Up/Gate, merge after attention
   double misc_kqv[2] = {8.0, 0.02}, misc_rest[2] = {4.0, 0.005}, misc_attn[2] = {4.0, 0.02};
+  // a dependency that crosses lanes (an event wait on another stream) lets the waiting kernel
+  // start this much later than a kernel that follows its predecessor on one stream (microseconds)
+  double sync_us = 0.0;
   // stand-alone attention: fixed cost + cost per byte of K/V read, at the best configuration
   double attn_fixed_us = 5.0;
   double attn_us_per_mb = 1.0 / 5.7;  // 5.7 TB/s

@@ -278,6 +278,39 @@ int measure(nf_ctx* ctx, const nf_model_desc* m, int max_tokens, int granule, Nf
     }
   }
 
+  // ---- latency of a dependency across the two lanes: a chain of tiny kernels that alternates
+  // between the streams (event record, event wait) against the same chain on one stream ----
+  if (!rc) {
+    constexpr int kHops = 16;
+    std::vector<hipEvent_t> ev(2 * kHops);
+    for (auto& e : ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) rc = NF_EHIP;
+    auto tiny = [&](hipStream_t s) { return nf_launch_rmsnorm(x, res, y, 1, m->hidden, m->rms_eps, s); };
+    double t_same = 0, t_cross = 0;
+    if (!rc)
+      rc = time_ms(ctx, sg, 3, [&] {
+        for (int i = 0; i < 2 * kHops; ++i)
+          if (tiny(sg) != hipSuccess) return NF_EHIP;
+        return NF_OK;
+      }, &t_same);
+    if (!rc)
+      rc = time_ms(ctx, sg, 3, [&] {
+        for (int i = 0; i < kHops; ++i) {
+          hipError_t e = tiny(sg);
+          if (e == hipSuccess) e = hipEventRecord(ev[2 * i], sg);
+          if (e == hipSuccess) e = hipStreamWaitEvent(sa, ev[2 * i], 0);
+          if (e == hipSuccess) e = tiny(sa);
+          if (e == hipSuccess) e = hipEventRecord(ev[2 * i + 1], sa);
+          if (e == hipSuccess) e = hipStreamWaitEvent(sg, ev[2 * i + 1], 0);
+          if (e != hipSuccess) return NF_EHIP;
+        }
+        return NF_OK;
+      }, &t_cross);
+    (void)hipDeviceSynchronize();
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (!rc) p->sync_us = std::max(0.0, (t_cross - t_same) * 1e3 / (2 * kHops));
+  }
+
   // ---- pairwise interference: the GEMM work of a two-nano-batch pipeline (O, Up/Gate, Down and
   // the next KQV on half of the batch, in every tile shape) || attention with k persistent
   // workgroups.  Performance is normalised to the best stand-alone implementation of each

@@ -19,7 +19,8 @@ def host_batch(b: wl.Batch) -> nf.BatchArgs:
                         b.page_ids, dev)
 
 
-def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_mb, rows, misc=None, tiles=None):
+def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_mb, rows, misc=None, tiles=None,
+                  sync=0.0):
     """tiles: {tile id: {op name: table}} interference-free times per GEMM implementation."""
     misc = misc or ((0, 0), (0, 0), (0, 0))
     with open(path, "w") as f:
@@ -35,6 +36,8 @@ def write_profile(path, model, granule, max_tokens, dense, attn_fixed, attn_per_
                     f.write(f"tile_us {t} {o} {(i + 1) * granule} {us:.4f}\n")
         f.write("misc " + " ".join(f"{v:.6f}" for pair in misc for v in pair) + "\n")
         f.write(f"attn {attn_fixed:.6f} {attn_per_mb:.8f}\n")
+        if sync:
+            f.write(f"sync {sync:.4f}\n")
         for r in rows:
             f.write(f"rp {r['attn_wgs']} {r['p_gemm']:.6f} {r['p_attn']:.6f} {r['p_attn_solo']:.6f} "
                     f"{r.get('gemm_tile', 0)} {r.get('p_gemm_solo', 1.0):.6f}\n")
@@ -379,14 +382,15 @@ def test_per_nano_operation_shares_and_order_match_the_oracle(tmp_path, seed):
     per_mb = r.uniform(0.8, 2.5) * sum(sum(v) for v in dense.values()) / n_gran / pre[-1]
     rows = table3_rows()
     path = str(tmp_path / "p.txt")
-    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows)
+    sync = 4.0 if seed == 1 else 0.0
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows, sync=sync)
     import itertools
     for bounds in ([0, 24, 48], [0, 8, 24, 48], [0, 16, 24, 40, 48]):
         n = len(bounds) - 1
         for order in itertools.permutations(range(n)):
             idx = [int(x) for x in r.integers(0, len(rows), size=n)]
             want = pm.makespan(dense, g, 2.0, per_mb, pre, start, bounds, True, None, dt=0.01,
-                               rows=[rows[i] for i in idx], order=list(order))
+                               rows=[rows[i] for i in idx], order=list(order), sync=sync)
             if want is None:
                 with pytest.raises(nf.NfError) as e:
                     nf.nf_simulate_pipeline_ops(MODEL, host_batch(b), bounds, idx, list(order), path)
@@ -523,6 +527,9 @@ def test_partition_model_closed_forms():
     parts = {"KQV": [0, 20, 40], "ATTN": [0, 40], "O": [0, 10, 40], "UG": [0, 40], "D": [0, 30, 40]}
     t = pm.makespan_parts(dense, g, 0.0, 1.0, pre, start, parts, True, None, dt=0.01)
     assert t == pytest.approx(12.0 + 20.0 + 8.0 + 20.0 + 16.0, abs=0.1)
+    # a latency of 1.5 behind every dependency that crosses the resources: KQV -> attention -> O
+    t = pm.makespan_parts(dense, g, 0.0, 1.0, pre, start, parts, True, None, dt=0.01, sync=1.5)
+    assert t == pytest.approx(12.0 + 1.5 + 20.0 + 1.5 + 8.0 + 20.0 + 16.0, abs=0.1)
     parts["ATTN"] = [0, 20, 40]
     t = pm.makespan_parts(dense, g, 0.0, 1.0, pre, start, parts, True, None, dt=0.01)
     # KQV0 6, then attention 10 + 10 on its lane (KQV1 hidden), O waits for the attention of its rows:
@@ -536,11 +543,12 @@ def test_partition_model_matches_the_oracle(tmp_path, seed):
     prefill request cut by some of the boundaries, one layer and a run of layers, overlapped and
     back to back: the event-driven C++ model against the oracle's time stepping."""
     misc = ((1.0, 0.01), (0.5, 0.02), (0.7, 0.03))
+    sync = (0.0, 3.0, 0.0, 7.5)[seed]           # latency of a dependency that crosses the two lanes
     r, b, dense, pre, start, per_mb = random_instance(200 + seed)
     g, n_tok = 8, b.n_tokens
     rows = table3_rows()
     path = str(tmp_path / "p.txt")
-    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows, misc=misc)
+    write_profile(path, MODEL, g, n_tok, dense, 2.0, per_mb, rows, misc=misc, sync=sync)
 
     def random_partition():
         cuts = sorted(int(c) * g for c in r.choice(np.arange(1, n_tok // g), size=int(r.integers(0, 4)), replace=False))
@@ -556,10 +564,10 @@ def test_partition_model_matches_the_oracle(tmp_path, seed):
         want_seq = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, False, None, 0.01, misc)
         assert nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, False, None, path) == \
             pytest.approx(want_seq, rel=1e-6)        # the profile file keeps four to eight decimals
-        t1 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc)
+        t1 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc, sync=sync)
         assert nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, True, idx, path) == \
             pytest.approx(t1, rel=2e-3, abs=0.2), parts
-        t4 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc, layers=4)
+        t4 = pm.makespan_parts(dense, g, 2.0, per_mb, pre, start, parts, True, chosen, 0.01, misc, layers=4, sync=sync)
         nf.nf_tune_set("search.layers", 4)
         try:
             got = nf.nf_simulate_pipeline_parts(MODEL, host_batch(b), parts, True, idx, path)
