@@ -244,7 +244,9 @@ int nf_probe_load_latency(nf_ctx *ctx, int n_workgroups, int iters, float *out, 
  * with every GEMM tile shape (keeping the best: the kernel -> implementation map),
  * times decode attention alone for every persistent-workgroup count in the search
  * set, and times GEMM || attention pairs to obtain the R -> P resource-mapping
- * table (dominated pairs are dropped).  Results are kept in ctx and, if cache_path
+ * table (pairs dominated by more than the scatter of the measurement are dropped), the small
+ * row-wise kernels, and how much later a kernel starts when it waits for a kernel of the other
+ * lane than when it follows one on its own lane.  Results are kept in ctx and, if cache_path
  * (host string) is not NULL, read from that text file when it matches, else
  * written to it.  Synchronous; allocates and frees its own scratch device memory
  * (weights of one layer plus a few GB of synthetic KV cache).
