@@ -109,6 +109,10 @@ def test_c2_full_size_sampled_parity_and_plan_invariance(c2, tmp_path):
         with pytest.raises(nf.NfError) as e:
             nf.nf_plan_search(case.ctx, m, case.args, 0, cfg.granule, **bad)
         assert e.value.status == nf.NF_EINVAL
+    # the profile holds the latency of a dependency across the two lanes: a few microseconds
+    sync = [float(l.split()[1]) for l in open(tmp_path / "profile.txt") if l.startswith("sync ")]
+    assert len(sync) == 1 and 0.0 <= sync[0] < 100.0, sync
+    say("cross-lane latency", sync[0], "us")
     # the profile file round-trips through the host-only search
     got = nf.nf_search_pipeline(m, case.args, str(tmp_path / "profile.txt"), 0, cfg.granule)
     assert got["bounds"] == plans[0].describe()["bounds"]
